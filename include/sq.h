@@ -1,0 +1,191 @@
+/*
+ * sq.h -- C boundary of the SqueezeNet forward library for AMD MI355X (gfx950).
+ *
+ * The library computes the forward path of the network the paper accelerates
+ * (section "Convolutional Neural Networks"): convolution layers with
+ * numInputLayers -> numOutputLayers feature maps, K x K kernels slid by stride
+ * S, the fire layer (one squeeze and two expand convolutions), max and average
+ * pooling and softmax (section "Pooling and Softmax"), and the whole SqueezeNet
+ * chain.  Bias and ReLU are fused into every convolution.
+ *
+ * Conventions that hold for every entry point
+ *   - Every data pointer is a DEVICE pointer to memory of the current HIP
+ *     device, owned by the caller.  The library never allocates, frees, copies
+ *     to the host or synchronises: work is enqueued on the stream given to
+ *     sq_set_stream() (default: the null stream) and the call returns.
+ *     The one host-side array is the parameter table of
+ *     sq_squeezenet_forward, which is read before the call returns.
+ *   - Tensors are dense and row-major.  Activations are [N][C][H][W] ("row
+ *     major" order D of section "Data Reordering", one image after another),
+ *     kernels are [Cout][Cin][K][K], biases [Cout].  fp32 unless stated.
+ *   - Inputs and outputs must not overlap.
+ *   - Convolution is a cross-correlation (no kernel flip) with P pixels of
+ *     zero padding on every side; output extent is floor((H + 2P - K)/S) + 1.
+ *   - Every function returns SQ_OK (0) or a negative sq_status.  Arguments are
+ *     validated on the host before any GPU work is issued; on an argument
+ *     error nothing has been enqueued and no output is touched.  SQ_ERR_HIP
+ *     reports a failed launch; sq_last_hip_error() then gives the HIP code.
+ *   - Calls are not re-entrant with respect to sq_set_stream(): the stream is
+ *     a per-host-thread setting.
+ */
+#ifndef SQ_H
+#define SQ_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sq_status {
+    SQ_OK = 0,
+    SQ_ERR_NULL = -1,        /* a required pointer is NULL                         */
+    SQ_ERR_SHAPE = -2,       /* a dimension is <= 0, S < 1, P < 0, or K > H + 2P   */
+    SQ_ERR_UNSUPPORTED = -3, /* dtype / algorithm / shape no kernel here covers    */
+    SQ_ERR_WORKSPACE = -4,   /* workspace missing, misaligned or too small         */
+    SQ_ERR_HIP = -5          /* a HIP launch failed; see sq_last_hip_error()       */
+} sq_status;
+
+typedef enum sq_dtype {
+    SQ_F32 = 0,  /* IEEE binary32 inputs and kernels                               */
+    SQ_BF16 = 1  /* bfloat16 inputs and kernels, fp32 accumulate, fp32 bias/output */
+} sq_dtype;
+
+/* Algorithm selector of sq_conv2d_forward_ex.  Values >= SQ_ALGO_VARIANT0 pick
+ * one tiling of the matrix-core kernel family (how much output one workgroup
+ * and one wavefront produce -- the counterpart of the thread granularity g of
+ * section "Optimizing Thread Granularity"); sq_conv_variant_count() says how
+ * many exist.  Every algorithm must give the same result up to rounding. */
+enum {
+    SQ_ALGO_AUTO = 0,     /* library's per-shape choice                            */
+    SQ_ALGO_DIRECT = 1,   /* one thread per output element, any K, S, P            */
+    SQ_ALGO_VARIANT0 = 2  /* first matrix-core tiling; VARIANT0 + i is the i-th    */
+};
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char *sq_strerror(int status);
+
+/* hipError_t (as int) of the last failed launch on this host thread, 0 if none. */
+int sq_last_hip_error(void);
+
+/* Stream (a hipStream_t passed as void*, NULL = null stream) on which every
+ * later call from this host thread enqueues its kernels. */
+int sq_set_stream(void *hip_stream);
+
+/* Number of matrix-core tilings and a short name for each ("" if out of range). */
+int sq_conv_variant_count(void);
+const char *sq_conv_variant_name(int index);
+
+/*
+ * Convolution layer (section "Convolutional Neural Networks"; sequential form in
+ * section "Parallel Algorithm Design"), with bias and optional ReLU:
+ *   out[n][m][oh][ow] = act( b[m] + sum_{c,i,j} in[n][c][oh*S+i-P][ow*S+j-P] * w[m][c][i][j] )
+ * taps outside the image contribute zero; act = max(.,0) if relu != 0.
+ *   in  [N][Cin][H][W], w [Cout][Cin][K][K], b [Cout] or NULL (= zero),
+ *   out [N][Cout][Ho][Wo], Ho = floor((H+2P-K)/S)+1, Wo likewise.  All fp32.
+ * Errors: SQ_ERR_NULL (in, w or out NULL), SQ_ERR_SHAPE, SQ_ERR_HIP.
+ */
+int sq_conv2d_forward(const void *in, const void *w, const float *b, float *out,
+                      int N, int Cin, int H, int W, int Cout, int K, int S, int P,
+                      int relu);
+
+/*
+ * Same operation with three extras.
+ *   out_channels, c_offset: the result is written into layers
+ *     [c_offset, c_offset + Cout) of an output tensor [N][out_channels][Ho][Wo];
+ *     other layers are left untouched.  This is how the two expand convolutions
+ *     of a fire layer produce one concatenated tensor with no copy (the paper
+ *     likewise stores results directly in the layout the next layer reads,
+ *     section "Zero-overhead Vectorization").  Need 0 <= c_offset and
+ *     c_offset + Cout <= out_channels, else SQ_ERR_SHAPE.
+ *   in_dtype: SQ_F32, or SQ_BF16 = `in` and `w` hold bfloat16 (2 bytes each,
+ *     the upper half of the binary32 pattern); products are accumulated in fp32,
+ *     b and out stay fp32.  This is the reduced-precision mode standing in for
+ *     the paper's relaxed arithmetic (section "Imprecise Computing").
+ *   algo: SQ_ALGO_AUTO, SQ_ALGO_DIRECT or SQ_ALGO_VARIANT0 + i.  A variant
+ *     that cannot run the given shape returns SQ_ERR_UNSUPPORTED.
+ */
+int sq_conv2d_forward_ex(const void *in, const void *w, const float *b, float *out,
+                         int N, int Cin, int H, int W, int Cout, int K, int S, int P,
+                         int relu, int out_channels, int c_offset, int in_dtype,
+                         int algo);
+
+/*
+ * Max pooling (section "Pooling and Softmax"): out[n][c][oh][ow] = largest of the
+ * K x K window whose corner is (oh*S, ow*S).  No padding, floor mode:
+ * Ho = floor((H-K)/S)+1.  in [N][C][H][W], out [N][C][Ho][Wo], fp32.
+ * Errors: SQ_ERR_NULL, SQ_ERR_SHAPE (incl. K > H or K > W), SQ_ERR_HIP.
+ */
+int sq_maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int S);
+
+/*
+ * Average pooling over the whole plane (section "Pooling and Softmax"; the
+ * network applies it to the 13 x 13 classifier maps):
+ * out[n][c] = mean over h,w of in[n][c][h][w].  in [N][C][H][W], out [N][C].
+ */
+int sq_avgpool_global(const float *in, float *out, int N, int C, int H, int W);
+
+/*
+ * Softmax over the C scores of each image (section "Pooling and Softmax"; the
+ * paper leaves it on the CPU, here it runs on the GPU so the network call has no
+ * host round trip): out[n][c] = exp(in[n][c] - max_n) / sum_c exp(in[n][c] - max_n).
+ * in, out [N][C].
+ */
+int sq_softmax(const float *in, float *out, int N, int C);
+
+/*
+ * Fire layer (section "Convolutional Neural Networks": one squeeze layer and two
+ * expand layers).  s = relu(conv1x1(in; w_sq, b_sq)) with Csq layers;
+ * out layers [0, Ce1)        = relu(conv1x1(s; w_e1, b_e1)),
+ * out layers [Ce1, Ce1+Ce3)  = relu(conv3x3 pad 1 (s; w_e3, b_e3)); the padding
+ * of the 3x3 is zero in the squeeze map s.
+ *   in [N][Cin][H][W]; w_sq [Csq][Cin][1][1]; w_e1 [Ce1][Csq][1][1];
+ *   w_e3 [Ce3][Csq][3][3]; biases [Csq], [Ce1], [Ce3] (each may be NULL);
+ *   out [N][Ce1+Ce3][H][W].  All fp32.
+ *   workspace: device scratch of at least sq_fire_workspace_bytes(N, H, W, Csq)
+ *   bytes, 256-byte aligned, holding the squeeze map during the call; contents on
+ *   return are unspecified.
+ * Errors: SQ_ERR_NULL, SQ_ERR_SHAPE, SQ_ERR_WORKSPACE, SQ_ERR_HIP.
+ */
+int sq_fire_forward(const void *in, const void *w_sq, const float *b_sq,
+                    const void *w_e1, const float *b_e1, const void *w_e3,
+                    const float *b_e3, float *out, int N, int Cin, int H, int W,
+                    int Csq, int Ce1, int Ce3, void *workspace, size_t workspace_bytes);
+
+size_t sq_fire_workspace_bytes(int N, int H, int W, int Csq);
+
+/*
+ * SqueezeNet v1.0 forward (section "Convolutional Neural Networks": two
+ * convolution layers and eight fire layers; 224 x 224 RGB input, 1000 classes):
+ *   conv1 96@7x7 stride 2 pad 2 +ReLU -> maxpool 3/2 -> fire2 (16, 64+64) ->
+ *   fire3 (16, 64+64) -> fire4 (32, 128+128) -> maxpool 3/2 -> fire5 (32, 128+128)
+ *   -> fire6 (48, 192+192) -> fire7 (48, 192+192) -> fire8 (64, 256+256) ->
+ *   maxpool 3/2 -> fire9 (64, 256+256) -> conv10 1x1 to 1000 +ReLU ->
+ *   global average pool 13x13 -> softmax.
+ * (conv1 takes pad 2 so that 224 -> 111 -> 55 -> 27 -> 13.)
+ *   in     [N][3][224][224] fp32 (device).
+ *   params HOST array of 52 DEVICE pointers: kernel then bias of each of the 26
+ *          convolutions in network order (conv1; squeeze, expand1x1, expand3x3 of
+ *          fire2..fire9; conv10), shapes as above, fp32.  No bias may be NULL.
+ *   probs  [N][1000] fp32 (device), rows sum to 1.
+ *   workspace: device scratch of at least sq_squeezenet_workspace_bytes(N) bytes,
+ *          256-byte aligned; holds every intermediate activation.
+ *   taps   NULL, or a HOST array of 16 DEVICE pointers; each non-NULL entry
+ *          receives a copy of one stage's result: 0 conv1 [N][96][111][111],
+ *          1 pool1 [N][96][55][55], 2 fire2, 3 fire3 [N][128][55][55], 4 fire4
+ *          [N][256][55][55], 5 pool4 [N][256][27][27], 6 fire5, 7 fire6, 8 fire7
+ *          [N][384][27][27], 9 fire8 [N][512][27][27], 10 pool8, 11 fire9
+ *          [N][512][13][13], 12 conv10 [N][1000][13][13], 13 class means
+ *          [N][1000], 14 probabilities [N][1000], 15 reserved (must be NULL).
+ * Errors: SQ_ERR_NULL, SQ_ERR_SHAPE (N <= 0), SQ_ERR_WORKSPACE, SQ_ERR_HIP.
+ */
+int sq_squeezenet_forward(const void *in, const void *const *params, float *probs,
+                          int N, void *workspace, size_t workspace_bytes,
+                          float *const *taps);
+
+size_t sq_squeezenet_workspace_bytes(int N);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SQ_H */

@@ -1,0 +1,13 @@
+"""SqueezeNet forward path for AMD MI355X: Python binding of libsq.so.
+
+The functions here have the names of the C entry points in include/sq.h and do
+argument marshalling only (tensor checks, output allocation, pointer passing);
+every step of the computation runs in the library's HIP kernels.  PyTorch
+supplies device memory and the current stream, nothing else.  There is no CPU
+fallback: if the library is missing the import fails.
+"""
+from .binding import (  # noqa: F401
+    SQ_ALGO_AUTO, SQ_ALGO_DIRECT, SQ_ALGO_VARIANT0, SQ_BF16, SQ_F32, SqError, lib,
+    sq_avgpool_global, sq_conv2d_forward, sq_conv2d_forward_ex, sq_conv_variant_count,
+    sq_conv_variant_name, sq_fire_forward, sq_fire_workspace_bytes, sq_maxpool, sq_softmax,
+    sq_squeezenet_forward, sq_squeezenet_workspace_bytes, sq_strerror, TAP_NAMES, TAP_SHAPES)

@@ -1,0 +1,216 @@
+"""ctypes binding of libsq.so; see include/sq.h for the contract of each call."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsq.so")
+
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        f"{_LIB_PATH} is missing: build it with `python paper_1611_07151_amd/build.py` "
+        "(there is no fallback path)")
+
+lib = ctypes.CDLL(_LIB_PATH)
+
+SQ_F32, SQ_BF16 = 0, 1
+SQ_ALGO_AUTO, SQ_ALGO_DIRECT, SQ_ALGO_VARIANT0 = 0, 1, 2
+
+_vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+lib.sq_strerror.restype = ctypes.c_char_p
+lib.sq_strerror.argtypes = [_i]
+lib.sq_last_hip_error.restype = _i
+lib.sq_set_stream.argtypes = [_vp]
+lib.sq_conv_variant_count.restype = _i
+lib.sq_conv_variant_name.restype = ctypes.c_char_p
+lib.sq_conv_variant_name.argtypes = [_i]
+lib.sq_conv2d_forward.argtypes = [_vp] * 4 + [_i] * 9
+lib.sq_conv2d_forward_ex.argtypes = [_vp] * 4 + [_i] * 13
+lib.sq_maxpool.argtypes = [_vp, _vp] + [_i] * 6
+lib.sq_avgpool_global.argtypes = [_vp, _vp] + [_i] * 4
+lib.sq_softmax.argtypes = [_vp, _vp, _i, _i]
+lib.sq_fire_forward.argtypes = [_vp] * 8 + [_i] * 7 + [_vp, _sz]
+lib.sq_fire_workspace_bytes.restype = _sz
+lib.sq_fire_workspace_bytes.argtypes = [_i] * 4
+lib.sq_squeezenet_forward.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _i, _vp, _sz, ctypes.POINTER(_vp)]
+lib.sq_squeezenet_workspace_bytes.restype = _sz
+lib.sq_squeezenet_workspace_bytes.argtypes = [_i]
+
+TAP_NAMES = ("conv1", "pool1", "fire2", "fire3", "fire4", "pool4", "fire5", "fire6",
+             "fire7", "fire8", "pool8", "fire9", "conv10", "means", "probs")
+TAP_SHAPES = ((96, 111), (96, 55), (128, 55), (128, 55), (256, 55), (256, 27), (256, 27),
+              (384, 27), (384, 27), (512, 27), (512, 13), (512, 13), (1000, 13))
+
+
+class SqError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        msg = lib.sq_strerror(status).decode()
+        if status == -5:
+            msg += f" (hipError {lib.sq_last_hip_error()})"
+        super().__init__(f"{what}: {msg} [{status}]")
+
+
+def sq_strerror(status: int) -> str:
+    return lib.sq_strerror(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise SqError(status, what)
+
+
+def _dev(t, dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}")
+    return t.data_ptr()
+
+
+def _use_current_stream():
+    lib.sq_set_stream(torch.cuda.current_stream().cuda_stream)
+
+
+def sq_conv_variant_count() -> int:
+    return int(lib.sq_conv_variant_count())
+
+
+def sq_conv_variant_name(i: int) -> str:
+    return lib.sq_conv_variant_name(int(i)).decode()
+
+
+def _out_extent(h, k, s, p):
+    return (h + 2 * p - k) // s + 1
+
+
+def sq_conv2d_forward(x, w, b=None, stride=1, pad=0, relu=False):
+    N, Cin, H, W = x.shape
+    Cout, _, K, _ = w.shape
+    if w.shape[1] != Cin or w.shape[3] != K:
+        raise ValueError("kernel shape does not match the input")
+    if H + 2 * pad < K or W + 2 * pad < K:
+        _check(-2, "sq_conv2d_forward")
+    out = torch.empty((N, Cout, _out_extent(H, K, stride, pad), _out_extent(W, K, stride, pad)),
+                      device=x.device, dtype=torch.float32)
+    _use_current_stream()
+    rc = lib.sq_conv2d_forward(_dev(x, torch.float32, "x"), _dev(w, torch.float32, "w"),
+                               _dev(b, torch.float32, "b"), _dev(out), N, Cin, H, W, Cout, K,
+                               int(stride), int(pad), int(bool(relu)))
+    _check(rc, "sq_conv2d_forward")
+    return out
+
+
+def sq_conv2d_forward_ex(x, w, b=None, stride=1, pad=0, relu=False, out=None, c_offset=0,
+                         algo=SQ_ALGO_AUTO):
+    """x and w float32 or both bfloat16.  `out` may be a larger [N][C'][Ho][Wo] tensor; the
+    result lands in layers [c_offset, c_offset+Cout)."""
+    N, Cin, H, W = x.shape
+    Cout, _, K, _ = w.shape
+    if w.shape[1] != Cin or w.shape[3] != K:
+        raise ValueError("kernel shape does not match the input")
+    if x.dtype != w.dtype or x.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("x and w must both be float32 or both bfloat16")
+    if H + 2 * pad < K or W + 2 * pad < K:
+        _check(-2, "sq_conv2d_forward_ex")
+    Ho, Wo = _out_extent(H, K, stride, pad), _out_extent(W, K, stride, pad)
+    if out is None:
+        out = torch.empty((N, Cout + c_offset, Ho, Wo), device=x.device, dtype=torch.float32)
+    if out.shape[0] != N or out.shape[2] != Ho or out.shape[3] != Wo:
+        raise ValueError("out has the wrong shape")
+    dt = SQ_F32 if x.dtype == torch.float32 else SQ_BF16
+    _use_current_stream()
+    rc = lib.sq_conv2d_forward_ex(_dev(x, None, "x"), _dev(w, None, "w"), _dev(b, torch.float32, "b"),
+                                  _dev(out, torch.float32, "out"), N, Cin, H, W, Cout, K, int(stride),
+                                  int(pad), int(bool(relu)), out.shape[1], int(c_offset), dt, int(algo))
+    _check(rc, "sq_conv2d_forward_ex")
+    return out
+
+
+def sq_maxpool(x, k=3, stride=2):
+    N, C, H, W = x.shape
+    if k > H or k > W:
+        _check(-2, "sq_maxpool")
+    out = torch.empty((N, C, (H - k) // stride + 1, (W - k) // stride + 1), device=x.device,
+                      dtype=torch.float32)
+    _use_current_stream()
+    _check(lib.sq_maxpool(_dev(x, torch.float32, "x"), _dev(out), N, C, H, W, int(k), int(stride)),
+           "sq_maxpool")
+    return out
+
+
+def sq_avgpool_global(x):
+    N, C, H, W = x.shape
+    out = torch.empty((N, C), device=x.device, dtype=torch.float32)
+    _use_current_stream()
+    _check(lib.sq_avgpool_global(_dev(x, torch.float32, "x"), _dev(out), N, C, H, W), "sq_avgpool_global")
+    return out
+
+
+def sq_softmax(x):
+    N, C = x.shape
+    out = torch.empty((N, C), device=x.device, dtype=torch.float32)
+    _use_current_stream()
+    _check(lib.sq_softmax(_dev(x, torch.float32, "x"), _dev(out), N, C), "sq_softmax")
+    return out
+
+
+def sq_fire_workspace_bytes(N, H, W, Csq) -> int:
+    return int(lib.sq_fire_workspace_bytes(N, H, W, Csq))
+
+
+def sq_fire_forward(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, workspace=None, out=None):
+    N, Cin, H, W = x.shape
+    Csq, Ce1, Ce3 = w_sq.shape[0], w_e1.shape[0], w_e3.shape[0]
+    if tuple(w_sq.shape) != (Csq, Cin, 1, 1) or tuple(w_e1.shape) != (Ce1, Csq, 1, 1) \
+            or tuple(w_e3.shape) != (Ce3, Csq, 3, 3):
+        raise ValueError("fire kernel shapes")
+    need = sq_fire_workspace_bytes(N, H, W, Csq)
+    if workspace is None:
+        workspace = torch.empty(need, device=x.device, dtype=torch.uint8)
+    if out is None:
+        out = torch.empty((N, Ce1 + Ce3, H, W), device=x.device, dtype=torch.float32)
+    f32 = torch.float32
+    _use_current_stream()
+    rc = lib.sq_fire_forward(_dev(x, f32, "x"), _dev(w_sq, f32, "w_sq"), _dev(b_sq, f32, "b_sq"),
+                             _dev(w_e1, f32, "w_e1"), _dev(b_e1, f32, "b_e1"), _dev(w_e3, f32, "w_e3"),
+                             _dev(b_e3, f32, "b_e3"), _dev(out, f32, "out"), N, Cin, H, W, Csq, Ce1, Ce3,
+                             _dev(workspace), workspace.numel() * workspace.element_size())
+    _check(rc, "sq_fire_forward")
+    return out
+
+
+def sq_squeezenet_workspace_bytes(N) -> int:
+    return int(lib.sq_squeezenet_workspace_bytes(int(N)))
+
+
+def sq_squeezenet_forward(x, params, workspace=None, probs=None, want_taps=False):
+    """x [N,3,224,224] float32; params: 52 device tensors (kernel, bias per convolution in
+    network order).  Returns probs [N,1000], or (probs, {stage: tensor}) with want_taps."""
+    N = x.shape[0]
+    if tuple(x.shape[1:]) != (3, 224, 224) or len(params) != 52:
+        raise ValueError("expects [N,3,224,224] and 52 parameter tensors")
+    if workspace is None:
+        workspace = torch.empty(sq_squeezenet_workspace_bytes(N), device=x.device, dtype=torch.uint8)
+    if probs is None:
+        probs = torch.empty((N, 1000), device=x.device, dtype=torch.float32)
+    parr = (_vp * 52)(*[_dev(p, torch.float32, f"params[{i}]") for i, p in enumerate(params)])
+    taps, tarr = {}, None
+    if want_taps:
+        for name, (c, h) in zip(TAP_NAMES, TAP_SHAPES):
+            taps[name] = torch.empty((N, c, h, h), device=x.device, dtype=torch.float32)
+        taps["means"] = torch.empty((N, 1000), device=x.device, dtype=torch.float32)
+        taps["probs"] = torch.empty((N, 1000), device=x.device, dtype=torch.float32)
+        tarr = (_vp * 16)(*([taps[n].data_ptr() for n in TAP_NAMES] + [None]))
+    _use_current_stream()
+    rc = lib.sq_squeezenet_forward(_dev(x, torch.float32, "x"), parr, _dev(probs, torch.float32, "probs"),
+                                   N, _dev(workspace), workspace.numel() * workspace.element_size(), tarr)
+    _check(rc, "sq_squeezenet_forward")
+    return (probs, taps) if want_taps else probs

@@ -1,0 +1,44 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "sq.h"
+
+namespace sq {
+
+// Stream of the calling host thread (set by sq_set_stream).
+hipStream_t current_stream();
+
+// Folds the sticky launch error into a status code and records it.
+int check_launch();
+
+// One convolution call after validation.  Ho/Wo are precomputed; the result goes
+// to layers [c_offset, c_offset+Cout) of an [N][out_channels][Ho][Wo] tensor.
+struct ConvArgs {
+    const void *in;
+    const void *w;
+    const float *b;
+    float *out;
+    int N, Cin, H, W, Cout, K, S, P, relu;
+    int Ho, Wo, out_channels, c_offset;
+    int dtype;  // sq_dtype of in and w
+};
+
+int conv_direct(const ConvArgs &a);
+
+// Matrix-core family.  variant < 0 = pick by shape; returns SQ_ERR_UNSUPPORTED when
+// the (variant, shape, dtype) combination has no kernel.
+int conv_mfma(const ConvArgs &a, int variant);
+int conv_mfma_variant_count();
+const char *conv_mfma_variant_name(int i);
+
+int maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int S);
+int avgpool_global(const float *in, float *out, int N, int C, int H, int W);
+int softmax(const float *in, float *out, int N, int C);
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace sq

@@ -1,0 +1,119 @@
+"""The C boundary on a machine without a GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching HIP."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sq.h")
+LIB = os.path.join(ROOT, "paper_1611_07151_amd", "libsq.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    assert os.path.exists(LIB), "build the library first: python paper_1611_07151_amd/build.py"
+    l = ctypes.CDLL(LIB)
+    l.sq_strerror.restype = ctypes.c_char_p
+    l.sq_fire_workspace_bytes.restype = ctypes.c_size_t
+    l.sq_squeezenet_workspace_bytes.restype = ctypes.c_size_t
+    l.sq_conv_variant_name.restype = ctypes.c_char_p
+    return l
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert {"sq_conv2d_forward", "sq_maxpool", "sq_fire_forward", "sq_squeezenet_forward"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_strerror_covers_all_codes(lib):
+    seen = {lib.sq_strerror(c) for c in range(0, -6, -1)}
+    assert len(seen) == 6 and b"unknown status" not in seen
+    assert lib.sq_strerror(-99) == b"unknown status"
+
+
+FAKE = ctypes.c_void_p(0x1000)   # never dereferenced: validation fails first
+NULL = ctypes.c_void_p(0)
+
+
+def test_conv_rejects_bad_arguments_before_any_gpu_call(lib):
+    f = lib.sq_conv2d_forward
+    good = [1, 3, 8, 8, 4, 3, 1, 1, 1]
+    assert f(NULL, FAKE, FAKE, FAKE, *good) == -1
+    assert f(FAKE, NULL, FAKE, FAKE, *good) == -1
+    assert f(FAKE, FAKE, FAKE, NULL, *good) == -1
+    for idx, bad in [(0, 0), (1, -1), (2, 0), (3, 0), (4, 0), (5, 0), (6, 0), (7, -1)]:
+        args = list(good)
+        args[idx] = bad
+        assert f(FAKE, FAKE, FAKE, FAKE, *args) == -2, (idx, bad)
+    # window larger than the padded image
+    assert f(FAKE, FAKE, FAKE, FAKE, 1, 3, 4, 4, 4, 7, 1, 1, 0) == -2
+    g = lib.sq_conv2d_forward_ex
+    assert g(FAKE, FAKE, FAKE, FAKE, *good, 4, 1, 0, 0) == -2      # c_offset + Cout > out_channels
+    assert g(FAKE, FAKE, FAKE, FAKE, *good, 4, -1, 0, 0) == -2
+    assert g(FAKE, FAKE, FAKE, FAKE, *good, 4, 0, 7, 0) == -3      # unknown dtype
+    assert g(FAKE, FAKE, FAKE, FAKE, *good, 4, 0, 0, 2 + lib.sq_conv_variant_count()) == -3
+
+
+def test_pool_and_softmax_reject_bad_arguments(lib):
+    assert lib.sq_maxpool(NULL, FAKE, 1, 1, 8, 8, 3, 2) == -1
+    assert lib.sq_maxpool(FAKE, FAKE, 1, 1, 2, 8, 3, 2) == -2
+    assert lib.sq_maxpool(FAKE, FAKE, 1, 1, 8, 8, 3, 0) == -2
+    assert lib.sq_avgpool_global(FAKE, NULL, 1, 1, 8, 8) == -1
+    assert lib.sq_avgpool_global(FAKE, FAKE, 1, 0, 8, 8) == -2
+    assert lib.sq_softmax(NULL, FAKE, 1, 10) == -1
+    assert lib.sq_softmax(FAKE, FAKE, 1, 0) == -2
+
+
+def test_fire_and_network_check_workspace(lib):
+    need = lib.sq_fire_workspace_bytes(2, 55, 55, 16)
+    assert need >= 2 * 16 * 55 * 55 * 4 and need % 256 == 0
+    sz = ctypes.c_size_t
+    fire = lambda ws, nbytes, n=2: lib.sq_fire_forward(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                                       n, 96, 55, 55, 16, 64, 64, ws, sz(nbytes))
+    assert fire(NULL, need) == -4
+    assert fire(FAKE, need - 1) == -4
+    assert fire(ctypes.c_void_p(0x1004), need) == -4       # misaligned
+    assert fire(FAKE, need, n=0) == -2
+    assert lib.sq_fire_forward(NULL, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 2, 96, 55, 55, 16, 64, 64,
+                               FAKE, sz(need)) == -1
+
+    wsb = lib.sq_squeezenet_workspace_bytes(1)
+    assert wsb >= (96 * 111 * 111 + 256 * 55 * 55) * 4
+    assert lib.sq_squeezenet_workspace_bytes(0) == 0
+    params = (ctypes.c_void_p * 52)(*[0x1000] * 52)
+    net = lib.sq_squeezenet_forward
+    assert net(FAKE, params, FAKE, 1, FAKE, sz(wsb - 1), None) == -4
+    assert net(FAKE, params, FAKE, 0, FAKE, sz(wsb), None) == -2
+    assert net(NULL, params, FAKE, 1, FAKE, sz(wsb), None) == -1
+    params[17] = None
+    assert net(FAKE, params, FAKE, 1, FAKE, sz(wsb), None) == -1
+
+
+def test_variant_names(lib):
+    n = lib.sq_conv_variant_count()
+    assert n >= 0
+    names = [lib.sq_conv_variant_name(i) for i in range(n)]
+    assert all(names) and len(set(names)) == n
+    assert lib.sq_conv_variant_name(n) == b""
+    assert lib.sq_conv_variant_name(-1) == b""
+
+
+def test_product_package_does_not_touch_the_oracle():
+    pkg = os.path.join(ROOT, "paper_1611_07151_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, fn)

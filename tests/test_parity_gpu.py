@@ -1,0 +1,292 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the
+C boundary (the Python binding only marshals arguments).
+
+Tolerances are the stated ones: |gpu - ref| <= 1e-4 * (1 + |ref|) for fp32 and
+<= 2e-2 * (1 + |ref|) for bf16 inputs with fp32 accumulation.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+FP32_TOL = 1e-4
+BF16_TOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def sq():
+    import paper_1611_07151_amd as m
+    return m
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+def assert_close(got, ref, tol, what=""):
+    got = got.detach().float().cpu().numpy() if isinstance(got, torch.Tensor) else np.asarray(got)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    assert np.isfinite(got).all(), what
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    bound = tol * (1 + np.abs(ref.astype(np.float64)))
+    bad = err > bound
+    assert not bad.any(), (f"{what}: {int(bad.sum())} of {bad.size} outside tolerance; worst "
+                           f"{float((err / bound).max()):.3g}x at {np.unravel_index(np.argmax(err / bound), err.shape)}")
+
+
+def algos(sq):
+    return [sq.SQ_ALGO_AUTO, sq.SQ_ALGO_DIRECT] + [sq.SQ_ALGO_VARIANT0 + i for i in range(sq.sq_conv_variant_count())]
+
+
+# Shapes small enough for the oracle in seconds, yet spanning several tiles of the
+# matrix-core kernels with ragged tails in pixels, output layers and input layers.
+CONV_CASES = [
+    # N, Cin, H,  W,  Cout, K, S, P
+    (2, 3, 37, 41, 96, 7, 2, 2),      # conv1-like, odd sizes
+    (1, 3, 224, 224, 96, 7, 2, 2),    # conv1 at full size
+    (1, 3, 227, 227, 96, 7, 2, 0),    # the other reading of conv1 (227, no pad)
+    (3, 16, 13, 13, 64, 3, 1, 1),     # expand3x3, several images per tile
+    (2, 16, 55, 55, 64, 3, 1, 1),
+    (1, 48, 27, 27, 192, 3, 1, 1),
+    (2, 64, 13, 13, 256, 3, 1, 1),
+    (2, 96, 55, 55, 16, 1, 1, 0),     # squeeze
+    (2, 16, 55, 55, 64, 1, 1, 0),     # expand1x1
+    (3, 256, 27, 27, 48, 1, 1, 0),
+    (2, 512, 13, 13, 1000, 1, 1, 0),  # conv10
+    (1, 5, 9, 11, 7, 3, 1, 1),        # nothing divides anything
+    (2, 7, 10, 9, 33, 1, 1, 0),
+    (1, 4, 12, 12, 5, 5, 1, 2),       # a kernel size outside the network
+    (1, 2, 9, 9, 3, 3, 2, 0),
+    (1, 1, 1, 1, 1, 1, 1, 0),         # degenerate: one element
+    (1, 3, 3, 3, 2, 3, 1, 0),         # single output pixel
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "x".join(map(str, c)))
+@pytest.mark.parametrize("relu", [True, False])
+def test_conv_every_algorithm_matches_oracle(sq, case, relu):
+    N, Cin, H, W, Cout, K, S, P = case
+    rng = np.random.default_rng(100 + Cin * K + Cout)
+    x = synth.normal01(rng, (N, Cin, H, W))
+    w, b = synth.conv_params(rng, Cout, Cin, K)
+    ref = oracle.conv2d(x, w, b, S, P, relu)
+    xd, wd, bd = dev(x), dev(w), dev(b)
+    ran = 0
+    for algo in algos(sq):
+        try:
+            got = sq.sq_conv2d_forward_ex(xd, wd, bd, S, P, relu, algo=algo)
+        except sq.SqError as e:
+            assert e.status == -3 and algo >= sq.SQ_ALGO_VARIANT0, (algo, str(e))
+            continue
+        ran += 1
+        assert_close(got, ref, FP32_TOL, f"algo {algo}")
+    assert ran >= 2
+    # the literal entry point, and a NULL bias
+    assert_close(sq.sq_conv2d_forward(xd, wd, bd, S, P, relu), ref, FP32_TOL, "sq_conv2d_forward")
+    ref0 = oracle.conv2d(x, w, None, S, P, relu)
+    assert_close(sq.sq_conv2d_forward(xd, wd, None, S, P, relu), ref0, FP32_TOL, "no bias")
+
+
+def test_conv_channel_offset_leaves_other_layers_untouched(sq):
+    rng = np.random.default_rng(7)
+    x = synth.normal01(rng, (2, 16, 27, 27))
+    w, b = synth.conv_params(rng, 24, 16, 3)
+    ref = oracle.conv2d(x, w, b, 1, 1, True)
+    for algo in algos(sq):
+        out = torch.full((2, 40, 27, 27), -7.0, device="cuda")
+        try:
+            sq.sq_conv2d_forward_ex(dev(x), dev(w), dev(b), 1, 1, True, out=out, c_offset=9, algo=algo)
+        except sq.SqError as e:
+            assert e.status == -3
+            continue
+        assert_close(out[:, 9:33], ref, FP32_TOL, f"algo {algo}")
+        assert (out[:, :9] == -7.0).all() and (out[:, 33:] == -7.0).all()
+
+
+@pytest.mark.parametrize("case", [(2, 96, 55, 55, 16, 1, 1, 0), (2, 16, 27, 27, 64, 3, 1, 1),
+                                  (1, 3, 64, 64, 96, 7, 2, 2), (2, 512, 13, 13, 1000, 1, 1, 0),
+                                  (1, 5, 9, 11, 7, 3, 1, 1)], ids=lambda c: "x".join(map(str, c)))
+def test_conv_bf16_inputs(sq, case):
+    N, Cin, H, W, Cout, K, S, P = case
+    rng = np.random.default_rng(200 + Cout)
+    x = synth.normal01(rng, (N, Cin, H, W))
+    w, b = synth.conv_params(rng, Cout, Cin, K)
+    ref = oracle.conv2d(x, w, b, S, P, True)                  # the oracle sees unrounded fp32
+    xb, wb = dev(x, torch.bfloat16), dev(w, torch.bfloat16)  # round-to-nearest-even, once
+    # reference fed the rounded values isolates accumulation error from quantisation
+    ref_q = oracle.conv2d(xb.float().cpu().numpy(), wb.float().cpu().numpy(), b, S, P, True)
+    for algo in algos(sq):
+        try:
+            got = sq.sq_conv2d_forward_ex(xb, wb, dev(b), S, P, True, algo=algo)
+        except sq.SqError as e:
+            assert e.status == -3 and algo >= sq.SQ_ALGO_VARIANT0
+            continue
+        assert_close(got, ref, BF16_TOL, f"bf16 algo {algo}")
+        assert_close(got, ref_q, FP32_TOL, f"bf16 algo {algo} vs rounded-input reference")
+
+
+@pytest.mark.parametrize("shape,k,s", [((2, 96, 111, 111), 3, 2), ((1, 256, 55, 55), 3, 2),
+                                       ((3, 512, 27, 27), 3, 2), ((1, 3, 10, 13), 2, 2),
+                                       ((1, 1, 3, 3), 3, 1), ((2, 5, 9, 8), 3, 3)])
+def test_maxpool_exact(sq, shape, k, s):
+    rng = np.random.default_rng(11)
+    x = synth.normal01(rng, shape) - np.float32(3.0)
+    got = sq.sq_maxpool(dev(x), k, s).cpu().numpy()
+    np.testing.assert_array_equal(got, oracle.maxpool(x, k, s))
+
+
+@pytest.mark.parametrize("shape", [(2, 1000, 13, 13), (1, 7, 5, 3), (3, 2, 1, 1), (1, 1, 30, 30)])
+def test_avgpool(sq, shape):
+    rng = np.random.default_rng(12)
+    x = synth.normal01(rng, shape)
+    assert_close(sq.sq_avgpool_global(dev(x)), oracle.avgpool_global(x), FP32_TOL, "avgpool")
+
+
+@pytest.mark.parametrize("shape,scale", [((3, 1000), 1.0), ((1, 1000), 30.0), ((2, 10), 1.0),
+                                         ((1, 1), 1.0), ((2, 1500), 5.0)])
+def test_softmax(sq, shape, scale):
+    rng = np.random.default_rng(13)
+    x = synth.normal01(rng, shape) * np.float32(scale)
+    got = sq.sq_softmax(dev(x))
+    assert_close(got, oracle.softmax(x), FP32_TOL, "softmax")
+    assert np.abs(got.double().sum(1).cpu().numpy() - 1).max() < 1e-5
+
+
+def test_softmax_large_scores_do_not_overflow(sq):
+    x = np.array([[1e4, -1e4, 0, 1e4]], np.float32)
+    got = sq.sq_softmax(dev(x)).cpu().numpy()
+    np.testing.assert_allclose(got, [[0.5, 0, 0, 0.5]], atol=1e-6)
+
+
+# ----------------------------------------------------------------- workload 1
+@pytest.mark.parametrize("n", [1, 3])
+def test_fire2_workload(sq, n):
+    c = synth.config_fire2(seed=0, n=n)
+    ref = oracle.fire(c["x"], c["w_sq"], c["b_sq"], c["w_e1"], c["b_e1"], c["w_e3"], c["b_e3"])
+    got = sq.sq_fire_forward(*(dev(c[k]) for k in ("x", "w_sq", "b_sq", "w_e1", "b_e1", "w_e3", "b_e3")))
+    assert got.shape == (n, 128, 55, 55)
+    assert_close(got, ref, FP32_TOL, "fire2")
+
+
+def test_fire_border_sees_zero_padding_not_relu_of_bias(sq):
+    # large positive squeeze bias: relu(b_sq) != 0, so a halo filled with the
+    # squeeze of zero-padded input (instead of zeros) would be visibly wrong
+    rng = np.random.default_rng(5)
+    x = synth.normal01(rng, (2, 24, 13, 17))
+    w_sq, _ = synth.conv_params(rng, 8, 24, 1)
+    b_sq = np.full(8, 3.0, np.float32)
+    w_e1, b_e1 = synth.conv_params(rng, 16, 8, 1)
+    w_e3, b_e3 = synth.conv_params(rng, 16, 8, 3)
+    ref = oracle.fire(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3)
+    got = sq.sq_fire_forward(dev(x), dev(w_sq), dev(b_sq), dev(w_e1), dev(b_e1), dev(w_e3), dev(b_e3))
+    assert_close(got, ref, FP32_TOL, "fire border")
+
+
+@pytest.mark.parametrize("cin,sq_c,e,h", [(256, 48, 192, 27), (512, 64, 256, 13), (128, 32, 128, 55)])
+def test_other_fire_shapes(sq, cin, sq_c, e, h):
+    rng = np.random.default_rng(cin + e)
+    x = synth.uniform01(rng, (2, cin, h, h))
+    w_sq, b_sq = synth.conv_params(rng, sq_c, cin, 1)
+    w_e1, b_e1 = synth.conv_params(rng, e, sq_c, 1)
+    w_e3, b_e3 = synth.conv_params(rng, e, sq_c, 3)
+    ref = oracle.fire(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3)
+    got = sq.sq_fire_forward(dev(x), dev(w_sq), dev(b_sq), dev(w_e1), dev(b_e1), dev(w_e3), dev(b_e3))
+    assert_close(got, ref, FP32_TOL, "fire")
+
+
+# ----------------------------------------------------------------- workload 2
+@pytest.mark.parametrize("size", [224, 227])
+def test_conv1_then_pool_workload(sq, size):
+    c = synth.config_conv1(seed=1, n=1, size=size)
+    ref = oracle.conv2d(c["x"], c["w"], c["b"], 2, c["pad"], True)
+    got = sq.sq_conv2d_forward(dev(c["x"]), dev(c["w"]), dev(c["b"]), 2, c["pad"], True)
+    assert got.shape == (1, 96, 111, 111)
+    assert_close(got, ref, FP32_TOL, "conv1")
+    pooled = sq.sq_maxpool(got, 3, 2)
+    assert pooled.shape == (1, 96, 55, 55)
+    assert_close(pooled, oracle.maxpool(ref, 3, 2), FP32_TOL, "pool1")
+    np.testing.assert_array_equal(pooled.cpu().numpy(), oracle.maxpool(got.cpu().numpy(), 3, 2))
+
+
+# ----------------------------------------------------------------- workload 3
+def _check_network(sq, cfg, images):
+    params = [dev(p) for p in cfg["params"]]
+    x = dev(cfg["x"])
+    probs, taps = sq.sq_squeezenet_forward(x, params, want_taps=True)
+    plain = sq.sq_squeezenet_forward(x, params)
+    assert torch.equal(plain, probs)                       # taps do not change the result
+    for i in images:
+        ref_p, ref_t = oracle.squeezenet(cfg["x"][i:i + 1], cfg["params"], want_taps=True)
+        for name in oracle.TAP_NAMES:
+            assert_close(taps[name][i:i + 1], ref_t[name], FP32_TOL, f"image {i} {name}")
+        assert_close(probs[i:i + 1], ref_p, FP32_TOL, f"image {i} probs")
+        assert int(probs[i].argmax()) == int(ref_p[0].argmax())
+    assert np.abs(probs.double().sum(1).cpu().numpy() - 1).max() < 1e-5
+    return taps
+
+
+def test_squeezenet_batch1_every_stage(sq):
+    cfg = synth.config_squeezenet(seed=2, n=1)
+    taps = _check_network(sq, cfg, [0])
+    # each layer fed the ORACLE's input of that layer: kernel error without propagation
+    _, ref_t = oracle.squeezenet(cfg["x"], cfg["params"], want_taps=True)
+    p = cfg["params"]
+    got = sq.sq_fire_forward(dev(ref_t["pool8"]), *(dev(a) for a in p[44:50]))
+    assert_close(got, ref_t["fire9"], FP32_TOL, "fire9 from oracle input")
+    got = sq.sq_conv2d_forward(dev(ref_t["fire9"]), dev(p[50]), dev(p[51]), 1, 0, True)
+    assert_close(got, ref_t["conv10"], FP32_TOL, "conv10 from oracle input")
+    assert taps["conv1"].shape == (1, 96, 111, 111)
+
+
+def test_squeezenet_small_batch(sq):
+    _check_network(sq, synth.config_squeezenet(seed=21, n=3), [0, 1, 2])
+
+
+# ----------------------------------------------------------------- workload 4
+def test_squeezenet_batch64_sampled_images(sq):
+    """Full size, same launch configuration the benchmark times; the oracle checks
+    sampled images one by one (images are independent of each other)."""
+    cfg = synth.config_squeezenet(seed=3, n=64)
+    _check_network(sq, cfg, [0, 37, 63])
+
+
+# ----------------------------------------------------------------- workload 5
+def test_layer_sweep_bf16_batch256_sampled_images(sq):
+    """Every convolution shape at batch 256 with bf16 inputs and kernels; the
+    oracle (fed the unrounded fp32 tensors) checks the first and last image."""
+    n = 256
+    for name, x, w, b, s, p in synth.config_layer_sweep(seed=4, n=n):
+        xb, wb = dev(x, torch.bfloat16), dev(w, torch.bfloat16)
+        got = sq.sq_conv2d_forward_ex(xb, wb, dev(b), s, p, True)
+        for i in (0, n - 1):
+            ref = oracle.conv2d(x[i:i + 1], w, b, s, p, True)
+            assert_close(got[i:i + 1], ref, BF16_TOL, f"{name} image {i}")
+        del xb, wb, got
+        torch.cuda.empty_cache()
+
+
+def test_same_input_twice_is_bit_identical(sq):
+    c = synth.config_fire2(seed=0, n=2)
+    args = [dev(c[k]) for k in ("x", "w_sq", "b_sq", "w_e1", "b_e1", "w_e3", "b_e3")]
+    a = sq.sq_fire_forward(*args)
+    b = sq.sq_fire_forward(*args)
+    assert torch.equal(a, b)
+
+
+def test_runs_on_a_side_stream(sq):
+    rng = np.random.default_rng(3)
+    x = synth.normal01(rng, (1, 16, 20, 20))
+    w, b = synth.conv_params(rng, 32, 16, 3)
+    ref = oracle.conv2d(x, w, b, 1, 1, True)
+    s = torch.cuda.Stream()
+    xd, wd, bd = dev(x), dev(w), dev(b)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        got = sq.sq_conv2d_forward(xd, wd, bd, 1, 1, True)
+    s.synchronize()
+    assert_close(got, ref, FP32_TOL, "side stream")

@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the SqueezeNet v1.0 forward path on one MI355X.
+
+One "step" is one pass of the whole hot path -- sq_squeezenet_forward: conv1, three max
+poolings, eight fire layers, conv10, global average pooling, softmax -- over one batch of
+synthetic images already resident in HBM.  The workload is the full network at batch 64
+(fp32, uniform[0,1) inputs, He-normal kernels, seed 3); batch 1 (seed 2) is timed beside it.
+
+Prints ONE JSON line.  `value` is images/s at batch 64.  `roofline` describes the kernel
+that takes the most GPU time, measured with HIP events the library records around each of
+its launches on its own stream during the timed region.  `cpu_baseline` is the CPU oracle
+timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP32_MFMA_PEAK_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+HBM_PEAK_GBS = 8000.0
+FLOP_PER_IMAGE = 2 * 832_667_936  # 2 x multiply-accumulates of the 26 convolutions
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--cpu-sample", type=int, default=32,
+                    help="images of the workload the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (images are independent, so more GPUs "
+              "would each take a slice of the batch with no communication); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_1611_07151_amd as sq
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    torch.cuda.set_device(0)
+    K, W, B = args.steps, args.warmup, args.batch
+
+    def setup(seed, n):
+        cfg = synth.config_squeezenet(seed=seed, n=n)
+        x = torch.from_numpy(cfg["x"]).cuda()
+        params = [torch.from_numpy(p).cuda() for p in cfg["params"]]
+        ws = torch.empty(sq.sq_squeezenet_workspace_bytes(n), device="cuda", dtype=torch.uint8)
+        probs = torch.empty((n, 1000), device="cuda")
+        return cfg, x, params, ws, probs
+
+    def timed(x, params, ws, probs, steps, profile):
+        if profile:
+            sq.sq_profile_begin(steps * 48)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            sq.sq_squeezenet_forward(x, params, workspace=ws, probs=probs)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        return dt, (sq.sq_profile_end() if profile else None)
+
+    # ---------------------------------------------------------------- batch 64 (the metric)
+    cfg, x, params, ws, probs = setup(3, B)
+    for _ in range(W):
+        sq.sq_squeezenet_forward(x, params, workspace=ws, probs=probs)
+    dt_plain, _ = timed(x, params, ws, probs, K, False)          # no events: event overhead check
+    dt, recs = timed(x, params, ws, probs, K, True)              # THE timed region, with events
+    ms_per_step = dt / K * 1e3
+    images_per_s = B * K / dt
+    assert torch.isfinite(probs).all()
+
+    kernels, stages = {}, {}
+    for r in recs:
+        stage, kernel = r["name"].split("|")
+        for table, key in ((kernels, kernel), (stages, stage)):
+            e = table.setdefault(key, dict(launches=0, ms=0.0, flops=0.0, bytes=0.0))
+            for f in ("launches", "ms", "flops", "bytes"):
+                e[f] += r[f]
+    dom_name, dom = max(kernels.items(), key=lambda kv: kv[1]["ms"])
+    dom_ms = dom["ms"] / dom["launches"]
+    achieved = dom["flops"] / dom["launches"] / (dom_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(dom_name)
+    roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=FP32_MFMA_PEAK_TFLOPS,
+                    unit="TFLOP/s", frac=round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), traffic=traffic,
+                    kernel=dom_name, launches_per_step=dom["launches"] / K,
+                    avg_launch_us=round(dom_ms * 1e3, 2),
+                    flop_per_launch=dom["flops"] / dom["launches"],
+                    share_of_gpu_time=round(dom["ms"] / sum(k["ms"] for k in kernels.values()), 3))
+    layers = {}
+    for name, e in stages.items():
+        us = e["ms"] / K * 1e3
+        layers[name] = dict(us=round(us, 1),
+                            tflops=round(e["flops"] / K / us / 1e6, 1) if e["flops"] else None,
+                            gbs=round(e["bytes"] / K / us / 1e3, 0))
+    conv_ms = sum(e["ms"] for e in stages.values() if e["flops"]) / K
+    conv_tflops = B * FLOP_PER_IMAGE / (conv_ms * 1e-3) / 1e12
+
+    # ---------------------------------------------------------------- batch 1
+    cfg1, x1, params1, ws1, probs1 = setup(2, 1)
+    for _ in range(20):
+        sq.sq_squeezenet_forward(x1, params1, workspace=ws1, probs=probs1)
+    k1 = max(200, K)
+    dt1, _ = timed(x1, params1, ws1, probs1, k1, False)
+
+    # ---------------------------------------------------------------- CPU oracle baseline
+    cpu = None
+    if args.cpu_sample > 0:
+        import oracle
+        n = min(args.cpu_sample, B)
+        t0 = time.perf_counter()
+        ref = oracle.squeezenet(cfg["x"][:n], cfg["params"])
+        cdt = time.perf_counter() - t0
+        got = probs[:n].cpu().numpy()
+        err = float(np.max(np.abs(got - ref) / (1 + np.abs(ref))))
+        cpu = dict(value=round(n / cdt, 3), unit="images/s", cores=oracle.num_threads(), kind="oracle",
+                   sample=f"first {n} images of the batch-{B} workload, one oracle.squeezenet call "
+                          f"({cdt:.1f} s)", gflops=round(n * FLOP_PER_IMAGE / cdt / 1e9, 2),
+                   max_scaled_error_gpu_vs_oracle=err)
+
+    out = {
+        "metric": "SqueezeNet v1.0 forward images/sec at batch 64 (conv TFLOP/s and % fp32 MFMA peak beside it)",
+        "value": round(images_per_s, 1), "unit": "images/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"full SqueezeNet v1.0 forward, batch {B}, fp32 NCHW, 3x224x224 "
+                               "uniform[0,1) inputs, He-normal kernels, seed 3", "batch": B},
+        "conv_tflops": round(conv_tflops, 2),
+        "pct_fp32_mfma_peak": round(100 * conv_tflops / FP32_MFMA_PEAK_TFLOPS, 2),
+        "end_to_end_tflops": round(B * FLOP_PER_IMAGE / (ms_per_step * 1e-3) / 1e12, 2),
+        "batch1_images_per_sec": round(k1 / dt1, 1), "batch1_ms": round(dt1 / k1 * 1e3, 4),
+        "ms_per_step_without_events": round(dt_plain / K * 1e3, 4),
+        "roofline": roofline, "cpu_baseline": cpu, "layers": layers,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

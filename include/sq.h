@@ -185,6 +185,27 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
 
 size_t sq_squeezenet_workspace_bytes(int N);
 
+/*
+ * Per-launch timing, off by default.  Between sq_profile_begin() and sq_profile_end()
+ * every kernel the library launches from this host thread is bracketed by a pair of
+ * HIP events on the library's stream.  These two calls are the only ones in the
+ * library that create and destroy HIP objects; sq_profile_end() also waits for the
+ * recorded work.  Launches beyond max_launches are not recorded.
+ * After sq_profile_end(), sq_profile_count() entries can be read with
+ * sq_profile_get(): one entry per distinct "stage|kernel" name (stage is the network
+ * stage, e.g. "fire4/e3", empty outside sq_squeezenet_forward and sq_fire_forward),
+ * with its launch count, summed duration in milliseconds and summed algorithmic FLOPs
+ * (2 x multiply-accumulates of the layer definition, nothing for padding or tile
+ * waste) and algorithmic bytes (each input, kernel and output element once).
+ * Errors: SQ_ERR_SHAPE (bad count/index), SQ_ERR_UNSUPPORTED (begin twice / end
+ * without begin), SQ_ERR_NULL, SQ_ERR_HIP.
+ */
+int sq_profile_begin(int max_launches);
+int sq_profile_end(void);
+int sq_profile_count(void);
+int sq_profile_get(int index, char *name, int name_cap, long long *launches,
+                   double *total_ms, double *flops, double *bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -39,6 +39,11 @@ lib.sq_squeezenet_forward.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _i, _vp, _s
 lib.sq_squeezenet_workspace_bytes.restype = _sz
 lib.sq_squeezenet_workspace_bytes.argtypes = [_i]
 
+lib.sq_profile_begin.argtypes = [_i]
+lib.sq_profile_get.argtypes = [_i, ctypes.c_char_p, _i, ctypes.POINTER(ctypes.c_longlong),
+                               ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                               ctypes.POINTER(ctypes.c_double)]
+
 TAP_NAMES = ("conv1", "pool1", "fire2", "fire3", "fire4", "pool4", "fire5", "fire6",
              "fire7", "fire8", "pool8", "fire9", "conv10", "means", "probs")
 TAP_SHAPES = ((96, 111), (96, 55), (128, 55), (128, 55), (256, 55), (256, 27), (256, 27),
@@ -214,3 +219,23 @@ def sq_squeezenet_forward(x, params, workspace=None, probs=None, want_taps=False
                                    N, _dev(workspace), workspace.numel() * workspace.element_size(), tarr)
     _check(rc, "sq_squeezenet_forward")
     return (probs, taps) if want_taps else probs
+
+
+def sq_profile_begin(max_launches: int = 4096) -> None:
+    _use_current_stream()
+    _check(lib.sq_profile_begin(int(max_launches)), "sq_profile_begin")
+
+
+def sq_profile_end():
+    """Returns a list of dicts: name ("stage|kernel"), launches, ms, flops, bytes."""
+    _check(lib.sq_profile_end(), "sq_profile_end")
+    out = []
+    for i in range(lib.sq_profile_count()):
+        name = ctypes.create_string_buffer(128)
+        n, ms = ctypes.c_longlong(), ctypes.c_double()
+        fl, by = ctypes.c_double(), ctypes.c_double()
+        _check(lib.sq_profile_get(i, name, 128, ctypes.byref(n), ctypes.byref(ms), ctypes.byref(fl),
+                                  ctypes.byref(by)), "sq_profile_get")
+        out.append(dict(name=name.value.decode(), launches=n.value, ms=ms.value, flops=fl.value,
+                        bytes=by.value))
+    return out

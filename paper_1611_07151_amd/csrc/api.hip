@@ -2,6 +2,9 @@
 // fire-layer and whole-network drivers that sequence the kernels.
 #include "sq_internal.h"
 
+#include <stdio.h>
+#include <string.h>
+
 namespace sq {
 namespace {
 thread_local hipStream_t g_stream = nullptr;
@@ -9,6 +12,42 @@ thread_local int g_last_hip = 0;
 }  // namespace
 
 hipStream_t current_stream() { return g_stream; }
+
+// ---- per-launch profiler --------------------------------------------------------------
+namespace {
+struct ProfRecord {
+    hipEvent_t start, stop;
+    const char *kernel;
+    const char *stage;
+    double flops, bytes;
+};
+struct ProfEntry {
+    char name[96];
+    long long launches;
+    double ms, flops, bytes;
+};
+thread_local ProfRecord *g_prof = nullptr;
+thread_local int g_prof_cap = 0, g_prof_used = 0;
+thread_local const char *g_stage = "";
+thread_local ProfEntry g_entries[128];
+thread_local int g_num_entries = 0;
+}  // namespace
+
+void set_stage(const char *stage) { g_stage = stage ? stage : ""; }
+
+LaunchScope::LaunchScope(const char *kernel, double flops, double bytes) : slot(-1)
+{
+    if (!g_prof || g_prof_used >= g_prof_cap) return;
+    slot = g_prof_used++;
+    ProfRecord &r = g_prof[slot];
+    r.kernel = kernel; r.stage = g_stage; r.flops = flops; r.bytes = bytes;
+    (void)hipEventRecord(r.start, g_stream);
+}
+
+LaunchScope::~LaunchScope()
+{
+    if (slot >= 0) (void)hipEventRecord(g_prof[slot].stop, g_stream);
+}
 
 int check_launch()
 {
@@ -66,19 +105,30 @@ ConvArgs make_args(const void *in, const void *w, const float *b, float *out, in
 // Unchecked fire layer: squeeze into `sq_map`, then both expands into `out`.
 int fire_impl(const void *in, const void *w_sq, const float *b_sq, const void *w_e1,
               const float *b_e1, const void *w_e3, const float *b_e3, float *out, int N, int Cin,
-              int H, int W, int Csq, int Ce1, int Ce3, float *sq_map)
+              int H, int W, int Csq, int Ce1, int Ce3, float *sq_map, const char *const *stages)
 {
+    set_stage(stages[0]);
     int rc = run_conv(make_args(in, w_sq, b_sq, sq_map, N, Cin, H, W, Csq, 1, 1, 0, 1, Csq, 0, SQ_F32),
                       SQ_ALGO_AUTO);
     if (rc) return rc;
+    set_stage(stages[1]);
     rc = run_conv(make_args(sq_map, w_e1, b_e1, out, N, Csq, H, W, Ce1, 1, 1, 0, 1, Ce1 + Ce3, 0, SQ_F32),
                   SQ_ALGO_AUTO);
     if (rc) return rc;
-    return run_conv(make_args(sq_map, w_e3, b_e3, out, N, Csq, H, W, Ce3, 3, 1, 1, 1, Ce1 + Ce3, Ce1, SQ_F32),
-                    SQ_ALGO_AUTO);
+    set_stage(stages[2]);
+    rc = run_conv(make_args(sq_map, w_e3, b_e3, out, N, Csq, H, W, Ce3, 3, 1, 1, 1, Ce1 + Ce3, Ce1, SQ_F32),
+                  SQ_ALGO_AUTO);
+    set_stage("");
+    return rc;
 }
 
 struct FireCfg { int cin, sq, e; };
+const char *const kFireStages[8][3] = {
+    {"fire2/sq", "fire2/e1", "fire2/e3"}, {"fire3/sq", "fire3/e1", "fire3/e3"},
+    {"fire4/sq", "fire4/e1", "fire4/e3"}, {"fire5/sq", "fire5/e1", "fire5/e3"},
+    {"fire6/sq", "fire6/e1", "fire6/e3"}, {"fire7/sq", "fire7/e1", "fire7/e3"},
+    {"fire8/sq", "fire8/e1", "fire8/e3"}, {"fire9/sq", "fire9/e1", "fire9/e3"}};
+const char *const kFireAlone[3] = {"fire/sq", "fire/e1", "fire/e3"};
 const FireCfg kFires[8] = {{96, 16, 64},   {128, 16, 64},  {128, 32, 128}, {256, 32, 128},
                            {256, 48, 192}, {384, 48, 192}, {384, 64, 256}, {512, 64, 256}};
 
@@ -126,6 +176,72 @@ int sq_last_hip_error(void) { return g_last_hip; }
 int sq_set_stream(void *hip_stream)
 {
     g_stream = (hipStream_t)hip_stream;
+    return SQ_OK;
+}
+
+int sq_profile_begin(int max_launches)
+{
+    if (max_launches <= 0) return SQ_ERR_SHAPE;
+    if (g_prof) return SQ_ERR_UNSUPPORTED;  // already profiling
+    ProfRecord *recs = new ProfRecord[max_launches];
+    for (int i = 0; i < max_launches; ++i) {
+        if (hipEventCreate(&recs[i].start) != hipSuccess || hipEventCreate(&recs[i].stop) != hipSuccess) {
+            delete[] recs;  // events made so far are left to the runtime; this path means HIP is unusable
+            (void)check_launch();
+            return SQ_ERR_HIP;
+        }
+    }
+    g_prof = recs; g_prof_cap = max_launches; g_prof_used = 0; g_num_entries = 0;
+    return SQ_OK;
+}
+
+int sq_profile_end(void)
+{
+    if (!g_prof) return SQ_ERR_UNSUPPORTED;
+    int rc = SQ_OK;
+    g_num_entries = 0;
+    for (int i = 0; i < g_prof_used; ++i) {
+        ProfRecord &r = g_prof[i];
+        float ms = 0.f;
+        if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) {
+            rc = SQ_ERR_HIP;
+            continue;
+        }
+        char name[96];
+        snprintf(name, sizeof(name), "%s|%s", r.stage, r.kernel);
+        int e = 0;
+        for (; e < g_num_entries; ++e)
+            if (!strcmp(g_entries[e].name, name)) break;
+        if (e == g_num_entries) {
+            if (g_num_entries == 128) continue;
+            ++g_num_entries;
+            snprintf(g_entries[e].name, sizeof(g_entries[e].name), "%s", name);
+            g_entries[e].launches = 0; g_entries[e].ms = g_entries[e].flops = g_entries[e].bytes = 0;
+        }
+        g_entries[e].launches += 1; g_entries[e].ms += ms; g_entries[e].flops += r.flops; g_entries[e].bytes += r.bytes;
+    }
+    for (int i = 0; i < g_prof_cap; ++i) {
+        (void)hipEventDestroy(g_prof[i].start);
+        (void)hipEventDestroy(g_prof[i].stop);
+    }
+    delete[] g_prof;
+    g_prof = nullptr; g_prof_cap = g_prof_used = 0;
+    if (rc) (void)check_launch();
+    return rc;
+}
+
+int sq_profile_count(void) { return g_num_entries; }
+
+int sq_profile_get(int index, char *name, int name_cap, long long *launches, double *total_ms,
+                   double *flops, double *bytes)
+{
+    if (index < 0 || index >= g_num_entries) return SQ_ERR_SHAPE;
+    if (!name || name_cap <= 0 || !launches || !total_ms || !flops || !bytes) return SQ_ERR_NULL;
+    snprintf(name, (size_t)name_cap, "%s", g_entries[index].name);
+    *launches = g_entries[index].launches;
+    *total_ms = g_entries[index].ms;
+    *flops = g_entries[index].flops;
+    *bytes = g_entries[index].bytes;
     return SQ_OK;
 }
 
@@ -195,7 +311,7 @@ int sq_fire_forward(const void *in, const void *w_sq, const float *b_sq, const v
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < sq_fire_workspace_bytes(N, H, W, Csq))
         return SQ_ERR_WORKSPACE;
     return fire_impl(in, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, out, N, Cin, H, W, Csq, Ce1, Ce3,
-                     (float *)workspace);
+                     (float *)workspace, kFireAlone);
 }
 
 size_t sq_squeezenet_workspace_bytes(int N)
@@ -225,10 +341,12 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
     float *means = (float *)((char *)bufS + align_up(n * kBufS * 4, 256));
     auto P = [&](int i) { return (const float *)params[i]; };
 
+    set_stage("conv1");
     int rc = run_conv(make_args(in, params[0], P(1), bufA, N, 3, 224, 224, 96, 7, 2, 2, 1, 96, 0, SQ_F32),
                       SQ_ALGO_AUTO);
     if (rc) return rc;
     if ((rc = copy_tap(taps, 0, bufA, n * 96 * 111 * 111))) return rc;
+    set_stage("pool1");
     if ((rc = maxpool(bufA, bufB, N, 96, 111, 111, 3, 2))) return rc;
     if ((rc = copy_tap(taps, 1, bufB, n * 96 * 55 * 55))) return rc;
 
@@ -237,26 +355,31 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
     for (int f = 0; f < 8; ++f) {
         const FireCfg &fc = kFires[f];
         rc = fire_impl(cur, params[p], P(p + 1), params[p + 2], P(p + 3), params[p + 4], P(p + 5), nxt,
-                       N, C, H, H, fc.sq, fc.e, fc.e, bufS);
+                       N, C, H, H, fc.sq, fc.e, fc.e, bufS, kFireStages[f]);
         if (rc) return rc;
         p += 6;
         C = 2 * fc.e;
         if ((rc = copy_tap(taps, tap++, nxt, n * C * H * H))) return rc;
         { float *t = cur; cur = nxt; nxt = t; }
         if (f == 2 || f == 6) {  // pooling follows fire4 and fire8
+            set_stage(f == 2 ? "pool4" : "pool8");
             if ((rc = maxpool(cur, nxt, N, C, H, H, 3, 2))) return rc;
             H = (H - 3) / 2 + 1;
             if ((rc = copy_tap(taps, tap++, nxt, n * C * H * H))) return rc;
             { float *t = cur; cur = nxt; nxt = t; }
         }
     }
+    set_stage("conv10");
     rc = run_conv(make_args(cur, params[50], P(51), nxt, N, 512, H, H, 1000, 1, 1, 0, 1, 1000, 0, SQ_F32),
                   SQ_ALGO_AUTO);
     if (rc) return rc;
     if ((rc = copy_tap(taps, 12, nxt, n * 1000 * H * H))) return rc;
+    set_stage("avgpool");
     if ((rc = avgpool_global(nxt, means, N, 1000, H, H))) return rc;
     if ((rc = copy_tap(taps, 13, means, n * 1000))) return rc;
+    set_stage("softmax");
     if ((rc = softmax(means, probs, N, 1000))) return rc;
+    set_stage("");
     return copy_tap(taps, 14, probs, n * 1000);
 }
 

@@ -25,65 +25,12 @@
 // register holds consecutive pixels across lanes and the NCHW store is coalesced.
 // The KQ (2 or 4) k-values one MFMA consumes are the same tap of KQ consecutive
 // input layers, which makes the per-lane LDS offsets loop-invariant.
-#include "sq_internal.h"
+#include "conv_mfma_common.h"
 
 namespace sq {
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kLdsBytes = 160 * 1024;
-
-struct KParams {
-    const float *in;
-    const float *w;
-    const float *b;
-    float *out;
-    int N, Cin, H, W, Cout, P, relu;
-    int Ho, Wo, HoWo, HW, ldc, coff;
-    int PT;      // N*Ho*Wo
-    int VH;      // virtual rows per image
-    int LW;      // patch columns staged
-    int LWs;     // LDS row stride of the patch
-    int PRcap;   // patch rows the LDS plane can hold
-    int plane;   // LDS floats per input layer
-    int mtiles;  // tiles along output layers
-    int ntiles;  // tiles along pixels
-    int nchunks;
-};
-
-template <int MT> struct Mfma;
-template <> struct Mfma<32> {
-    using Acc = f32x16;
-    static constexpr int KQ = 2, NR = 16;
-    static __device__ __forceinline__ Acc run(float a, float b, Acc c)
-    {
-        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
-    }
-    // output-layer row held by accumulator register r of this lane
-    static __device__ __forceinline__ int row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
-};
-template <> struct Mfma<16> {
-    using Acc = f32x4;
-    static constexpr int KQ = 4, NR = 4;
-    static __device__ __forceinline__ Acc run(float a, float b, Acc c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ int row(int r, int lane) { return 4 * (lane >> 4) + r; }
-};
-
-// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber so
-// that every XCD works on one contiguous range of tiles (neighbouring tiles share
-// halo rows and the same kernels).
-__device__ __forceinline__ int xcd_remap(int b, int total)
-{
-    const int q = total >> 3, r = total & 7;
-    const int xcd = b & 7, idx = b >> 3;
-    const int start = xcd < r ? xcd * (q + 1) : r * (q + 1) + (xcd - r) * q;
-    return start + idx;
-}
+using namespace mfma;
 
 template <int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int NBUF, int MINW>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const KParams p)
@@ -304,12 +251,13 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
 struct Variant {
     const char *name;
     int KS, S, BM, BN, MT, CC, PE, NBUF, NT;
-    void (*kernel)(const KParams);
+    KernelFn kernel;
+    bool conv1_type;  // the persistent 7x7/stride-2/three-layer kernel
 };
 
 #define SQ_VARIANT(KS, S, BM, BN, WM, WN, MT, CC, PE, NBUF, MINW)                                     \
     {"k" #KS "s" #S "_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC "_b" #NBUF "_o" #MINW, KS, S, BM, BN, MT, CC, PE, NBUF, \
-     WM * WN * 64, conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, NBUF, MINW>}
+     WM * WN * 64, conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, NBUF, MINW>, false}
 
 const Variant kVariants[] = {
     // 3x3 stride 1 (expand3x3)
@@ -325,7 +273,10 @@ const Variant kVariants[] = {
     SQ_VARIANT(1, 1, 16, 256, 1, 4, 16, 16, 0, 2, 2),
     SQ_VARIANT(1, 1, 32, 128, 1, 4, 16, 16, 0, 2, 2),
     SQ_VARIANT(1, 1, 48, 128, 1, 4, 16, 16, 0, 2, 2),
-    // 7x7 stride 2 (conv1): all input layers in one chunk
+    // 7x7 stride 2 with three input layers (conv1): persistent kernel, 148-long contraction
+    {"k7s2c3_persist_96x256", 7, 2, 96, 256, 32, 3, 8, 2, 512, conv7s2c3_kernel_for(256), true},
+    {"k7s2c3_persist_96x128", 7, 2, 96, 128, 32, 3, 15, 2, 256, conv7s2c3_kernel_for(128), true},
+    // 7x7 stride 2, generic: all input layers in one chunk, padded to four
     SQ_VARIANT(7, 2, 96, 128, 1, 4, 32, 4, 15, 1, 1),
     SQ_VARIANT(7, 2, 96, 64, 1, 4, 16, 4, 13, 1, 1),
 };
@@ -337,6 +288,21 @@ struct Plan {
     unsigned blocks;
 };
 
+int num_cus()
+{
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+        (void)hipGetLastError();
+    }
+    return cus;
+}
+
 // Fills the launch parameters of variant v for this call; false if v cannot run it.
 bool plan(const Variant &v, const ConvArgs &a, Plan &pl)
 {
@@ -347,6 +313,7 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl)
     const long long pixels = (long long)a.N * a.Ho * a.Wo;
     if (in_elems >= (1ll << 31) || out_elems >= (1ll << 31) || pixels + v.BN >= (1ll << 31)) return false;
     if (v.NBUF == 1 && a.Cin > v.CC) return false;
+    if (v.conv1_type && (a.Cin != 3 || a.Cout > 96)) return false;
 
     KParams &k = pl.kp;
     k.in = (const float *)a.in; k.w = (const float *)a.w; k.b = a.b; k.out = a.out;
@@ -376,9 +343,18 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl)
         const int raw = k.PRcap * k.LWs;
         k.plane = raw + (((v.MT - raw) % 64) + 64) % 64;  // plane = MT (mod 64): the KQ lane groups hit different banks
     }
-    pl.lds_bytes = ((size_t)v.NBUF * v.BM * LDK + (size_t)v.NBUF * v.CC * k.plane) * sizeof(float);
+    long long blocks = (long long)k.mtiles * k.ntiles;
+    if (v.conv1_type) {
+        // kernels [96][149] + bias [96] + two patch buffers of three planes; if the bank
+        // padding of the plane does not fit, fall back to the unpadded plane
+        const size_t fixed = (size_t)96 * 149 + 96;
+        if ((fixed + (size_t)6 * k.plane) * sizeof(float) > (size_t)kLdsBytes) k.plane = k.PRcap * k.LWs;
+        pl.lds_bytes = (fixed + (size_t)6 * k.plane) * sizeof(float);
+        if (blocks > num_cus()) blocks = num_cus();  // persistent: one workgroup per CU
+    } else {
+        pl.lds_bytes = ((size_t)v.NBUF * v.BM * LDK + (size_t)v.NBUF * v.CC * k.plane) * sizeof(float);
+    }
     if (pl.lds_bytes > (size_t)kLdsBytes) return false;
-    const long long blocks = (long long)k.mtiles * k.ntiles;
     if (blocks >= (1ll << 31)) return false;
     pl.blocks = (unsigned)blocks;
     return true;
@@ -386,7 +362,7 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl)
 
 bool g_attr_done[kNumVariants] = {};
 
-int launch(int vi, const Plan &pl)
+int launch(int vi, const Plan &pl, const ConvArgs &a)
 {
     const Variant &v = kVariants[vi];
     if (!g_attr_done[vi]) {
@@ -397,25 +373,24 @@ int launch(int vi, const Plan &pl)
         }
         g_attr_done[vi] = true;
     }
+    LaunchScope scope(v.name, conv_flops(a), conv_bytes(a));
     hipLaunchKernelGGL(v.kernel, dim3(pl.blocks), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
     return check_launch();
 }
 
-// Estimated cost of a variant for a shape: MFMA work including tile padding, scaled by
-// how evenly the tiles fill the 256 CUs.  Lower is better.
+// Estimated cost of a variant for a shape: MFMA work including tile and contraction
+// padding, times the number of rounds the tiles need on the CUs.  Lower is better.
 double estimate(const Variant &v, const Plan &pl, const ConvArgs &a)
 {
-    const double tiles = (double)pl.blocks;
-    const int kq = v.MT == 32 ? 2 : 4;
-    const double kpad = (double)pl.kp.nchunks * v.CC * v.KS * v.KS;
-    (void)kq;
-    const double work_per_tile = (double)v.BM * v.BN * kpad;
-    const double slots = 256.0 * (v.NT == 256 ? 2 : 1);
-    const double rounds = ceil(tiles / slots);
-    // small tiles pay more LDS traffic per flop
-    const double tile_eff = 1.0 / (1.0 + 24.0 / v.BM + 24.0 / v.BN);
     (void)a;
-    return rounds * work_per_tile / tile_eff;
+    const double tiles = (double)pl.kp.mtiles * pl.kp.ntiles;
+    const double kpad = v.conv1_type ? 148.0 : (double)pl.kp.nchunks * v.CC * v.KS * v.KS;
+    const double work_per_tile = (double)v.BM * v.BN * kpad;
+    const double occ = v.conv1_type ? 1.0 : ((size_t)2 * pl.lds_bytes <= (size_t)kLdsBytes ? 2.0 : 1.0);
+    const double rounds = ceil(tiles / (num_cus() * occ));
+    // small tiles pay more LDS traffic and staging per flop
+    const double tile_eff = v.conv1_type ? 1.0 : 1.0 / (1.0 + 24.0 / v.BM + 24.0 / v.BN);
+    return rounds * occ * work_per_tile / tile_eff;
 }
 
 }  // namespace
@@ -428,7 +403,7 @@ int conv_mfma(const ConvArgs &a, int variant)
     Plan pl;
     if (variant >= 0) {
         if (variant >= kNumVariants || !plan(kVariants[variant], a, pl)) return SQ_ERR_UNSUPPORTED;
-        return launch(variant, pl);
+        return launch(variant, pl, a);
     }
     int best = -1;
     double best_cost = 0;
@@ -441,7 +416,7 @@ int conv_mfma(const ConvArgs &a, int variant)
         }
     }
     if (best < 0) return SQ_ERR_UNSUPPORTED;
-    return launch(best, best_plan);
+    return launch(best, best_plan, a);
 }
 
 }  // namespace sq

@@ -92,6 +92,7 @@ int maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int 
     const size_t planes = (size_t)N * C;
     size_t blocks = (planes * Ho * Wo + 255) / 256;
     if (blocks > (1u << 20)) blocks = 1u << 20;
+    LaunchScope scope("maxpool", 0.0, 4.0 * planes * ((double)H * W + (double)Ho * Wo));
     hipLaunchKernelGGL(maxpool_kernel, dim3((unsigned)blocks), dim3(256), 0, current_stream(), in,
                        out, planes, H, W, K, S, Ho, Wo);
     return check_launch();
@@ -100,6 +101,7 @@ int maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int 
 int avgpool_global(const float *in, float *out, int N, int C, int H, int W)
 {
     const size_t planes = (size_t)N * C;
+    LaunchScope scope("avgpool", 0.0, 4.0 * planes * ((double)H * W + 1.0));
     hipLaunchKernelGGL(avgpool_kernel, dim3((unsigned)((planes + 3) / 4)), dim3(256), 0,
                        current_stream(), in, out, planes, H * W);
     return check_launch();
@@ -107,6 +109,7 @@ int avgpool_global(const float *in, float *out, int N, int C, int H, int W)
 
 int softmax(const float *in, float *out, int N, int C)
 {
+    LaunchScope scope("softmax", 0.0, 8.0 * N * C);
     hipLaunchKernelGGL(softmax_kernel, dim3((unsigned)N), dim3(256), 0, current_stream(), in, out, C);
     return check_launch();
 }

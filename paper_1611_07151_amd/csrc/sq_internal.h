@@ -27,6 +27,17 @@ struct ConvArgs {
     int dtype;  // sq_dtype of in and w
 };
 
+inline double conv_flops(const ConvArgs &a)
+{
+    return 2.0 * a.N * a.Cout * a.Ho * a.Wo * (double)a.Cin * a.K * a.K;
+}
+inline double conv_bytes(const ConvArgs &a)
+{
+    const double esz = a.dtype == SQ_BF16 ? 2.0 : 4.0;
+    return esz * ((double)a.N * a.Cin * a.H * a.W + (double)a.Cout * a.Cin * a.K * a.K) +
+           4.0 * ((double)a.N * a.Cout * a.Ho * a.Wo + a.Cout);
+}
+
 int conv_direct(const ConvArgs &a);
 
 // Matrix-core family.  variant < 0 = pick by shape; returns SQ_ERR_UNSUPPORTED when
@@ -38,6 +49,18 @@ const char *conv_mfma_variant_name(int i);
 int maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int S);
 int avgpool_global(const float *in, float *out, int N, int C, int H, int W);
 int softmax(const float *in, float *out, int N, int C);
+
+// Optional per-launch timing (sq_profile_begin/end).  A LaunchScope brackets one kernel
+// launch with a pair of HIP events on the library's stream when profiling is on and
+// costs one thread-local load when it is off.  flops and bytes are the algorithmic
+// figures of the launch (2 * MACs; compulsory input + kernel + output bytes).
+struct LaunchScope {
+    LaunchScope(const char *kernel, double flops, double bytes);
+    ~LaunchScope();
+    int slot;
+};
+// Name of the network stage the next launches belong to ("" outside the network call).
+void set_stage(const char *stage);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

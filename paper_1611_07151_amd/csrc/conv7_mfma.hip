@@ -48,14 +48,14 @@ __global__ __launch_bounds__(BN / 32 * 64, MINW) void conv7s2c3_kernel(const KPa
 
     extern __shared__ float smem[];
     float *const Ws = smem;                 // [96][149]
-    float *const Bs = Ws + kBM * kLDK;      // [96]
-    float *const Xs = Bs + kBM;             // [2][3*plane]
+    float *const Xs = Ws + kBM * kLDK;      // [2][3*plane]
     const int plane = p.plane, LWs = p.LWs;
 
-    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
     const int li = lane & 31, kk = lane >> 5;
 
-    // ---- kernels and bias, once per workgroup -----------------------------------------
+    // ---- kernels, once per workgroup -----------------------------------------------------
     for (int e = t; e < kBM * kK; e += NT) {
         const int m = e / kK, k = e - m * kK;
         Ws[m * kLDK + pair_slot(k)] = m < p.Cout ? p.w[e] : 0.f;
@@ -63,49 +63,68 @@ __global__ __launch_bounds__(BN / 32 * 64, MINW) void conv7s2c3_kernel(const KPa
     if (t < kBM) {
         Ws[t * kLDK + 147] = 0.f;
         Ws[t * kLDK + 148] = 0.f;
-        Bs[t] = (p.b && t < p.Cout) ? p.b[t] : 0.f;
     }
 
     int aoff[kTM];
 #pragma unroll
     for (int x = 0; x < kTM; ++x) aoff[x] = (x * 32 + li) * kLDK + kk;
 
-    // ---- per-tile patch geometry ---------------------------------------------------------
+    // bias of the 48 output layers this lane stores (layer = x*32 + row_reg(r) + row_lane)
+    const int lrow = M::row_lane(lane);
+    float bias[kTM][16];
+#pragma unroll
+    for (int x = 0; x < kTM; ++x)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = x * 32 + M::row_reg(r) + lrow;
+            bias[x][r] = (p.b && m < p.Cout) ? p.b[m] : 0.f;
+        }
+
+    // ---- staging map: element e = t + NT*r of a [rows][LW] plane; row and column of e do
+    // not depend on the tile, only the first virtual row va does -------------------------
+    int evr[PE], epc[PE];
+#pragma unroll
+    for (int r = 0; r < PE; ++r) {
+        const int e = t + NT * r;
+        evr[r] = fdiv(e, p.dLW);
+        epc[r] = e - evr[r] * p.LW;
+    }
+
     int va = 0, PRt = 0;
-    auto tile_geometry = [&](int tile) {
+    auto tile_geometry = [&](int tile) {  // uniform
         const int P0 = tile * BN;
-        const int Ra = P0 / p.Wo;
-        const int last = min(P0 + BN, p.PT) - 1;
-        const int Rb = last / p.Wo;
-        const int na = Ra / p.Ho, nb = Rb / p.Ho;
+        const int Ra = fdiv(P0, p.dWo);
+        const int Rb = fdiv(min(P0 + BN, p.PT) - 1, p.dWo);
+        const int na = fdiv(Ra, p.dHo), nb = fdiv(Rb, p.dHo);
         va = na * p.VH + (Ra - na * p.Ho) * kS;
         PRt = nb * p.VH + (Rb - nb * p.Ho) * kS + kKS - va;
     };
 
     float xreg[3 * PE];
-    int xdst[PE];
+    bool xstage[PE];
     auto load_patch = [&]() {  // uses va / PRt of the tile being fetched
 #pragma unroll
         for (int r = 0; r < PE; ++r) {
-            const int e = t + NT * r;
-            const int vr = e / p.LW, pc = e - vr * p.LW;
-            const int v = va + vr;
-            const int n = v / p.VH, ih = v - n * p.VH - p.P, iw = pc - p.P;
-            const bool stage = vr < PRt;
-            const bool inb = stage && n < p.N && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-            const size_t src = (size_t)((n * 3) * p.H + ih) * p.W + iw;
-            xdst[r] = stage ? vr * LWs + pc : -1;
+            const int v = va + evr[r];
+            const int n = fdiv(v, p.dVH), ih = v - n * p.VH - p.P, iw = epc[r] - p.P;
+            xstage[r] = evr[r] < PRt;
+            const bool inb = xstage[r] && n < p.N && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+            const uint32_t src = inb ? (uint32_t)(((n * 3 * p.H + ih) * p.W + iw) * 4) : 0u;
 #pragma unroll
-            for (int c = 0; c < 3; ++c) xreg[c * PE + r] = inb ? p.in[src + (size_t)c * p.HW] : 0.f;
+            for (int c = 0; c < 3; ++c) {
+                const float x = ld_f32(p.in + (size_t)c * p.HW, src);
+                xreg[c * PE + r] = inb ? x : 0.f;
+            }
         }
     };
     auto store_patch = [&](int buf) {
         float *xs = Xs + buf * (3 * plane);
 #pragma unroll
         for (int r = 0; r < PE; ++r)
-            if (xdst[r] >= 0) {
+            if (xstage[r]) {
+                const int d = evr[r] * LWs + epc[r];
 #pragma unroll
-                for (int c = 0; c < 3; ++c) xs[c * plane + xdst[r]] = xreg[c * PE + r];
+                for (int c = 0; c < 3; ++c) xs[c * plane + d] = xreg[c * PE + r];
             }
     };
 
@@ -120,13 +139,12 @@ __global__ __launch_bounds__(BN / 32 * 64, MINW) void conv7s2c3_kernel(const KPa
     for (int it = 0; tile < p.ntiles; ++it, tile += gridDim.x) {
         // B-operand base of this lane's pixel in the current tile
         tile_geometry(tile);
-        const int P0 = tile * BN;
-        const int pp = P0 + wv * 32 + li;
+        const int pp = tile * BN + wv * 32 + li;
         int base;
         {
             const int pc = min(pp, p.PT - 1);
-            const int R = pc / p.Wo, ow = pc - R * p.Wo;
-            const int n = R / p.Ho;
+            const int R = fdiv(pc, p.dWo), ow = pc - R * p.Wo;
+            const int n = fdiv(R, p.dHo);
             base = (n * p.VH + (R - n * p.Ho) * kS - va) * LWs + ow * kS;
         }
         const int b1 = base + kk * plane;
@@ -148,40 +166,48 @@ __global__ __launch_bounds__(BN / 32 * 64, MINW) void conv7s2c3_kernel(const KPa
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[x][r] = 0.f;
 
-        auto step = [&](int s, float b) {
-#pragma unroll
-            for (int x = 0; x < kTM; ++x) acc[x] = M::run(Ws[aoff[x] + 2 * s], b, acc[x]);
+        // The operands of MFMA step s+1 are fetched from LDS before the MFMAs of step s are
+        // issued, so the LDS latency hides behind three MFMAs.
+        auto b_addr = [&](int s) -> int {
+            if (s < 49) return b1 + (s / 7) * LWs + s % 7;
+            if (s < 70) return b2 + ((s - 49) / 7) * LWs + (s - 49) % 7;
+            if (s < 73) return b3 + (s - 70);
+            return b4;
         };
+        float av[2][kTM], bv[2];
+        auto fetch = [&](int s, float *a, float &b) {
 #pragma unroll
-        for (int i = 0; i < 7; ++i)
+            for (int x = 0; x < kTM; ++x) a[x] = Ws[aoff[x] + 2 * s];
+            b = xs[b_addr(s)];
+        };
+        fetch(0, av[0], bv[0]);
 #pragma unroll
-            for (int j = 0; j < 7; ++j) step(i * 7 + j, xs[b1 + i * LWs + j]);
+        for (int s = 0; s < 74; ++s) {
+            if (s + 1 < 74) fetch(s + 1, av[(s + 1) & 1], bv[(s + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);  // reads of step s+1 stay ahead of the MFMAs of step s
 #pragma unroll
-        for (int i = 0; i < 3; ++i)
-#pragma unroll
-            for (int j = 0; j < 7; ++j) step(49 + i * 7 + j, xs[b2 + i * LWs + j]);
-#pragma unroll
-        for (int j = 0; j < 3; ++j) step(70 + j, xs[b3 + j]);
-        step(73, xs[b4]);
+            for (int x = 0; x < kTM; ++x) acc[x] = M::run(av[s & 1][x], bv[s & 1], acc[x]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        // The prefetched patch goes to the other LDS buffer BEFORE the output stores are
+        // issued: the wait for its global loads would otherwise also wait for the stores.
+        if (more) store_patch((it + 1) & 1);
 
         // epilogue: bias, ReLU, coalesced store of 32 consecutive pixels per register
         if (pp < p.PT) {
-            const int n = pp / p.HoWo, q = pp - n * p.HoWo;
-            float *obase = p.out + ((size_t)n * p.ldc + p.coff) * p.HoWo + q;
+            const int n = fdiv(pp, p.dHoWo), q = pp - n * p.HoWo;
+            const uint32_t lbase = (uint32_t)(((n * p.ldc + p.coff + lrow) * p.HoWo + q) * 4);
 #pragma unroll
             for (int x = 0; x < kTM; ++x)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int m = x * 32 + M::row(r, lane);
-                    if (m < p.Cout) {
-                        float v = acc[x][r] + Bs[m];
-                        if (p.relu) v = fmaxf(v, 0.f);
-                        obase[(size_t)m * p.HoWo] = v;
-                    }
+                    const int mu = x * 32 + M::row_reg(r);
+                    float v = acc[x][r] + bias[x][r];
+                    if (p.relu) v = fmaxf(v, 0.f);
+                    if (p.Cout == kBM || mu + lrow < p.Cout) st_f32(p.out + (size_t)mu * p.HoWo, lbase, v);
                 }
         }
-
-        if (more) store_patch((it + 1) & 1);
         __syncthreads();
     }
 }

@@ -32,7 +32,7 @@ namespace {
 
 using namespace mfma;
 
-template <int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int NBUF, int MINW>
+template <int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const KParams p)
 {
     using M = Mfma<MT>;
@@ -41,32 +41,39 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
     constexpr int TM = BM / WM / MT, TN = BN / WN / MT;
     constexpr int RUN = CC * KK;
     constexpr int LDK = RUN + ((RUN & 1) ? 0 : 1);
+    constexpr int WBUF = BM * LDK;
     constexpr int WREG = (BM * RUN + NT - 1) / NT;
+    constexpr bool WEXACT = (BM * RUN) % NT == 0;
     constexpr bool POINTWISE = (KS == 1 && S == 1);
+    constexpr int XMAP = POINTWISE ? 1 : PE;
     constexpr int XREG = POINTWISE ? (CC * BN / NT) : CC * PE;
     static_assert(BM % (WM * MT) == 0 && BN % (WN * MT) == 0, "tile split");
     static_assert(CC % KQ == 0, "chunk must hold whole MFMA k-groups");
-    static_assert(!POINTWISE || (NT % BN == 0 && (CC * BN) % NT == 0), "pointwise staging split");
+    static_assert(!POINTWISE || (NT % BN == 0 && BN % 64 == 0 && (CC * BN) % NT == 0), "pointwise staging split");
 
     extern __shared__ float smem[];
-    float *const Ws = smem;                       // [NBUF][BM*LDK]
-    float *const Xs = smem + NBUF * BM * LDK;     // [NBUF][CC*plane]
+    float *const Ws = smem;               // [2][BM*LDK]
+    float *const Xs = smem + 2 * WBUF;    // [2][CC*plane]
     const int plane = p.plane;
+    const int XBUF = CC * plane;
 
-    const int tile = xcd_remap(blockIdx.x, p.mtiles * p.ntiles);
-    const int mt = tile % p.mtiles, pt = tile / p.mtiles;
-    const int P0 = pt * BN, m0 = mt * BM;
-    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wv / WN, wn = wv % WN;
     const int li = lane % MT, kk = lane / MT;
+
+    const int tile = xcd_remap(blockIdx.x, p.mtiles * p.ntiles);
+    const int pt = fdiv(tile, p.dMtiles), mt = tile - pt * p.mtiles;
+    const int P0 = pt * BN, m0 = mt * BM;
+    const bool full_m = m0 + BM <= p.Cout;
+    const bool tail_c = p.Cin % CC != 0;
 
     // ---- geometry of the staged patch ------------------------------------------------
     int va = 0, PRt = 0;
     if constexpr (!POINTWISE) {
-        const int Ra = P0 / p.Wo;
-        const int last = min(P0 + BN, p.PT) - 1;
-        const int Rb = last / p.Wo;
-        const int na = Ra / p.Ho, nb = Rb / p.Ho;
+        const int Ra = fdiv(P0, p.dWo);
+        const int Rb = fdiv(min(P0 + BN, p.PT) - 1, p.dWo);
+        const int na = fdiv(Ra, p.dHo), nb = fdiv(Rb, p.dHo);
         va = na * p.VH + (Ra - na * p.Ho) * S;
         PRt = nb * p.VH + (Rb - nb * p.Ho) * S + KS - va;
     }
@@ -82,94 +89,112 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
             boff[j] = pl + kk * plane;
         } else {
             const int pp = min(P0 + pl, p.PT - 1);
-            const int R = pp / p.Wo, ow = pp - R * p.Wo;
-            const int n = R / p.Ho;
+            const int R = fdiv(pp, p.dWo), ow = pp - R * p.Wo;
+            const int n = fdiv(R, p.dHo);
             const int v = n * p.VH + (R - n * p.Ho) * S;
             boff[j] = (v - va) * p.LWs + ow * S + kk * plane;
         }
     }
 
-    // ---- staging maps (what this thread copies for every chunk) ----------------------
-    // kernels: element e = t + NT*r of the [BM][RUN] slab
-    // patch:   general  -> element e = t + NT*r of one [rows][LW] plane, all CC layers
-    //          pointwise-> pixel t % BN, layers t / BN + (NT/BN)*r
-    int xsrc[POINTWISE ? 1 : PE], xdst[POINTWISE ? 1 : PE];
+    // ---- staging maps: what this thread copies for every chunk -------------------------
+    // kernels: element e = t + NT*r of the [BM][RUN] slab (k contiguous, as in memory)
+    // patch:   general   -> element e = t + NT*r of one [rows][LW] plane, all CC layers
+    //          pointwise -> pixel t % BN, layers t / BN + (NT/BN)*r
+    // *src are byte offsets (0 where nothing is to be read), *ok says whether the value
+    // is real or zero, *dst the LDS float index (-1 = nothing to store).
+    uint32_t wsrc[WREG];
+    int wdst[WREG];
+    bool wok[WREG];
+#pragma unroll
+    for (int r = 0; r < WREG; ++r) {
+        const int e = t + NT * r;
+        const int m = e / RUN, q = e - m * RUN;
+        const bool inrange = WEXACT || e < BM * RUN;
+        wok[r] = inrange && (m0 + m < p.Cout);
+        wsrc[r] = wok[r] ? (uint32_t)(((m0 + m) * p.Cin * KK + q) * 4) : 0u;
+        wdst[r] = inrange ? m * LDK + q : -1;
+    }
+    uint32_t xsrc[XMAP];
+    int xdst[XMAP];
+    bool xok[XMAP];
     if constexpr (POINTWISE) {
         const int pl = t % BN, pp = P0 + pl;
-        if (pp < p.PT) {
-            const int n = pp / p.HW;
-            xsrc[0] = n * p.Cin * p.HW + (pp - n * p.HW);
-        } else {
-            xsrc[0] = -1;
-        }
+        xok[0] = pp < p.PT;
+        const int n = fdiv(pp, p.dHW);
+        xsrc[0] = xok[0] ? (uint32_t)((n * p.Cin * p.HW + (pp - n * p.HW)) * 4) : 0u;
         xdst[0] = pl;
     } else {
 #pragma unroll
         for (int r = 0; r < PE; ++r) {
             const int e = t + NT * r;
-            const int vr = e / p.LW, pc = e - vr * p.LW;
+            const int vr = fdiv(e, p.dLW), pc = e - vr * p.LW;
             const int v = va + vr;
-            const int n = v / p.VH, ih = v - n * p.VH - p.P, iw = pc - p.P;
+            const int n = fdiv(v, p.dVH), ih = v - n * p.VH - p.P, iw = pc - p.P;
             const bool stage = vr < PRt;
-            const bool inb = stage && n < p.N && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-            xsrc[r] = inb ? (n * p.Cin * p.H + ih) * p.W + iw : -1;
+            xok[r] = stage && n < p.N && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+            xsrc[r] = xok[r] ? (uint32_t)(((n * p.Cin * p.H + ih) * p.W + iw) * 4) : 0u;
             xdst[r] = stage ? vr * p.LWs + pc : -1;
         }
     }
+    const int cpart = POINTWISE ? __builtin_amdgcn_readfirstlane(t / BN) : 0;
 
-    // Register staging (NBUF == 2) keeps one chunk in flight while the previous one is
-    // being multiplied; with a single buffer the copy goes straight through.
-    float wreg[NBUF == 2 ? WREG : 1], xreg[NBUF == 2 ? XREG : 1];
+    float wreg[WREG], xreg[XREG];
 
-    auto w_value = [&](int c0, int r) -> float {
-        const int e = t + NT * r;
-        const int m = e / RUN, q = e - m * RUN;
-        const bool ok = (BM * RUN % NT == 0 || e < BM * RUN) && (m0 + m < p.Cout) && (c0 + q / KK < p.Cin);
-        return ok ? p.w[(size_t)(m0 + m) * p.Cin * KK + c0 * KK + q] : 0.f;
-    };
-    auto w_store = [&](float *ws, int r, float v) {
-        const int e = t + NT * r;
-        const int m = e / RUN, q = e - m * RUN;
-        if (BM * RUN % NT == 0 || e < BM * RUN) ws[m * LDK + q] = v;
-    };
-    // patch value r of this thread: pointwise -> layer t/BN + (NT/BN)*r of pixel xsrc[0];
-    // general -> layer r / PE, plane element r % PE
-    auto x_value = [&](int c0, int r) -> float {
-        const int c = POINTWISE ? t / BN + (NT / BN) * r : r / (POINTWISE ? 1 : PE);
-        const int src = xsrc[POINTWISE ? 0 : r % (POINTWISE ? 1 : PE)];
-        const bool ok = src >= 0 && c0 + c < p.Cin;
-        return ok ? p.in[(size_t)src + (size_t)(c0 + c) * p.HW] : 0.f;
-    };
-    auto x_store = [&](float *xs, int r, float v) {
-        if constexpr (POINTWISE) {
-            xs[(t / BN + (NT / BN) * r) * plane + xdst[0]] = v;
+    // Global loads of one chunk.  The common case reads unconditionally from in-bounds
+    // addresses and zeroes what is padding with a select; only a last chunk that runs past
+    // the input layers (Cin not a multiple of CC) takes the fully predicated path.
+    auto load_chunk = [&](int ch) {
+        const int c0 = ch * CC;
+        const float *wbase = p.w + c0 * KK;
+        if (tail_c && ch == p.nchunks - 1) {
+#pragma unroll
+            for (int r = 0; r < WREG; ++r) {
+                const int e = t + NT * r;
+                const int q = e % RUN;
+                wreg[r] = (wok[r] && c0 + q / KK < p.Cin) ? ld_f32(wbase, wsrc[r]) : 0.f;
+            }
+#pragma unroll
+            for (int r = 0; r < XREG; ++r) {
+                const int c = POINTWISE ? cpart + (NT / BN) * r : r / XMAP;
+                const int i = POINTWISE ? 0 : r % XMAP;
+                xreg[r] = (xok[i] && c0 + c < p.Cin) ? ld_f32(p.in + (size_t)(c0 + c) * p.HW, xsrc[i]) : 0.f;
+            }
+            return;
+        }
+        if (full_m) {
+#pragma unroll
+            for (int r = 0; r < WREG; ++r)
+                if (WEXACT || r + 1 < WREG || wok[r]) wreg[r] = ld_f32(wbase, wsrc[r]);
         } else {
-            const int d = xdst[r % (POINTWISE ? 1 : PE)];
-            if (d >= 0) xs[(r / (POINTWISE ? 1 : PE)) * plane + d] = v;
+#pragma unroll
+            for (int r = 0; r < WREG; ++r) {
+                const float v = ld_f32(wbase, wsrc[r]);
+                wreg[r] = wok[r] ? v : 0.f;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < XREG; ++r) {
+            const int c = POINTWISE ? cpart + (NT / BN) * r : r / XMAP;
+            const int i = POINTWISE ? 0 : r % XMAP;
+            const float v = ld_f32(p.in + (size_t)(c0 + c) * p.HW, xsrc[i]);
+            xreg[r] = xok[i] ? v : 0.f;
         }
     };
 
-    auto load_chunk = [&](int ch) {
-        const int c0 = ch * CC;
-#pragma unroll
-        for (int r = 0; r < WREG; ++r) wreg[r] = w_value(c0, r);
-#pragma unroll
-        for (int r = 0; r < XREG; ++r) xreg[r] = x_value(c0, r);
-    };
     auto store_chunk = [&](int buf) {
-        float *ws = Ws + buf * (BM * LDK);
-        float *xs = Xs + buf * (CC * plane);
+        float *ws = Ws + buf * WBUF;
+        float *xs = Xs + buf * XBUF;
 #pragma unroll
-        for (int r = 0; r < WREG; ++r) w_store(ws, r, wreg[r]);
+        for (int r = 0; r < WREG; ++r)
+            if (WEXACT || r + 1 < WREG || wdst[r] >= 0) ws[wdst[r]] = wreg[r];
 #pragma unroll
-        for (int r = 0; r < XREG; ++r) x_store(xs, r, xreg[r]);
-    };
-    auto copy_chunk = [&](int ch) {  // single-buffer path
-        const int c0 = ch * CC;
-#pragma unroll 8
-        for (int r = 0; r < WREG; ++r) w_store(Ws, r, w_value(c0, r));
-#pragma unroll 8
-        for (int r = 0; r < XREG; ++r) x_store(Xs, r, x_value(c0, r));
+        for (int r = 0; r < XREG; ++r) {
+            if constexpr (POINTWISE) {
+                xs[(cpart + (NT / BN) * r) * plane + xdst[0]] = xreg[r];
+            } else {
+                if (xdst[r % XMAP] >= 0) xs[(r / XMAP) * plane + xdst[r % XMAP]] = xreg[r];
+            }
+        }
     };
 
     Acc acc[TM][TN];
@@ -180,68 +205,87 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
 #pragma unroll
             for (int r = 0; r < M::NR; ++r) acc[i][j][r] = 0.f;
 
+    // One MFMA step consumes, for every lane, one kernel value per layer block and one patch
+    // value per pixel block.  LDS latency (~120 cycles) is longer than a short group of
+    // MFMAs, so the operands are fetched PD steps ahead into a small register ring, and
+    // scheduling barriers keep the compiler from sinking the reads back next to their use.
     auto compute_chunk = [&](int buf) {
-        const float *ws = Ws + buf * (BM * LDK);
-        const float *xs = Xs + buf * (CC * plane);
+        const float *ws = Ws + buf * WBUF;
+        const float *xs = Xs + buf * XBUF;
+        constexpr int STEPS = (CC / KQ) * KK;
+        constexpr int STEP_CYCLES = TM * TN * (MT == 32 ? 64 : 32);
+        constexpr int PD0 = (240 + STEP_CYCLES - 1) / STEP_CYCLES;      // steps to cover the latency
+        constexpr int PD = PD0 < 1 ? 1 : (PD0 > 3 ? 3 : PD0);
+        constexpr int RING = PD + 1;
+        float a[RING][TM], b[RING][TN];
+        auto fetch = [&](int s, float *av, float *bv) {
+            const int cq = s / KK, tap = s - cq * KK, i = tap / KS, j = tap - i * KS;
+            const int rowoff = cq * KQ * plane + (POINTWISE ? 0 : i * p.LWs) + j;
 #pragma unroll
-        for (int cq = 0; cq < CC / KQ; ++cq) {
+            for (int x = 0; x < TM; ++x) av[x] = ws[aoff[x] + cq * KQ * KK + tap];
 #pragma unroll
-            for (int i = 0; i < KS; ++i) {
-                const int rowoff = cq * KQ * plane + (POINTWISE ? 0 : i * p.LWs);
+            for (int y = 0; y < TN; ++y) bv[y] = xs[boff[y] + rowoff];
+        };
 #pragma unroll
-                for (int j = 0; j < KS; ++j) {
-                    float a[TM], b[TN];
+        for (int s = 0; s < PD && s < STEPS; ++s) fetch(s, a[s % RING], b[s % RING]);
 #pragma unroll
-                    for (int x = 0; x < TM; ++x) a[x] = ws[aoff[x] + cq * KQ * KK + i * KS + j];
+        for (int s = 0; s < STEPS; ++s) {
+            if (s + PD < STEPS) fetch(s + PD, a[(s + PD) % RING], b[(s + PD) % RING]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int y = 0; y < TN; ++y) b[y] = xs[boff[y] + rowoff + j];
+            for (int x = 0; x < TM; ++x)
 #pragma unroll
-                    for (int x = 0; x < TM; ++x)
-#pragma unroll
-                        for (int y = 0; y < TN; ++y) acc[x][y] = M::run(a[x], b[y], acc[x][y]);
-                }
-            }
+                for (int y = 0; y < TN; ++y) acc[x][y] = M::run(a[s % RING][x], b[s % RING][y], acc[x][y]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // ---- main loop -------------------------------------------------------------------
-    if constexpr (NBUF == 2) {
-        load_chunk(0);
-        store_chunk(0);
+    // ---- main loop, two chunks per trip so the LDS buffer index is a constant -------------
+    load_chunk(0);
+    store_chunk(0);
+    __syncthreads();
+    for (int ch = 0; ch < p.nchunks; ch += 2) {
+        const bool more1 = ch + 1 < p.nchunks;
+        if (more1) load_chunk(ch + 1);
+        compute_chunk(0);
+        if (more1) store_chunk(1);
         __syncthreads();
-        for (int ch = 0; ch < p.nchunks; ++ch) {
-            const bool more = ch + 1 < p.nchunks;
-            if (more) load_chunk(ch + 1);
-            compute_chunk(ch & 1);
-            if (more) store_chunk((ch + 1) & 1);
-            __syncthreads();
-        }
-    } else {
-        for (int ch = 0; ch < p.nchunks; ++ch) {
-            copy_chunk(ch);
-            __syncthreads();
-            compute_chunk(0);
-            __syncthreads();
-        }
+        if (!more1) break;
+        const bool more2 = ch + 2 < p.nchunks;
+        if (more2) load_chunk(ch + 2);
+        compute_chunk(1);
+        if (more2) store_chunk(0);
+        __syncthreads();
     }
 
     // ---- epilogue: bias, ReLU, store into layers [coff, coff+Cout) ---------------------
+    // An accumulator register holds MT consecutive pixels across lanes, so each store
+    // instruction writes contiguous runs.  The layer index splits into a uniform part
+    // (scalar address arithmetic) and a per-lane part folded into the lane's byte offset.
+    const int mw = m0 + wm * (BM / WM);          // uniform: first layer of this wavefront
+    const int lrow = M::row_lane(lane);          // per lane
+    float bias[TM][M::NR];
+#pragma unroll
+    for (int x = 0; x < TM; ++x)
+#pragma unroll
+        for (int r = 0; r < M::NR; ++r) {
+            const int mu = mw + x * MT + M::row_reg(r);
+            bias[x][r] = (p.b && (full_m || mu + lrow < p.Cout)) ? ld_f32(p.b + mu, (uint32_t)(lrow * 4)) : 0.f;
+        }
 #pragma unroll
     for (int y = 0; y < TN; ++y) {
         const int pp = P0 + wn * (BN / WN) + y * MT + li;
         if (pp >= p.PT) continue;
-        const int n = pp / p.HoWo, q = pp - n * p.HoWo;
-        float *obase = p.out + ((size_t)n * p.ldc + p.coff) * p.HoWo + q;
+        const int n = fdiv(pp, p.dHoWo), q = pp - n * p.HoWo;
+        const uint32_t lbase = (uint32_t)(((n * p.ldc + p.coff + lrow) * p.HoWo + q) * 4);
 #pragma unroll
         for (int x = 0; x < TM; ++x) {
 #pragma unroll
             for (int r = 0; r < M::NR; ++r) {
-                const int m = m0 + wm * (BM / WM) + x * MT + M::row(r, lane);
-                if (m < p.Cout) {
-                    float v = acc[x][y][r] + (p.b ? p.b[m] : 0.f);
-                    if (p.relu) v = fmaxf(v, 0.f);
-                    obase[(size_t)m * p.HoWo] = v;
-                }
+                const int mu = mw + x * MT + M::row_reg(r);
+                float v = acc[x][y][r] + bias[x][r];
+                if (p.relu) v = fmaxf(v, 0.f);
+                if (full_m || mu + lrow < p.Cout) st_f32(p.out + (size_t)mu * p.HoWo, lbase, v);
             }
         }
     }
@@ -255,30 +299,41 @@ struct Variant {
     bool conv1_type;  // the persistent 7x7/stride-2/three-layer kernel
 };
 
-#define SQ_VARIANT(KS, S, BM, BN, WM, WN, MT, CC, PE, NBUF, MINW)                                     \
-    {"k" #KS "s" #S "_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC "_b" #NBUF "_o" #MINW, KS, S, BM, BN, MT, CC, PE, NBUF, \
-     WM * WN * 64, conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, NBUF, MINW>, false}
+#define SQ_VARIANT(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                          \
+    {"k" #KS "s" #S "_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC "_o" #MINW, KS, S, BM, BN, MT, CC, PE, 2, \
+     WM * WN * 64, conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW>, false}
 
 const Variant kVariants[] = {
     // 3x3 stride 1 (expand3x3)
-    SQ_VARIANT(3, 1, 128, 128, 2, 2, 32, 4, 2, 2, 2),
-    SQ_VARIANT(3, 1, 64, 128, 2, 2, 32, 4, 2, 2, 2),
-    SQ_VARIANT(3, 1, 64, 64, 2, 2, 32, 4, 2, 2, 2),
-    SQ_VARIANT(3, 1, 64, 128, 1, 4, 16, 4, 2, 2, 2),
-    SQ_VARIANT(3, 1, 32, 64, 2, 2, 16, 4, 8, 2, 2),
+    SQ_VARIANT(3, 1, 128, 128, 2, 2, 32, 4, 2, 2),
+    SQ_VARIANT(3, 1, 64, 128, 2, 2, 32, 4, 2, 2),
+    SQ_VARIANT(3, 1, 64, 128, 1, 4, 32, 4, 2, 2),
+    SQ_VARIANT(3, 1, 64, 64, 2, 2, 32, 4, 2, 2),
+    SQ_VARIANT(3, 1, 64, 128, 1, 4, 16, 4, 2, 2),
+    SQ_VARIANT(3, 1, 32, 64, 2, 2, 16, 4, 8, 2),
+    SQ_VARIANT(3, 1, 64, 128, 2, 2, 32, 8, 2, 2),
+    SQ_VARIANT(3, 1, 64, 256, 1, 4, 32, 4, 3, 2),
+    SQ_VARIANT(3, 1, 128, 128, 2, 2, 32, 8, 2, 1),
+    SQ_VARIANT(3, 1, 128, 256, 2, 2, 32, 4, 3, 1),
     // 1x1 (squeeze, expand1x1, conv10)
-    SQ_VARIANT(1, 1, 128, 128, 2, 2, 32, 16, 0, 2, 2),
-    SQ_VARIANT(1, 1, 64, 128, 2, 2, 32, 16, 0, 2, 2),
-    SQ_VARIANT(1, 1, 64, 64, 2, 2, 32, 16, 0, 2, 2),
-    SQ_VARIANT(1, 1, 16, 256, 1, 4, 16, 16, 0, 2, 2),
-    SQ_VARIANT(1, 1, 32, 128, 1, 4, 16, 16, 0, 2, 2),
-    SQ_VARIANT(1, 1, 48, 128, 1, 4, 16, 16, 0, 2, 2),
+    SQ_VARIANT(1, 1, 128, 128, 2, 2, 32, 16, 0, 2),
+    SQ_VARIANT(1, 1, 64, 128, 2, 2, 32, 16, 0, 2),
+    SQ_VARIANT(1, 1, 64, 128, 1, 4, 32, 16, 0, 2),
+    SQ_VARIANT(1, 1, 64, 64, 2, 2, 32, 16, 0, 2),
+    SQ_VARIANT(1, 1, 16, 256, 1, 4, 16, 16, 0, 2),
+    SQ_VARIANT(1, 1, 32, 128, 1, 4, 16, 16, 0, 2),
+    SQ_VARIANT(1, 1, 32, 128, 1, 4, 32, 16, 0, 2),
+    SQ_VARIANT(1, 1, 32, 256, 1, 4, 32, 16, 0, 2),
+    SQ_VARIANT(1, 1, 48, 128, 1, 4, 16, 16, 0, 2),
+    SQ_VARIANT(1, 1, 64, 256, 1, 4, 32, 16, 0, 2),
+    SQ_VARIANT(1, 1, 128, 128, 2, 2, 16, 16, 0, 2),
+    SQ_VARIANT(1, 1, 64, 64, 2, 2, 16, 32, 0, 3),
+    SQ_VARIANT(1, 1, 128, 128, 2, 2, 32, 32, 0, 2),
     // 7x7 stride 2 with three input layers (conv1): persistent kernel, 148-long contraction
     {"k7s2c3_persist_96x256", 7, 2, 96, 256, 32, 3, 8, 2, 512, conv7s2c3_kernel_for(256), true},
     {"k7s2c3_persist_96x128", 7, 2, 96, 128, 32, 3, 15, 2, 256, conv7s2c3_kernel_for(128), true},
-    // 7x7 stride 2, generic: all input layers in one chunk, padded to four
-    SQ_VARIANT(7, 2, 96, 128, 1, 4, 32, 4, 15, 1, 1),
-    SQ_VARIANT(7, 2, 96, 64, 1, 4, 16, 4, 13, 1, 1),
+    // 7x7 stride 2, any number of input layers, two per chunk
+    SQ_VARIANT(7, 2, 96, 128, 1, 4, 32, 2, 15, 1),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -311,8 +366,11 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl)
     const long long in_elems = (long long)a.N * a.Cin * a.H * a.W;
     const long long out_elems = (long long)a.N * a.out_channels * a.Ho * a.Wo;
     const long long pixels = (long long)a.N * a.Ho * a.Wo;
-    if (in_elems >= (1ll << 31) || out_elems >= (1ll << 31) || pixels + v.BN >= (1ll << 31)) return false;
-    if (v.NBUF == 1 && a.Cin > v.CC) return false;
+    // per-lane addresses are 32-bit byte offsets from a uniform base
+    const long long w_elems = (long long)a.Cout * a.Cin * a.K * a.K;
+    if (in_elems >= (1ll << 30) || out_elems >= (1ll << 30) || w_elems >= (1ll << 30) ||
+        pixels + v.BN >= (1ll << 30))
+        return false;
     if (v.conv1_type && (a.Cin != 3 || a.Cout > 96)) return false;
 
     KParams &k = pl.kp;
@@ -343,11 +401,14 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl)
         const int raw = k.PRcap * k.LWs;
         k.plane = raw + (((v.MT - raw) % 64) + 64) % 64;  // plane = MT (mod 64): the KQ lane groups hit different banks
     }
+    k.dWo = make_fastdiv(k.Wo); k.dHo = make_fastdiv(k.Ho); k.dLW = make_fastdiv(k.LW);
+    k.dVH = make_fastdiv(k.VH); k.dHW = make_fastdiv(k.HW); k.dHoWo = make_fastdiv(k.HoWo);
+    k.dMtiles = make_fastdiv(k.mtiles);
     long long blocks = (long long)k.mtiles * k.ntiles;
     if (v.conv1_type) {
-        // kernels [96][149] + bias [96] + two patch buffers of three planes; if the bank
+        // kernels [96][149] + two patch buffers of three planes; if the bank
         // padding of the plane does not fit, fall back to the unpadded plane
-        const size_t fixed = (size_t)96 * 149 + 96;
+        const size_t fixed = (size_t)96 * 149;
         if ((fixed + (size_t)6 * k.plane) * sizeof(float) > (size_t)kLdsBytes) k.plane = k.PRcap * k.LWs;
         pl.lds_bytes = (fixed + (size_t)6 * k.plane) * sizeof(float);
         if (blocks > num_cus()) blocks = num_cus();  // persistent: one workgroup per CU
@@ -394,6 +455,17 @@ double estimate(const Variant &v, const Plan &pl, const ConvArgs &a)
 }
 
 }  // namespace
+
+// Host-side self check of the division-by-multiplication used in the kernels: number of
+// x in [0, x_max] for which it disagrees with x / d (exported for the tests, not part of
+// the public interface).
+extern "C" long long sq_internal_fastdiv_mismatches(unsigned d, unsigned x_max)
+{
+    const mfma::FastDiv f = mfma::make_fastdiv(d);
+    long long bad = 0;
+    for (unsigned long long x = 0; x <= x_max; ++x) bad += mfma::fastdiv_host((unsigned)x, f) != (unsigned)x / (d ? d : 1);
+    return bad;
+}
 
 int conv_mfma_variant_count() { return kNumVariants; }
 const char *conv_mfma_variant_name(int i) { return kVariants[i].name; }

@@ -1,5 +1,14 @@
 // Shared pieces of the matrix-core convolution kernels (internal).
+//
+// On gfx950 the fp32 MFMA instructions do not overlap with ordinary vector-ALU
+// instructions of the same SIMD (measured: every VALU instruction adds its four issue
+// cycles to the MFMA time), so these kernels are written to keep the VALU instruction
+// count per MFMA low: runtime divisions go through precomputed multipliers, every global
+// access is "uniform base + 32-bit per-lane byte offset" with the per-lane part computed
+// once per tile, and padding is applied with one select per staged element.
 #pragma once
+
+#include <stdint.h>
 
 #include "sq_internal.h"
 
@@ -10,6 +19,40 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kLdsBytes = 160 * 1024;
+
+// Division of x < 2^31 by a runtime constant d >= 1:  q = (umulhi(x, mul) + (x & add)) >> shift.
+// For d >= 2: l = ceil(log2 d), mul = ceil(2^(31+l) / d) (fits 32 bits), shift = l - 1, add = 0.
+// For d == 1: mul = 0, add = all ones, shift = 0.
+struct FastDiv {
+    uint32_t mul, add, shift;
+};
+
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    if (d <= 1) {
+        f.mul = 0; f.add = 0xffffffffu; f.shift = 0;
+        return f;
+    }
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    const unsigned long long num = 1ull << (31 + l);
+    f.mul = (uint32_t)((num + d - 1) / d);
+    f.add = 0;
+    f.shift = l - 1;
+    return f;
+}
+
+inline uint32_t fastdiv_host(uint32_t x, FastDiv f)
+{
+    const uint32_t hi = (uint32_t)(((unsigned long long)x * f.mul) >> 32);
+    return (hi + (x & f.add)) >> f.shift;
+}
+
+__device__ __forceinline__ int fdiv(int x, FastDiv f)
+{
+    return (int)((__umulhi((uint32_t)x, f.mul) + ((uint32_t)x & f.add)) >> f.shift);
+}
 
 struct KParams {
     const float *in;
@@ -27,6 +70,7 @@ struct KParams {
     int mtiles;  // tiles along output layers
     int ntiles;  // tiles along pixels
     int nchunks;
+    FastDiv dWo, dHo, dLW, dVH, dHW, dHoWo, dMtiles;
 };
 
 template <int MT> struct Mfma;
@@ -37,8 +81,9 @@ template <> struct Mfma<32> {
     {
         return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
     }
-    // output-layer row held by accumulator register r of this lane
-    static __device__ __forceinline__ int row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+    // output-layer row of accumulator register r in this lane = row_reg(r) + row_lane(lane)
+    static __device__ __forceinline__ constexpr int row_reg(int r) { return 8 * (r >> 2) + (r & 3); }
+    static __device__ __forceinline__ int row_lane(int lane) { return 4 * (lane >> 5); }
 };
 template <> struct Mfma<16> {
     using Acc = f32x4;
@@ -47,7 +92,8 @@ template <> struct Mfma<16> {
     {
         return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
     }
-    static __device__ __forceinline__ int row(int r, int lane) { return 4 * (lane >> 4) + r; }
+    static __device__ __forceinline__ constexpr int row_reg(int r) { return r; }
+    static __device__ __forceinline__ int row_lane(int lane) { return 4 * (lane >> 4); }
 };
 
 // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber so
@@ -61,6 +107,15 @@ __device__ __forceinline__ int xcd_remap(int b, int total)
     return start + idx;
 }
 
+// base + 32-bit byte offset: the addressing form that needs no per-lane 64-bit arithmetic
+__device__ __forceinline__ float ld_f32(const float *base, uint32_t byte_off)
+{
+    return *(const float *)((const char *)base + byte_off);
+}
+__device__ __forceinline__ void st_f32(float *base, uint32_t byte_off, float v)
+{
+    *(float *)((char *)base + byte_off) = v;
+}
 
 // conv1-type layers (7x7, stride 2, three input layers, at most 96 output layers) have
 // their own persistent kernel; BN (pixels per tile) is 256 or 128.

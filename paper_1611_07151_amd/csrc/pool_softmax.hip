@@ -27,6 +27,34 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const float *__restrict__ 
     }
 }
 
+// Workgroup per group of G consecutive planes: the planes (contiguous in memory) are
+// copied once, coalesced, into LDS and every output reads its window from there, so HBM
+// sees each input element exactly once and each output once.
+__global__ __launch_bounds__(256) void maxpool_lds_kernel(const float *__restrict__ in,
+                                                          float *__restrict__ out, size_t planes, int G,
+                                                          int H, int W, int K, int S, int Ho, int Wo)
+{
+    extern __shared__ float tile[];
+    const size_t first = (size_t)blockIdx.x * G;
+    const int g = (int)min((size_t)G, planes - first);
+    const int HW = H * W, HoWo = Ho * Wo;
+    const float *src = in + first * HW;
+    const int n_in = g * HW;
+    for (int i = threadIdx.x; i < n_in; i += 256) tile[i] = src[i];
+    __syncthreads();
+    float *dst = out + first * HoWo;
+    const int n_out = g * HoWo;
+    for (int x = threadIdx.x; x < n_out; x += 256) {
+        const int pl = x / HoWo, r = x - pl * HoWo;
+        const int oh = r / Wo, ow = r - oh * Wo;
+        const float *win = tile + pl * HW + (oh * S) * W + ow * S;
+        float best = win[0];
+        for (int i = 0; i < K; ++i)
+            for (int j = 0; j < K; ++j) best = fmaxf(best, win[i * W + j]);
+        dst[x] = best;
+    }
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -93,6 +121,18 @@ int maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int 
     size_t blocks = (planes * Ho * Wo + 255) / 256;
     if (blocks > (1u << 20)) blocks = 1u << 20;
     LaunchScope scope("maxpool", 0.0, 4.0 * planes * ((double)H * W + (double)Ho * Wo));
+    const size_t plane_bytes = (size_t)H * W * sizeof(float);
+    if (plane_bytes <= 50 * 1024) {  // up to three workgroups per CU
+        int G = (int)(50 * 1024 / plane_bytes);
+        // keep at least ~4 workgroups per CU in flight when there are few planes
+        while (G > 1 && (planes + G - 1) / G < 1024) --G;
+        const size_t groups = (planes + G - 1) / G;
+        if (groups < (1u << 31)) {
+            hipLaunchKernelGGL(maxpool_lds_kernel, dim3((unsigned)groups), dim3(256), (size_t)G * plane_bytes,
+                               current_stream(), in, out, planes, G, H, W, K, S, Ho, Wo);
+            return check_launch();
+        }
+    }
     hipLaunchKernelGGL(maxpool_kernel, dim3((unsigned)blocks), dim3(256), 0, current_stream(), in,
                        out, planes, H, W, K, S, Ho, Wo);
     return check_launch();

@@ -5,19 +5,26 @@
 // Why it has its own kernel.  The contraction length is 3*49 = 147, which the generic
 // kernel can only cover by padding the three input layers to four (196, a third of the
 // MFMA work wasted).  Here the two k-values of each v_mfma_f32_32x32x2_f32 are chosen so
-// that the LDS offset between the pair is a per-lane constant and only one slot is padding
-// (148 = 74 MFMA steps):
+// that the LDS offset between the pair is a per-lane constant and the one spare slot
+// carries the bias (148 = 74 MFMA steps):
 //     steps  0..48   tap (i,j) of input layer 0   with the same tap of input layer 1
 //     steps 49..69   tap (i,j), i<3, of layer 2   with tap (i+3, j) of layer 2
-//     steps 70..72   tap (6,j), j<3, of layer 2   with tap (6, j+3) of layer 2
-//     step  73       tap (6,6) of layer 2         with a zero kernel value
-// The kernels are stored in LDS in exactly that order (slot 2*step + pair member), so the
-// A-operand address is uniform; the B operand uses four per-lane base offsets.
+//     steps 70..72   tap (6,j), j in {0,1,4}, of layer 2 with tap (6, j+2) of layer 2
+//     step  73       tap (6,5) of layer 2         with bias[m] * 1.0
+// The kernels are stored in LDS in exactly that order (slot 2*step + pair member).
 //
-// The workgroup is persistent: it stages all 96 x 147 kernel values once, then walks over
-// pixel tiles (BN consecutive output pixels of the batch-flattened image, which may
-// straddle two images), prefetching the next tile's input patch into registers while the
-// MFMAs of the current tile run, and double-buffering the patch in LDS.
+// Execution model.  fp32 MFMA shares the SIMD with ordinary vector instructions (they do
+// not overlap), and a workgroup barrier per tile keeps all wavefronts in the same phase,
+// so here each wavefront is autonomous after the kernels are staged once per workgroup:
+//   * a wavefront owns tiles of 2 x 16 output pixels (one 32-wide MFMA pixel block, all
+//     96 layers: 74 x 3 MFMAs) and walks over them with a fixed stride;
+//   * it stages the 9 x 37 x 3 input patch of its next tile into its own double-buffered
+//     LDS area (global loads before the MFMA loop, LDS writes after it), columns
+//     de-interleaved into even | odd so that the stride-2 reads are conflict free;
+//     every LDS offset of the MFMA loop is a compile-time constant;
+//   * results are kept in a second accumulator set and stored, one store per MFMA step,
+//     during the MFMA loop of the following tile;
+//   * the bias comes out of the contraction and ReLU is the only vector work per result.
 #include "conv_mfma_common.h"
 
 namespace sq {
@@ -25,6 +32,19 @@ namespace mfma {
 namespace {
 
 constexpr int kKS = 7, kS = 2, kKK = 49, kK = 147, kLDK = 149, kBM = 96, kTM = 3;
+constexpr int kTR = kConv7TileRows, kTC = kConv7TileCols;
+constexpr int kPR = (kTR - 1) * kS + kKS;      // 9 patch rows
+constexpr int kPC = (kTC - 1) * kS + kKS;      // 37 patch columns
+constexpr int kHalf = (kPC + 1) / 2;           // even columns first (19), then the odd ones
+constexpr int kLWs = 40;                       // LDS row stride: the two pixel rows of a tile on disjoint banks
+constexpr int kPlane = 416;                    // >= 9*40, = 32 (mod 64): the two k-halves on disjoint banks
+constexpr int kOne = 3 * kPlane;               // word holding 1.0 (multiplier of the bias slot)
+constexpr int kXbuf = 3 * kPlane + 32;         // floats per patch buffer
+constexpr int kWsFloats = kBM * kLDK + 32 - (kBM * kLDK) % 32;
+static_assert(kPR * kLWs <= kPlane && kPC <= kLWs, "patch plane");
+
+// position of patch column c inside a row: even columns, then odd columns
+__host__ __device__ constexpr int col_slot(int c) { return (c & 1) * kHalf + (c >> 1); }
 
 // LDS slot of kernel value k = (c, i, j) in the pairing order above.
 __device__ __forceinline__ int pair_slot(int k)
@@ -34,151 +54,154 @@ __device__ __forceinline__ int pair_slot(int k)
     const int i = tap / kKS, j = tap - i * kKS;
     if (i < 3) return 2 * (49 + tap);
     if (i < 6) return 2 * (49 + tap - 21) + 1;
-    if (j < 3) return 2 * (70 + j);
-    if (j < 6) return 2 * (70 + j - 3) + 1;
-    return 146;
+    switch (j) {
+        case 0: return 140;
+        case 2: return 141;
+        case 1: return 142;
+        case 3: return 143;
+        case 4: return 144;
+        case 6: return 145;
+        default: return 146;  // j == 5, paired with the bias
+    }
 }
 
-template <int BN, int PE, int MINW>
-__global__ __launch_bounds__(BN / 32 * 64, MINW) void conv7s2c3_kernel(const KParams p)
+// B-operand LDS offset of MFMA step s relative to the lane's base (compile-time)
+__host__ __device__ constexpr int step_offset(int s)
+{
+    if (s < 49) return (s / 7) * kLWs + col_slot(s % 7);
+    if (s < 70) return ((s - 49) / 7) * kLWs + col_slot((s - 49) % 7);
+    if (s == 70) return col_slot(0);
+    if (s == 71) return col_slot(1);
+    return col_slot(4);  // s == 72; step 73 has its own per-lane address
+}
+
+// FULL: the layer has exactly 96 output layers, so no store needs a layer test.
+template <int NW, bool FULL, int MINW>
+__global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams p)
 {
     using M = Mfma<32>;
     using Acc = typename M::Acc;
-    constexpr int NW = BN / 32, NT = NW * 64;
+    constexpr int NT = NW * 64;
 
     extern __shared__ float smem[];
-    float *const Ws = smem;                 // [96][149]
-    float *const Xs = Ws + kBM * kLDK;      // [2][3*plane]
-    const int plane = p.plane, LWs = p.LWs;
-
+    float *const Ws = smem;
     const int t = threadIdx.x, lane = t & 63;
     const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+    float *const Xw = smem + kWsFloats + wv * (2 * kXbuf);   // this wavefront's two patch buffers
     const int li = lane & 31, kk = lane >> 5;
 
-    // ---- kernels, once per workgroup -----------------------------------------------------
-    for (int e = t; e < kBM * kK; e += NT) {
-        const int m = e / kK, k = e - m * kK;
-        Ws[m * kLDK + pair_slot(k)] = m < p.Cout ? p.w[e] : 0.f;
+    // ---- kernels (pairing order) and bias, once per workgroup ---------------------------
+    // all loads are issued before the first use so their latencies overlap
+    {
+        constexpr int WR = (kBM * kK + NT - 1) / NT;
+        const rsrc_t rw = make_rsrc(p.w, p.w_bytes);   // rows beyond Cout read zero
+        float wv_[WR];
+#pragma unroll
+        for (int r = 0; r < WR; ++r) {
+            const int e = t + NT * r;
+            wv_[r] = buf_ld(rw, e < kBM * kK ? (uint32_t)(e * 4) : kOob, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < WR; ++r) {
+            const int e = t + NT * r;
+            const int m = e / kK, k = e - m * kK;
+            if (e < kBM * kK) Ws[m * kLDK + pair_slot(k)] = wv_[r];
+        }
     }
     if (t < kBM) {
-        Ws[t * kLDK + 147] = 0.f;
+        Ws[t * kLDK + 147] = (p.b && t < p.Cout) ? p.b[t] : 0.f;
         Ws[t * kLDK + 148] = 0.f;
     }
+    if (lane < 2) Xw[lane * kXbuf + kOne] = 1.0f;
+    int *const next_tile = reinterpret_cast<int *>(smem + kBM * kLDK + 8);   // in the padding after the kernels
+    if (t == 0) *next_tile = 0;
+    __syncthreads();   // the only workgroup barrier
 
+    // ---- loop-invariant per-lane LDS offsets ---------------------------------------------
     int aoff[kTM];
 #pragma unroll
     for (int x = 0; x < kTM; ++x) aoff[x] = (x * 32 + li) * kLDK + kk;
+    const int prow = li >> 4, pcol = li & 15;                 // this lane's pixel inside the tile
+    const int lbase = prow * kS * kLWs + pcol;                // even/odd split makes the column stride 1
+    const int b1 = lbase + kk * kPlane;
+    const int b2 = lbase + 2 * kPlane + kk * 3 * kLWs;
+    const int b3 = lbase + 2 * kPlane + 6 * kLWs + kk;
+    const int b4 = kk ? kOne : lbase + 2 * kPlane + 6 * kLWs + col_slot(5);
+    const int xdst = col_slot(lane < kPC ? lane : 0);        // patch column staged by this lane
 
-    // bias of the 48 output layers this lane stores (layer = x*32 + row_reg(r) + row_lane)
-    const int lrow = M::row_lane(lane);
-    float bias[kTM][16];
-#pragma unroll
-    for (int x = 0; x < kTM; ++x)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int m = x * 32 + M::row_reg(r) + lrow;
-            bias[x][r] = (p.b && m < p.Cout) ? p.b[m] : 0.f;
-        }
+    const int tiles_per_image = p.RG * p.CB;
+    const int ntiles = p.N * tiles_per_image;
+    const uint32_t hs1 = (uint32_t)(p.HoWo * 4);
 
-    // ---- staging map: element e = t + NT*r of a [rows][LW] plane; row and column of e do
-    // not depend on the tile, only the first virtual row va does -------------------------
-    int evr[PE], epc[PE];
-#pragma unroll
-    for (int r = 0; r < PE; ++r) {
-        const int e = t + NT * r;
-        evr[r] = fdiv(e, p.dLW);
-        epc[r] = e - evr[r] * p.LW;
-    }
-
-    int va = 0, PRt = 0;
-    auto tile_geometry = [&](int tile) {  // uniform
-        const int P0 = tile * BN;
-        const int Ra = fdiv(P0, p.dWo);
-        const int Rb = fdiv(min(P0 + BN, p.PT) - 1, p.dWo);
-        const int na = fdiv(Ra, p.dHo), nb = fdiv(Rb, p.dHo);
-        va = na * p.VH + (Ra - na * p.Ho) * kS;
-        PRt = nb * p.VH + (Rb - nb * p.Ho) * kS + kKS - va;
+    // tile -> image n, first output row oh0, first output column ow0 (all uniform)
+    // (readfirstlane tells the compiler these are wavefront-uniform, so all row arithmetic
+    // below runs on the scalar unit)
+    auto decode = [&](int tile_, int &n, int &oh0, int &ow0) {
+        const int tile = __builtin_amdgcn_readfirstlane(tile_);
+        n = fdiv(tile, p.dMtiles);               // dMtiles divides by tiles_per_image here
+        const int rem = tile - n * tiles_per_image;
+        const int rg = fdiv(rem, p.dCB);
+        n = __builtin_amdgcn_readfirstlane(n);
+        oh0 = __builtin_amdgcn_readfirstlane(rg * kTR);
+        ow0 = __builtin_amdgcn_readfirstlane((rem - rg * p.CB) * kTC);
     };
 
-    float xreg[3 * PE];
-    bool xstage[PE];
-    auto load_patch = [&]() {  // uses va / PRt of the tile being fetched
+    const rsrc_t rin = make_rsrc(p.in, p.in_bytes), rout = make_rsrc(p.out, p.out_bytes);
+
+    float xreg[3 * kPR];
+    auto load_patch = [&](int tile) {
+        int n, oh0, ow0;
+        decode(tile, n, oh0, ow0);
+        const int ih0 = oh0 * kS - p.P, iw = ow0 * kS - p.P + lane;
+        // columns outside the image (and lanes beyond the patch width) read zero through the
+        // buffer range check; rows outside the image are skipped by a uniform branch
+        const uint32_t coff = (lane < kPC && iw >= 0 && iw < p.W) ? (uint32_t)(iw * 4) : kOob;
 #pragma unroll
-        for (int r = 0; r < PE; ++r) {
-            const int v = va + evr[r];
-            const int n = fdiv(v, p.dVH), ih = v - n * p.VH - p.P, iw = epc[r] - p.P;
-            xstage[r] = evr[r] < PRt;
-            const bool inb = xstage[r] && n < p.N && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-            const uint32_t src = inb ? (uint32_t)(((n * 3 * p.H + ih) * p.W + iw) * 4) : 0u;
+        for (int r = 0; r < kPR; ++r) {
+            const int ih = ih0 + r;                                   // uniform
+            if (ih >= 0 && ih < p.H) {
+                const uint32_t row = (uint32_t)((n * 3 * p.H + ih) * p.W) * 4u;
 #pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                const float x = ld_f32(p.in + (size_t)c * p.HW, src);
-                xreg[c * PE + r] = inb ? x : 0.f;
+                for (int c = 0; c < 3; ++c) xreg[c * kPR + r] = buf_ld(rin, coff, row + (uint32_t)c * (uint32_t)p.HW * 4u);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 3; ++c) xreg[c * kPR + r] = 0.f;
             }
         }
     };
     auto store_patch = [&](int buf) {
-        float *xs = Xs + buf * (3 * plane);
+        float *xs = Xw + buf * kXbuf;
+        if (lane < kPC) {
 #pragma unroll
-        for (int r = 0; r < PE; ++r)
-            if (xstage[r]) {
-                const int d = evr[r] * LWs + epc[r];
+            for (int r = 0; r < kPR; ++r)
 #pragma unroll
-                for (int c = 0; c < 3; ++c) xs[c * plane + d] = xreg[c * PE + r];
-            }
+                for (int c = 0; c < 3; ++c) xs[c * kPlane + r * kLWs + xdst] = xreg[c * kPR + r];
+        }
+    };
+    // lane byte offset of this lane's output pixel; pixels outside the image get an offset the
+    // buffer range check rejects, so their stores vanish.  The layer part is a uniform offset.
+    auto out_offset = [&](int tile) -> uint32_t {
+        int n, oh0, ow0;
+        decode(tile, n, oh0, ow0);
+        const int oh = oh0 + prow, ow = ow0 + pcol;
+        const uint32_t off = (uint32_t)(((n * p.ldc + p.coff + M::row_lane(lane)) * p.HoWo + oh * p.Wo + ow) * 4);
+        return (oh < p.Ho && ow < p.Wo) ? off : kOob;
     };
 
-    int tile = blockIdx.x;
-    if (tile < p.ntiles) {
-        tile_geometry(tile);
-        load_patch();
-        store_patch(0);
-    }
-    __syncthreads();
-
-    for (int it = 0; tile < p.ntiles; ++it, tile += gridDim.x) {
-        // B-operand base of this lane's pixel in the current tile
-        tile_geometry(tile);
-        const int pp = tile * BN + wv * 32 + li;
-        int base;
-        {
-            const int pc = min(pp, p.PT - 1);
-            const int R = fdiv(pc, p.dWo), ow = pc - R * p.Wo;
-            const int n = fdiv(R, p.dHo);
-            base = (n * p.VH + (R - n * p.Ho) * kS - va) * LWs + ow * kS;
-        }
-        const int b1 = base + kk * plane;
-        const int b2 = base + 2 * plane + kk * 3 * LWs;
-        const int b3 = base + 2 * plane + 6 * LWs + kk * 3;
-        const int b4 = base + 2 * plane + 6 * LWs + 6;
-
-        const int next = tile + gridDim.x;
-        const bool more = next < p.ntiles;
-        if (more) {
-            tile_geometry(next);
-            load_patch();
-        }
-
-        const float *xs = Xs + (it & 1) * (3 * plane);
-        Acc acc[kTM];
-#pragma unroll
-        for (int x = 0; x < kTM; ++x)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[x][r] = 0.f;
-
-        // The operands of MFMA step s+1 are fetched from LDS before the MFMAs of step s are
-        // issued, so the LDS latency hides behind three MFMAs.
-        auto b_addr = [&](int s) -> int {
-            if (s < 49) return b1 + (s / 7) * LWs + s % 7;
-            if (s < 70) return b2 + ((s - 49) / 7) * LWs + (s - 49) % 7;
-            if (s < 73) return b3 + (s - 70);
-            return b4;
+    // One tile: 74 MFMA steps into `acc`, with the previous tile's results (`prev`, already
+    // ReLU'd) stored one per MFMA step at the walking byte offset prev_off.
+    auto tile_mfma = [&](int buf, Acc (&acc)[kTM], const Acc (&prev)[kTM], uint32_t prev_off) {
+        const float *xs = Xw + buf * kXbuf;
+        auto b_read = [&](int s) -> float {
+            if (s == 73) return xs[b4];
+            const int base = s < 49 ? b1 : s < 70 ? b2 : b3;
+            return xs[base + step_offset(s)];
         };
         float av[2][kTM], bv[2];
         auto fetch = [&](int s, float *a, float &b) {
 #pragma unroll
             for (int x = 0; x < kTM; ++x) a[x] = Ws[aoff[x] + 2 * s];
-            b = xs[b_addr(s)];
+            b = b_read(s);
         };
         fetch(0, av[0], bv[0]);
 #pragma unroll
@@ -186,40 +209,101 @@ __global__ __launch_bounds__(BN / 32 * 64, MINW) void conv7s2c3_kernel(const KPa
             if (s + 1 < 74) fetch(s + 1, av[(s + 1) & 1], bv[(s + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);  // reads of step s+1 stay ahead of the MFMAs of step s
 #pragma unroll
-            for (int x = 0; x < kTM; ++x) acc[x] = M::run(av[s & 1][x], bv[s & 1], acc[x]);
+            for (int x = 0; x < kTM; ++x) {
+                if (s == 0) {
+                    Acc z;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+                    acc[x] = M::run(av[0][x], bv[0], z);
+                } else {
+                    acc[x] = M::run(av[s & 1][x], bv[s & 1], acc[x]);
+                }
+            }
+            if (s < 48) {
+                // layers come in groups of 8 (rows mu..mu+3 in the lower half-wave, +4 in the
+                // upper), and Cout is a multiple of 8, so the layer test is uniform
+                const int x = s / 16, r = s % 16;
+                const int mu = x * 32 + M::row_reg(r);
+                if (FULL || mu < p.Cout) buf_st(rout, prev_off, (uint32_t)mu * hs1, prev[x][r]);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
-
-        // The prefetched patch goes to the other LDS buffer BEFORE the output stores are
-        // issued: the wait for its global loads would otherwise also wait for the stores.
-        if (more) store_patch((it + 1) & 1);
-
-        // epilogue: bias, ReLU, coalesced store of 32 consecutive pixels per register
-        if (pp < p.PT) {
-            const int n = fdiv(pp, p.dHoWo), q = pp - n * p.HoWo;
-            const uint32_t lbase = (uint32_t)(((n * p.ldc + p.coff + lrow) * p.HoWo + q) * 4);
+        if (p.relu) {
 #pragma unroll
             for (int x = 0; x < kTM; ++x)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int mu = x * 32 + M::row_reg(r);
-                    float v = acc[x][r] + bias[x][r];
-                    if (p.relu) v = fmaxf(v, 0.f);
-                    if (p.Cout == kBM || mu + lrow < p.Cout) st_f32(p.out + (size_t)mu * p.HoWo, lbase, v);
-                }
+                for (int r = 0; r < 16; ++r) acc[x][r] = fmaxf(acc[x][r], 0.f);
         }
-        __syncthreads();
+    };
+
+    // Tiles of this workgroup are blockIdx.x + k * gridDim.x; its wavefronts draw k from a
+    // counter in LDS, so a wavefront that gets less of the SIMD (the hardware favours the
+    // older one of two) simply takes fewer tiles and all finish together.  Every wavefront
+    // leaves the loop as soon as its draw is past the last tile.
+    auto draw = [&]() -> int {
+        int k = 0;
+        if (lane == 0) k = atomicAdd(next_tile, 1);
+        k = __builtin_amdgcn_readfirstlane(k);
+        return (int)blockIdx.x + k * (int)gridDim.x;
+    };
+    int tile = draw();
+    if (tile >= ntiles) return;
+    load_patch(tile);
+    store_patch(0);
+
+    Acc accA[kTM], accB[kTM];
+#pragma unroll
+    for (int x = 0; x < kTM; ++x)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accA[x][r] = accB[x][r] = 0.f;
+    uint32_t offA = kOob, offB = kOob;   // nothing to store yet
+    bool lastA = true;
+
+    // two tiles per trip: even tiles use patch buffer 0 and accumulators A, odd ones 1 and B
+    while (true) {
+        {
+            const int next = draw();
+            const bool more = next < ntiles;
+            if (more) load_patch(next);
+            tile_mfma(0, accA, accB, offB);
+            offA = out_offset(tile);
+            lastA = true;
+            if (!more) break;
+            store_patch(1);
+            tile = next;
+        }
+        {
+            const int next = draw();
+            const bool more = next < ntiles;
+            if (more) load_patch(next);
+            tile_mfma(1, accB, accA, offA);
+            offB = out_offset(tile);
+            lastA = false;
+            if (!more) break;
+            store_patch(0);
+            tile = next;
+        }
     }
+    // results of the last tile
+#pragma unroll
+    for (int x = 0; x < kTM; ++x)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int mu = x * 32 + M::row_reg(r);
+            if (FULL || mu < p.Cout) buf_st(rout, lastA ? offA : offB, (uint32_t)mu * hs1, lastA ? accA[x][r] : accB[x][r]);
+        }
 }
 
 }  // namespace
 
-KernelFn conv7s2c3_kernel_for(int BN)
+KernelFn conv7s2c3_kernel_for(int NW, bool full)
 {
-    if (BN == 256) return conv7s2c3_kernel<256, 8, 1>;
-    if (BN == 128) return conv7s2c3_kernel<128, 15, 1>;
+    if (NW == 8) return full ? conv7s2c3_kernel<8, true, 1> : conv7s2c3_kernel<8, false, 1>;
+    if (NW == 4) return full ? conv7s2c3_kernel<4, true, 1> : conv7s2c3_kernel<4, false, 1>;
     return nullptr;
 }
+
+size_t conv7s2c3_lds_bytes(int NW) { return ((size_t)kWsFloats + (size_t)NW * 2 * kXbuf) * sizeof(float); }
 
 }  // namespace mfma
 }  // namespace sq

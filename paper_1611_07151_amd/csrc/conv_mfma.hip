@@ -27,6 +27,9 @@
 // input layers, which makes the per-lane LDS offsets loop-invariant.
 #include "conv_mfma_common.h"
 
+#include <math.h>
+#include <string.h>
+
 namespace sq {
 namespace {
 
@@ -104,24 +107,20 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
     // is real or zero, *dst the LDS float index (-1 = nothing to store).
     uint32_t wsrc[WREG];
     int wdst[WREG];
-    bool wok[WREG];
 #pragma unroll
     for (int r = 0; r < WREG; ++r) {
         const int e = t + NT * r;
         const int m = e / RUN, q = e - m * RUN;
         const bool inrange = WEXACT || e < BM * RUN;
-        wok[r] = inrange && (m0 + m < p.Cout);
-        wsrc[r] = wok[r] ? (uint32_t)(((m0 + m) * p.Cin * KK + q) * 4) : 0u;
+        wsrc[r] = (inrange && m0 + m < p.Cout) ? (uint32_t)(((m0 + m) * p.Cin * KK + q) * 4) : kOob;
         wdst[r] = inrange ? m * LDK + q : -1;
     }
     uint32_t xsrc[XMAP];
     int xdst[XMAP];
-    bool xok[XMAP];
     if constexpr (POINTWISE) {
         const int pl = t % BN, pp = P0 + pl;
-        xok[0] = pp < p.PT;
         const int n = fdiv(pp, p.dHW);
-        xsrc[0] = xok[0] ? (uint32_t)((n * p.Cin * p.HW + (pp - n * p.HW)) * 4) : 0u;
+        xsrc[0] = pp < p.PT ? (uint32_t)((n * p.Cin * p.HW + (pp - n * p.HW)) * 4) : kOob;
         xdst[0] = pl;
     } else {
 #pragma unroll
@@ -131,8 +130,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
             const int v = va + vr;
             const int n = fdiv(v, p.dVH), ih = v - n * p.VH - p.P, iw = pc - p.P;
             const bool stage = vr < PRt;
-            xok[r] = stage && n < p.N && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-            xsrc[r] = xok[r] ? (uint32_t)(((n * p.Cin * p.H + ih) * p.W + iw) * 4) : 0u;
+            const bool inb = stage && n < p.N && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+            xsrc[r] = inb ? (uint32_t)(((n * p.Cin * p.H + ih) * p.W + iw) * 4) : kOob;
             xdst[r] = stage ? vr * p.LWs + pc : -1;
         }
     }
@@ -140,44 +139,32 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
 
     float wreg[WREG], xreg[XREG];
 
-    // Global loads of one chunk.  The common case reads unconditionally from in-bounds
-    // addresses and zeroes what is padding with a select; only a last chunk that runs past
-    // the input layers (Cin not a multiple of CC) takes the fully predicated path.
+    // Global loads of one chunk through buffer addressing: the per-lane offsets were fixed
+    // above (kOob where the value is padding, which the hardware turns into zero), the chunk
+    // and input-layer offsets are uniform.  Only a last chunk that runs past the input
+    // layers (Cin not a multiple of CC) needs extra tests.
+    const rsrc_t rw = make_rsrc(p.w, p.w_bytes), rin = make_rsrc(p.in, p.in_bytes);
     auto load_chunk = [&](int ch) {
         const int c0 = ch * CC;
-        const float *wbase = p.w + c0 * KK;
-        if (tail_c && ch == p.nchunks - 1) {
+        const bool tail = tail_c && ch == p.nchunks - 1;
+        const uint32_t wchunk = (uint32_t)(c0 * KK * 4);
 #pragma unroll
-            for (int r = 0; r < WREG; ++r) {
-                const int e = t + NT * r;
-                const int q = e % RUN;
-                wreg[r] = (wok[r] && c0 + q / KK < p.Cin) ? ld_f32(wbase, wsrc[r]) : 0.f;
+        for (int r = 0; r < WREG; ++r) {
+            uint32_t off = wsrc[r];
+            if (tail) {
+                const int q = (t + NT * r) % RUN;
+                if (c0 + q / KK >= p.Cin) off = kOob;
             }
-#pragma unroll
-            for (int r = 0; r < XREG; ++r) {
-                const int c = POINTWISE ? cpart + (NT / BN) * r : r / XMAP;
-                const int i = POINTWISE ? 0 : r % XMAP;
-                xreg[r] = (xok[i] && c0 + c < p.Cin) ? ld_f32(p.in + (size_t)(c0 + c) * p.HW, xsrc[i]) : 0.f;
-            }
-            return;
-        }
-        if (full_m) {
-#pragma unroll
-            for (int r = 0; r < WREG; ++r)
-                if (WEXACT || r + 1 < WREG || wok[r]) wreg[r] = ld_f32(wbase, wsrc[r]);
-        } else {
-#pragma unroll
-            for (int r = 0; r < WREG; ++r) {
-                const float v = ld_f32(wbase, wsrc[r]);
-                wreg[r] = wok[r] ? v : 0.f;
-            }
+            wreg[r] = buf_ld(rw, off, wchunk);
         }
 #pragma unroll
         for (int r = 0; r < XREG; ++r) {
-            const int c = POINTWISE ? cpart + (NT / BN) * r : r / XMAP;
+            const int c = POINTWISE ? cpart + (NT / BN) * r : r / XMAP;   // uniform
             const int i = POINTWISE ? 0 : r % XMAP;
-            const float v = ld_f32(p.in + (size_t)(c0 + c) * p.HW, xsrc[i]);
-            xreg[r] = xok[i] ? v : 0.f;
+            if (!tail || c0 + c < p.Cin)
+                xreg[r] = buf_ld(rin, xsrc[i], (uint32_t)((c0 + c) * p.HW) * 4u);
+            else
+                xreg[r] = 0.f;
         }
     };
 
@@ -264,20 +251,35 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
     // (scalar address arithmetic) and a per-lane part folded into the lane's byte offset.
     const int mw = m0 + wm * (BM / WM);          // uniform: first layer of this wavefront
     const int lrow = M::row_lane(lane);          // per lane
+    const rsrc_t rout = make_rsrc(p.out, p.out_bytes);
     float bias[TM][M::NR];
+    if (p.b) {
+        const rsrc_t rb = make_rsrc(p.b, (uint32_t)p.Cout * 4u);   // layers beyond Cout read zero
 #pragma unroll
-    for (int x = 0; x < TM; ++x)
+        for (int x = 0; x < TM; ++x)
 #pragma unroll
-        for (int r = 0; r < M::NR; ++r) {
-            const int mu = mw + x * MT + M::row_reg(r);
-            bias[x][r] = (p.b && (full_m || mu + lrow < p.Cout)) ? ld_f32(p.b + mu, (uint32_t)(lrow * 4)) : 0.f;
-        }
+            for (int r = 0; r < M::NR; ++r)
+            {
+                // with a partial layer tile the whole index goes into the range-checked lane
+                // offset, so nothing is read past the end of the bias array
+                const int mu = mw + x * MT + M::row_reg(r);
+                bias[x][r] = full_m ? buf_ld(rb, (uint32_t)(lrow * 4), (uint32_t)mu * 4u)
+                                    : buf_ld(rb, (uint32_t)((mu + lrow) * 4), 0u);
+            }
+    } else {
+#pragma unroll
+        for (int x = 0; x < TM; ++x)
+#pragma unroll
+            for (int r = 0; r < M::NR; ++r) bias[x][r] = 0.f;
+    }
+    const uint32_t hs = (uint32_t)p.HoWo * 4u;
 #pragma unroll
     for (int y = 0; y < TN; ++y) {
         const int pp = P0 + wn * (BN / WN) + y * MT + li;
-        if (pp >= p.PT) continue;
-        const int n = fdiv(pp, p.dHoWo), q = pp - n * p.HoWo;
-        const uint32_t lbase = (uint32_t)(((n * p.ldc + p.coff + lrow) * p.HoWo + q) * 4);
+        const int ppc = min(pp, p.PT - 1);
+        const int n = fdiv(ppc, p.dHoWo), q = ppc - n * p.HoWo;
+        // pixels past the end get an offset the range check rejects
+        const uint32_t lbase = pp < p.PT ? (uint32_t)(((n * p.ldc + p.coff + lrow) * p.HoWo + q) * 4) : kOob;
 #pragma unroll
         for (int x = 0; x < TM; ++x) {
 #pragma unroll
@@ -285,7 +287,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
                 const int mu = mw + x * MT + M::row_reg(r);
                 float v = acc[x][y][r] + bias[x][r];
                 if (p.relu) v = fmaxf(v, 0.f);
-                if (full_m || mu + lrow < p.Cout) st_f32(p.out + (size_t)mu * p.HoWo, lbase, v);
+                if (full_m)
+                    buf_st(rout, lbase, (uint32_t)mu * hs, v);
+                else
+                    buf_st(rout, mu + lrow < p.Cout ? lbase : kOob, (uint32_t)mu * hs, v);
             }
         }
     }
@@ -329,9 +334,10 @@ const Variant kVariants[] = {
     SQ_VARIANT(1, 1, 128, 128, 2, 2, 16, 16, 0, 2),
     SQ_VARIANT(1, 1, 64, 64, 2, 2, 16, 32, 0, 3),
     SQ_VARIANT(1, 1, 128, 128, 2, 2, 32, 32, 0, 2),
-    // 7x7 stride 2 with three input layers (conv1): persistent kernel, 148-long contraction
-    {"k7s2c3_persist_96x256", 7, 2, 96, 256, 32, 3, 8, 2, 512, conv7s2c3_kernel_for(256), true},
-    {"k7s2c3_persist_96x128", 7, 2, 96, 128, 32, 3, 15, 2, 256, conv7s2c3_kernel_for(128), true},
+    // 7x7 stride 2 with three input layers (conv1): persistent autonomous wavefronts,
+    // 148-long contraction (BN and PE are unused for these two)
+    {"k7s2c3_waves8", 7, 2, 96, 256, 32, 3, 64, 2, 512, conv7s2c3_kernel_for(8, true), true},
+    {"k7s2c3_waves4", 7, 2, 96, 128, 32, 3, 64, 2, 256, conv7s2c3_kernel_for(4, true), true},
     // 7x7 stride 2, any number of input layers, two per chunk
     SQ_VARIANT(7, 2, 96, 128, 1, 4, 32, 2, 15, 1),
 };
@@ -368,10 +374,10 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl)
     const long long pixels = (long long)a.N * a.Ho * a.Wo;
     // per-lane addresses are 32-bit byte offsets from a uniform base
     const long long w_elems = (long long)a.Cout * a.Cin * a.K * a.K;
-    if (in_elems >= (1ll << 30) || out_elems >= (1ll << 30) || w_elems >= (1ll << 30) ||
-        pixels + v.BN >= (1ll << 30))
+    if (in_elems >= kMaxBufferElems || out_elems >= kMaxBufferElems || w_elems >= kMaxBufferElems ||
+        pixels + v.BN >= kMaxBufferElems)
         return false;
-    if (v.conv1_type && (a.Cin != 3 || a.Cout > 96)) return false;
+    if (v.conv1_type && (a.Cin != 3 || a.Cout > 96 || a.Cout % 8 != 0)) return false;
 
     KParams &k = pl.kp;
     k.in = (const float *)a.in; k.w = (const float *)a.w; k.b = a.b; k.out = a.out;
@@ -404,14 +410,22 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl)
     k.dWo = make_fastdiv(k.Wo); k.dHo = make_fastdiv(k.Ho); k.dLW = make_fastdiv(k.LW);
     k.dVH = make_fastdiv(k.VH); k.dHW = make_fastdiv(k.HW); k.dHoWo = make_fastdiv(k.HoWo);
     k.dMtiles = make_fastdiv(k.mtiles);
+    k.in_bytes = (uint32_t)(in_elems * 4); k.out_bytes = (uint32_t)(out_elems * 4); k.w_bytes = (uint32_t)(w_elems * 4);
     long long blocks = (long long)k.mtiles * k.ntiles;
     if (v.conv1_type) {
-        // kernels [96][149] + two patch buffers of three planes; if the bank
-        // padding of the plane does not fit, fall back to the unpadded plane
-        const size_t fixed = (size_t)96 * 149;
-        if ((fixed + (size_t)6 * k.plane) * sizeof(float) > (size_t)kLdsBytes) k.plane = k.PRcap * k.LWs;
-        pl.lds_bytes = (fixed + (size_t)6 * k.plane) * sizeof(float);
-        if (blocks > num_cus()) blocks = num_cus();  // persistent: one workgroup per CU
+        // autonomous wavefronts: tiles of 2 x 16 output pixels, NW = NT/64 wavefronts per
+        // workgroup, one workgroup per CU at most
+        const int NW = v.NT / 64;
+        k.RG = (a.Ho + kConv7TileRows - 1) / kConv7TileRows;
+        k.CB = (a.Wo + kConv7TileCols - 1) / kConv7TileCols;
+        const long long tiles = (long long)a.N * k.RG * k.CB;
+        if (tiles >= (1ll << 30)) return false;
+        k.dRG = make_fastdiv(k.RG); k.dCB = make_fastdiv(k.CB);
+        k.dMtiles = make_fastdiv(k.RG * k.CB);
+        k.ntiles = (int)tiles;
+        pl.lds_bytes = conv7s2c3_lds_bytes(NW);
+        blocks = (tiles + NW - 1) / NW;
+        if (blocks > num_cus()) blocks = num_cus();
     } else {
         pl.lds_bytes = ((size_t)v.NBUF * v.BM * LDK + (size_t)v.NBUF * v.CC * k.plane) * sizeof(float);
     }
@@ -421,22 +435,60 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl)
     return true;
 }
 
-bool g_attr_done[kNumVariants] = {};
+// Dynamic LDS above the default limit must be opted into once per kernel function.
+bool allow_big_lds(KernelFn fn)
+{
+    static KernelFn done[2 * kNumVariants + 4];
+    static int ndone = 0;
+    for (int i = 0; i < ndone; ++i)
+        if (done[i] == fn) return true;
+    if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
+        return false;
+    if (ndone < (int)(sizeof(done) / sizeof(done[0]))) done[ndone++] = fn;
+    return true;
+}
 
 int launch(int vi, const Plan &pl, const ConvArgs &a)
 {
     const Variant &v = kVariants[vi];
-    if (!g_attr_done[vi]) {
-        // dynamic LDS above the default limit must be opted into once per kernel
-        if (hipFuncSetAttribute((const void *)v.kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess) {
-            const int rc = check_launch();
-            return rc ? rc : SQ_ERR_HIP;
-        }
-        g_attr_done[vi] = true;
+    KernelFn fn = v.kernel;
+    if (v.conv1_type && a.Cout != 96) fn = conv7s2c3_kernel_for(v.NT / 64, false);
+    if (!allow_big_lds(fn)) {
+        const int rc = check_launch();
+        return rc ? rc : SQ_ERR_HIP;
     }
     LaunchScope scope(v.name, conv_flops(a), conv_bytes(a));
-    hipLaunchKernelGGL(v.kernel, dim3(pl.blocks), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
+    hipLaunchKernelGGL(fn, dim3(pl.blocks), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
     return check_launch();
+}
+
+// Measured winners (written by tune.py).  An entry applies to its exact layer shape and to
+// the batch sizes nearest to the one it was measured at.
+struct Tuned {
+    int K, S, P, Cin, Cout, H, W, N;
+    const char *variant;
+};
+const Tuned kTuned[] = {
+#include "tuned_table.inc"
+    {0, 0, 0, 0, 0, 0, 0, 0, ""}};
+
+int tuned_variant(const ConvArgs &a)
+{
+    const Tuned *best = nullptr;
+    double best_dist = 0;
+    for (const Tuned *e = kTuned; e->K; ++e) {
+        if (e->K != a.K || e->S != a.S || e->P != a.P || e->Cin != a.Cin || e->Cout != a.Cout || e->H != a.H ||
+            e->W != a.W)
+            continue;
+        const double d = fabs(log((double)a.N / e->N));
+        if (!best || d < best_dist) {
+            best = e; best_dist = d;
+        }
+    }
+    if (!best) return -1;
+    for (int i = 0; i < kNumVariants; ++i)
+        if (!strcmp(kVariants[i].name, best->variant)) return i;
+    return -1;
 }
 
 // Estimated cost of a variant for a shape: MFMA work including tile and contraction
@@ -477,6 +529,8 @@ int conv_mfma(const ConvArgs &a, int variant)
         if (variant >= kNumVariants || !plan(kVariants[variant], a, pl)) return SQ_ERR_UNSUPPORTED;
         return launch(variant, pl, a);
     }
+    const int tv = tuned_variant(a);
+    if (tv >= 0 && plan(kVariants[tv], a, pl)) return launch(tv, pl, a);
     int best = -1;
     double best_cost = 0;
     Plan best_plan;

@@ -71,6 +71,9 @@ struct KParams {
     int ntiles;  // tiles along pixels
     int nchunks;
     FastDiv dWo, dHo, dLW, dVH, dHW, dHoWo, dMtiles;
+    uint32_t in_bytes, out_bytes, w_bytes;
+    int RG, CB;  // conv1-type kernel: tile grid per image (row groups, column blocks)
+    FastDiv dRG, dCB;
 };
 
 template <int MT> struct Mfma;
@@ -107,6 +110,29 @@ __device__ __forceinline__ int xcd_remap(int b, int total)
     return start + idx;
 }
 
+// Buffer addressing: a uniform 128-bit resource (base, size) + per-lane 32-bit byte offset
+// + uniform 32-bit byte offset.  Needs no vector arithmetic per access, and the hardware
+// range check does the zero padding: a lane whose offset is >= the buffer size reads 0 and
+// its stores are dropped.  kOob is such an offset for every buffer this library describes
+// (tensors handled through buffers are kept below 2 GiB).
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr uint32_t kOob = 0x80000000u;
+constexpr long long kMaxBufferElems = 1ll << 29;
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    // word 3: DATA_FORMAT = 32-bit, raw (unstructured) buffer
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ float buf_ld(rsrc_t r, uint32_t lane_off, uint32_t uni_off)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_off, (int)uni_off, 0));
+}
+__device__ __forceinline__ void buf_st(rsrc_t r, uint32_t lane_off, uint32_t uni_off, float v)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)lane_off, (int)uni_off, 0);
+}
+
 // base + 32-bit byte offset: the addressing form that needs no per-lane 64-bit arithmetic
 __device__ __forceinline__ float ld_f32(const float *base, uint32_t byte_off)
 {
@@ -118,9 +144,11 @@ __device__ __forceinline__ void st_f32(float *base, uint32_t byte_off, float v)
 }
 
 // conv1-type layers (7x7, stride 2, three input layers, at most 96 output layers) have
-// their own persistent kernel; BN (pixels per tile) is 256 or 128.
+// their own persistent kernel with NW autonomous wavefronts per workgroup (8 or 4).
 typedef void (*KernelFn)(const KParams);
-KernelFn conv7s2c3_kernel_for(int BN);
+KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers);
+constexpr int kConv7TileRows = 2, kConv7TileCols = 16;   // output pixels per wavefront tile
+size_t conv7s2c3_lds_bytes(int NW);
 
 }  // namespace mfma
 }  // namespace sq

@@ -27,31 +27,34 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const float *__restrict__ 
     }
 }
 
-// Workgroup per group of G consecutive planes: the planes (contiguous in memory) are
-// copied once, coalesced, into LDS and every output reads its window from there, so HBM
-// sees each input element exactly once and each output once.
-__global__ __launch_bounds__(256) void maxpool_lds_kernel(const float *__restrict__ in,
-                                                          float *__restrict__ out, size_t planes, int G,
-                                                          int H, int W, int K, int S, int Ho, int Wo)
+// 3x3 / stride 2 pooling, the only kind the network uses.  A group of LP lanes (64, 32 or
+// 16, the smallest with 2*LP >= W) owns one plane and walks down its rows: lane l holds
+// columns 2l and 2l+1 of the current input rows, keeps the last row of one window as the
+// first row of the next (every input element is loaded exactly once, coalesced), and gets
+// column 2l+2 from its neighbour lane.  Output row oh is written by lanes l < Wo.
+template <int LP>
+__global__ __launch_bounds__(256) void maxpool3s2_kernel(const float *__restrict__ in, float *__restrict__ out,
+                                                         size_t planes, int H, int W, int Ho, int Wo)
 {
-    extern __shared__ float tile[];
-    const size_t first = (size_t)blockIdx.x * G;
-    const int g = (int)min((size_t)G, planes - first);
-    const int HW = H * W, HoWo = Ho * Wo;
-    const float *src = in + first * HW;
-    const int n_in = g * HW;
-    for (int i = threadIdx.x; i < n_in; i += 256) tile[i] = src[i];
-    __syncthreads();
-    float *dst = out + first * HoWo;
-    const int n_out = g * HoWo;
-    for (int x = threadIdx.x; x < n_out; x += 256) {
-        const int pl = x / HoWo, r = x - pl * HoWo;
-        const int oh = r / Wo, ow = r - oh * Wo;
-        const float *win = tile + pl * HW + (oh * S) * W + ow * S;
-        float best = win[0];
-        for (int i = 0; i < K; ++i)
-            for (int j = 0; j < K; ++j) best = fmaxf(best, win[i * W + j]);
-        dst[x] = best;
+    const int lane = threadIdx.x & 63, sub = lane / LP, l = lane % LP;
+    const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const size_t pl = wave * (64 / LP) + sub;
+    const bool live = pl < planes;
+    const float *src = in + (live ? pl : 0) * (size_t)H * W;
+    float *dst = out + (live ? pl : 0) * (size_t)Ho * Wo;
+    const bool has0 = live && 2 * l < W, has1 = live && 2 * l + 1 < W;
+    const int c0 = has0 ? 2 * l : 0, c1 = has1 ? 2 * l + 1 : 0;
+    float a0 = src[c0], b0 = src[c1];
+#pragma unroll 4
+    for (int oh = 0; oh < Ho; ++oh) {
+        const float *r1 = src + (size_t)(2 * oh + 1) * W, *r2 = r1 + W;
+        const float a1 = r1[c0], b1 = r1[c1], a2 = r2[c0], b2 = r2[c1];
+        const float ma = has0 ? fmaxf(fmaxf(a0, a1), a2) : -INFINITY;
+        const float mb = has1 ? fmaxf(fmaxf(b0, b1), b2) : -INFINITY;
+        const float mc = __shfl_down(ma, 1, LP);     // column 2l+2
+        if (live && l < Wo) dst[(size_t)oh * Wo + l] = fmaxf(fmaxf(ma, mb), mc);
+        a0 = a2;
+        b0 = b2;
     }
 }
 
@@ -121,15 +124,13 @@ int maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int 
     size_t blocks = (planes * Ho * Wo + 255) / 256;
     if (blocks > (1u << 20)) blocks = 1u << 20;
     LaunchScope scope("maxpool", 0.0, 4.0 * planes * ((double)H * W + (double)Ho * Wo));
-    const size_t plane_bytes = (size_t)H * W * sizeof(float);
-    if (plane_bytes <= 50 * 1024) {  // up to three workgroups per CU
-        int G = (int)(50 * 1024 / plane_bytes);
-        // keep at least ~4 workgroups per CU in flight when there are few planes
-        while (G > 1 && (planes + G - 1) / G < 1024) --G;
-        const size_t groups = (planes + G - 1) / G;
+    if (K == 3 && S == 2 && W <= 128) {
+        const int LP = W <= 32 ? 16 : W <= 64 ? 32 : 64;
+        const size_t waves = (planes + (64 / LP) - 1) / (64 / LP);
+        const size_t groups = (waves + 3) / 4;
         if (groups < (1u << 31)) {
-            hipLaunchKernelGGL(maxpool_lds_kernel, dim3((unsigned)groups), dim3(256), (size_t)G * plane_bytes,
-                               current_stream(), in, out, planes, G, H, W, K, S, Ho, Wo);
+            auto fn = LP == 16 ? maxpool3s2_kernel<16> : LP == 32 ? maxpool3s2_kernel<32> : maxpool3s2_kernel<64>;
+            hipLaunchKernelGGL(fn, dim3((unsigned)groups), dim3(256), 0, current_stream(), in, out, planes, H, W, Ho, Wo);
             return check_launch();
         }
     }

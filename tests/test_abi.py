@@ -117,3 +117,23 @@ def test_product_package_does_not_touch_the_oracle():
             if fn.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, fn)).read()
                 assert "oracle" not in text.lower(), os.path.join(dirpath, fn)
+
+
+def test_division_by_multiplication_is_exact(lib):
+    """The kernels divide by runtime constants with a precomputed multiplier; the host
+    twin of that routine must agree with integer division over the ranges in use."""
+    f = lib.sq_internal_fastdiv_mismatches
+    f.restype = ctypes.c_longlong
+    f.argtypes = [ctypes.c_uint, ctypes.c_uint]
+    for d in (1, 2, 3, 5, 7, 13, 15, 16, 27, 29, 55, 57, 111, 169, 227, 392, 729, 3025, 12321, 65536, 1000003):
+        assert f(d, 3_000_000) == 0, d
+    for d in (3, 111, 12321, 2_000_003):
+        assert f(d, 40_000_000) == 0, d
+
+
+def test_tuned_table_names_exist(lib):
+    names = {lib.sq_conv_variant_name(i).decode() for i in range(lib.sq_conv_variant_count())}
+    inc = os.path.join(ROOT, "paper_1611_07151_amd", "csrc", "tuned_table.inc")
+    rows = re.findall(r'^\{[^"]*"([^"]+)"\},', open(inc).read(), flags=re.M)
+    assert rows, "tuned table is empty"
+    assert set(rows) <= names, set(rows) - names

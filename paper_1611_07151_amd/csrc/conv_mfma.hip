@@ -35,7 +35,9 @@ namespace {
 
 using namespace mfma;
 
-template <int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW>
+// TAIL: the number of input layers is not a multiple of CC, so the last chunk is partly
+// padding (compiled separately to keep the common loop free of the test).
+template <int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW, bool TAIL>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const KParams p)
 {
     using M = Mfma<MT>;
@@ -69,7 +71,6 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
     const int pt = fdiv(tile, p.dMtiles), mt = tile - pt * p.mtiles;
     const int P0 = pt * BN, m0 = mt * BM;
     const bool full_m = m0 + BM <= p.Cout;
-    const bool tail_c = p.Cin % CC != 0;
 
     // ---- geometry of the staged patch ------------------------------------------------
     int va = 0, PRt = 0;
@@ -144,27 +145,36 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
     // and input-layer offsets are uniform.  Only a last chunk that runs past the input
     // layers (Cin not a multiple of CC) needs extra tests.
     const rsrc_t rw = make_rsrc(p.w, p.w_bytes), rin = make_rsrc(p.in, p.in_bytes);
-    auto load_chunk = [&](int ch) {
-        const int c0 = ch * CC;
-        const bool tail = tail_c && ch == p.nchunks - 1;
+    auto load_chunk = [&](int ch_) {
+        // readfirstlane keeps the chunk offsets in scalar registers (otherwise every buffer
+        // load is wrapped in a loop over the distinct values of its "uniform" offset)
+        const int c0 = __builtin_amdgcn_readfirstlane(ch_ * CC);
         const uint32_t wchunk = (uint32_t)(c0 * KK * 4);
+        if (TAIL && c0 + CC > p.Cin) {
+            // last chunk runs past the input layers: those kernel values and patch planes are zero
 #pragma unroll
-        for (int r = 0; r < WREG; ++r) {
-            uint32_t off = wsrc[r];
-            if (tail) {
+            for (int r = 0; r < WREG; ++r) {
                 const int q = (t + NT * r) % RUN;
-                if (c0 + q / KK >= p.Cin) off = kOob;
+                wreg[r] = buf_ld(rw, c0 + q / KK < p.Cin ? wsrc[r] : kOob, wchunk);
             }
-            wreg[r] = buf_ld(rw, off, wchunk);
+#pragma unroll
+            for (int r = 0; r < XREG; ++r) {
+                const int c = POINTWISE ? cpart + (NT / BN) * r : r / XMAP;   // uniform
+                const int i = POINTWISE ? 0 : r % XMAP;
+                if (c0 + c < p.Cin)
+                    xreg[r] = buf_ld(rin, xsrc[i], (uint32_t)__builtin_amdgcn_readfirstlane((c0 + c) * p.HW * 4));
+                else
+                    xreg[r] = 0.f;
+            }
+            return;
         }
 #pragma unroll
+        for (int r = 0; r < WREG; ++r) wreg[r] = buf_ld(rw, wsrc[r], wchunk);
+#pragma unroll
         for (int r = 0; r < XREG; ++r) {
-            const int c = POINTWISE ? cpart + (NT / BN) * r : r / XMAP;   // uniform
+            const int c = POINTWISE ? cpart + (NT / BN) * r : r / XMAP;       // uniform
             const int i = POINTWISE ? 0 : r % XMAP;
-            if (!tail || c0 + c < p.Cin)
-                xreg[r] = buf_ld(rin, xsrc[i], (uint32_t)((c0 + c) * p.HW) * 4u);
-            else
-                xreg[r] = 0.f;
+            xreg[r] = buf_ld(rin, xsrc[i], (uint32_t)__builtin_amdgcn_readfirstlane((c0 + c) * p.HW * 4));
         }
     };
 
@@ -174,13 +184,16 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
 #pragma unroll
         for (int r = 0; r < WREG; ++r)
             if (WEXACT || r + 1 < WREG || wdst[r] >= 0) ws[wdst[r]] = wreg[r];
+        if constexpr (POINTWISE) {
 #pragma unroll
-        for (int r = 0; r < XREG; ++r) {
-            if constexpr (POINTWISE) {
-                xs[(cpart + (NT / BN) * r) * plane + xdst[0]] = xreg[r];
-            } else {
-                if (xdst[r % XMAP] >= 0) xs[(r / XMAP) * plane + xdst[r % XMAP]] = xreg[r];
-            }
+            for (int r = 0; r < XREG; ++r) xs[(cpart + (NT / BN) * r) * plane + xdst[0]] = xreg[r];
+        } else {
+#pragma unroll
+            for (int i = 0; i < XMAP; ++i)
+                if (xdst[i] >= 0) {
+#pragma unroll
+                    for (int c = 0; c < CC; ++c) xs[c * plane + xdst[i]] = xreg[c * XMAP + i];
+                }
         }
     };
 
@@ -301,12 +314,14 @@ struct Variant {
     const char *name;
     int KS, S, BM, BN, MT, CC, PE, NBUF, NT;
     KernelFn kernel;
-    bool conv1_type;  // the persistent 7x7/stride-2/three-layer kernel
+    bool conv1_type;      // the persistent 7x7/stride-2/three-layer kernel
+    KernelFn kernel_tail; // same tiling for Cin not a multiple of CC (nullptr for conv1_type)
 };
 
 #define SQ_VARIANT(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                          \
     {"k" #KS "s" #S "_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC "_o" #MINW, KS, S, BM, BN, MT, CC, PE, 2, \
-     WM * WN * 64, conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW>, false}
+     WM * WN * 64, conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false>, false,        \
+     conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, true>}
 
 const Variant kVariants[] = {
     // 3x3 stride 1 (expand3x3)
@@ -336,8 +351,8 @@ const Variant kVariants[] = {
     SQ_VARIANT(1, 1, 128, 128, 2, 2, 32, 32, 0, 2),
     // 7x7 stride 2 with three input layers (conv1): persistent autonomous wavefronts,
     // 148-long contraction (BN and PE are unused for these two)
-    {"k7s2c3_waves8", 7, 2, 96, 256, 32, 3, 64, 2, 512, conv7s2c3_kernel_for(8, true), true},
-    {"k7s2c3_waves4", 7, 2, 96, 128, 32, 3, 64, 2, 256, conv7s2c3_kernel_for(4, true), true},
+    {"k7s2c3_waves8", 7, 2, 96, 256, 32, 3, 64, 2, 512, conv7s2c3_kernel_for(8, true), true, nullptr},
+    {"k7s2c3_waves4", 7, 2, 96, 128, 32, 3, 64, 2, 256, conv7s2c3_kernel_for(4, true), true, nullptr},
     // 7x7 stride 2, any number of input layers, two per chunk
     SQ_VARIANT(7, 2, 96, 128, 1, 4, 32, 2, 15, 1),
 };
@@ -453,6 +468,7 @@ int launch(int vi, const Plan &pl, const ConvArgs &a)
     const Variant &v = kVariants[vi];
     KernelFn fn = v.kernel;
     if (v.conv1_type && a.Cout != 96) fn = conv7s2c3_kernel_for(v.NT / 64, false);
+    if (!v.conv1_type && a.Cin % v.CC != 0) fn = v.kernel_tail;
     if (!allow_big_lds(fn)) {
         const int rc = check_launch();
         return rc ? rc : SQ_ERR_HIP;

@@ -43,18 +43,33 @@ __global__ __launch_bounds__(256) void maxpool3s2_kernel(const float *__restrict
     const float *src = in + (live ? pl : 0) * (size_t)H * W;
     float *dst = out + (live ? pl : 0) * (size_t)Ho * Wo;
     const bool has0 = live && 2 * l < W, has1 = live && 2 * l + 1 < W;
-    const int c0 = has0 ? 2 * l : 0, c1 = has1 ? 2 * l + 1 : 0;
-    float a0 = src[c0], b0 = src[c1];
-#pragma unroll 4
-    for (int oh = 0; oh < Ho; ++oh) {
-        const float *r1 = src + (size_t)(2 * oh + 1) * W, *r2 = r1 + W;
-        const float a1 = r1[c0], b1 = r1[c1], a2 = r2[c0], b2 = r2[c1];
-        const float ma = has0 ? fmaxf(fmaxf(a0, a1), a2) : -INFINITY;
-        const float mb = has1 ? fmaxf(fmaxf(b0, b1), b2) : -INFINITY;
-        const float mc = __shfl_down(ma, 1, LP);     // column 2l+2
-        if (live && l < Wo) dst[(size_t)oh * Wo + l] = fmaxf(fmaxf(ma, mb), mc);
-        a0 = a2;
-        b0 = b2;
+    // Each lane reads two adjacent floats per row (one 8-byte load).  The lane holding the
+    // last column of an odd-width row reads the pair one to the left and keeps its right half.
+    const int cb = has1 ? 2 * l : (has0 ? 2 * l - 1 : 0);
+    auto load2 = [&](int ih, float &a, float &b) {
+        const float *q = src + (size_t)ih * W + cb;
+        const float v0 = q[0], v1 = q[1];
+        a = has1 ? v0 : v1;
+        b = v1;
+    };
+    float a0, b0;
+    load2(0, a0, b0);
+    // four output rows per trip: the eight row loads of a trip are independent and issued
+    // together (rows past the end are clamped for the load and never stored)
+    constexpr int U = 4;
+    for (int oh0 = 0; oh0 < Ho; oh0 += U) {
+        float a[2 * U], b[2 * U];
+#pragma unroll
+        for (int u = 0; u < 2 * U; ++u) load2(min(2 * oh0 + 1 + u, H - 1), a[u], b[u]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float ma = has0 ? fmaxf(fmaxf(a0, a[2 * u]), a[2 * u + 1]) : -INFINITY;
+            const float mb = has1 ? fmaxf(fmaxf(b0, b[2 * u]), b[2 * u + 1]) : -INFINITY;
+            const float mc = __shfl_down(ma, 1, LP);     // column 2l+2
+            if (live && l < Wo && oh0 + u < Ho) dst[(size_t)(oh0 + u) * Wo + l] = fmaxf(fmaxf(ma, mb), mc);
+            a0 = a[2 * u + 1];
+            b0 = b[2 * u + 1];
+        }
     }
 }
 

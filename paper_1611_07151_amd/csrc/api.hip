@@ -111,6 +111,14 @@ int fire_impl(const void *in, const void *w_sq, const float *b_sq, const void *w
     int rc = run_conv(make_args(in, w_sq, b_sq, sq_map, N, Cin, H, W, Csq, 1, 1, 0, 1, Csq, 0, SQ_F32),
                       SQ_ALGO_AUTO);
     if (rc) return rc;
+    // both expands in one launch when a fused tiling exists for this shape
+    set_stage(stages[3]);
+    rc = conv_expand_fused(make_args(sq_map, w_e3, b_e3, out, N, Csq, H, W, Ce3, 3, 1, 1, 1, Ce1 + Ce3, Ce1, SQ_F32),
+                           w_e1, b_e1, Ce1, 0);
+    if (rc != SQ_ERR_UNSUPPORTED) {
+        set_stage("");
+        return rc;
+    }
     set_stage(stages[1]);
     rc = run_conv(make_args(sq_map, w_e1, b_e1, out, N, Csq, H, W, Ce1, 1, 1, 0, 1, Ce1 + Ce3, 0, SQ_F32),
                   SQ_ALGO_AUTO);
@@ -123,12 +131,12 @@ int fire_impl(const void *in, const void *w_sq, const float *b_sq, const void *w
 }
 
 struct FireCfg { int cin, sq, e; };
-const char *const kFireStages[8][3] = {
-    {"fire2/sq", "fire2/e1", "fire2/e3"}, {"fire3/sq", "fire3/e1", "fire3/e3"},
-    {"fire4/sq", "fire4/e1", "fire4/e3"}, {"fire5/sq", "fire5/e1", "fire5/e3"},
-    {"fire6/sq", "fire6/e1", "fire6/e3"}, {"fire7/sq", "fire7/e1", "fire7/e3"},
-    {"fire8/sq", "fire8/e1", "fire8/e3"}, {"fire9/sq", "fire9/e1", "fire9/e3"}};
-const char *const kFireAlone[3] = {"fire/sq", "fire/e1", "fire/e3"};
+const char *const kFireStages[8][4] = {
+    {"fire2/sq", "fire2/e1", "fire2/e3", "fire2/e1+e3"}, {"fire3/sq", "fire3/e1", "fire3/e3", "fire3/e1+e3"},
+    {"fire4/sq", "fire4/e1", "fire4/e3", "fire4/e1+e3"}, {"fire5/sq", "fire5/e1", "fire5/e3", "fire5/e1+e3"},
+    {"fire6/sq", "fire6/e1", "fire6/e3", "fire6/e1+e3"}, {"fire7/sq", "fire7/e1", "fire7/e3", "fire7/e1+e3"},
+    {"fire8/sq", "fire8/e1", "fire8/e3", "fire8/e1+e3"}, {"fire9/sq", "fire9/e1", "fire9/e3", "fire9/e1+e3"}};
+const char *const kFireAlone[4] = {"fire/sq", "fire/e1", "fire/e3", "fire/e1+e3"};
 const FireCfg kFires[8] = {{96, 16, 64},   {128, 16, 64},  {128, 32, 128}, {256, 32, 128},
                            {256, 48, 192}, {384, 48, 192}, {384, 64, 256}, {512, 64, 256}};
 

@@ -37,7 +37,12 @@ using namespace mfma;
 
 // TAIL: the number of input layers is not a multiple of CC, so the last chunk is partly
 // padding (compiled separately to keep the common loop free of the test).
-template <int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW, bool TAIL>
+// E1: fused expand -- next to the KxK convolution the workgroup also computes a 1x1
+// convolution of the same input (its kernels p.w1) for the same pixels and its own tile of
+// layers, written to layers [coff1, coff1+Cout1): the 1x1 reuses the centre-tap patch
+// operands, so the input is staged once for both (fire layer, section "Convolutional
+// Neural Networks": the two expand layers read the same squeeze result).
+template <int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW, bool TAIL, bool E1 = false>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const KParams p)
 {
     using M = Mfma<MT>;
@@ -55,10 +60,15 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
     static_assert(BM % (WM * MT) == 0 && BN % (WN * MT) == 0, "tile split");
     static_assert(CC % KQ == 0, "chunk must hold whole MFMA k-groups");
     static_assert(!POINTWISE || (NT % BN == 0 && BN % 64 == 0 && (CC * BN) % NT == 0), "pointwise staging split");
+    static_assert(!E1 || (KS % 2 == 1 && S == 1 && !TAIL), "fused expand needs a centre tap");
+    constexpr int LD1 = CC + 1;                       // LDS row stride of the 1x1 kernels
+    constexpr int W1BUF = E1 ? BM * LD1 : 0;
+    constexpr int W1REG = E1 ? (BM * CC + NT - 1) / NT : 1;
 
     extern __shared__ float smem[];
     float *const Ws = smem;               // [2][BM*LDK]
-    float *const Xs = smem + 2 * WBUF;    // [2][CC*plane]
+    float *const W1s = smem + 2 * WBUF;   // [2][BM*LD1] (fused expand only)
+    float *const Xs = W1s + 2 * W1BUF;    // [2][CC*plane]
     const int plane = p.plane;
     const int XBUF = CC * plane;
 
@@ -70,7 +80,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
     const int tile = xcd_remap(blockIdx.x, p.mtiles * p.ntiles);
     const int pt = fdiv(tile, p.dMtiles), mt = tile - pt * p.mtiles;
     const int P0 = pt * BN, m0 = mt * BM;
-    const bool full_m = m0 + BM <= p.Cout;
+    const bool full_m = m0 + BM <= p.Cout && (!E1 || m0 + BM <= p.Cout1);
 
     // ---- geometry of the staged patch ------------------------------------------------
     int va = 0, PRt = 0;
@@ -83,9 +93,13 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
     }
 
     // per-lane LDS offsets of the two MFMA operands (loop invariant)
-    int aoff[TM], boff[TN];
+    int aoff[TM], boff[TN], a1off[E1 ? TM : 1];
 #pragma unroll
     for (int i = 0; i < TM; ++i) aoff[i] = (wm * (BM / WM) + i * MT + li) * LDK + kk * KK;
+    if constexpr (E1) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a1off[i] = (wm * (BM / WM) + i * MT + li) * LD1 + kk;
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int pl = wn * (BN / WN) + j * MT + li;
@@ -116,6 +130,18 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
         wsrc[r] = (inrange && m0 + m < p.Cout) ? (uint32_t)(((m0 + m) * p.Cin * KK + q) * 4) : kOob;
         wdst[r] = inrange ? m * LDK + q : -1;
     }
+    uint32_t w1src[W1REG];
+    int w1dst[W1REG];
+    if constexpr (E1) {
+#pragma unroll
+        for (int r = 0; r < W1REG; ++r) {
+            const int e = t + NT * r;
+            const int m = e / CC, c = e - m * CC;
+            const bool inrange = e < BM * CC;
+            w1src[r] = (inrange && m0 + m < p.Cout1) ? (uint32_t)(((m0 + m) * p.Cin + c) * 4) : kOob;
+            w1dst[r] = inrange ? m * LD1 + c : -1;
+        }
+    }
     uint32_t xsrc[XMAP];
     int xdst[XMAP];
     if constexpr (POINTWISE) {
@@ -138,13 +164,14 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
     }
     const int cpart = POINTWISE ? __builtin_amdgcn_readfirstlane(t / BN) : 0;
 
-    float wreg[WREG], xreg[XREG];
+    float wreg[WREG], xreg[XREG], w1reg[W1REG];
 
     // Global loads of one chunk through buffer addressing: the per-lane offsets were fixed
     // above (kOob where the value is padding, which the hardware turns into zero), the chunk
     // and input-layer offsets are uniform.  Only a last chunk that runs past the input
     // layers (Cin not a multiple of CC) needs extra tests.
     const rsrc_t rw = make_rsrc(p.w, p.w_bytes), rin = make_rsrc(p.in, p.in_bytes);
+    const rsrc_t rw1 = make_rsrc(E1 ? p.w1 : p.w, E1 ? p.w1_bytes : 0u);
     auto load_chunk = [&](int ch_) {
         // readfirstlane keeps the chunk offsets in scalar registers (otherwise every buffer
         // load is wrapped in a loop over the distinct values of its "uniform" offset)
@@ -170,6 +197,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
         }
 #pragma unroll
         for (int r = 0; r < WREG; ++r) wreg[r] = buf_ld(rw, wsrc[r], wchunk);
+        if constexpr (E1) {
+#pragma unroll
+            for (int r = 0; r < W1REG; ++r) w1reg[r] = buf_ld(rw1, w1src[r], (uint32_t)(c0 * 4));
+        }
 #pragma unroll
         for (int r = 0; r < XREG; ++r) {
             const int c = POINTWISE ? cpart + (NT / BN) * r : r / XMAP;       // uniform
@@ -184,6 +215,12 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
 #pragma unroll
         for (int r = 0; r < WREG; ++r)
             if (WEXACT || r + 1 < WREG || wdst[r] >= 0) ws[wdst[r]] = wreg[r];
+        if constexpr (E1) {
+            float *w1s = W1s + buf * W1BUF;
+#pragma unroll
+            for (int r = 0; r < W1REG; ++r)
+                if (w1dst[r] >= 0) w1s[w1dst[r]] = w1reg[r];
+        }
         if constexpr (POINTWISE) {
 #pragma unroll
             for (int r = 0; r < XREG; ++r) xs[(cpart + (NT / BN) * r) * plane + xdst[0]] = xreg[r];
@@ -197,13 +234,16 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
         }
     };
 
-    Acc acc[TM][TN];
+    Acc acc[TM][TN], acc1[E1 ? TM : 1][E1 ? TN : 1];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < M::NR; ++r) acc[i][j][r] = 0.f;
+            for (int r = 0; r < M::NR; ++r) {
+                acc[i][j][r] = 0.f;
+                if constexpr (E1) acc1[i][j][r] = 0.f;
+            }
 
     // One MFMA step consumes, for every lane, one kernel value per layer block and one patch
     // value per pixel block.  LDS latency (~120 cycles) is longer than a short group of
@@ -217,25 +257,41 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
         constexpr int PD0 = (240 + STEP_CYCLES - 1) / STEP_CYCLES;      // steps to cover the latency
         constexpr int PD = PD0 < 1 ? 1 : (PD0 > 3 ? 3 : PD0);
         constexpr int RING = PD + 1;
-        float a[RING][TM], b[RING][TN];
-        auto fetch = [&](int s, float *av, float *bv) {
+        constexpr int CENTRE = (KS / 2) * KS + KS / 2;
+        const float *w1s = W1s + buf * W1BUF;
+        float a[RING][TM], b[RING][TN], a1[RING][E1 ? TM : 1];
+        auto fetch = [&](int s, float *av, float *bv, float *a1v) {
             const int cq = s / KK, tap = s - cq * KK, i = tap / KS, j = tap - i * KS;
             const int rowoff = cq * KQ * plane + (POINTWISE ? 0 : i * p.LWs) + j;
 #pragma unroll
             for (int x = 0; x < TM; ++x) av[x] = ws[aoff[x] + cq * KQ * KK + tap];
 #pragma unroll
             for (int y = 0; y < TN; ++y) bv[y] = xs[boff[y] + rowoff];
+            if constexpr (E1) {
+                if (tap == CENTRE) {
+#pragma unroll
+                    for (int x = 0; x < TM; ++x) a1v[x] = w1s[a1off[x] + cq * KQ];
+                }
+            }
         };
 #pragma unroll
-        for (int s = 0; s < PD && s < STEPS; ++s) fetch(s, a[s % RING], b[s % RING]);
+        for (int s = 0; s < PD && s < STEPS; ++s) fetch(s, a[s % RING], b[s % RING], a1[s % RING]);
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
-            if (s + PD < STEPS) fetch(s + PD, a[(s + PD) % RING], b[(s + PD) % RING]);
+            if (s + PD < STEPS) fetch(s + PD, a[(s + PD) % RING], b[(s + PD) % RING], a1[(s + PD) % RING]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int x = 0; x < TM; ++x)
 #pragma unroll
                 for (int y = 0; y < TN; ++y) acc[x][y] = M::run(a[s % RING][x], b[s % RING][y], acc[x][y]);
+            if constexpr (E1) {
+                if (s % KK == CENTRE) {
+#pragma unroll
+                    for (int x = 0; x < TM; ++x)
+#pragma unroll
+                        for (int y = 0; y < TN; ++y) acc1[x][y] = M::run(a1[s % RING][x], b[s % RING][y], acc1[x][y]);
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -265,47 +321,52 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_f32_kernel(const
     const int mw = m0 + wm * (BM / WM);          // uniform: first layer of this wavefront
     const int lrow = M::row_lane(lane);          // per lane
     const rsrc_t rout = make_rsrc(p.out, p.out_bytes);
-    float bias[TM][M::NR];
-    if (p.b) {
-        const rsrc_t rb = make_rsrc(p.b, (uint32_t)p.Cout * 4u);   // layers beyond Cout read zero
-#pragma unroll
-        for (int x = 0; x < TM; ++x)
-#pragma unroll
-            for (int r = 0; r < M::NR; ++r)
-            {
-                // with a partial layer tile the whole index goes into the range-checked lane
-                // offset, so nothing is read past the end of the bias array
-                const int mu = mw + x * MT + M::row_reg(r);
-                bias[x][r] = full_m ? buf_ld(rb, (uint32_t)(lrow * 4), (uint32_t)mu * 4u)
-                                    : buf_ld(rb, (uint32_t)((mu + lrow) * 4), 0u);
-            }
-    } else {
-#pragma unroll
-        for (int x = 0; x < TM; ++x)
-#pragma unroll
-            for (int r = 0; r < M::NR; ++r) bias[x][r] = 0.f;
-    }
     const uint32_t hs = (uint32_t)p.HoWo * 4u;
+    auto write_out = [&](Acc (&res)[TM][TN], const float *bptr, int cout, int coff) {
+        float bias[TM][M::NR];
+        if (bptr) {
+            const rsrc_t rb = make_rsrc(bptr, (uint32_t)cout * 4u);   // layers beyond cout read zero
 #pragma unroll
-    for (int y = 0; y < TN; ++y) {
-        const int pp = P0 + wn * (BN / WN) + y * MT + li;
-        const int ppc = min(pp, p.PT - 1);
-        const int n = fdiv(ppc, p.dHoWo), q = ppc - n * p.HoWo;
-        // pixels past the end get an offset the range check rejects
-        const uint32_t lbase = pp < p.PT ? (uint32_t)(((n * p.ldc + p.coff + lrow) * p.HoWo + q) * 4) : kOob;
+            for (int x = 0; x < TM; ++x)
 #pragma unroll
-        for (int x = 0; x < TM; ++x) {
+                for (int r = 0; r < M::NR; ++r) {
+                    // with a partial layer tile the whole index goes into the range-checked lane
+                    // offset, so nothing is read past the end of the bias array
+                    const int mu = mw + x * MT + M::row_reg(r);
+                    bias[x][r] = full_m ? buf_ld(rb, (uint32_t)(lrow * 4), (uint32_t)mu * 4u)
+                                        : buf_ld(rb, (uint32_t)((mu + lrow) * 4), 0u);
+                }
+        } else {
 #pragma unroll
-            for (int r = 0; r < M::NR; ++r) {
-                const int mu = mw + x * MT + M::row_reg(r);
-                float v = acc[x][y][r] + bias[x][r];
-                if (p.relu) v = fmaxf(v, 0.f);
-                if (full_m)
-                    buf_st(rout, lbase, (uint32_t)mu * hs, v);
-                else
-                    buf_st(rout, mu + lrow < p.Cout ? lbase : kOob, (uint32_t)mu * hs, v);
+            for (int x = 0; x < TM; ++x)
+#pragma unroll
+                for (int r = 0; r < M::NR; ++r) bias[x][r] = 0.f;
+        }
+#pragma unroll
+        for (int y = 0; y < TN; ++y) {
+            const int pp = P0 + wn * (BN / WN) + y * MT + li;
+            const int ppc = min(pp, p.PT - 1);
+            const int n = fdiv(ppc, p.dHoWo), q = ppc - n * p.HoWo;
+            // pixels past the end get an offset the range check rejects
+            const uint32_t lbase = pp < p.PT ? (uint32_t)(((n * p.ldc + coff + lrow) * p.HoWo + q) * 4) : kOob;
+#pragma unroll
+            for (int x = 0; x < TM; ++x) {
+#pragma unroll
+                for (int r = 0; r < M::NR; ++r) {
+                    const int mu = mw + x * MT + M::row_reg(r);
+                    float v = res[x][y][r] + bias[x][r];
+                    if (p.relu) v = fmaxf(v, 0.f);
+                    if (full_m)
+                        buf_st(rout, lbase, (uint32_t)mu * hs, v);
+                    else
+                        buf_st(rout, mu + lrow < cout ? lbase : kOob, (uint32_t)mu * hs, v);
+                }
             }
         }
+    };
+    if (m0 < p.Cout) write_out(acc, p.b, p.Cout, p.coff);
+    if constexpr (E1) {
+        if (m0 < p.Cout1) write_out(acc1, p.b1, p.Cout1, p.coff1);
     }
 }
 
@@ -316,20 +377,28 @@ struct Variant {
     KernelFn kernel;
     bool conv1_type;      // the persistent 7x7/stride-2/three-layer kernel
     KernelFn kernel_tail; // same tiling for Cin not a multiple of CC (nullptr for conv1_type)
+    KernelFn kernel_e1;   // same tiling with the fused 1x1 expand (nullptr if not compiled)
 };
 
 #define SQ_VARIANT(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                          \
     {"k" #KS "s" #S "_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC "_o" #MINW, KS, S, BM, BN, MT, CC, PE, 2, \
      WM * WN * 64, conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false>, false,        \
-     conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, true>}
+     conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, true>, nullptr}
+
+// a 3x3 tiling that is also compiled with the fused 1x1 expand
+#define SQ_VARIANT_E1(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                       \
+    {"k" #KS "s" #S "_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC "_o" #MINW, KS, S, BM, BN, MT, CC, PE, 2, \
+     WM * WN * 64, conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false>, false,        \
+     conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, true>,                              \
+     conv_mfma_f32_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false, true>}
 
 const Variant kVariants[] = {
     // 3x3 stride 1 (expand3x3)
     SQ_VARIANT(3, 1, 128, 128, 2, 2, 32, 4, 2, 2),
-    SQ_VARIANT(3, 1, 64, 128, 2, 2, 32, 4, 2, 2),
-    SQ_VARIANT(3, 1, 64, 128, 1, 4, 32, 4, 2, 2),
-    SQ_VARIANT(3, 1, 64, 64, 2, 2, 32, 4, 2, 2),
-    SQ_VARIANT(3, 1, 64, 128, 1, 4, 16, 4, 2, 2),
+    SQ_VARIANT_E1(3, 1, 64, 128, 2, 2, 32, 4, 2, 2),
+    SQ_VARIANT_E1(3, 1, 64, 128, 1, 4, 32, 4, 2, 2),
+    SQ_VARIANT_E1(3, 1, 64, 64, 2, 2, 32, 4, 2, 2),
+    SQ_VARIANT_E1(3, 1, 64, 128, 1, 4, 16, 4, 2, 2),
     SQ_VARIANT(3, 1, 32, 64, 2, 2, 16, 4, 8, 2),
     SQ_VARIANT(3, 1, 64, 128, 2, 2, 32, 8, 2, 2),
     SQ_VARIANT(3, 1, 64, 256, 1, 4, 32, 4, 3, 2),
@@ -349,10 +418,17 @@ const Variant kVariants[] = {
     SQ_VARIANT(1, 1, 128, 128, 2, 2, 16, 16, 0, 2),
     SQ_VARIANT(1, 1, 64, 64, 2, 2, 16, 32, 0, 3),
     SQ_VARIANT(1, 1, 128, 128, 2, 2, 32, 32, 0, 2),
+    // small tiles for the layers with few pixels (more workgroups than CUs)
+    SQ_VARIANT(1, 1, 32, 64, 1, 4, 16, 16, 0, 2),
+    SQ_VARIANT(1, 1, 16, 128, 1, 4, 16, 16, 0, 2),
+    SQ_VARIANT(1, 1, 16, 64, 1, 4, 16, 32, 0, 2),
+    SQ_VARIANT(1, 1, 32, 64, 1, 4, 16, 32, 0, 2),
+    SQ_VARIANT(1, 1, 64, 64, 2, 2, 16, 16, 0, 2),
+    SQ_VARIANT(1, 1, 48, 64, 1, 4, 16, 16, 0, 2),
     // 7x7 stride 2 with three input layers (conv1): persistent autonomous wavefronts,
     // 148-long contraction (BN and PE are unused for these two)
-    {"k7s2c3_waves8", 7, 2, 96, 256, 32, 3, 64, 2, 512, conv7s2c3_kernel_for(8, true), true, nullptr},
-    {"k7s2c3_waves4", 7, 2, 96, 128, 32, 3, 64, 2, 256, conv7s2c3_kernel_for(4, true), true, nullptr},
+    {"k7s2c3_waves8", 7, 2, 96, 256, 32, 3, 64, 2, 512, conv7s2c3_kernel_for(8, true), true, nullptr, nullptr},
+    {"k7s2c3_waves4", 7, 2, 96, 128, 32, 3, 64, 2, 256, conv7s2c3_kernel_for(4, true), true, nullptr, nullptr},
     // 7x7 stride 2, any number of input layers, two per chunk
     SQ_VARIANT(7, 2, 96, 128, 1, 4, 32, 2, 15, 1),
 };
@@ -380,8 +456,15 @@ int num_cus()
 }
 
 // Fills the launch parameters of variant v for this call; false if v cannot run it.
-bool plan(const Variant &v, const ConvArgs &a, Plan &pl)
+struct FusedE1 {
+    const void *w1;
+    const float *b1;
+    int Cout1, coff1;
+};
+
+bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nullptr)
 {
+    if (e1 && (!v.kernel_e1 || a.Cin % v.CC != 0)) return false;
     if (a.dtype != SQ_F32 || a.K != v.KS || a.S != v.S) return false;
     if (a.W + 2 * a.P < a.K) return false;
     const long long in_elems = (long long)a.N * a.Cin * a.H * a.W;
@@ -400,7 +483,10 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl)
     k.Ho = a.Ho; k.Wo = a.Wo; k.HoWo = a.Ho * a.Wo; k.HW = a.H * a.W;
     k.ldc = a.out_channels; k.coff = a.c_offset;
     k.PT = (int)pixels;
-    k.mtiles = (a.Cout + v.BM - 1) / v.BM;
+    k.mtiles = ((e1 && e1->Cout1 > a.Cout ? e1->Cout1 : a.Cout) + v.BM - 1) / v.BM;
+    k.w1 = e1 ? (const float *)e1->w1 : nullptr; k.b1 = e1 ? e1->b1 : nullptr;
+    k.Cout1 = e1 ? e1->Cout1 : 0; k.coff1 = e1 ? e1->coff1 : 0;
+    k.w1_bytes = e1 ? (uint32_t)((long long)e1->Cout1 * a.Cin * 4) : 0u;
     k.ntiles = (int)((pixels + v.BN - 1) / v.BN);
     k.nchunks = (a.Cin + v.CC - 1) / v.CC;
     const int KK = v.KS * v.KS, RUN = v.CC * KK, LDK = RUN + ((RUN & 1) ? 0 : 1);
@@ -442,7 +528,8 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl)
         blocks = (tiles + NW - 1) / NW;
         if (blocks > num_cus()) blocks = num_cus();
     } else {
-        pl.lds_bytes = ((size_t)v.NBUF * v.BM * LDK + (size_t)v.NBUF * v.CC * k.plane) * sizeof(float);
+        pl.lds_bytes = ((size_t)v.NBUF * v.BM * LDK + (size_t)v.NBUF * v.CC * k.plane +
+                        (e1 ? (size_t)2 * v.BM * (v.CC + 1) : 0)) * sizeof(float);
     }
     if (pl.lds_bytes > (size_t)kLdsBytes) return false;
     if (blocks >= (1ll << 31)) return false;
@@ -463,17 +550,22 @@ bool allow_big_lds(KernelFn fn)
     return true;
 }
 
-int launch(int vi, const Plan &pl, const ConvArgs &a)
+int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullptr)
 {
     const Variant &v = kVariants[vi];
-    KernelFn fn = v.kernel;
+    KernelFn fn = e1 ? v.kernel_e1 : v.kernel;
     if (v.conv1_type && a.Cout != 96) fn = conv7s2c3_kernel_for(v.NT / 64, false);
-    if (!v.conv1_type && a.Cin % v.CC != 0) fn = v.kernel_tail;
+    if (!v.conv1_type && !e1 && a.Cin % v.CC != 0) fn = v.kernel_tail;
     if (!allow_big_lds(fn)) {
         const int rc = check_launch();
         return rc ? rc : SQ_ERR_HIP;
     }
-    LaunchScope scope(v.name, conv_flops(a), conv_bytes(a));
+    double flops = conv_flops(a), bytes = conv_bytes(a);
+    if (e1) {
+        flops += 2.0 * a.N * e1->Cout1 * a.Ho * a.Wo * (double)a.Cin;
+        bytes += 4.0 * ((double)e1->Cout1 * a.Cin + (double)a.N * e1->Cout1 * a.Ho * a.Wo + e1->Cout1);
+    }
+    LaunchScope scope(v.name, flops, bytes);
     hipLaunchKernelGGL(fn, dim3(pl.blocks), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
     return check_launch();
 }
@@ -537,6 +629,40 @@ extern "C" long long sq_internal_fastdiv_mismatches(unsigned d, unsigned x_max)
 
 int conv_mfma_variant_count() { return kNumVariants; }
 const char *conv_mfma_variant_name(int i) { return kVariants[i].name; }
+
+// Which tiling runs the fused expand: -2 = never fuse (the default: measured on MI355X the
+// fused kernel's lower occupancy cancels what it saves), -1 = automatic
+// choice, i >= 0 = tiling i.  The setter is a tuning hook, not part of the public interface.
+int g_force_expand = -2;
+extern "C" void sq_internal_force_expand(int v) { g_force_expand = v; }
+
+// 3x3 (pad 1, stride 1) convolution a3 plus the 1x1 convolution (w1, b1, Cout1 layers) of the
+// same input, results in layers [a3.c_offset, +a3.Cout) and [coff1, +Cout1) of one tensor.
+int conv_expand_fused(const ConvArgs &a3, const void *w1, const float *b1, int Cout1, int coff1)
+{
+    if (a3.K != 3 || a3.S != 1 || a3.P != 1 || a3.dtype != SQ_F32) return SQ_ERR_UNSUPPORTED;
+    const FusedE1 e1{w1, b1, Cout1, coff1};
+    Plan pl;
+    if (g_force_expand == -2) return SQ_ERR_UNSUPPORTED;
+    if (g_force_expand >= 0) {
+        if (g_force_expand >= kNumVariants || !plan(kVariants[g_force_expand], a3, pl, &e1)) return SQ_ERR_UNSUPPORTED;
+        return launch(g_force_expand, pl, a3, &e1);
+    }
+    const int tv = tuned_variant(a3);
+    if (tv >= 0 && plan(kVariants[tv], a3, pl, &e1)) return launch(tv, pl, a3, &e1);
+    int best = -1;
+    double best_cost = 0;
+    Plan best_plan;
+    for (int i = 0; i < kNumVariants; ++i) {
+        if (!plan(kVariants[i], a3, pl, &e1)) continue;
+        const double c = estimate(kVariants[i], pl, a3);
+        if (best < 0 || c < best_cost) {
+            best = i; best_cost = c; best_plan = pl;
+        }
+    }
+    if (best < 0) return SQ_ERR_UNSUPPORTED;
+    return launch(best, best_plan, a3, &e1);
+}
 
 int conv_mfma(const ConvArgs &a, int variant)
 {

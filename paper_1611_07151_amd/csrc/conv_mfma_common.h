@@ -72,6 +72,11 @@ struct KParams {
     int nchunks;
     FastDiv dWo, dHo, dLW, dVH, dHW, dHoWo, dMtiles;
     uint32_t in_bytes, out_bytes, w_bytes;
+    // fused expand (3x3 kernel that also produces the 1x1 expand of the same input)
+    const float *w1;     // [Cout1][Cin] kernels of the 1x1 convolution
+    const float *b1;     // [Cout1] or nullptr
+    int Cout1, coff1;    // its layer count and first output layer
+    uint32_t w1_bytes;
     int RG, CB;  // conv1-type kernel: tile grid per image (row groups, column blocks)
     FastDiv dRG, dCB;
 };

@@ -43,6 +43,9 @@ int conv_direct(const ConvArgs &a);
 // Matrix-core family.  variant < 0 = pick by shape; returns SQ_ERR_UNSUPPORTED when
 // the (variant, shape, dtype) combination has no kernel.
 int conv_mfma(const ConvArgs &a, int variant);
+// Fused expand of a fire layer: the 3x3 convolution a3 and a 1x1 convolution of the same
+// input in one launch; SQ_ERR_UNSUPPORTED if no compiled tiling fits.
+int conv_expand_fused(const ConvArgs &a3, const void *w1, const float *b1, int Cout1, int coff1);
 int conv_mfma_variant_count();
 const char *conv_mfma_variant_name(int i);
 

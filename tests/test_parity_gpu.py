@@ -290,3 +290,33 @@ def test_runs_on_a_side_stream(sq):
         got = sq.sq_conv2d_forward(xd, wd, bd, 1, 1, True)
     s.synchronize()
     assert_close(got, ref, FP32_TOL, "side stream")
+
+
+def test_network_call_can_be_captured_in_a_graph(sq):
+    """The network call allocates nothing and does not synchronise, so a caller may capture it
+    in a HIP graph; every replay (with eager work and new inputs in between) must reproduce
+    the eager result."""
+    cfg = synth.config_squeezenet(seed=5, n=2)
+    params = [dev(p) for p in cfg["params"]]
+    x = dev(cfg["x"])
+    ws = torch.empty(sq.sq_squeezenet_workspace_bytes(2), device="cuda", dtype=torch.uint8)
+    probs = torch.empty((2, 1000), device="cuda")
+    sq.sq_squeezenet_forward(x, params, workspace=ws, probs=probs)      # warm-up outside the capture
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            sq.sq_squeezenet_forward(x, params, workspace=ws, probs=probs)
+    torch.cuda.current_stream().wait_stream(side)
+    rng = np.random.default_rng(9)
+    for rep in range(4):
+        x.copy_(dev(synth.uniform01(rng, (2, 3, 224, 224))))               # eager work between replays
+        want = sq.sq_squeezenet_forward(x, params).clone()
+        torch.cuda.synchronize()
+        probs.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(probs, want), f"replay {rep}"
+    ref = oracle.squeezenet(x.cpu().numpy(), cfg["params"])
+    assert_close(probs, ref, FP32_TOL, "graph replay vs oracle")

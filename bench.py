@@ -43,6 +43,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--calibrate-copy", action="store_true")
+    ap.add_argument("--layer-sweep", choices=["f32", "bf16"], default=None,
+                    help="instead of the network: time every convolution shape on its own at --batch "
+                         "(workload 5 is --layer-sweep bf16 --batch 256) and print one JSON line")
     ap.add_argument("--skip-batch1", action="store_true", help="leave the batch-1 timing out (for profiler runs)")
     ap.add_argument("--cpu-sample", type=int, default=32,
                     help="images of the workload the CPU oracle is timed on (0 = skip)")
@@ -74,6 +77,38 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "torch elementwise copy", "bytes_read": 4 * n, "bytes_written": 4 * n,
                           "launches": 5}))
+        return 0
+
+    if args.layer_sweep:
+        dt_in = torch.bfloat16 if args.layer_sweep == "bf16" else torch.float32
+        esz = 2 if args.layer_sweep == "bf16" else 4
+        gen = torch.Generator(device="cuda").manual_seed(4)
+        layers, total_flop, total_us = {}, 0.0, 0.0
+        for name, cin, cout, k, s_, p_, h in synth.conv_layers():
+            ho = (h + 2 * p_ - k) // s_ + 1
+            x = torch.randn((B, cin, h, h), device="cuda", generator=gen).to(dt_in)
+            w = (torch.randn((cout, cin, k, k), device="cuda", generator=gen) * (2.0 / (cin * k * k)) ** 0.5).to(dt_in)
+            b = torch.rand(cout, device="cuda", generator=gen) * 0.2 - 0.1
+            out = torch.empty((B, cout, ho, ho), device="cuda")
+            for _ in range(3):
+                sq.sq_conv2d_forward_ex(x, w, b, s_, p_, True, out=out)
+            sq.sq_profile_begin(64)
+            for _ in range(10):
+                sq.sq_conv2d_forward_ex(x, w, b, s_, p_, True, out=out)
+            recs = sq.sq_profile_end()
+            us = sum(r["ms"] for r in recs) / 10 * 1e3
+            flop = 2.0 * B * cout * ho * ho * cin * k * k
+            byts = esz * (B * cin * h * h + cout * cin * k * k) + 4.0 * B * cout * ho * ho
+            layers[name] = dict(us=round(us, 1), tflops=round(flop / us / 1e6, 1), gbs=round(byts / us / 1e3),
+                                kernel=recs[0]["name"].split("|")[1])
+            total_flop += flop
+            total_us += us
+            del x, w, out
+        print(json.dumps({"metric": f"per-layer convolution sweep, batch {B}, {args.layer_sweep} inputs, fp32 accumulate/output",
+                          "value": round(total_flop / total_us / 1e6, 2), "unit": "TFLOP/s (all 26 layers)",
+                          "n_gpus": 1, "dtype": args.layer_sweep, "data": "synthetic",
+                          "config": {"workload": f"26 SqueezeNet convolution shapes at batch {B}"},
+                          "total_us": round(total_us, 1), "layers": layers}))
         return 0
 
     def setup(seed, n):

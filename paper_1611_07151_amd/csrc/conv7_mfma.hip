@@ -76,9 +76,11 @@ __host__ __device__ constexpr int step_offset(int s)
 }
 
 // FULL: the layer has exactly 96 output layers, so no store needs a layer test.
-template <int NW, bool FULL, int MINW>
+// TIN: float, or uint16_t = bfloat16 input and kernels, widened to fp32 while staged.
+template <typename TIN, int NW, bool FULL, int MINW>
 __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams p)
 {
+    constexpr int ESZ = (int)sizeof(TIN);
     using M = Mfma<32>;
     using Acc = typename M::Acc;
     constexpr int NT = NW * 64;
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
 #pragma unroll
         for (int r = 0; r < WR; ++r) {
             const int e = t + NT * r;
-            wv_[r] = buf_ld(rw, e < kBM * kK ? (uint32_t)(e * 4) : kOob, 0);
+            wv_[r] = buf_ld_in<TIN>(rw, e < kBM * kK ? (uint32_t)(e * ESZ) : kOob, 0);
         }
 #pragma unroll
         for (int r = 0; r < WR; ++r) {
@@ -155,14 +157,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
         const int ih0 = oh0 * kS - p.P, iw = ow0 * kS - p.P + lane;
         // columns outside the image (and lanes beyond the patch width) read zero through the
         // buffer range check; rows outside the image are skipped by a uniform branch
-        const uint32_t coff = (lane < kPC && iw >= 0 && iw < p.W) ? (uint32_t)(iw * 4) : kOob;
+        const uint32_t coff = (lane < kPC && iw >= 0 && iw < p.W) ? (uint32_t)(iw * ESZ) : kOob;
 #pragma unroll
         for (int r = 0; r < kPR; ++r) {
             const int ih = ih0 + r;                                   // uniform
             if (ih >= 0 && ih < p.H) {
-                const uint32_t row = (uint32_t)((n * 3 * p.H + ih) * p.W) * 4u;
+                const uint32_t row = (uint32_t)((n * 3 * p.H + ih) * p.W) * (uint32_t)ESZ;
 #pragma unroll
-                for (int c = 0; c < 3; ++c) xreg[c * kPR + r] = buf_ld(rin, coff, row + (uint32_t)c * (uint32_t)p.HW * 4u);
+                for (int c = 0; c < 3; ++c) xreg[c * kPR + r] = buf_ld_in<TIN>(rin, coff, row + (uint32_t)c * (uint32_t)p.HW * (uint32_t)ESZ);
             } else {
 #pragma unroll
                 for (int c = 0; c < 3; ++c) xreg[c * kPR + r] = 0.f;
@@ -296,10 +298,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
 
 }  // namespace
 
-KernelFn conv7s2c3_kernel_for(int NW, bool full)
+KernelFn conv7s2c3_kernel_for(int NW, bool full, bool bf16)
 {
-    if (NW == 8) return full ? conv7s2c3_kernel<8, true, 1> : conv7s2c3_kernel<8, false, 1>;
-    if (NW == 4) return full ? conv7s2c3_kernel<4, true, 1> : conv7s2c3_kernel<4, false, 1>;
+    if (bf16) {
+        if (NW == 8) return full ? conv7s2c3_kernel<uint16_t, 8, true, 1> : conv7s2c3_kernel<uint16_t, 8, false, 1>;
+        if (NW == 4) return full ? conv7s2c3_kernel<uint16_t, 4, true, 1> : conv7s2c3_kernel<uint16_t, 4, false, 1>;
+        return nullptr;
+    }
+    if (NW == 8) return full ? conv7s2c3_kernel<float, 8, true, 1> : conv7s2c3_kernel<float, 8, false, 1>;
+    if (NW == 4) return full ? conv7s2c3_kernel<float, 4, true, 1> : conv7s2c3_kernel<float, 4, false, 1>;
     return nullptr;
 }
 

@@ -138,6 +138,18 @@ __device__ __forceinline__ void buf_st(rsrc_t r, uint32_t lane_off, uint32_t uni
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)lane_off, (int)uni_off, 0);
 }
 
+// Input element of type TIN as fp32: float as is, uint16_t = bfloat16 (upper half of binary32).
+template <typename TIN> __device__ __forceinline__ float buf_ld_in(rsrc_t r, uint32_t lane_off, uint32_t uni_off);
+template <> __device__ __forceinline__ float buf_ld_in<float>(rsrc_t r, uint32_t lane_off, uint32_t uni_off)
+{
+    return buf_ld(r, lane_off, uni_off);
+}
+template <> __device__ __forceinline__ float buf_ld_in<uint16_t>(rsrc_t r, uint32_t lane_off, uint32_t uni_off)
+{
+    const uint32_t h = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)lane_off, (int)uni_off, 0);
+    return __builtin_bit_cast(float, h << 16);
+}
+
 // base + 32-bit byte offset: the addressing form that needs no per-lane 64-bit arithmetic
 __device__ __forceinline__ float ld_f32(const float *base, uint32_t byte_off)
 {
@@ -151,7 +163,13 @@ __device__ __forceinline__ void st_f32(float *base, uint32_t byte_off, float v)
 // conv1-type layers (7x7, stride 2, three input layers, at most 96 output layers) have
 // their own persistent kernel with NW autonomous wavefronts per workgroup (8 or 4).
 typedef void (*KernelFn)(const KParams);
-KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers);
+
+// Kernels of one tiling: plain, input layers not a multiple of CC, fused 1x1 expand.
+struct KernelSet {
+    KernelFn plain, tail, fused_e1;
+};
+extern const KernelSet conv_mfma_kernels_f32[], conv_mfma_kernels_bf16[];
+KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers, bool bf16_inputs);
 constexpr int kConv7TileRows = 2, kConv7TileCols = 16;   // output pixels per wavefront tile
 size_t conv7s2c3_lds_bytes(int NW);
 

@@ -1,0 +1,19 @@
+// Instantiates every tiling of the matrix-core convolution kernel for fp32 inputs.
+#include "conv_mfma_kernel.h"
+#include "conv_mfma_variants.h"
+
+namespace sq {
+namespace mfma {
+
+#define SQ_V(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                                 \
+    {conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false>,                       \
+     conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, true>, nullptr},
+#define SQ_E(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                                 \
+    {conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false>,                       \
+     conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, true>,                        \
+     conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false, true>},
+#define SQ_C(NW) {nullptr, nullptr, nullptr},
+const KernelSet conv_mfma_kernels_f32[] = {SQ_VARIANT_LIST(SQ_V, SQ_E, SQ_C)};
+
+}  // namespace mfma
+}  // namespace sq

@@ -111,6 +111,28 @@ int sq_conv2d_forward_ex(const void *in, const void *w, const float *b, float *o
                          int algo);
 
 /*
+ * sq_conv2d_forward_ex with caller scratch.  Some algorithms first rewrite the
+ * kernels into another form (the 3x3 stride-1 pad-1 layers can run as a
+ * minimal-filtering convolution: 16 instead of 36 multiplications per input layer
+ * and 2x2 output pixels, on once-transformed kernels); they need device scratch
+ * for that and are only chosen, or selectable through `algo`, when it is given.
+ *   workspace: device scratch, 256-byte aligned (else SQ_ERR_WORKSPACE), of
+ *     workspace_bytes bytes; NULL = none.  With at least
+ *     sq_conv2d_workspace_bytes(Cin, Cout, K, S, P) bytes every algorithm that
+ *     fits the shape can run; a smaller one only rules those algorithms out.
+ *     Contents on return are unspecified; the same scratch must not be used by
+ *     two calls in flight at once.
+ * Everything else as for sq_conv2d_forward_ex; the result is the same up to
+ * rounding whichever algorithm runs.
+ */
+int sq_conv2d_forward_ws(const void *in, const void *w, const float *b, float *out,
+                         int N, int Cin, int H, int W, int Cout, int K, int S, int P,
+                         int relu, int out_channels, int c_offset, int in_dtype,
+                         int algo, void *workspace, size_t workspace_bytes);
+
+size_t sq_conv2d_workspace_bytes(int Cin, int Cout, int K, int S, int P);
+
+/*
  * Max pooling (section "Pooling and Softmax"): out[n][c][oh][ow] = largest of the
  * K x K window whose corner is (oh*S, ow*S).  No padding, floor mode:
  * Ho = floor((H-K)/S)+1.  in [N][C][H][W], out [N][C][Ho][Wo], fp32.
@@ -142,9 +164,9 @@ int sq_softmax(const float *in, float *out, int N, int C);
  *   in [N][Cin][H][W]; w_sq [Csq][Cin][1][1]; w_e1 [Ce1][Csq][1][1];
  *   w_e3 [Ce3][Csq][3][3]; biases [Csq], [Ce1], [Ce3] (each may be NULL);
  *   out [N][Ce1+Ce3][H][W].  All fp32.
- *   workspace: device scratch of at least sq_fire_workspace_bytes(N, H, W, Csq)
- *   bytes, 256-byte aligned, holding the squeeze map during the call; contents on
- *   return are unspecified.
+ *   workspace: device scratch of at least sq_fire_workspace_bytes(N, H, W, Csq, Ce3)
+ *   bytes, 256-byte aligned, holding the squeeze map and the transformed 3x3
+ *   kernels during the call; contents on return are unspecified.
  * Errors: SQ_ERR_NULL, SQ_ERR_SHAPE, SQ_ERR_WORKSPACE, SQ_ERR_HIP.
  */
 int sq_fire_forward(const void *in, const void *w_sq, const float *b_sq,
@@ -152,7 +174,7 @@ int sq_fire_forward(const void *in, const void *w_sq, const float *b_sq,
                     const float *b_e3, float *out, int N, int Cin, int H, int W,
                     int Csq, int Ce1, int Ce3, void *workspace, size_t workspace_bytes);
 
-size_t sq_fire_workspace_bytes(int N, int H, int W, int Csq);
+size_t sq_fire_workspace_bytes(int N, int H, int W, int Csq, int Ce3);
 
 /*
  * SqueezeNet v1.0 forward (section "Convolutional Neural Networks": two

@@ -8,6 +8,7 @@ fallback: if the library is missing the import fails.
 """
 from .binding import (  # noqa: F401
     SQ_ALGO_AUTO, SQ_ALGO_DIRECT, SQ_ALGO_VARIANT0, SQ_BF16, SQ_F32, SqError, lib,
-    sq_avgpool_global, sq_conv2d_forward, sq_conv2d_forward_ex, sq_conv_variant_count,
+    sq_avgpool_global, sq_conv2d_forward, sq_conv2d_forward_ex, sq_conv2d_forward_ws,
+    sq_conv2d_workspace_bytes, sq_conv_variant_count,
     sq_conv_variant_name, sq_fire_forward, sq_fire_workspace_bytes, sq_maxpool, sq_softmax,
     sq_profile_begin, sq_profile_end, sq_squeezenet_forward, sq_squeezenet_workspace_bytes, sq_strerror, TAP_NAMES, TAP_SHAPES)

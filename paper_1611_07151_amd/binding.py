@@ -29,12 +29,15 @@ lib.sq_conv_variant_name.restype = ctypes.c_char_p
 lib.sq_conv_variant_name.argtypes = [_i]
 lib.sq_conv2d_forward.argtypes = [_vp] * 4 + [_i] * 9
 lib.sq_conv2d_forward_ex.argtypes = [_vp] * 4 + [_i] * 13
+lib.sq_conv2d_forward_ws.argtypes = [_vp] * 4 + [_i] * 13 + [_vp, _sz]
+lib.sq_conv2d_workspace_bytes.restype = _sz
+lib.sq_conv2d_workspace_bytes.argtypes = [_i] * 5
 lib.sq_maxpool.argtypes = [_vp, _vp] + [_i] * 6
 lib.sq_avgpool_global.argtypes = [_vp, _vp] + [_i] * 4
 lib.sq_softmax.argtypes = [_vp, _vp, _i, _i]
 lib.sq_fire_forward.argtypes = [_vp] * 8 + [_i] * 7 + [_vp, _sz]
 lib.sq_fire_workspace_bytes.restype = _sz
-lib.sq_fire_workspace_bytes.argtypes = [_i] * 4
+lib.sq_fire_workspace_bytes.argtypes = [_i] * 5
 lib.sq_squeezenet_forward.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _i, _vp, _sz, ctypes.POINTER(_vp)]
 lib.sq_squeezenet_workspace_bytes.restype = _sz
 lib.sq_squeezenet_workspace_bytes.argtypes = [_i]
@@ -117,6 +120,25 @@ def sq_conv2d_forward_ex(x, w, b=None, stride=1, pad=0, relu=False, out=None, c_
                          algo=SQ_ALGO_AUTO):
     """x and w float32 or both bfloat16.  `out` may be a larger [N][C'][Ho][Wo] tensor; the
     result lands in layers [c_offset, c_offset+Cout)."""
+    return _conv_ex(x, w, b, stride, pad, relu, out, c_offset, algo, None, False)
+
+
+def sq_conv2d_workspace_bytes(Cin, Cout, K, stride, pad) -> int:
+    return int(lib.sq_conv2d_workspace_bytes(Cin, Cout, K, stride, pad))
+
+
+def sq_conv2d_forward_ws(x, w, b=None, stride=1, pad=0, relu=False, out=None, c_offset=0,
+                         algo=SQ_ALGO_AUTO, workspace=None):
+    """sq_conv2d_forward_ex with device scratch (a uint8 tensor; allocated here at the size
+    sq_conv2d_workspace_bytes reports when None), which makes the kernel-transforming
+    algorithms available."""
+    if workspace is None:
+        need = sq_conv2d_workspace_bytes(x.shape[1], w.shape[0], w.shape[2], stride, pad)
+        workspace = torch.empty(max(need, 256), device=x.device, dtype=torch.uint8)
+    return _conv_ex(x, w, b, stride, pad, relu, out, c_offset, algo, workspace, True)
+
+
+def _conv_ex(x, w, b, stride, pad, relu, out, c_offset, algo, workspace, with_ws):
     N, Cin, H, W = x.shape
     Cout, _, K, _ = w.shape
     if w.shape[1] != Cin or w.shape[3] != K:
@@ -132,10 +154,15 @@ def sq_conv2d_forward_ex(x, w, b=None, stride=1, pad=0, relu=False, out=None, c_
         raise ValueError("out has the wrong shape")
     dt = SQ_F32 if x.dtype == torch.float32 else SQ_BF16
     _use_current_stream()
-    rc = lib.sq_conv2d_forward_ex(_dev(x, None, "x"), _dev(w, None, "w"), _dev(b, torch.float32, "b"),
-                                  _dev(out, torch.float32, "out"), N, Cin, H, W, Cout, K, int(stride),
-                                  int(pad), int(bool(relu)), out.shape[1], int(c_offset), dt, int(algo))
-    _check(rc, "sq_conv2d_forward_ex")
+    args = (_dev(x, None, "x"), _dev(w, None, "w"), _dev(b, torch.float32, "b"),
+            _dev(out, torch.float32, "out"), N, Cin, H, W, Cout, K, int(stride),
+            int(pad), int(bool(relu)), out.shape[1], int(c_offset), dt, int(algo))
+    if with_ws:
+        rc = lib.sq_conv2d_forward_ws(*args, _dev(workspace, torch.uint8, "workspace"), workspace.numel())
+        _check(rc, "sq_conv2d_forward_ws")
+    else:
+        rc = lib.sq_conv2d_forward_ex(*args)
+        _check(rc, "sq_conv2d_forward_ex")
     return out
 
 
@@ -167,8 +194,8 @@ def sq_softmax(x):
     return out
 
 
-def sq_fire_workspace_bytes(N, H, W, Csq) -> int:
-    return int(lib.sq_fire_workspace_bytes(N, H, W, Csq))
+def sq_fire_workspace_bytes(N, H, W, Csq, Ce3) -> int:
+    return int(lib.sq_fire_workspace_bytes(N, H, W, Csq, Ce3))
 
 
 def sq_fire_forward(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, workspace=None, out=None):
@@ -177,7 +204,7 @@ def sq_fire_forward(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, workspace=None, out=N
     if tuple(w_sq.shape) != (Csq, Cin, 1, 1) or tuple(w_e1.shape) != (Ce1, Csq, 1, 1) \
             or tuple(w_e3.shape) != (Ce3, Csq, 3, 3):
         raise ValueError("fire kernel shapes")
-    need = sq_fire_workspace_bytes(N, H, W, Csq)
+    need = sq_fire_workspace_bytes(N, H, W, Csq, Ce3)
     if workspace is None:
         workspace = torch.empty(need, device=x.device, dtype=torch.uint8)
     if out is None:

@@ -99,13 +99,15 @@ ConvArgs make_args(const void *in, const void *w, const float *b, float *out, in
     a.out_channels = out_channels;
     a.c_offset = c_offset;
     a.dtype = dtype;
+    a.ws = nullptr; a.ws_bytes = 0; a.ws_ready = false;
     return a;
 }
 
 // Unchecked fire layer: squeeze into `sq_map`, then both expands into `out`.
 int fire_impl(const void *in, const void *w_sq, const float *b_sq, const void *w_e1,
               const float *b_e1, const void *w_e3, const float *b_e3, float *out, int N, int Cin,
-              int H, int W, int Csq, int Ce1, int Ce3, float *sq_map, const char *const *stages)
+              int H, int W, int Csq, int Ce1, int Ce3, float *sq_map, void *conv_ws, size_t conv_ws_bytes,
+              bool conv_ws_ready, const char *const *stages)
 {
     set_stage(stages[0]);
     int rc = run_conv(make_args(in, w_sq, b_sq, sq_map, N, Cin, H, W, Csq, 1, 1, 0, 1, Csq, 0, SQ_F32),
@@ -124,8 +126,9 @@ int fire_impl(const void *in, const void *w_sq, const float *b_sq, const void *w
                   SQ_ALGO_AUTO);
     if (rc) return rc;
     set_stage(stages[2]);
-    rc = run_conv(make_args(sq_map, w_e3, b_e3, out, N, Csq, H, W, Ce3, 3, 1, 1, 1, Ce1 + Ce3, Ce1, SQ_F32),
-                  SQ_ALGO_AUTO);
+    ConvArgs a3 = make_args(sq_map, w_e3, b_e3, out, N, Csq, H, W, Ce3, 3, 1, 1, 1, Ce1 + Ce3, Ce1, SQ_F32);
+    a3.ws = conv_ws; a3.ws_bytes = conv_ws_bytes; a3.ws_ready = conv_ws_ready;
+    rc = run_conv(a3, SQ_ALGO_AUTO);
     set_stage("");
     return rc;
 }
@@ -261,9 +264,15 @@ const char *sq_conv_variant_name(int index)
     return conv_mfma_variant_name(index);
 }
 
-int sq_conv2d_forward_ex(const void *in, const void *w, const float *b, float *out, int N, int Cin,
+size_t sq_conv2d_workspace_bytes(int Cin, int Cout, int K, int S, int P)
+{
+    if (Cin <= 0 || Cout <= 0 || K <= 0 || S < 1 || P < 0) return 0;
+    return conv_workspace_bytes(Cin, Cout, K, S, P);
+}
+
+int sq_conv2d_forward_ws(const void *in, const void *w, const float *b, float *out, int N, int Cin,
                          int H, int W, int Cout, int K, int S, int P, int relu, int out_channels,
-                         int c_offset, int in_dtype, int algo)
+                         int c_offset, int in_dtype, int algo, void *workspace, size_t workspace_bytes)
 {
     const int rc = validate_conv(in, w, out, N, Cin, H, W, Cout, K, S, P);
     if (rc) return rc;
@@ -271,8 +280,18 @@ int sq_conv2d_forward_ex(const void *in, const void *w, const float *b, float *o
         return SQ_ERR_SHAPE;
     if (in_dtype != SQ_F32 && in_dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
     if (algo < 0) return SQ_ERR_UNSUPPORTED;
-    return run_conv(make_args(in, w, b, out, N, Cin, H, W, Cout, K, S, P, relu, out_channels,
-                              c_offset, in_dtype), algo);
+    if (workspace && ((uintptr_t)workspace & 255)) return SQ_ERR_WORKSPACE;
+    ConvArgs a = make_args(in, w, b, out, N, Cin, H, W, Cout, K, S, P, relu, out_channels, c_offset, in_dtype);
+    a.ws = workspace; a.ws_bytes = workspace ? workspace_bytes : 0;
+    return run_conv(a, algo);
+}
+
+int sq_conv2d_forward_ex(const void *in, const void *w, const float *b, float *out, int N, int Cin,
+                         int H, int W, int Cout, int K, int S, int P, int relu, int out_channels,
+                         int c_offset, int in_dtype, int algo)
+{
+    return sq_conv2d_forward_ws(in, w, b, out, N, Cin, H, W, Cout, K, S, P, relu, out_channels, c_offset,
+                                in_dtype, algo, nullptr, 0);
 }
 
 int sq_conv2d_forward(const void *in, const void *w, const float *b, float *out, int N, int Cin,
@@ -303,10 +322,10 @@ int sq_softmax(const float *in, float *out, int N, int C)
     return softmax(in, out, N, C);
 }
 
-size_t sq_fire_workspace_bytes(int N, int H, int W, int Csq)
+size_t sq_fire_workspace_bytes(int N, int H, int W, int Csq, int Ce3)
 {
-    if (N <= 0 || H <= 0 || W <= 0 || Csq <= 0) return 0;
-    return align_up((size_t)N * Csq * H * W * sizeof(float), 256);
+    if (N <= 0 || H <= 0 || W <= 0 || Csq <= 0 || Ce3 <= 0) return 0;
+    return align_up((size_t)N * Csq * H * W * sizeof(float), 256) + conv_workspace_bytes(Csq, Ce3, 3, 1, 1);
 }
 
 int sq_fire_forward(const void *in, const void *w_sq, const float *b_sq, const void *w_e1,
@@ -316,18 +335,21 @@ int sq_fire_forward(const void *in, const void *w_sq, const float *b_sq, const v
 {
     if (!in || !w_sq || !w_e1 || !w_e3 || !out) return SQ_ERR_NULL;
     if (N <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Csq <= 0 || Ce1 <= 0 || Ce3 <= 0) return SQ_ERR_SHAPE;
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < sq_fire_workspace_bytes(N, H, W, Csq))
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < sq_fire_workspace_bytes(N, H, W, Csq, Ce3))
         return SQ_ERR_WORKSPACE;
+    const size_t map_bytes = align_up((size_t)N * Csq * H * W * sizeof(float), 256);
     return fire_impl(in, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, out, N, Cin, H, W, Csq, Ce1, Ce3,
-                     (float *)workspace, kFireAlone);
+                     (float *)workspace, (char *)workspace + map_bytes, workspace_bytes - map_bytes, false, kFireAlone);
 }
 
 size_t sq_squeezenet_workspace_bytes(int N)
 {
     if (N <= 0) return 0;
     const size_t n = (size_t)N;
+    size_t conv_ws = 0;   // every expand3x3 layer has its own area: all are filled by one launch
+    for (const FireCfg &fc : kFires) conv_ws += conv_workspace_bytes(fc.sq, fc.e, 3, 1, 1);
     return align_up(n * kBufA * 4, 256) + align_up(n * kBufB * 4, 256) + align_up(n * kBufS * 4, 256) +
-           align_up(n * 1000 * 4, 256);
+           align_up(n * 1000 * 4, 256) + conv_ws;
 }
 
 int sq_squeezenet_forward(const void *in, const void *const *params, float *probs, int N,
@@ -348,9 +370,37 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
     float *bufS = (float *)((char *)bufB + align_up(n * kBufB * 4, 256));
     float *means = (float *)((char *)bufS + align_up(n * kBufS * 4, 256));
     auto P = [&](int i) { return (const float *)params[i]; };
-
+    // transformed kernels of those expand3x3 layers whose algorithm wants them, written by
+    // one launch up front
+    char *conv_ws[8];
+    size_t conv_ws_bytes[8];
+    bool conv_ws_ready[8];
+    KernelPrepJob prep[8];
+    int nprep = 0;
+    {
+        char *next = (char *)means + align_up(n * 1000 * 4, 256);
+        int h = 55;
+        for (int f = 0; f < 8; ++f) {
+            const FireCfg &fc = kFires[f];
+            conv_ws[f] = next;
+            conv_ws_bytes[f] = conv_workspace_bytes(fc.sq, fc.e, 3, 1, 1);
+            next += conv_ws_bytes[f];
+            ConvArgs a3 = make_args(bufS, params[2 + 6 * f + 4], nullptr, bufA, N, fc.sq, h, h, fc.e, 3, 1, 1, 1,
+                                    2 * fc.e, fc.e, SQ_F32);
+            a3.ws = conv_ws[f]; a3.ws_bytes = conv_ws_bytes[f];
+            conv_ws_ready[f] = conv_wants_prepared_kernels(a3);
+            if (conv_ws_ready[f]) prep[nprep++] = KernelPrepJob{params[2 + 6 * f + 4], conv_ws[f], fc.sq, fc.e};
+            if (f == 2) h = 27;
+            if (f == 6) h = 13;
+        }
+    }
+    int rc = SQ_OK;
+    if (nprep) {
+        set_stage("kernel transform");
+        if ((rc = conv_prepare_kernels(prep, nprep, SQ_F32))) return rc;
+    }
     set_stage("conv1");
-    int rc = run_conv(make_args(in, params[0], P(1), bufA, N, 3, 224, 224, 96, 7, 2, 2, 1, 96, 0, SQ_F32),
+    rc = run_conv(make_args(in, params[0], P(1), bufA, N, 3, 224, 224, 96, 7, 2, 2, 1, 96, 0, SQ_F32),
                       SQ_ALGO_AUTO);
     if (rc) return rc;
     if ((rc = copy_tap(taps, 0, bufA, n * 96 * 111 * 111))) return rc;
@@ -363,7 +413,7 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
     for (int f = 0; f < 8; ++f) {
         const FireCfg &fc = kFires[f];
         rc = fire_impl(cur, params[p], P(p + 1), params[p + 2], P(p + 3), params[p + 4], P(p + 5), nxt,
-                       N, C, H, H, fc.sq, fc.e, fc.e, bufS, kFireStages[f]);
+                       N, C, H, H, fc.sq, fc.e, fc.e, bufS, conv_ws[f], conv_ws_bytes[f], conv_ws_ready[f], kFireStages[f]);
         if (rc) return rc;
         p += 6;
         C = 2 * fc.e;

@@ -33,6 +33,7 @@
 #include <string.h>
 
 namespace sq {
+size_t wino_transformed_bytes(int Cout, int Cin);
 namespace {
 
 using namespace mfma;
@@ -42,15 +43,19 @@ struct Variant {
     const char *name;
     int KS, S, BM, BN, MT, CC, PE, NBUF, NT;
     bool conv1_type;      // the persistent 7x7/stride-2/three-layer kernel
+    bool wino;            // the minimal-filtering F(2x2, 3x3) kernel (BN = tiles of 2x2 pixels)
 };
 
 #define SQ_V(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                               \
     {"k" #KS "s" #S "_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC "_o" #MINW, KS, S, BM, BN, MT, CC, PE, 2, \
-     WM * WN * 64, false},
-#define SQ_C(NW) {"k7s2c3_waves" #NW, 7, 2, 96, 32 * NW, 32, 3, 64, 2, 64 * NW, true},
-const Variant kVariants[] = {SQ_VARIANT_LIST(SQ_V, SQ_V, SQ_C)};
+     WM * WN * 64, false, false},
+#define SQ_C(NW) {"k7s2c3_waves" #NW, 7, 2, 96, 32 * NW, 32, 3, 64, 2, 64 * NW, true, false},
+#define SQ_W(BM, BT, CC) {"k3s1_f2x2_" #BM "x" #BT "_c" #CC, 3, 1, BM, BT, 32, CC, 0, 2, 256, false, true},
+static_assert(kWinoBM == 64 && kWinoBT == 32 && kWinoCC == 8, "the W() entry of the variant list names these");
+const Variant kVariants[] = {SQ_VARIANT_LIST(SQ_V, SQ_V, SQ_C, SQ_W)};
 #undef SQ_V
 #undef SQ_C
+#undef SQ_W
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 struct Plan {
@@ -104,6 +109,9 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
         pixels + v.BN >= kMaxBufferElems)
         return false;
     if (v.conv1_type && (a.Cin != 3 || a.Cout > 96 || a.Cout % 8 != 0)) return false;
+    if (v.wino && (a.P != 1 || a.Cin % v.CC != 0 || a.Cout % 32 != 0 || !a.ws || ((uintptr_t)a.ws & 15) ||
+                   a.ws_bytes < wino_transformed_bytes(a.Cout, a.Cin)))
+        return false;
 
     KParams &k = pl.kp;
     k.in = (const float *)a.in; k.w = (const float *)a.w; k.b = a.b; k.out = a.out;
@@ -119,7 +127,18 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
     k.nchunks = (a.Cin + v.CC - 1) / v.CC;
     const int KK = v.KS * v.KS, RUN = v.CC * KK, LDK = RUN + ((RUN & 1) ? 0 : 1);
 
-    if (v.KS == 1 && v.S == 1) {
+    if (v.wino) {
+        k.TX = (a.Wo + 1) / 2;
+        k.TXY = k.TX * ((a.Ho + 1) / 2);
+        const long long tiles = (long long)a.N * k.TXY;
+        if (tiles + v.BN >= kMaxBufferElems) return false;
+        k.T = (int)tiles;
+        k.dTX = make_fastdiv(k.TX); k.dTXY = make_fastdiv(k.TXY);
+        k.ntiles = (int)((tiles + v.BN - 1) / v.BN);
+        k.VH = a.Ho; k.LW = a.Wo; k.LWs = a.Wo; k.PRcap = 0; k.plane = 0;
+        k.wu = (const float *)a.ws;
+        k.wu_bytes = (uint32_t)wino_transformed_bytes(a.Cout, a.Cin);
+    } else if (v.KS == 1 && v.S == 1) {
         if (a.P != 0) return false;  // a padded 1x1 is left to the direct kernel
         k.VH = a.Ho; k.LW = a.Wo; k.LWs = a.Wo; k.PRcap = 0;
         k.plane = v.BN + v.MT;
@@ -156,6 +175,8 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
         pl.lds_bytes = conv7s2c3_lds_bytes(NW);
         blocks = (tiles + NW - 1) / NW;
         if (blocks > num_cus()) blocks = num_cus();
+    } else if (v.wino) {
+        pl.lds_bytes = (size_t)(kWinoImage + 16 * 2 * kWinoBT * 4) * sizeof(float);
     } else {
         pl.lds_bytes = ((size_t)v.NBUF * v.BM * LDK + (size_t)v.NBUF * v.CC * k.plane +
                         (e1 ? (size_t)2 * v.BM * (v.CC + 1) : 0)) * sizeof(float);
@@ -185,7 +206,7 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
     const KernelSet &ks = kernel_set(v, a.dtype);
     KernelFn fn = e1 ? ks.fused_e1 : ks.plain;
     if (v.conv1_type) fn = conv7s2c3_kernel_for(v.NT / 64, a.Cout == 96, a.dtype == SQ_BF16);
-    if (!v.conv1_type && !e1 && a.Cin % v.CC != 0) fn = ks.tail;
+    if (!v.conv1_type && !v.wino && !e1 && a.Cin % v.CC != 0) fn = ks.tail;
     if (!allow_big_lds(fn)) {
         const int rc = check_launch();
         return rc ? rc : SQ_ERR_HIP;
@@ -194,6 +215,11 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
     if (e1) {
         flops += 2.0 * a.N * e1->Cout1 * a.Ho * a.Wo * (double)a.Cin;
         bytes += 4.0 * ((double)e1->Cout1 * a.Cin + (double)a.N * e1->Cout1 * a.Ho * a.Wo + e1->Cout1);
+    }
+    if (v.wino && !a.ws_ready) {
+        const KernelPrepJob job{a.w, a.ws, a.Cin, a.Cout};
+        const int rc = conv_prepare_kernels(&job, 1, a.dtype);
+        if (rc) return rc;
     }
     LaunchScope scope(v.name, flops, bytes);
     hipLaunchKernelGGL(fn, dim3(pl.blocks), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
@@ -204,11 +230,12 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
 // the batch sizes nearest to the one it was measured at.
 struct Tuned {
     int K, S, P, Cin, Cout, H, W, N;
-    const char *variant;
+    const char *variant;        // fastest of all
+    const char *variant_plain;  // fastest of those that need no caller scratch
 };
 const Tuned kTuned[] = {
 #include "tuned_table.inc"
-    {0, 0, 0, 0, 0, 0, 0, 0, ""}};
+    {0, 0, 0, 0, 0, 0, 0, 0, "", ""}};
 
 int tuned_variant(const ConvArgs &a)
 {
@@ -224,8 +251,13 @@ int tuned_variant(const ConvArgs &a)
         }
     }
     if (!best) return -1;
-    for (int i = 0; i < kNumVariants; ++i)
-        if (!strcmp(kVariants[i].name, best->variant)) return i;
+    for (int pass = 0; pass < 2; ++pass) {
+        const char *name = pass ? best->variant_plain : best->variant;
+        for (int i = 0; i < kNumVariants; ++i) {
+            if (strcmp(kVariants[i].name, name)) continue;
+            if (!kVariants[i].wino || a.ws_bytes >= conv_workspace_bytes(a.Cin, a.Cout, a.K, a.S, a.P)) return i;
+        }
+    }
     return -1;
 }
 
@@ -235,7 +267,9 @@ double estimate(const Variant &v, const Plan &pl, const ConvArgs &a)
 {
     (void)a;
     const double tiles = (double)pl.kp.mtiles * pl.kp.ntiles;
-    const double kpad = v.conv1_type ? 148.0 : (double)pl.kp.nchunks * v.CC * v.KS * v.KS;
+    // the minimal-filtering kernel multiplies 16 times per 2x2 pixels and input layer, i.e.
+    // 4 per pixel where the direct form needs 9; BN counts tiles of 4 pixels there
+    const double kpad = v.conv1_type ? 148.0 : (double)pl.kp.nchunks * v.CC * (v.wino ? 16 : v.KS * v.KS);
     const double work_per_tile = (double)v.BM * v.BN * kpad;
     const double occ = v.conv1_type ? 1.0 : ((size_t)2 * pl.lds_bytes <= (size_t)kLdsBytes ? 2.0 : 1.0);
     const double rounds = ceil(tiles / (num_cus() * occ));
@@ -255,6 +289,20 @@ extern "C" long long sq_internal_fastdiv_mismatches(unsigned d, unsigned x_max)
     long long bad = 0;
     for (unsigned long long x = 0; x <= x_max; ++x) bad += mfma::fastdiv_host((unsigned)x, f) != (unsigned)x / (d ? d : 1);
     return bad;
+}
+
+size_t conv_workspace_bytes(int Cin, int Cout, int K, int S, int P)
+{
+    if (K == 3 && S == 1 && P == 1 && Cin % kWinoCC == 0 && Cout % 32 == 0)
+        return align_up(wino_transformed_bytes(Cout, Cin), 256);
+    return 0;
+}
+
+bool conv_wants_prepared_kernels(const ConvArgs &a)
+{
+    const int tv = tuned_variant(a);
+    Plan pl;
+    return tv >= 0 && kVariants[tv].wino && plan(kVariants[tv], a, pl);
 }
 
 int conv_mfma_variant_count() { return kNumVariants; }

@@ -79,6 +79,10 @@ struct KParams {
     uint32_t w1_bytes;
     int RG, CB;  // conv1-type kernel: tile grid per image (row groups, column blocks)
     FastDiv dRG, dCB;
+    int T, TX, TXY;  // minimal-filtering kernel: 2x2-pixel tiles in all, per image row, per image
+    FastDiv dTX, dTXY;
+    const float *wu;     // its transformed kernels (written by wino_kernel_transform)
+    uint32_t wu_bytes;
 };
 
 template <int MT> struct Mfma;
@@ -170,6 +174,13 @@ struct KernelSet {
 };
 extern const KernelSet conv_mfma_kernels_f32[], conv_mfma_kernels_bf16[];
 KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers, bool bf16_inputs);
+
+// Minimal-filtering F(2x2, 3x3) kernel: workgroup tile (output layers x tiles of 2x2 pixels),
+// input layers per chunk, and the floats of the kernel image [16 positions][2][64][4] of one chunk.
+constexpr int kWinoBM = 64, kWinoBT = 32, kWinoCC = 8;
+constexpr int kWinoImage = 16 * 2 * 64 * 4;
+constexpr int kWinoMaxJobs = 8;
+
 constexpr int kConv7TileRows = 2, kConv7TileCols = 16;   // output pixels per wavefront tile
 size_t conv7s2c3_lds_bytes(int NW);
 

@@ -1,0 +1,311 @@
+// 3x3 / stride 1 / pad 1 convolution through the minimal-filtering form F(2x2, 3x3) on the
+// fp32 matrix cores of gfx950 (internal).
+//
+// The layer of section "Convolutional Neural Networks" computes, per 2x2 block of output
+// pixels ("tile") and output layer m,  Y = sum_c  g[m][c] (*) d[c]  with d the 4x4 input patch
+// under the tile.  With the transforms  U = G g G^T,  V = B^T d B  (both 4x4) the same Y is
+// A^T ( sum_c U (.) V ) A:  per position xi of the 4x4 grid one small matrix product
+//   M_xi[m][tile] = sum_c U_xi[m][c] * V_xi[c][tile],
+// i.e. 16 multiplies per input layer and tile where the direct form needs 36.  The sixteen
+// products are independent contractions over the input layers and run on the MFMA units;
+// the transforms are a few additions per element on the vector ALU.
+//
+//   B^T = | 1  0 -1  0 |   G = | 1    0    0  |   A^T = | 1  1  1  0 |
+//         | 0  1  1  0 |       | 1/2  1/2  1/2|         | 0  1 -1 -1 |
+//         | 0 -1  1  0 |       | 1/2 -1/2  1/2|
+//         | 0  1  0 -1 |       | 0    0    1  |
+//
+// Two kernels.  wino_kernel_transform writes U for all (m, c) once per call (for several
+// layers at once when the caller has several), already in
+// the order the main kernel keeps it in LDS, so the main kernel copies it with 16-byte
+// loads and spends no arithmetic on it.  conv_wino_kernel: a workgroup owns 64 output
+// layers x 32 tiles and has 4 wavefronts (pr, x): wavefront (pr, x) accumulates the eight
+// positions of grid rows 2pr and 2pr+1 for layers 32x..32x+31 and all 32 tiles in eight
+// accumulators of v_mfma_f32_32x32x2_f32 (A operand = output layers, B operand = tiles).
+// Input layers are taken eight at a time; both LDS images hold, per position and per lane
+// half kk, the four values c = kk, kk+2, kk+4, kk+6 of a layer (tile) side by side, so one
+// 16-byte LDS read feeds four MFMAs.  Every thread transforms the patch of one (tile, input
+// layer) and copies eight 16-byte pieces of U per chunk: the global loads of chunk c+1 are
+// issued before the MFMAs of chunk c and their results go to LDS between two barriers
+// afterwards.  Two workgroups share a CU (256 registers per wavefront), so one multiplies
+// while the other stages, transforms or stores.  At the end a wavefront folds its two grid
+// rows with A and half of A^T, swaps the other half with its partner (pr ^ 1) through LDS,
+// and writes output row pr of its tiles.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "conv_mfma_common.h"
+
+namespace sq {
+namespace mfma {
+
+// U = G g G^T for every (m, c) of up to kWinoMaxJobs layers in one launch, written per layer as
+// [m / 64][c / 8][xi][c & 1][m % 64][(c % 8) / 2]; layers past Cout (up to the next multiple of
+// 64) are written as zeros.  Thread i of the grid handles element i - first of the job that
+// holds it.
+struct WinoJobs {
+    const void *w[kWinoMaxJobs];
+    float *u[kWinoMaxJobs];
+    int Cout[kWinoMaxJobs], Cin[kWinoMaxJobs];
+    int first[kWinoMaxJobs + 1];   // running totals of Cout (rounded up to 64) * Cin
+    int n;
+};
+
+template <typename TIN>
+__global__ __launch_bounds__(256) void wino_kernel_transform(const WinoJobs jobs)
+{
+    const int gi = blockIdx.x * 256 + threadIdx.x;
+    if (gi >= jobs.first[jobs.n]) return;
+    int j = 0;
+    while (gi >= jobs.first[j + 1]) ++j;
+    const int i = gi - jobs.first[j], Cin = jobs.Cin[j], Cout = jobs.Cout[j];
+    const TIN *w = (const TIN *)jobs.w[j];
+    const int m = i / Cin, c = i - m * Cin;
+    float g[9];
+#pragma unroll
+    for (int q = 0; q < 9; ++q) {
+        if (m >= Cout) g[q] = 0.f;
+        else if constexpr (sizeof(TIN) == 2) g[q] = __builtin_bit_cast(float, (uint32_t)w[(size_t)i * 9 + q] << 16);
+        else g[q] = w[(size_t)i * 9 + q];
+    }
+    float tt[4][3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        const float s = g[k] + g[6 + k];
+        tt[0][k] = g[k];
+        tt[1][k] = 0.5f * (s + g[3 + k]);
+        tt[2][k] = 0.5f * (s - g[3 + k]);
+        tt[3][k] = g[6 + k];
+    }
+    const int cl = c % kWinoCC;
+    float *dst = jobs.u[j] + ((size_t)(m / kWinoBM) * (Cin / kWinoCC) + c / kWinoCC) * kWinoImage + (cl & 1) * 256 +
+                 (m % kWinoBM) * 4 + (cl >> 1);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float s = tt[r][0] + tt[r][2];
+        dst[(4 * r + 0) * 512] = tt[r][0];
+        dst[(4 * r + 1) * 512] = 0.5f * (s + tt[r][1]);
+        dst[(4 * r + 2) * 512] = 0.5f * (s - tt[r][1]);
+        dst[(4 * r + 3) * 512] = tt[r][2];
+    }
+}
+
+template <typename TIN>
+__global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
+{
+    constexpr int BM = kWinoBM, BT = kWinoBT, CC = kWinoCC;
+    static_assert(BM == 64 && BT == 32 && CC == 8, "thread roles below are written for this tile");
+    constexpr int US = kWinoImage;             // floats of the U image [16][2][64][4]
+    constexpr int VS = 16 * 2 * BT * 4;        // floats of the V image [16][2][32][4]
+    constexpr uint32_t ESZ = sizeof(TIN);
+    using M = Mfma<32>;
+    using Acc = M::Acc;
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int pr = wv & 1, wx = wv >> 1;
+    const int li = lane & 31, kk = lane >> 5;
+
+    const int bid = xcd_remap(blockIdx.x, gridDim.x);
+    const int tb = fdiv(bid, p.dMtiles);
+    const int mt = bid - tb * p.mtiles, m0 = mt * BM, t0 = tb * BT;
+
+    const rsrc_t rx = make_rsrc(p.in, p.in_bytes);
+
+    // ---- staging maps ----------------------------------------------------------------------
+    // patches: thread -> (tile vt = t % 32, input layer vc = t / 32 of the chunk).
+    // Per patch row two lane offsets: the first column on its own (rows outside the image, a
+    // tile past the end, or column -1 get the top bit, which the buffer range check turns
+    // into zeros) and columns 2, 3, 4 of the patch as one 12-byte run.  Offsets of real
+    // elements are never negative.  Columns 3 and 4 may lie right of the image; there the
+    // run reads valid addresses of the next row and the factors mc2, mc3 (0 or 1) cancel
+    // them inside the column transform.
+    const int vt = t & 31, vc = t >> 5;
+    uint32_t xrow[4], xcol0[4];
+    float mc2, mc3;
+    {
+        const int tg = t0 + vt, tgc = min(tg, p.T - 1);
+        const int n = fdiv(tgc, p.dTXY), rem = tgc - n * p.TXY;
+        const int ty = fdiv(rem, p.dTX), tx = rem - ty * p.TX;
+        const int ih0 = 2 * ty - 1, iw0 = 2 * tx - 1;
+        const uint32_t base = (uint32_t)((n * p.Cin + vc) * p.HW + ih0 * p.W + iw0 + 1) * ESZ;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const uint32_t bad = tg < p.T && (unsigned)(ih0 + a) < (unsigned)p.H ? 0u : kOob;
+            xrow[a] = (base + (uint32_t)(a * p.W) * ESZ) | bad;
+            xcol0[a] = (base + (uint32_t)(a * p.W) * ESZ - ESZ) | bad | (iw0 >= 0 ? 0u : kOob);
+        }
+        mc2 = iw0 + 2 < p.W ? 1.f : 0.f;
+        mc3 = iw0 + 3 < p.W ? 1.f : 0.f;
+    }
+    // V image position of (tile vt, layer vc): lane half vc & 1, slot vc >> 1
+    const int vdst = US + (vc & 1) * (BT * 4) + vt * 4 + (vc >> 1);
+
+    float dpatch[16];
+    f32x4 ucopy[8];
+    auto load_chunk = [&](int ch) {
+        const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(ch * CC * p.HW) * ESZ;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            asm volatile("" : "+v"(xrow[a]));   // keeps the column steps immediates, so the run is one load
+            dpatch[4 * a] = buf_ld_in<TIN>(rx, xcol0[a], so);
+#pragma unroll
+            for (int b = 1; b < 4; ++b) dpatch[4 * a + b] = buf_ld_in<TIN>(rx, xrow[a] + (b - 1) * ESZ, so);
+        }
+        // U image of this (layer block, chunk): uniform 64-bit base + 32-bit lane offset
+        const char *ub = (const char *)p.wu + (size_t)__builtin_amdgcn_readfirstlane(mt * p.nchunks + ch) * (US * 4);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ucopy[i] = *(const f32x4 *)(ub + i * 4096 + (size_t)(uint32_t)(t * 16));
+    };
+    auto store_chunk = [&]() {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *(f32x4 *)(lds + (i * 256 + t) * 4) = ucopy[i];
+        // V = B^T d B
+        float rr[4][4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            rr[0][b] = dpatch[0 + b] - dpatch[8 + b];
+            rr[1][b] = dpatch[4 + b] + dpatch[8 + b];
+            rr[2][b] = dpatch[8 + b] - dpatch[4 + b];
+            rr[3][b] = dpatch[4 + b] - dpatch[12 + b];
+        }
+        float *vs = lds + vdst;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const float r2 = rr[a][2] * mc2;          // columns 0 (zero-filled) and 1 need no factor
+            vs[(4 * a + 0) * (2 * BT * 4)] = rr[a][0] - r2;
+            vs[(4 * a + 1) * (2 * BT * 4)] = rr[a][1] + r2;
+            vs[(4 * a + 2) * (2 * BT * 4)] = r2 - rr[a][1];
+            vs[(4 * a + 3) * (2 * BT * 4)] = __builtin_fmaf(-rr[a][3], mc3, rr[a][1]);
+        }
+    };
+
+    Acc acc[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[s][q] = 0.f;
+
+    // per-lane operand addresses: A = U[xi][kk][32 wx + li][0..3], B = V[xi][kk][li][0..3]
+    const float *ua = lds + 8 * pr * 512 + kk * 256 + (32 * wx + li) * 4;
+    const float *vb = lds + US + 8 * pr * (2 * BT * 4) + kk * (BT * 4) + li * 4;
+    auto compute_chunk = [&]() {
+        // two grid positions at a time, their MFMAs interleaved: consecutive MFMAs never
+        // wait for each other's accumulator
+        f32x4 a[4], b[4];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            a[e] = *(const f32x4 *)(ua + e * 512);
+            b[e] = *(const f32x4 *)(vb + e * (2 * BT * 4));
+        }
+#pragma unroll
+        for (int s = 0; s < 8; s += 2) {
+            const int cur2 = s & 2, nxt2 = cur2 ^ 2;
+            if (s + 2 < 8) {
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    a[nxt2 + e] = *(const f32x4 *)(ua + (s + 2 + e) * 512);
+                    b[nxt2 + e] = *(const f32x4 *)(vb + (s + 2 + e) * (2 * BT * 4));
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            acc[s] = M::run(a[cur2].x, b[cur2].x, acc[s]);
+            acc[s + 1] = M::run(a[cur2 + 1].x, b[cur2 + 1].x, acc[s + 1]);
+            acc[s] = M::run(a[cur2].y, b[cur2].y, acc[s]);
+            acc[s + 1] = M::run(a[cur2 + 1].y, b[cur2 + 1].y, acc[s + 1]);
+            acc[s] = M::run(a[cur2].z, b[cur2].z, acc[s]);
+            acc[s + 1] = M::run(a[cur2 + 1].z, b[cur2 + 1].z, acc[s + 1]);
+            acc[s] = M::run(a[cur2].w, b[cur2].w, acc[s]);
+            acc[s + 1] = M::run(a[cur2 + 1].w, b[cur2 + 1].w, acc[s + 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ---- main loop ---------------------------------------------------------------------------
+    load_chunk(0);
+    store_chunk();
+    __syncthreads();
+    for (int ch = 0; ch < p.nchunks; ++ch) {
+        const bool more = ch + 1 < p.nchunks;
+        if (more) load_chunk(ch + 1);
+        compute_chunk();
+        __syncthreads();               // every wavefront is done reading the images
+        if (more) {
+            store_chunk();
+            __syncthreads();
+        }
+    }
+
+    // ---- output transform -------------------------------------------------------------------
+    // acc[4i + s] is grid position (row 2pr+i, column s).  Folding a row with A gives
+    //   z(row)[0] = m0 + m1 + m2,   z(row)[1] = m1 - m2 - m3,
+    // and the output rows are  Y[0] = z(0) + z(1) + z(2),  Y[1] = z(1) - z(2) - z(3).
+    // pr = 0 holds rows 0, 1: keeps z(0) + z(1) for Y[0] and hands z(1) to its partner;
+    // pr = 1 holds rows 2, 3: keeps -z(2) - z(3) for Y[1] and hands z(2) over.
+    // Exchange area: [wavefront][zz][register][lane]; the images are free by now.
+    constexpr int ZQ = 16 * 64;
+    static_assert(4 * 2 * ZQ <= US + VS, "exchange area must fit the staging images");
+    Acc keep[2];
+    {
+        float *z = lds + wv * 2 * ZQ + lane;
+        const float sg = pr ? -1.f : 1.f;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const float z0a = acc[0][q] + acc[1][q] + acc[2][q], z1a = acc[1][q] - acc[2][q] - acc[3][q];
+            const float z0b = acc[4][q] + acc[5][q] + acc[6][q], z1b = acc[5][q] - acc[6][q] - acc[7][q];
+            keep[0][q] = sg * (z0a + z0b);
+            keep[1][q] = sg * (z1a + z1b);
+            z[q * 64] = pr ? z0a : z0b;          // grid row 2 (pr = 1) or grid row 1 (pr = 0)
+            z[ZQ + q * 64] = pr ? z1a : z1b;
+        }
+    }
+    __syncthreads();
+    const int mw = m0 + wx * 32;                 // uniform: first layer this wavefront writes
+    if (mw >= p.Cout) return;
+    const int lrow = M::row_lane(lane);
+    const rsrc_t rout = make_rsrc(p.out, p.out_bytes);
+    const uint32_t hs = (uint32_t)p.HoWo * 4u;
+    // this wavefront writes output row pr of its tiles: pixels (2ty + pr, 2tx) and (.., 2tx + 1)
+    uint32_t o2, o1;   // lane offsets for a tile with both columns inside the image / only the first
+    {
+        const int tg = t0 + li, tgc = min(tg, p.T - 1);
+        const int n = fdiv(tgc, p.dTXY), rem = tgc - n * p.TXY;
+        const int ty = fdiv(rem, p.dTX), tx = rem - ty * p.TX;
+        const int oh = 2 * ty + pr, ow = 2 * tx;
+        const bool ok = tg < p.T && oh < p.Ho;
+        const uint32_t o = (uint32_t)(((n * p.ldc + p.coff + lrow) * p.HoWo + oh * p.Wo + ow) * 4);
+        o2 = ok && ow + 1 < p.Wo ? o : kOob;
+        o1 = ok && ow + 1 >= p.Wo ? o : kOob;
+    }
+    float bias[16];
+    if (p.b) {
+        const rsrc_t rb = make_rsrc(p.b, (uint32_t)p.Cout * 4u);
+#pragma unroll
+        for (int q = 0; q < 16; ++q) bias[q] = buf_ld(rb, (uint32_t)(lrow * 4), (uint32_t)(mw + M::row_reg(q)) * 4u);
+    } else {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) bias[q] = 0.f;
+    }
+    const float *zr = lds + (wv ^ 1) * 2 * ZQ + lane;
+    const bool odd_w = p.Wo & 1;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(mw + M::row_reg(q)) * hs;
+        float y0 = keep[0][q] + zr[q * 64] + bias[q];
+        float y1 = keep[1][q] + zr[ZQ + q * 64] + bias[q];
+        if (p.relu) {
+            y0 = fmaxf(y0, 0.f);
+            y1 = fmaxf(y1, 0.f);
+        }
+        u32x2 both;
+        both.x = __builtin_bit_cast(unsigned, y0); both.y = __builtin_bit_cast(unsigned, y1);
+        __builtin_amdgcn_raw_buffer_store_b64(both, rout, (int)o2, (int)so, 0);
+        if (odd_w) buf_st(rout, o1, so, y0);
+    }
+}
+
+}  // namespace mfma
+}  // namespace sq

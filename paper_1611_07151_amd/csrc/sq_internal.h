@@ -25,6 +25,9 @@ struct ConvArgs {
     int N, Cin, H, W, Cout, K, S, P, relu;
     int Ho, Wo, out_channels, c_offset;
     int dtype;  // sq_dtype of in and w
+    void *ws;         // caller scratch some algorithms need (16-byte aligned), or nullptr
+    size_t ws_bytes;
+    bool ws_ready;    // ws already holds this layer's transformed kernels (conv_prepare_kernels)
 };
 
 inline double conv_flops(const ConvArgs &a)
@@ -46,6 +49,18 @@ int conv_mfma(const ConvArgs &a, int variant);
 // Fused expand of a fire layer: the 3x3 convolution a3 and a 1x1 convolution of the same
 // input in one launch; SQ_ERR_UNSUPPORTED if no compiled tiling fits.
 int conv_expand_fused(const ConvArgs &a3, const void *w1, const float *b1, int Cout1, int coff1);
+// Scratch bytes with which every algorithm can run this layer shape (0 if none needs any).
+size_t conv_workspace_bytes(int Cin, int Cout, int K, int S, int P);
+// Transforms the 3x3 kernels of n <= 8 layers (fp32) into their scratch areas in one launch;
+// a layer whose ConvArgs then carries that area with ws_ready set skips its own transform.
+struct KernelPrepJob {
+    const void *w;
+    void *ws;
+    int Cin, Cout;
+};
+int conv_prepare_kernels(const KernelPrepJob *jobs, int n, int dtype);
+// Whether the automatic choice for this call is an algorithm that runs on transformed kernels.
+bool conv_wants_prepared_kernels(const ConvArgs &a);
 int conv_mfma_variant_count();
 const char *conv_mfma_variant_name(int i);
 

@@ -54,6 +54,8 @@ CONV_CASES = [
     (2, 16, 55, 55, 64, 3, 1, 1),
     (1, 48, 27, 27, 192, 3, 1, 1),
     (2, 64, 13, 13, 256, 3, 1, 1),
+    (2, 8, 28, 30, 32, 3, 1, 1),      # even extents, one layer block, one input-layer chunk
+    (3, 24, 7, 5, 96, 3, 1, 1),       # image smaller than a tile block, partial layer tile
     (2, 96, 55, 55, 16, 1, 1, 0),     # squeeze
     (2, 16, 55, 55, 64, 1, 1, 0),     # expand1x1
     (3, 256, 27, 27, 48, 1, 1, 0),
@@ -79,7 +81,7 @@ def test_conv_every_algorithm_matches_oracle(sq, case, relu):
     ran = 0
     for algo in algos(sq):
         try:
-            got = sq.sq_conv2d_forward_ex(xd, wd, bd, S, P, relu, algo=algo)
+            got = sq.sq_conv2d_forward_ws(xd, wd, bd, S, P, relu, algo=algo)
         except sq.SqError as e:
             assert e.status == -3 and algo >= sq.SQ_ALGO_VARIANT0, (algo, str(e))
             continue
@@ -92,20 +94,24 @@ def test_conv_every_algorithm_matches_oracle(sq, case, relu):
     assert_close(sq.sq_conv2d_forward(xd, wd, None, S, P, relu), ref0, FP32_TOL, "no bias")
 
 
-def test_conv_channel_offset_leaves_other_layers_untouched(sq):
+@pytest.mark.parametrize("cout", [24, 32])
+def test_conv_channel_offset_leaves_other_layers_untouched(sq, cout):
     rng = np.random.default_rng(7)
     x = synth.normal01(rng, (2, 16, 27, 27))
-    w, b = synth.conv_params(rng, 24, 16, 3)
+    w, b = synth.conv_params(rng, cout, 16, 3)
     ref = oracle.conv2d(x, w, b, 1, 1, True)
+    ran = 0
     for algo in algos(sq):
-        out = torch.full((2, 40, 27, 27), -7.0, device="cuda")
+        out = torch.full((2, cout + 16, 27, 27), -7.0, device="cuda")
         try:
-            sq.sq_conv2d_forward_ex(dev(x), dev(w), dev(b), 1, 1, True, out=out, c_offset=9, algo=algo)
+            sq.sq_conv2d_forward_ws(dev(x), dev(w), dev(b), 1, 1, True, out=out, c_offset=9, algo=algo)
         except sq.SqError as e:
             assert e.status == -3
             continue
-        assert_close(out[:, 9:33], ref, FP32_TOL, f"algo {algo}")
-        assert (out[:, :9] == -7.0).all() and (out[:, 33:] == -7.0).all()
+        ran += 1
+        assert_close(out[:, 9:9 + cout], ref, FP32_TOL, f"algo {algo}")
+        assert (out[:, :9] == -7.0).all() and (out[:, 9 + cout:] == -7.0).all()
+    assert ran >= 3
 
 
 @pytest.mark.parametrize("case", [(2, 96, 55, 55, 16, 1, 1, 0), (2, 16, 27, 27, 64, 3, 1, 1),
@@ -122,7 +128,7 @@ def test_conv_bf16_inputs(sq, case):
     ref_q = oracle.conv2d(xb.float().cpu().numpy(), wb.float().cpu().numpy(), b, S, P, True)
     for algo in algos(sq):
         try:
-            got = sq.sq_conv2d_forward_ex(xb, wb, dev(b), S, P, True, algo=algo)
+            got = sq.sq_conv2d_forward_ws(xb, wb, dev(b), S, P, True, algo=algo)
         except sq.SqError as e:
             assert e.status == -3 and algo >= sq.SQ_ALGO_VARIANT0
             continue

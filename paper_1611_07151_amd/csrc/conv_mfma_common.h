@@ -142,6 +142,29 @@ __device__ __forceinline__ void buf_st(rsrc_t r, uint32_t lane_off, uint32_t uni
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)lane_off, (int)uni_off, 0);
 }
 
+// 8-byte store through a buffer resource.  The compiler's builtins for buffer accesses wider
+// than four bytes are not used in this library (the ROCm 7.2 compiler lowers the wide loads to
+// a single dword), so the instruction is written out; a store returns nothing the compiler
+// would have to wait for, and the data registers are read when it issues.
+typedef int rsrc_words_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ rsrc_words_t make_rsrc_words(const void *base, uint32_t bytes)
+{
+    const uint64_t a = (uint64_t)base;
+    rsrc_words_t r;
+    r.x = (int)(uint32_t)a;
+    r.y = (int)((uint32_t)(a >> 32) & 0xffffu);   // stride 0: raw buffer
+    r.z = (int)bytes;
+    r.w = 0x00020000;
+    return r;
+}
+__device__ __forceinline__ void buf_st2(rsrc_words_t r, uint32_t lane_off, uint32_t uni_off, float v0, float v1)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    f32x2 v;
+    v.x = v0; v.y = v1;
+    asm volatile("buffer_store_dwordx2 %0, %1, %2, %3 offen" : : "v"(v), "v"(lane_off), "s"(r), "s"(uni_off) : "memory");
+}
+
 // Input element of type TIN as fp32: float as is, uint16_t = bfloat16 (upper half of binary32).
 template <typename TIN> __device__ __forceinline__ float buf_ld_in(rsrc_t r, uint32_t lane_off, uint32_t uni_off);
 template <> __device__ __forceinline__ float buf_ld_in<float>(rsrc_t r, uint32_t lane_off, uint32_t uni_off)

@@ -35,6 +35,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "conv_mfma_common.h"
 
 namespace sq {
@@ -101,7 +103,6 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
     constexpr uint32_t ESZ = sizeof(TIN);
     using M = Mfma<32>;
     using Acc = M::Acc;
-    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
     extern __shared__ __attribute__((aligned(16))) float lds[];
 
     const int t = threadIdx.x, lane = t & 63;
@@ -183,16 +184,26 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
         }
     };
 
-    Acc acc[8];
+    // The accumulators start from the first MFMA of the first chunk, which takes a constant
+    // zero as its addend, except grid position (1, 1): that one enters all four outputs of a
+    // tile with weight +1, so starting it from the bias adds the bias to every pixel.
+    const int mw = m0 + wx * 32;                 // uniform: first layer this wavefront handles
+    const int lrow = M::row_lane(lane);
+    Acc acc[8], start11;
+    if (p.b && pr == 0) {
+        const rsrc_t rb = make_rsrc(p.b, (uint32_t)p.Cout * 4u);   // layers past Cout read zero
 #pragma unroll
-    for (int s = 0; s < 8; ++s)
+        for (int q = 0; q < 16; ++q) start11[q] = buf_ld(rb, (uint32_t)((mw + M::row_reg(q) + lrow) * 4), 0u);
+    } else {
 #pragma unroll
-        for (int q = 0; q < 16; ++q) acc[s][q] = 0.f;
+        for (int q = 0; q < 16; ++q) start11[q] = 0.f;
+    }
 
     // per-lane operand addresses: A = U[xi][kk][32 wx + li][0..3], B = V[xi][kk][li][0..3]
     const float *ua = lds + 8 * pr * 512 + kk * 256 + (32 * wx + li) * 4;
     const float *vb = lds + US + 8 * pr * (2 * BT * 4) + kk * (BT * 4) + li * 4;
-    auto compute_chunk = [&]() {
+    auto compute_chunk = [&](auto first_chunk) {
+        constexpr bool FIRST = decltype(first_chunk)::value;
         // two grid positions at a time, their MFMAs interleaved: consecutive MFMAs never
         // wait for each other's accumulator
         f32x4 a[4], b[4];
@@ -212,8 +223,18 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
-            acc[s] = M::run(a[cur2].x, b[cur2].x, acc[s]);
-            acc[s + 1] = M::run(a[cur2 + 1].x, b[cur2 + 1].x, acc[s + 1]);
+            if constexpr (FIRST) {
+                // grid position (1, 1) is accumulator 5 of the wavefronts with pr = 0; for pr = 1
+                // start11 is zero like the others
+                Acc zero;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) zero[q] = 0.f;
+                acc[s] = M::run(a[cur2].x, b[cur2].x, zero);
+                acc[s + 1] = M::run(a[cur2 + 1].x, b[cur2 + 1].x, s + 1 == 5 ? start11 : zero);
+            } else {
+                acc[s] = M::run(a[cur2].x, b[cur2].x, acc[s]);
+                acc[s + 1] = M::run(a[cur2 + 1].x, b[cur2 + 1].x, acc[s + 1]);
+            }
             acc[s] = M::run(a[cur2].y, b[cur2].y, acc[s]);
             acc[s + 1] = M::run(a[cur2 + 1].y, b[cur2 + 1].y, acc[s + 1]);
             acc[s] = M::run(a[cur2].z, b[cur2].z, acc[s]);
@@ -231,7 +252,8 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
     for (int ch = 0; ch < p.nchunks; ++ch) {
         const bool more = ch + 1 < p.nchunks;
         if (more) load_chunk(ch + 1);
-        compute_chunk();
+        if (ch == 0) compute_chunk(std::true_type{});
+        else compute_chunk(std::false_type{});
         __syncthreads();               // every wavefront is done reading the images
         if (more) {
             store_chunk();
@@ -248,25 +270,39 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
     // Exchange area: [wavefront][zz][register][lane]; the images are free by now.
     constexpr int ZQ = 16 * 64;
     static_assert(4 * 2 * ZQ <= US + VS, "exchange area must fit the staging images");
+    // keep[zz] = z(first row)[zz] + z(second row)[zz]; its sign (pr = 1: minus) goes into the
+    // final multiply-add.  The vector-ALU work here and below is kept minimal: it cannot
+    // overlap with the MFMAs of the workgroup sharing the SIMDs.
     Acc keep[2];
     {
         float *z = lds + wv * 2 * ZQ + lane;
-        const float sg = pr ? -1.f : 1.f;
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             const float z0a = acc[0][q] + acc[1][q] + acc[2][q], z1a = acc[1][q] - acc[2][q] - acc[3][q];
             const float z0b = acc[4][q] + acc[5][q] + acc[6][q], z1b = acc[5][q] - acc[6][q] - acc[7][q];
-            keep[0][q] = sg * (z0a + z0b);
-            keep[1][q] = sg * (z1a + z1b);
-            z[q * 64] = pr ? z0a : z0b;          // grid row 2 (pr = 1) or grid row 1 (pr = 0)
-            z[ZQ + q * 64] = pr ? z1a : z1b;
+            keep[0][q] = z0a + z0b;
+            keep[1][q] = z1a + z1b;
+            acc[0][q] = z0a; acc[1][q] = z1a; acc[2][q] = z0b; acc[3][q] = z1b;
+        }
+        if (pr) {   // hand over grid row 2 (first of this wavefront's rows) ...
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                z[q * 64] = acc[0][q];
+                z[ZQ + q * 64] = acc[1][q];
+            }
+        } else {    // ... or grid row 1 (second of them)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                z[q * 64] = acc[2][q];
+                z[ZQ + q * 64] = acc[3][q];
+            }
         }
     }
     __syncthreads();
-    const int mw = m0 + wx * 32;                 // uniform: first layer this wavefront writes
     if (mw >= p.Cout) return;
-    const int lrow = M::row_lane(lane);
+    const float sg = pr ? -1.f : 1.f;
     const rsrc_t rout = make_rsrc(p.out, p.out_bytes);
+    const rsrc_words_t rout2 = make_rsrc_words(p.out, p.out_bytes);
     const uint32_t hs = (uint32_t)p.HoWo * 4u;
     // this wavefront writes output row pr of its tiles: pixels (2ty + pr, 2tx) and (.., 2tx + 1)
     uint32_t o2, o1;   // lane offsets for a tile with both columns inside the image / only the first
@@ -280,30 +316,29 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
         o2 = ok && ow + 1 < p.Wo ? o : kOob;
         o1 = ok && ow + 1 >= p.Wo ? o : kOob;
     }
-    float bias[16];
-    if (p.b) {
-        const rsrc_t rb = make_rsrc(p.b, (uint32_t)p.Cout * 4u);
-#pragma unroll
-        for (int q = 0; q < 16; ++q) bias[q] = buf_ld(rb, (uint32_t)(lrow * 4), (uint32_t)(mw + M::row_reg(q)) * 4u);
-    } else {
-#pragma unroll
-        for (int q = 0; q < 16; ++q) bias[q] = 0.f;
-    }
+    // all LDS reads first, so that their latency is paid once and not per output register
     const float *zr = lds + (wv ^ 1) * 2 * ZQ + lane;
-    const bool odd_w = p.Wo & 1;
+    Acc zin[2];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        zin[0][q] = zr[q * 64];
+        zin[1][q] = zr[ZQ + q * 64];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // then all arithmetic, then all stores: a run of pure memory instructions proceeds while
+    // the other workgroup's MFMAs occupy the SIMD, a run mixed with vector-ALU work does not
+    const float lowest = p.relu ? 0.f : -__builtin_inff();
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        zin[0][q] = fmaxf(__builtin_fmaf(sg, keep[0][q], zin[0][q]), lowest);
+        zin[1][q] = fmaxf(__builtin_fmaf(sg, keep[1][q], zin[1][q]), lowest);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
         const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(mw + M::row_reg(q)) * hs;
-        float y0 = keep[0][q] + zr[q * 64] + bias[q];
-        float y1 = keep[1][q] + zr[ZQ + q * 64] + bias[q];
-        if (p.relu) {
-            y0 = fmaxf(y0, 0.f);
-            y1 = fmaxf(y1, 0.f);
-        }
-        u32x2 both;
-        both.x = __builtin_bit_cast(unsigned, y0); both.y = __builtin_bit_cast(unsigned, y1);
-        __builtin_amdgcn_raw_buffer_store_b64(both, rout, (int)o2, (int)so, 0);
-        if (odd_w) buf_st(rout, o1, so, y0);
+        buf_st2(rout2, o2, so, zin[0][q], zin[1][q]);
+        buf_st(rout, o1, so, zin[0][q]);   // tiles cut by the right edge (odd widths); dropped otherwise
     }
 }
 

@@ -5,6 +5,8 @@
 // Part 1: lane layout of the fp32 / bf16 MFMA builtins, MFMA-only throughput, copy bandwidth.
 // Part 2: does vector-ALU work overlap with fp32 MFMA?  (V extra v_fma per MFMA)
 // Part 3: cost of software-pipelined LDS reads next to fp32 MFMA (L ds_read_b32 per 4 MFMAs).
+// Part 4: two wavefronts per SIMD doing different things: one issues MFMAs only, the other
+//         vector-ALU work (or LDS writes, or global stores) only.  Do the two streams overlap?
 #include <hip/hip_runtime.h>
 #include <cmath>
 #include <cstdio>
@@ -181,10 +183,68 @@ int run_part(){ float* d; CK(hipMalloc(&d, 4096));
 
 }  // namespace part3
 
-int main()
+namespace part4 {
+// 512 threads = 8 wavefronts, two per SIMD.  Wavefronts 0-3 ("A") run 4 independent MFMAs per
+// iteration when mode & 1; wavefronts 4-7 ("B") run, per iteration, V v_fma on 4 chains, W
+// ds_write_b32 and G global stores when mode & 2.  A wavefront whose bit is clear exits at once.
+template<int KIND, int V, int W, int G> __global__ __launch_bounds__(512) void k(float* out, float* sink, int iters, int mode) {
+  __shared__ float lds[8192];
+  const int wave = threadIdx.x >> 6;
+  f16v c0={0},c1={0},c2={0},c3={0}; f4v d0={0},d1={0},d2={0},d3={0};
+  float a = threadIdx.x*0.001f, b = 1.0f, v0=a, v1=a+1, v2=a+2, v3=a+3;
+  if (wave < 4) {
+    if (!(mode & 1)) return;
+    for (int it=0; it<iters; ++it) {
+      if (KIND==0) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a,b,c0,0,0,0); c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a,b,c1,0,0,0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a,b,c2,0,0,0); c3 = __builtin_amdgcn_mfma_f32_32x32x2f32(a,b,c3,0,0,0);
+      } else {
+        d0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a,b,d0,0,0,0); d1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a,b,d1,0,0,0);
+        d2 = __builtin_amdgcn_mfma_f32_16x16x4f32(a,b,d2,0,0,0); d3 = __builtin_amdgcn_mfma_f32_16x16x4f32(a,b,d3,0,0,0);
+      }
+    }
+  } else {
+    if (!(mode & 2)) return;
+    float* g = sink + (size_t)blockIdx.x * 512 * 8 + threadIdx.x;
+    for (int it=0; it<iters; ++it) {
+#pragma unroll
+      for (int q=0;q<V;++q){ float& v = (q&3)==0?v0:(q&3)==1?v1:(q&3)==2?v2:v3; asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(v) : "v"(b), "v"(a)); }
+#pragma unroll
+      for (int q=0;q<W;++q) asm volatile("ds_write_b32 %0, %1" :: "v"((threadIdx.x*4 + q*2048) & 32767), "v"(v0) : "memory");
+#pragma unroll
+      for (int q=0;q<G;++q) g[q*512] = v1;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  }
+  float s = v0+v1+v2+v3+lds[threadIdx.x]; for (int r=0;r<16;++r) s += c0[r]+c1[r]+c2[r]+c3[r]; for (int r=0;r<4;++r) s += d0[r]+d1[r]+d2[r]+d3[r];
+  if (s == 12345.678f) out[0] = s;
+}
+template<int KIND, int V, int W, int G> void run(float* d, float* sink) {
+  const int blocks = 256, iters = 2000; hipEvent_t e0,e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+  float ms[4] = {0,0,0,0};
+  for (int mode = 1; mode <= 3; ++mode) {
+    k<KIND,V,W,G><<<blocks,512>>>(d, sink, 10, mode); CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0)); k<KIND,V,W,G><<<blocks,512>>>(d, sink, iters, mode); CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1));
+    CK(hipEventElapsedTime(&ms[mode],e0,e1));
+  }
+  printf("%s x4/iter | other wave per iter: %2d v_fma %2d ds_write %d global stores | MFMA alone %.3f ms, other alone %.3f ms, both %.3f ms (sum %.3f, max %.3f)\n",
+         KIND==0?"32x32x2":"16x16x4", V, W, G, ms[1], ms[2], ms[3], ms[1]+ms[2], ms[1]>ms[2]?ms[1]:ms[2]);
+}
+int run_part(){ float *d, *sink; CK(hipMalloc(&d, 4096)); CK(hipMalloc(&sink, (size_t)256*512*8*4));
+  run<0,16,0,0>(d,sink); run<0,32,0,0>(d,sink); run<0,64,0,0>(d,sink);
+  run<1,16,0,0>(d,sink); run<1,32,0,0>(d,sink);
+  run<0,0,16,0>(d,sink); run<0,0,32,0>(d,sink);
+  run<0,0,0,4>(d,sink); run<0,0,0,8>(d,sink);
+  run<0,16,8,2>(d,sink);
+  printf("done\n"); return 0; }
+}  // namespace part4
+
+int main(int argc, char** argv)
 {
-    part1::run_part();
-    part2::run_part();
-    part3::run_part();
+    const int only = argc > 1 ? atoi(argv[1]) : 0;   // 0 = every part
+    if (!only || only == 1) part1::run_part();
+    if (!only || only == 2) part2::run_part();
+    if (!only || only == 3) part3::run_part();
+    if (!only || only == 4) part4::run_part();
     return 0;
 }

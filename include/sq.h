@@ -10,11 +10,14 @@
  *
  * Conventions that hold for every entry point
  *   - Every data pointer is a DEVICE pointer to memory of the current HIP
- *     device, owned by the caller.  The library never allocates, frees, copies
- *     to the host or synchronises: work is enqueued on the stream given to
- *     sq_set_stream() (default: the null stream) and the call returns.
- *     The one host-side array is the parameter table of
- *     sq_squeezenet_forward, which is read before the call returns.
+ *     device, owned by the caller.  The forward calls never allocate, free,
+ *     copy to the host or synchronise: work is enqueued on the stream given
+ *     to sq_set_stream() (default: the null stream) and the call returns.
+ *     Scratch, where an operation needs it, is the caller's (the workspace
+ *     arguments).  The one host-side array is the parameter table of
+ *     sq_squeezenet_forward, which is read before the call returns.  Only the
+ *     opt-in profiler (sq_profile_begin / sq_profile_end) creates and
+ *     destroys HIP events and waits for them.
  *   - Tensors are dense and row-major.  Activations are [N][C][H][W] ("row
  *     major" order D of section "Data Reordering", one image after another),
  *     kernels are [Cout][Cin][K][K], biases [Cout].  fp32 unless stated.

@@ -64,6 +64,32 @@ def test_conv_rejects_bad_arguments_before_any_gpu_call(lib):
     assert g(FAKE, FAKE, FAKE, FAKE, *good, 4, 0, 0, 2 + lib.sq_conv_variant_count()) == -3
 
 
+def test_conv_workspace_entry_point_checks_its_scratch(lib):
+    sz = ctypes.c_size_t
+    lib.sq_conv2d_workspace_bytes.restype = sz
+    need = lib.sq_conv2d_workspace_bytes(32, 128, 3, 1, 1)
+    # transformed kernels: 16 values per (layer, input layer), layers rounded up to 64
+    assert need == 16 * 128 * 32 * 4
+    assert lib.sq_conv2d_workspace_bytes(32, 96, 3, 1, 1) == 16 * 128 * 32 * 4
+    assert lib.sq_conv2d_workspace_bytes(32, 128, 3, 2, 1) == 0     # stride 2: no algorithm needs scratch
+    assert lib.sq_conv2d_workspace_bytes(32, 128, 1, 1, 0) == 0
+    assert lib.sq_conv2d_workspace_bytes(30, 128, 3, 1, 1) == 0     # input layers not a multiple of 8
+    assert lib.sq_conv2d_workspace_bytes(0, 128, 3, 1, 1) == 0
+    h = lib.sq_conv2d_forward_ws
+    good = [1, 32, 8, 8, 128, 3, 1, 1, 1, 128, 0, 0, 0]
+    assert h(NULL, FAKE, FAKE, FAKE, *good, FAKE, sz(need)) == -1
+    assert h(FAKE, FAKE, FAKE, FAKE, *good, ctypes.c_void_p(0x1010), sz(need)) == -4   # misaligned scratch
+    bad = list(good); bad[9] = 100                                   # out_channels < Cout
+    assert h(FAKE, FAKE, FAKE, FAKE, *bad, FAKE, sz(need)) == -2
+    # the scratch-needing algorithm is refused when the scratch is missing or too small
+    names = [lib.sq_conv_variant_name(i).decode() for i in range(lib.sq_conv_variant_count())]
+    wino = 2 + [i for i, n in enumerate(names) if "f2x2" in n][0]
+    sel = list(good); sel[12] = wino
+    assert h(FAKE, FAKE, FAKE, FAKE, *sel, NULL, sz(0)) == -3
+    assert h(FAKE, FAKE, FAKE, FAKE, *sel, FAKE, sz(need - 1)) == -3
+    assert lib.sq_conv2d_forward_ex(FAKE, FAKE, FAKE, FAKE, *sel) == -3
+
+
 def test_pool_and_softmax_reject_bad_arguments(lib):
     assert lib.sq_maxpool(NULL, FAKE, 1, 1, 8, 8, 3, 2) == -1
     assert lib.sq_maxpool(FAKE, FAKE, 1, 1, 2, 8, 3, 2) == -2

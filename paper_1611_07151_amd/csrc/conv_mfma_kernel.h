@@ -236,16 +236,39 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KPa
         }
     };
 
+    // Accumulators start from the bias (zero without one), so the epilogue has no addition
+    // left: every vector-ALU instruction there would add to the run time, since such work
+    // does not overlap with the fp32 MFMAs of other wavefronts.  The layer index of a result
+    // register splits into a uniform part and a per-lane part; with a partial layer tile the
+    // whole index goes into the range-checked lane offset, so nothing is read past the end of
+    // the bias array.
+    const int mw = m0 + wm * (BM / WM);          // uniform: first layer of this wavefront
+    const int lrow = M::row_lane(lane);          // per lane
     Acc acc[TM][TN], acc1[E1 ? TM : 1][E1 ? TN : 1];
+    auto start_from_bias = [&](Acc (&a)[TM][TN], const float *bptr, int cout) {
+        if (bptr) {
+            const rsrc_t rb = make_rsrc(bptr, (uint32_t)cout * 4u);   // layers beyond cout read zero
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+            for (int x = 0; x < TM; ++x)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+                for (int r = 0; r < M::NR; ++r) {
+                    const int mu = mw + x * MT + M::row_reg(r);
+                    const float bv = full_m ? buf_ld(rb, (uint32_t)(lrow * 4), (uint32_t)mu * 4u)
+                                            : buf_ld(rb, (uint32_t)((mu + lrow) * 4), 0u);
 #pragma unroll
-            for (int r = 0; r < M::NR; ++r) {
-                acc[i][j][r] = 0.f;
-                if constexpr (E1) acc1[i][j][r] = 0.f;
-            }
+                    for (int y = 0; y < TN; ++y) a[x][y][r] = bv;
+                }
+        } else {
+#pragma unroll
+            for (int x = 0; x < TM; ++x)
+#pragma unroll
+                for (int y = 0; y < TN; ++y)
+#pragma unroll
+                    for (int r = 0; r < M::NR; ++r) a[x][y][r] = 0.f;
+        }
+    };
+    start_from_bias(acc, p.b, p.Cout);
+    if constexpr (E1) start_from_bias(acc1, p.b1, p.Cout1);
 
     // One MFMA step consumes, for every lane, one kernel value per layer block and one patch
     // value per pixel block.  LDS latency (~120 cycles) is longer than a short group of
@@ -316,34 +339,15 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KPa
         __syncthreads();
     }
 
-    // ---- epilogue: bias, ReLU, store into layers [coff, coff+Cout) ---------------------
+    // ---- epilogue: ReLU, store into layers [coff, coff+Cout) ------------------------------
     // An accumulator register holds MT consecutive pixels across lanes, so each store
-    // instruction writes contiguous runs.  The layer index splits into a uniform part
-    // (scalar address arithmetic) and a per-lane part folded into the lane's byte offset.
-    const int mw = m0 + wm * (BM / WM);          // uniform: first layer of this wavefront
-    const int lrow = M::row_lane(lane);          // per lane
+    // instruction writes contiguous runs: uniform layer part in the scalar offset, per-lane
+    // part in the lane's byte offset, one vector-ALU instruction (the ReLU) per register.
     const rsrc_t rout = make_rsrc(p.out, p.out_bytes);
     const uint32_t hs = (uint32_t)p.HoWo * 4u;
-    auto write_out = [&](Acc (&res)[TM][TN], const float *bptr, int cout, int coff) {
-        float bias[TM][M::NR];
-        if (bptr) {
-            const rsrc_t rb = make_rsrc(bptr, (uint32_t)cout * 4u);   // layers beyond cout read zero
-#pragma unroll
-            for (int x = 0; x < TM; ++x)
-#pragma unroll
-                for (int r = 0; r < M::NR; ++r) {
-                    // with a partial layer tile the whole index goes into the range-checked lane
-                    // offset, so nothing is read past the end of the bias array
-                    const int mu = mw + x * MT + M::row_reg(r);
-                    bias[x][r] = full_m ? buf_ld(rb, (uint32_t)(lrow * 4), (uint32_t)mu * 4u)
-                                        : buf_ld(rb, (uint32_t)((mu + lrow) * 4), 0u);
-                }
-        } else {
-#pragma unroll
-            for (int x = 0; x < TM; ++x)
-#pragma unroll
-                for (int r = 0; r < M::NR; ++r) bias[x][r] = 0.f;
-        }
+    const float lowest = p.relu ? 0.f : -__builtin_inff();
+    auto write_out = [&](Acc (&res)[TM][TN], int cout, int coff, auto full_tile) {
+        constexpr bool FULL = decltype(full_tile)::value;
 #pragma unroll
         for (int y = 0; y < TN; ++y) {
             const int pp = P0 + wn * (BN / WN) + y * MT + li;
@@ -356,9 +360,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KPa
 #pragma unroll
                 for (int r = 0; r < M::NR; ++r) {
                     const int mu = mw + x * MT + M::row_reg(r);
-                    float v = res[x][y][r] + bias[x][r];
-                    if (p.relu) v = fmaxf(v, 0.f);
-                    if (full_m)
+                    const float v = fmaxf(res[x][y][r], lowest);
+                    if constexpr (FULL)
                         buf_st(rout, lbase, (uint32_t)mu * hs, v);
                     else
                         buf_st(rout, mu + lrow < cout ? lbase : kOob, (uint32_t)mu * hs, v);
@@ -366,9 +369,14 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KPa
             }
         }
     };
-    if (m0 < p.Cout) write_out(acc, p.b, p.Cout, p.coff);
-    if constexpr (E1) {
-        if (m0 < p.Cout1) write_out(acc1, p.b1, p.Cout1, p.coff1);
+    if (full_m) {
+        write_out(acc, p.Cout, p.coff, std::true_type{});
+        if constexpr (E1) write_out(acc1, p.Cout1, p.coff1, std::true_type{});
+    } else {
+        if (m0 < p.Cout) write_out(acc, p.Cout, p.coff, std::false_type{});
+        if constexpr (E1) {
+            if (m0 < p.Cout1) write_out(acc1, p.Cout1, p.coff1, std::false_type{});
+        }
     }
 }
 

@@ -59,6 +59,10 @@ CONV_CASES = [
     (2, 96, 55, 55, 16, 1, 1, 0),     # squeeze
     (2, 16, 55, 55, 64, 1, 1, 0),     # expand1x1
     (3, 256, 27, 27, 48, 1, 1, 0),
+    (2, 32, 27, 27, 128, 1, 1, 0),    # more expand1x1 / squeeze shapes
+    (1, 64, 13, 13, 256, 1, 1, 0),
+    (3, 128, 55, 55, 32, 1, 1, 0),
+    (2, 16, 16, 24, 32, 1, 1, 0),     # pixel count a multiple of every tile width
     (2, 512, 13, 13, 1000, 1, 1, 0),  # conv10
     (1, 5, 9, 11, 7, 3, 1, 1),        # nothing divides anything
     (2, 7, 10, 9, 33, 1, 1, 0),
@@ -94,17 +98,17 @@ def test_conv_every_algorithm_matches_oracle(sq, case, relu):
     assert_close(sq.sq_conv2d_forward(xd, wd, None, S, P, relu), ref0, FP32_TOL, "no bias")
 
 
-@pytest.mark.parametrize("cout", [24, 32])
-def test_conv_channel_offset_leaves_other_layers_untouched(sq, cout):
+@pytest.mark.parametrize("cout,k", [(24, 3), (32, 3), (32, 1), (64, 1)])
+def test_conv_channel_offset_leaves_other_layers_untouched(sq, cout, k):
     rng = np.random.default_rng(7)
     x = synth.normal01(rng, (2, 16, 27, 27))
-    w, b = synth.conv_params(rng, cout, 16, 3)
-    ref = oracle.conv2d(x, w, b, 1, 1, True)
+    w, b = synth.conv_params(rng, cout, 16, k)
+    ref = oracle.conv2d(x, w, b, 1, k // 2, True)
     ran = 0
     for algo in algos(sq):
         out = torch.full((2, cout + 16, 27, 27), -7.0, device="cuda")
         try:
-            sq.sq_conv2d_forward_ws(dev(x), dev(w), dev(b), 1, 1, True, out=out, c_offset=9, algo=algo)
+            sq.sq_conv2d_forward_ws(dev(x), dev(w), dev(b), 1, k // 2, True, out=out, c_offset=9, algo=algo)
         except sq.SqError as e:
             assert e.status == -3
             continue

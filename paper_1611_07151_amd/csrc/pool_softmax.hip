@@ -4,6 +4,8 @@
 // its output once.
 #include "sq_internal.h"
 
+#include <algorithm>
+
 namespace sq {
 namespace {
 
@@ -34,8 +36,11 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const float *__restrict__ 
 // column 2l+2 from its neighbour lane.  Output row oh is written by lanes l < Wo.
 template <int LP>
 __global__ __launch_bounds__(256) void maxpool3s2_kernel(const float *__restrict__ in, float *__restrict__ out,
-                                                         size_t planes, int H, int W, int Ho, int Wo)
+                                                         size_t planes, int H, int W, int Ho, int Wo, int RB)
 {
+    // blockIdx.y selects a band of RB output rows (a multiple of four): small batches have too
+    // few planes to fill the chip with one wavefront group per plane
+    const int oh_begin = blockIdx.y * RB, oh_end = min(oh_begin + RB, Ho);
     const int lane = threadIdx.x & 63, sub = lane / LP, l = lane % LP;
     const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const size_t pl = wave * (64 / LP) + sub;
@@ -53,11 +58,11 @@ __global__ __launch_bounds__(256) void maxpool3s2_kernel(const float *__restrict
         b = v1;
     };
     float a0, b0;
-    load2(0, a0, b0);
+    load2(2 * oh_begin, a0, b0);
     // four output rows per trip: the eight row loads of a trip are independent and issued
     // together (rows past the end are clamped for the load and never stored)
     constexpr int U = 4;
-    for (int oh0 = 0; oh0 < Ho; oh0 += U) {
+    for (int oh0 = oh_begin; oh0 < oh_end; oh0 += U) {
         float a[2 * U], b[2 * U];
 #pragma unroll
         for (int u = 0; u < 2 * U; ++u) load2(min(2 * oh0 + 1 + u, H - 1), a[u], b[u]);
@@ -66,7 +71,7 @@ __global__ __launch_bounds__(256) void maxpool3s2_kernel(const float *__restrict
             const float ma = has0 ? fmaxf(fmaxf(a0, a[2 * u]), a[2 * u + 1]) : -INFINITY;
             const float mb = has1 ? fmaxf(fmaxf(b0, b[2 * u]), b[2 * u + 1]) : -INFINITY;
             const float mc = __shfl_down(ma, 1, LP);     // column 2l+2
-            if (live && l < Wo && oh0 + u < Ho) dst[(size_t)(oh0 + u) * Wo + l] = fmaxf(fmaxf(ma, mb), mc);
+            if (live && l < Wo && oh0 + u < oh_end) dst[(size_t)(oh0 + u) * Wo + l] = fmaxf(fmaxf(ma, mb), mc);
             a0 = a[2 * u + 1];
             b0 = b[2 * u + 1];
         }
@@ -145,7 +150,14 @@ int maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int 
         const size_t groups = (waves + 3) / 4;
         if (groups < (1u << 31)) {
             auto fn = LP == 16 ? maxpool3s2_kernel<16> : LP == 32 ? maxpool3s2_kernel<32> : maxpool3s2_kernel<64>;
-            hipLaunchKernelGGL(fn, dim3((unsigned)groups), dim3(256), 0, current_stream(), in, out, planes, H, W, Ho, Wo);
+            // with few planes, split the rows of a plane into bands so that about 2048 wavefronts exist
+            const int max_bands = (Ho + 3) / 4;
+            int bands = (int)std::min<size_t>((size_t)max_bands, (2048 + waves - 1) / waves);
+            if (bands < 1) bands = 1;
+            const int RB = ((Ho + bands - 1) / bands + 3) / 4 * 4;
+            bands = (Ho + RB - 1) / RB;
+            hipLaunchKernelGGL(fn, dim3((unsigned)groups, (unsigned)bands), dim3(256), 0, current_stream(), in, out, planes,
+                               H, W, Ho, Wo, RB);
             return check_launch();
         }
     }

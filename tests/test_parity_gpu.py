@@ -265,6 +265,26 @@ def test_squeezenet_batch64_sampled_images(sq):
     _check_network(sq, cfg, [0, 37, 63])
 
 
+def test_benchmark_configuration_runs_the_kernels_it_reports(sq):
+    """The batch-64 pass is served by the matrix-core kernels the benchmark's roofline names:
+    the persistent conv1 kernel, the minimal-filtering kernel on transformed kernels for the
+    large expand3x3 layers, the tiled family elsewhere -- never by the one-thread-per-output
+    fallback."""
+    cfg = synth.config_squeezenet(seed=3, n=64)
+    x, params = dev(cfg["x"]), [dev(p) for p in cfg["params"]]
+    sq.sq_squeezenet_forward(x, params)
+    sq.sq_profile_begin(64)
+    sq.sq_squeezenet_forward(x, params)
+    torch.cuda.synchronize()
+    names = [r["name"] for r in sq.sq_profile_end()]
+    kernels = {n.split("|")[1] for n in names}
+    assert "conv1|k7s2c3_waves8" in names
+    assert any(n.startswith("fire4/e3|k3s1_f2x2_") for n in names), names
+    assert "kernel transform|f2x2_kernel_transform" in names
+    assert not any("direct" in k for k in kernels), kernels
+    assert len(names) == 32          # 26 convolutions, 3 + 1 pools, softmax, kernel transform
+
+
 # ----------------------------------------------------------------- workload 5
 def test_layer_sweep_bf16_batch256_sampled_images(sq):
     """Every convolution shape at batch 256 with bf16 inputs and kernels; the

@@ -30,6 +30,7 @@
 #include "conv_mfma_variants.h"
 
 #include <math.h>
+#include <algorithm>
 #include <string.h>
 
 namespace sq {
@@ -176,6 +177,7 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
         blocks = (tiles + NW - 1) / NW;
         if (blocks > num_cus()) blocks = num_cus();
     } else if (v.wino) {
+        blocks = std::min<long long>(blocks, 2ll * num_cus());   // persistent: two workgroups per CU
         pl.lds_bytes = (size_t)(kWinoImage + 16 * 2 * kWinoBT * 4) * sizeof(float);
     } else {
         pl.lds_bytes = ((size_t)v.NBUF * v.BM * LDK + (size_t)v.NBUF * v.CC * k.plane +

@@ -27,8 +27,8 @@
 // 16-byte LDS read feeds four MFMAs.  Every thread transforms the patch of one (tile, input
 // layer) and copies eight 16-byte pieces of U per chunk: the global loads of chunk c+1 are
 // issued before the MFMAs of chunk c and their results go to LDS between two barriers
-// afterwards.  Two workgroups share a CU (256 registers per wavefront), so one multiplies
-// while the other stages, transforms or stores.  At the end a wavefront folds its two grid
+// afterwards.  Two persistent workgroups share a CU (256 registers per wavefront) and loop
+// over tiles.  At the end a wavefront folds its two grid
 // rows with A and half of A^T, swaps the other half with its partner (pr ^ 1) through LDS,
 // and writes output row pr of its tiles.
 #pragma once
@@ -110,7 +110,12 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
     const int pr = wv & 1, wx = wv >> 1;
     const int li = lane & 31, kk = lane >> 5;
 
-    const int bid = xcd_remap(blockIdx.x, gridDim.x);
+    // Persistent workgroups (two per CU): a workgroup that retires keeps its registers and LDS
+    // until its last stores have drained; looping over tiles lets the next tile start behind them.
+    const int ntile_blocks = p.mtiles * p.ntiles;
+    for (int bid_raw = blockIdx.x; bid_raw < ntile_blocks; bid_raw += gridDim.x) {
+    if (bid_raw != (int)blockIdx.x) __syncthreads();   // the exchange area of the previous tile has been read out
+    const int bid = xcd_remap(bid_raw, ntile_blocks);
     const int tb = fdiv(bid, p.dMtiles);
     const int mt = bid - tb * p.mtiles, m0 = mt * BM, t0 = tb * BT;
 
@@ -299,7 +304,7 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
         }
     }
     __syncthreads();
-    if (mw >= p.Cout) return;
+    if (mw >= p.Cout) continue;
     const float sg = pr ? -1.f : 1.f;
     const rsrc_t rout = make_rsrc(p.out, p.out_bytes);
     const rsrc_words_t rout2 = make_rsrc_words(p.out, p.out_bytes);
@@ -340,6 +345,7 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
         buf_st2(rout2, o2, so, zin[0][q], zin[1][q]);
         buf_st(rout, o1, so, zin[0][q]);   // tiles cut by the right edge (odd widths); dropped otherwise
     }
+    }   // tiles of this workgroup
 }
 
 }  // namespace mfma

@@ -292,7 +292,7 @@ def test_layer_sweep_bf16_batch256_sampled_images(sq):
     n = 256
     for name, x, w, b, s, p in synth.config_layer_sweep(seed=4, n=n):
         xb, wb = dev(x, torch.bfloat16), dev(w, torch.bfloat16)
-        got = sq.sq_conv2d_forward_ex(xb, wb, dev(b), s, p, True)
+        got = sq.sq_conv2d_forward_ws(xb, wb, dev(b), s, p, True)     # scratch given: every algorithm may be chosen
         for i in (0, n - 1):
             ref = oracle.conv2d(x[i:i + 1], w, b, s, p, True)
             assert_close(got[i:i + 1], ref, BF16_TOL, f"{name} image {i}")

@@ -16,6 +16,11 @@ durations behind `roofline` and `layers`, and its own step time is reported as
 launch, so it is a little slower).  `cpu_baseline` is the CPU oracle timed on the host
 cores on a bounded sample of the same workload.
 
+`energy` is the analogue of the paper's power table (section "Power Consumption"): the GPU's
+own power sensor is sampled while idle (before any kernel runs) and while forward passes run
+back to back for --energy-seconds; energy per image = power x time per image, given both for
+the total power and for the differential (load minus idle) power, as the paper does.
+
 `python bench.py --calibrate-copy` instead runs a plain 1 GiB device-to-device copy a few
 times and exits; it is the known-size kernel that the HBM byte counters are scaled by.
 """
@@ -36,6 +41,38 @@ HBM_PEAK_GBS = 8000.0
 FLOP_PER_IMAGE = 2 * 832_667_936  # 2 x multiply-accumulates of the 26 convolutions
 
 
+def power_sensor():
+    """Path of the GPU's power reading (hwmon, microwatts), or None."""
+    import glob
+    for pat in ("power1_input", "power1_average"):
+        hits = sorted(glob.glob(f"/sys/class/drm/card*/device/hwmon/hwmon*/{pat}"))
+        if hits:
+            return hits[0]
+    return None
+
+
+def sample_power(path, seconds, work, settle=0.0):
+    """Calls work() over and over for `seconds` and reads the sensor between calls (at most every
+    5 ms); readings of the first `settle` seconds are dropped.  Mean in watts."""
+    vals, t0, last = [], time.perf_counter(), 0.0
+    while True:
+        now = time.perf_counter() - t0
+        if now >= seconds + settle:
+            break
+        work()
+        if now - last >= 0.005:
+            last = now
+            try:
+                v = int(open(path).read())
+            except (OSError, ValueError):
+                continue
+            if now >= settle:
+                vals.append(v * 1e-6)
+    if not vals:
+        return dict(mean_w=float("nan"), samples=0)
+    return dict(mean_w=sum(vals) / len(vals), samples=len(vals))
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -46,6 +83,11 @@ def main() -> int:
     ap.add_argument("--layer-sweep", choices=["f32", "bf16"], default=None,
                     help="instead of the network: time every convolution shape on its own at --batch "
                          "(workload 5 is --layer-sweep bf16 --batch 256) and print one JSON line")
+    ap.add_argument("--net", choices=["squeezenet", "second"], default="squeezenet",
+                    help="layer list of --layer-sweep: SqueezeNet's 26 convolutions, or the five of a second CNN "
+                         "(11x11 stride 4, 5x5, 3x3)")
+    ap.add_argument("--energy-seconds", type=float, default=3.0,
+                    help="length of each power-sampling window (0 = leave the energy measurement out)")
     ap.add_argument("--skip-batch1", action="store_true", help="leave the batch-1 timing out (for profiler runs)")
     ap.add_argument("--cpu-sample", type=int, default=32,
                     help="images of the workload the CPU oracle is timed on (0 = skip)")
@@ -79,12 +121,19 @@ def main() -> int:
                           "launches": 5}))
         return 0
 
+    sensor = power_sensor()
+    idle_w = None
+    if sensor and args.energy_seconds > 0 and not args.layer_sweep:
+        torch.cuda.synchronize()                       # context is up, nothing has run yet
+        idle_w = sample_power(sensor, min(2.0, args.energy_seconds), lambda: time.sleep(0.01))
+
     if args.layer_sweep:
         dt_in = torch.bfloat16 if args.layer_sweep == "bf16" else torch.float32
         esz = 2 if args.layer_sweep == "bf16" else 4
         gen = torch.Generator(device="cuda").manual_seed(4)
         layers, total_flop, total_us = {}, 0.0, 0.0
-        for name, cin, cout, k, s_, p_, h in synth.conv_layers():
+        net_layers = synth.conv_layers() if args.net == "squeezenet" else synth.second_network_layers()
+        for name, cin, cout, k, s_, p_, h in net_layers:
             ho = (h + 2 * p_ - k) // s_ + 1
             x = torch.randn((B, cin, h, h), device="cuda", generator=gen).to(dt_in)
             w = (torch.randn((cout, cin, k, k), device="cuda", generator=gen) * (2.0 / (cin * k * k)) ** 0.5).to(dt_in)
@@ -107,9 +156,9 @@ def main() -> int:
             total_us += us
             del x, w, out
         print(json.dumps({"metric": f"per-layer convolution sweep, batch {B}, {args.layer_sweep} inputs, fp32 accumulate/output",
-                          "value": round(total_flop / total_us / 1e6, 2), "unit": "TFLOP/s (all 26 layers)",
+                          "value": round(total_flop / total_us / 1e6, 2), "unit": "TFLOP/s (all layers)",
                           "n_gpus": 1, "dtype": args.layer_sweep, "data": "synthetic",
-                          "config": {"workload": f"26 SqueezeNet convolution shapes at batch {B}"},
+                          "config": {"workload": f"{len(net_layers)} convolution shapes ({args.net}) at batch {B}"},
                           "total_us": round(total_us, 1), "layers": layers}))
         return 0
 
@@ -200,6 +249,30 @@ def main() -> int:
         torch.cuda.synchronize()
         dt1g = time.perf_counter() - t0
 
+    # ---------------------------------------------------------------- energy per image
+    energy = None
+    if idle_w is not None:
+        def run_for(xx, pp, ww, oo, n):
+            def burst():
+                for _ in range(8):
+                    sq.sq_squeezenet_forward(xx, pp, workspace=ww, probs=oo)
+                torch.cuda.synchronize()
+            load = sample_power(sensor, args.energy_seconds, burst, settle=0.5)
+            t0, reps = time.perf_counter(), 0
+            while time.perf_counter() - t0 < 0.5:
+                burst()
+                reps += 8
+            s_per_image = (time.perf_counter() - t0) / (reps * n)
+            return dict(load_w=round(load["mean_w"], 1), differential_w=round(load["mean_w"] - idle_w["mean_w"], 1),
+                        samples=load["samples"], ms_per_image=round(s_per_image * 1e3, 5),
+                        j_per_image_total=round(load["mean_w"] * s_per_image, 6),
+                        j_per_image_differential=round((load["mean_w"] - idle_w["mean_w"]) * s_per_image, 6))
+        energy = dict(source=sensor + " (GPU package power, microwatts)", idle_w=round(idle_w["mean_w"], 1),
+                      idle_samples=idle_w["samples"], window_s=args.energy_seconds)
+        energy[f"batch{B}"] = run_for(x, params, ws, probs, B)
+        if not args.skip_batch1:
+            energy["batch1"] = run_for(x1, params1, ws1, probs1, 1)
+
     # ---------------------------------------------------------------- CPU oracle baseline
     cpu = None
     if args.cpu_sample > 0:
@@ -230,7 +303,7 @@ def main() -> int:
         "batch1_graph_images_per_sec": None if args.skip_batch1 else round(k1 / dt1g, 1),
         "batch1_graph_matches_eager": graph_ok,
         "ms_per_step_with_events": round(dt_events / K * 1e3, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "layers": layers,
+        "roofline": roofline, "cpu_baseline": cpu, "energy": energy, "layers": layers,
     }
     print(json.dumps(out))
     return 0

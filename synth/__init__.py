@@ -35,6 +35,16 @@ def conv_layers():
     return layers
 
 
+def second_network_layers():
+    """Convolution shapes of a second, different CNN (the paper's scheme is meant for any CNN,
+    section "Introduction"): the five convolutions of the classic 2012 ImageNet network in its
+    ungrouped single-tower form -- 11x11 stride 4, 5x5 pad 2 and three 3x3 pad 1 layers on
+    227 -> 55 -> 27 -> 13 feature maps.  Same tuple layout as conv_layers()."""
+    return [("c1_11x11s4", 3, 96, 11, 4, 0, 227), ("c2_5x5p2", 96, 256, 5, 1, 2, 27),
+            ("c3_3x3p1", 256, 384, 3, 1, 1, 13), ("c4_3x3p1", 384, 384, 3, 1, 1, 13),
+            ("c5_3x3p1", 384, 256, 3, 1, 1, 13)]
+
+
 def fire_layers():
     return list(_FIRES)
 
@@ -97,12 +107,13 @@ def config_squeezenet(seed: int = 2, n: int = 1):
     return dict(x=x, params=squeezenet_params(rng))
 
 
-def config_layer_sweep(seed: int = 4, n: int = 256, only=None):
+def config_layer_sweep(seed: int = 4, n: int = 256, only=None, layers=None):
     """Workload 5: every convolution shape on its own, normal(0,1) inputs.
     Yields (name, x, w, b, stride, pad) one layer at a time (the tensors are large).
     Each layer has its own stream, keyed by (seed, layer name), so a selection of
-    layers sees the same numbers as the full sweep."""
-    for name, cin, cout, k, s, p, h in conv_layers():
+    layers sees the same numbers as the full sweep.  `layers` replaces the SqueezeNet
+    list (second_network_layers() for the second workload)."""
+    for name, cin, cout, k, s, p, h in (conv_layers() if layers is None else layers):
         if only is not None and name not in only:
             continue
         lrng = np.random.default_rng([seed, hash_name(name)])

@@ -68,6 +68,9 @@ CONV_CASES = [
     (2, 7, 10, 9, 33, 1, 1, 0),
     (1, 4, 12, 12, 5, 5, 1, 2),       # a kernel size outside the network
     (1, 2, 9, 9, 3, 3, 2, 0),
+    (2, 24, 27, 27, 80, 5, 1, 2),     # 5x5 and 11x11 stride 4: the second network's kernel sizes
+    (2, 3, 67, 71, 96, 11, 4, 0),
+    (1, 6, 30, 30, 16, 11, 4, 2),
     (1, 1, 1, 1, 1, 1, 1, 0),         # degenerate: one element
     (1, 3, 3, 3, 2, 3, 1, 0),         # single output pixel
 ]
@@ -298,6 +301,19 @@ def test_layer_sweep_bf16_batch256_sampled_images(sq):
             assert_close(got[i:i + 1], ref, BF16_TOL, f"{name} image {i}")
         del xb, wb, got
         torch.cuda.empty_cache()
+
+
+def test_second_network_layers_match_oracle(sq):
+    """The convolution shapes of a different CNN (11x11 stride 4, 5x5 pad 2, 3x3 pad 1 on
+    227/27/13 maps) through the same entry point, batch 2, fp32."""
+    kernels = set()
+    for name, x, w, b, s, p in synth.config_layer_sweep(seed=6, n=2, layers=synth.second_network_layers()):
+        ref = oracle.conv2d(x, w, b, s, p, True)
+        sq.sq_profile_begin(8)
+        got = sq.sq_conv2d_forward_ws(dev(x), dev(w), dev(b), s, p, True)
+        kernels |= {r["name"].split("|")[1] for r in sq.sq_profile_end()}
+        assert_close(got, ref, FP32_TOL, name)
+    assert not any("direct" in k for k in kernels), kernels     # served by the matrix-core kernels
 
 
 def test_same_input_twice_is_bit_identical(sq):

@@ -211,6 +211,66 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
 size_t sq_squeezenet_workspace_bytes(int N);
 
 /*
+ * Reduced-precision path (the counterpart of the paper's relaxed-precision mode,
+ * section "Imprecise computing", on the layer-private vector layout of sections
+ * "Data Reordering" and "Zero-overhead vectorization"): feature maps and kernels are
+ * bfloat16, every sum is accumulated in fp32, biases stay fp32, and every layer
+ * writes its result directly in the layout the next one reads.
+ *
+ * Blocked map: [N][ceil(C/8)][H][W][8] bfloat16 (device) -- the eight layers
+ * 8k..8k+7 of one pixel are adjacent; layers past C in the last block hold zero.
+ * sq_blocked_map_bytes() is its size.  sq_blocked_pack() converts an NCHW tensor
+ * (in_dtype SQ_F32 or SQ_BF16; fp32 values are rounded to nearest even) into it,
+ * sq_blocked_unpack() converts a blocked map back to fp32 NCHW (exact).
+ *
+ * Packed kernels: sq_blocked_pack_kernels() re-orders the kernels [Cout][Cin][K][K]
+ * (w_dtype SQ_F32 or SQ_BF16) of one convolution once, ahead of time, into the order
+ * the matrix cores read them (sq_blocked_kernel_bytes() bytes, 16-byte aligned).
+ *
+ * sq_blocked_conv2d_forward(): K x K convolution, stride 1, zero padding P = (K-1)/2
+ * (K = 1, 3 or 5), +bias, optional ReLU, on a blocked map; the Cout results, rounded
+ * to bfloat16, go to layers [c_offset, c_offset+Cout) of a blocked map with
+ * ldc_channels layers (the concatenation hook of the fire layer).  Cin must be a
+ * multiple of 16; Cout, ldc_channels and c_offset multiples of 8; the kernels of 32
+ * output layers (K*K*Cin*64 bytes) must fit half the LDS -- otherwise
+ * SQ_ERR_UNSUPPORTED.  in and out must not overlap.
+ * sq_blocked_maxpool(): K x K window, stride S, floor mode, no padding.
+ * sq_blocked_avgpool_global(): mean over H x W of each layer, fp32 [N][C] out.
+ * Errors: SQ_ERR_NULL, SQ_ERR_SHAPE, SQ_ERR_UNSUPPORTED, SQ_ERR_HIP.
+ */
+size_t sq_blocked_map_bytes(int N, int C, int H, int W);
+int sq_blocked_pack(const void *in, sq_dtype in_dtype, void *out, int N, int C, int H, int W);
+int sq_blocked_unpack(const void *in, float *out, int N, int C, int H, int W);
+size_t sq_blocked_kernel_bytes(int Cout, int Cin, int K);
+int sq_blocked_pack_kernels(const void *w, sq_dtype w_dtype, void *packed, int Cout, int Cin, int K);
+int sq_blocked_conv2d_forward(const void *in, const void *packed_w, const float *b, void *out,
+                              int N, int Cin, int H, int W, int Cout, int K, int P, int relu,
+                              int ldc_channels, int c_offset);
+int sq_blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S);
+int sq_blocked_avgpool_global(const void *in, float *out, int N, int C, int H, int W);
+
+/*
+ * SqueezeNet v1.0 forward in reduced precision: the network of sq_squeezenet_forward
+ * with bfloat16 feature maps and kernels (fp32 sums, fp32 biases, fp32 class means
+ * and probabilities).  conv1 reads the NCHW image (in_dtype SQ_F32, or SQ_BF16 for a
+ * bfloat16 image) and writes a blocked map; everything after it stays blocked.
+ *   params  as for sq_squeezenet_forward (fp32; only the biases are read here).
+ *   packed  device buffer of sq_squeezenet_bf16_packed_bytes() bytes, 256-byte
+ *           aligned, filled once by sq_squeezenet_bf16_pack_params(params, packed,
+ *           bytes) -- the ahead-of-time kernel re-ordering.
+ *   workspace: at least sq_squeezenet_bf16_workspace_bytes(N) bytes, 256-byte aligned.
+ *   taps    as for sq_squeezenet_forward: fp32 NCHW copies of the stage results
+ *           (converted back from the blocked maps); NULL in timed runs.
+ * Errors: SQ_ERR_NULL, SQ_ERR_SHAPE, SQ_ERR_WORKSPACE, SQ_ERR_UNSUPPORTED, SQ_ERR_HIP.
+ */
+size_t sq_squeezenet_bf16_packed_bytes(void);
+int sq_squeezenet_bf16_pack_params(const void *const *params, void *packed, size_t packed_bytes);
+size_t sq_squeezenet_bf16_workspace_bytes(int N);
+int sq_squeezenet_forward_bf16(const void *in, sq_dtype in_dtype, const void *const *params,
+                               const void *packed, float *probs, int N, void *workspace,
+                               size_t workspace_bytes, float *const *taps);
+
+/*
  * Per-launch timing, off by default.  Between sq_profile_begin() and sq_profile_end()
  * every kernel the library launches from this host thread is bracketed by a pair of
  * HIP events on the library's stream.  These two calls are the only ones in the

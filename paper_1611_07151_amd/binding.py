@@ -42,6 +42,23 @@ lib.sq_squeezenet_forward.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _i, _vp, _s
 lib.sq_squeezenet_workspace_bytes.restype = _sz
 lib.sq_squeezenet_workspace_bytes.argtypes = [_i]
 
+lib.sq_blocked_map_bytes.restype = _sz
+lib.sq_blocked_map_bytes.argtypes = [_i] * 4
+lib.sq_blocked_pack.argtypes = [_vp, _i, _vp] + [_i] * 4
+lib.sq_blocked_unpack.argtypes = [_vp, _vp] + [_i] * 4
+lib.sq_blocked_kernel_bytes.restype = _sz
+lib.sq_blocked_kernel_bytes.argtypes = [_i] * 3
+lib.sq_blocked_pack_kernels.argtypes = [_vp, _i, _vp] + [_i] * 3
+lib.sq_blocked_conv2d_forward.argtypes = [_vp] * 4 + [_i] * 10
+lib.sq_blocked_maxpool.argtypes = [_vp, _vp] + [_i] * 6
+lib.sq_blocked_avgpool_global.argtypes = [_vp, _vp] + [_i] * 4
+lib.sq_squeezenet_bf16_packed_bytes.restype = _sz
+lib.sq_squeezenet_bf16_packed_bytes.argtypes = []
+lib.sq_squeezenet_bf16_pack_params.argtypes = [ctypes.POINTER(_vp), _vp, _sz]
+lib.sq_squeezenet_bf16_workspace_bytes.restype = _sz
+lib.sq_squeezenet_bf16_workspace_bytes.argtypes = [_i]
+lib.sq_squeezenet_forward_bf16.argtypes = [_vp, _i, ctypes.POINTER(_vp), _vp, _vp, _i, _vp, _sz, ctypes.POINTER(_vp)]
+
 lib.sq_profile_begin.argtypes = [_i]
 lib.sq_profile_get.argtypes = [_i, ctypes.c_char_p, _i, ctypes.POINTER(ctypes.c_longlong),
                                ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
@@ -245,6 +262,141 @@ def sq_squeezenet_forward(x, params, workspace=None, probs=None, want_taps=False
     rc = lib.sq_squeezenet_forward(_dev(x, torch.float32, "x"), parr, _dev(probs, torch.float32, "probs"),
                                    N, _dev(workspace), workspace.numel() * workspace.element_size(), tarr)
     _check(rc, "sq_squeezenet_forward")
+    return (probs, taps) if want_taps else probs
+
+
+def _dtype_code(t, name):
+    if t.dtype == torch.float32:
+        return SQ_F32
+    if t.dtype == torch.bfloat16:
+        return SQ_BF16
+    raise ValueError(f"{name} must be float32 or bfloat16")
+
+
+def sq_blocked_map_bytes(N, C, H, W) -> int:
+    return int(lib.sq_blocked_map_bytes(N, C, H, W))
+
+
+def _new_map(N, C, H, W, device):
+    """Blocked map [N][ceil(C/8)][H][W][8] as a bfloat16 tensor."""
+    return torch.empty((N, (C + 7) // 8, H, W, 8), device=device, dtype=torch.bfloat16)
+
+
+def sq_blocked_pack(x):
+    """NCHW float32 / bfloat16 -> blocked bfloat16 map [N][ceil(C/8)][H][W][8]."""
+    N, C, H, W = x.shape
+    out = _new_map(N, C, H, W, x.device)
+    _use_current_stream()
+    _check(lib.sq_blocked_pack(_dev(x, None, "x"), _dtype_code(x, "x"), _dev(out), N, C, H, W), "sq_blocked_pack")
+    return out
+
+
+def sq_blocked_unpack(m, C):
+    """Blocked map -> NCHW float32 with C layers."""
+    N, CB, H, W, _ = m.shape
+    if m.shape[4] != 8 or (C + 7) // 8 != CB:
+        raise ValueError("not a blocked map of C layers")
+    out = torch.empty((N, C, H, W), device=m.device, dtype=torch.float32)
+    _use_current_stream()
+    _check(lib.sq_blocked_unpack(_dev(m, torch.bfloat16, "m"), _dev(out), N, C, H, W), "sq_blocked_unpack")
+    return out
+
+
+def sq_blocked_kernel_bytes(Cout, Cin, K) -> int:
+    return int(lib.sq_blocked_kernel_bytes(Cout, Cin, K))
+
+
+def sq_blocked_pack_kernels(w):
+    """Kernels [Cout][Cin][K][K] (float32 / bfloat16) -> packed buffer (uint8 tensor)."""
+    Cout, Cin, K, K2 = w.shape
+    if K != K2:
+        raise ValueError("square kernels only")
+    out = torch.empty(sq_blocked_kernel_bytes(Cout, Cin, K), device=w.device, dtype=torch.uint8)
+    _use_current_stream()
+    _check(lib.sq_blocked_pack_kernels(_dev(w, None, "w"), _dtype_code(w, "w"), _dev(out), Cout, Cin, K),
+           "sq_blocked_pack_kernels")
+    return out
+
+
+def sq_blocked_conv2d_forward(m, packed_w, b, Cin, Cout, K, pad, relu=False, out=None, c_offset=0):
+    """m: blocked map of Cin layers; out: blocked map (default: a new one of Cout layers)."""
+    N, CB, H, W, _ = m.shape
+    if m.shape[4] != 8 or (Cin + 7) // 8 != CB:
+        raise ValueError("not a blocked map of Cin layers")
+    if out is None:
+        out = _new_map(N, Cout, H, W, m.device)
+    if tuple(out.shape[:1] + out.shape[2:]) != (N, H, W, 8):
+        raise ValueError("output map shape")
+    _use_current_stream()
+    rc = lib.sq_blocked_conv2d_forward(_dev(m, torch.bfloat16, "m"), _dev(packed_w, torch.uint8, "packed_w"),
+                                       _dev(b, torch.float32, "b"), _dev(out, torch.bfloat16, "out"), N, Cin, H, W,
+                                       Cout, int(K), int(pad), 1 if relu else 0, out.shape[1] * 8, int(c_offset))
+    _check(rc, "sq_blocked_conv2d_forward")
+    return out
+
+
+def sq_blocked_maxpool(m, C, k, stride):
+    N, CB, H, W, _ = m.shape
+    if H < k or W < k:
+        _check(-2, "sq_blocked_maxpool")
+    out = _new_map(N, C, (H - k) // stride + 1, (W - k) // stride + 1, m.device)
+    _use_current_stream()
+    _check(lib.sq_blocked_maxpool(_dev(m, torch.bfloat16, "m"), _dev(out), N, C, H, W, int(k), int(stride)),
+           "sq_blocked_maxpool")
+    return out
+
+
+def sq_blocked_avgpool_global(m, C):
+    N, CB, H, W, _ = m.shape
+    out = torch.empty((N, C), device=m.device, dtype=torch.float32)
+    _use_current_stream()
+    _check(lib.sq_blocked_avgpool_global(_dev(m, torch.bfloat16, "m"), _dev(out), N, C, H, W),
+           "sq_blocked_avgpool_global")
+    return out
+
+
+def sq_squeezenet_bf16_packed_bytes() -> int:
+    return int(lib.sq_squeezenet_bf16_packed_bytes())
+
+
+def sq_squeezenet_bf16_pack_params(params):
+    """One-time re-ordering of the 26 kernels (52 float32 parameter tensors in) -> packed uint8 tensor."""
+    if len(params) != 52:
+        raise ValueError("expects 52 parameter tensors")
+    out = torch.empty(sq_squeezenet_bf16_packed_bytes(), device=params[0].device, dtype=torch.uint8)
+    parr = (_vp * 52)(*[_dev(p, torch.float32, f"params[{i}]") for i, p in enumerate(params)])
+    _use_current_stream()
+    _check(lib.sq_squeezenet_bf16_pack_params(parr, _dev(out), out.numel()), "sq_squeezenet_bf16_pack_params")
+    return out
+
+
+def sq_squeezenet_bf16_workspace_bytes(N) -> int:
+    return int(lib.sq_squeezenet_bf16_workspace_bytes(int(N)))
+
+
+def sq_squeezenet_forward_bf16(x, params, packed, workspace=None, probs=None, want_taps=False):
+    """x [N,3,224,224] float32 or bfloat16; params as for sq_squeezenet_forward; packed from
+    sq_squeezenet_bf16_pack_params.  Returns probs, or (probs, taps) with float32 NCHW stage copies."""
+    N = x.shape[0]
+    if tuple(x.shape[1:]) != (3, 224, 224) or len(params) != 52:
+        raise ValueError("expects [N,3,224,224] and 52 parameter tensors")
+    if workspace is None:
+        workspace = torch.empty(sq_squeezenet_bf16_workspace_bytes(N), device=x.device, dtype=torch.uint8)
+    if probs is None:
+        probs = torch.empty((N, 1000), device=x.device, dtype=torch.float32)
+    parr = (_vp * 52)(*[_dev(p, torch.float32, f"params[{i}]") for i, p in enumerate(params)])
+    taps, tarr = {}, None
+    if want_taps:
+        for name, (c, h) in zip(TAP_NAMES, TAP_SHAPES):
+            taps[name] = torch.empty((N, c, h, h), device=x.device, dtype=torch.float32)
+        taps["means"] = torch.empty((N, 1000), device=x.device, dtype=torch.float32)
+        taps["probs"] = torch.empty((N, 1000), device=x.device, dtype=torch.float32)
+        tarr = (_vp * 16)(*([taps[n].data_ptr() for n in TAP_NAMES] + [None]))
+    _use_current_stream()
+    rc = lib.sq_squeezenet_forward_bf16(_dev(x, None, "x"), _dtype_code(x, "x"), parr, _dev(packed, torch.uint8, "packed"),
+                                        _dev(probs, torch.float32, "probs"), N, _dev(workspace),
+                                        workspace.numel() * workspace.element_size(), tarr)
+    _check(rc, "sq_squeezenet_forward_bf16")
     return (probs, taps) if want_taps else probs
 
 

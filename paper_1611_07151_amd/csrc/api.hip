@@ -99,7 +99,7 @@ ConvArgs make_args(const void *in, const void *w, const float *b, float *out, in
     a.out_channels = out_channels;
     a.c_offset = c_offset;
     a.dtype = dtype;
-    a.ws = nullptr; a.ws_bytes = 0; a.ws_ready = false;
+    a.ws = nullptr; a.ws_bytes = 0; a.ws_ready = false; a.out_blocked = false;
     return a;
 }
 
@@ -434,6 +434,196 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
     if ((rc = copy_tap(taps, 12, nxt, n * 1000 * H * H))) return rc;
     set_stage("avgpool");
     if ((rc = avgpool_global(nxt, means, N, 1000, H, H))) return rc;
+    if ((rc = copy_tap(taps, 13, means, n * 1000))) return rc;
+    set_stage("softmax");
+    if ((rc = softmax(means, probs, N, 1000))) return rc;
+    set_stage("");
+    return copy_tap(taps, 14, probs, n * 1000);
+}
+
+// ---- reduced-precision path on blocked bfloat16 maps -------------------------------------
+size_t sq_blocked_map_bytes(int N, int C, int H, int W)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return 0;
+    return blocked_map_bytes(N, C, H, W);
+}
+
+int sq_blocked_pack(const void *in, sq_dtype in_dtype, void *out, int N, int C, int H, int W)
+{
+    if (!in || !out) return SQ_ERR_NULL;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return SQ_ERR_SHAPE;
+    if (in_dtype != SQ_F32 && in_dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    return blocked_pack_map(in, in_dtype, out, N, C, H, W);
+}
+
+int sq_blocked_unpack(const void *in, float *out, int N, int C, int H, int W)
+{
+    if (!in || !out) return SQ_ERR_NULL;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return SQ_ERR_SHAPE;
+    return blocked_unpack_map(in, out, N, C, H, W);
+}
+
+size_t sq_blocked_kernel_bytes(int Cout, int Cin, int K)
+{
+    if (Cout <= 0 || Cin <= 0 || K <= 0) return 0;
+    return blocked_packed_kernel_bytes(Cout, Cin, K);
+}
+
+int sq_blocked_pack_kernels(const void *w, sq_dtype w_dtype, void *packed, int Cout, int Cin, int K)
+{
+    if (!w || !packed) return SQ_ERR_NULL;
+    if (Cout <= 0 || Cin <= 0 || K <= 0) return SQ_ERR_SHAPE;
+    if (w_dtype != SQ_F32 && w_dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if ((uintptr_t)packed & 15) return SQ_ERR_UNSUPPORTED;
+    return blocked_pack_kernels(w, w_dtype, packed, Cout, Cin, K);
+}
+
+int sq_blocked_conv2d_forward(const void *in, const void *packed_w, const float *b, void *out, int N, int Cin, int H,
+                              int W, int Cout, int K, int P, int relu, int ldc_channels, int c_offset)
+{
+    if (!in || !packed_w || !out) return SQ_ERR_NULL;
+    if (N <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || K <= 0 || P < 0) return SQ_ERR_SHAPE;
+    if (c_offset < 0 || ldc_channels < c_offset + Cout) return SQ_ERR_SHAPE;
+    if (((uintptr_t)in & 15) || ((uintptr_t)out & 15) || ((uintptr_t)packed_w & 15)) return SQ_ERR_UNSUPPORTED;
+    return blocked_conv(in, packed_w, b, out, N, Cin, H, W, Cout, K, P, relu ? 1 : 0, ldc_channels, c_offset);
+}
+
+int sq_blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S)
+{
+    if (!in || !out) return SQ_ERR_NULL;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || S < 1 || H < K || W < K) return SQ_ERR_SHAPE;
+    return blocked_maxpool(in, out, N, C, H, W, K, S);
+}
+
+int sq_blocked_avgpool_global(const void *in, float *out, int N, int C, int H, int W)
+{
+    if (!in || !out) return SQ_ERR_NULL;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return SQ_ERR_SHAPE;
+    return blocked_avgpool_global(in, out, N, C, H, W);
+}
+
+namespace {
+// (Cout, Cin, K) of convolution i of the network, i = 0 (conv1) .. 25 (conv10)
+void net_conv_shape(int i, int &cout, int &cin, int &k)
+{
+    if (i == 0) { cout = 96; cin = 3; k = 7; return; }
+    if (i == 25) { cout = 1000; cin = 512; k = 1; return; }
+    const int f = (i - 1) / 3, part = (i - 1) % 3;
+    const FireCfg &fc = kFires[f];
+    if (part == 0) { cout = fc.sq; cin = fc.cin; k = 1; }
+    else { cout = fc.e; cin = fc.sq; k = part == 1 ? 1 : 3; }
+}
+// byte offset of convolution i's packed kernels inside the packed buffer (conv1: its kernels as plain
+// bfloat16 [96][3][7][7], which the conv1 kernel stages itself)
+size_t net_packed_offset(int i)
+{
+    size_t off = 0;
+    for (int q = 0; q < i; ++q) {
+        int cout, cin, k;
+        net_conv_shape(q, cout, cin, k);
+        off += align_up(q == 0 ? (size_t)96 * 3 * 49 * 2 : blocked_packed_kernel_bytes(cout, cin, k), 256);
+    }
+    return off;
+}
+}  // namespace
+
+size_t sq_squeezenet_bf16_packed_bytes(void) { return net_packed_offset(26); }
+
+int sq_squeezenet_bf16_pack_params(const void *const *params, void *packed, size_t packed_bytes)
+{
+    if (!params || !packed) return SQ_ERR_NULL;
+    for (int i = 0; i < 52; ++i)
+        if (!params[i]) return SQ_ERR_NULL;
+    if (((uintptr_t)packed & 255) || packed_bytes < sq_squeezenet_bf16_packed_bytes()) return SQ_ERR_WORKSPACE;
+    // conv1: [96][3][7][7] -> bfloat16, same order
+    int rc = blocked_convert_bf16((const float *)params[0], packed, 96 * 3 * 49);
+    if (rc) return rc;
+    for (int i = 1; i < 26; ++i) {
+        int cout, cin, k;
+        net_conv_shape(i, cout, cin, k);
+        if ((rc = blocked_pack_kernels(params[2 * i], SQ_F32, (char *)packed + net_packed_offset(i), cout, cin, k))) return rc;
+    }
+    return SQ_OK;
+}
+
+size_t sq_squeezenet_bf16_workspace_bytes(int N)
+{
+    if (N <= 0) return 0;
+    const size_t n = (size_t)N;
+    // two alternating maps, the squeeze map, the class means (element counts as in the fp32 network, 2 bytes each)
+    return align_up(n * kBufA * 2, 256) + align_up(n * kBufB * 2, 256) + align_up(n * kBufS * 2, 256) +
+           align_up(n * 1000 * 4, 256);
+}
+
+int sq_squeezenet_forward_bf16(const void *in, sq_dtype in_dtype, const void *const *params, const void *packed,
+                               float *probs, int N, void *workspace, size_t workspace_bytes, float *const *taps)
+{
+    if (!in || !params || !packed || !probs) return SQ_ERR_NULL;
+    if (N <= 0) return SQ_ERR_SHAPE;
+    if (in_dtype != SQ_F32 && in_dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    for (int i = 0; i < 52; ++i)
+        if (!params[i]) return SQ_ERR_NULL;
+    if (taps && taps[15]) return SQ_ERR_UNSUPPORTED;
+    if ((uintptr_t)packed & 255) return SQ_ERR_WORKSPACE;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < sq_squeezenet_bf16_workspace_bytes(N))
+        return SQ_ERR_WORKSPACE;
+
+    const size_t n = (size_t)N;
+    char *base = (char *)workspace;
+    char *bufA = base;
+    char *bufB = bufA + align_up(n * kBufA * 2, 256);
+    char *bufS = bufB + align_up(n * kBufB * 2, 256);
+    float *means = (float *)(bufS + align_up(n * kBufS * 2, 256));
+    auto B = [&](int conv) { return (const float *)params[2 * conv + 1]; };
+    auto WP = [&](int conv) { return (const void *)((const char *)packed + net_packed_offset(conv)); };
+    // fp32 NCHW copy of a blocked stage result for the caller
+    auto tap_out = [&](int i, const void *map, int C, int H) -> int {
+        if (!taps || !taps[i]) return SQ_OK;
+        return blocked_unpack_map(map, taps[i], N, C, H, H);
+    };
+
+    int rc = SQ_OK;
+    set_stage("conv1");
+    {
+        // the conv1 kernel reads image and kernels in one type: fp32 image with the fp32 kernels, bfloat16
+        // image with the bfloat16 copy of the kernels
+        ConvArgs a = make_args(in, in_dtype == SQ_BF16 ? WP(0) : params[0], B(0), (float *)bufA, N, 3, 224, 224, 96, 7, 2, 2,
+                               1, 96, 0, in_dtype);
+        a.out_blocked = true;
+        if ((rc = conv_mfma(a, -1))) return rc;
+    }
+    if ((rc = tap_out(0, bufA, 96, 111))) return rc;
+    set_stage("pool1");
+    if ((rc = blocked_maxpool(bufA, bufB, N, 96, 111, 111, 3, 2))) return rc;
+    if ((rc = tap_out(1, bufB, 96, 55))) return rc;
+
+    char *cur = bufB, *nxt = bufA;
+    int C = 96, H = 55, tap = 2;
+    for (int f = 0; f < 8; ++f) {
+        const FireCfg &fc = kFires[f];
+        const int c0 = 1 + 3 * f;
+        set_stage(kFireStages[f][0]);
+        if ((rc = blocked_conv(cur, WP(c0), B(c0), bufS, N, C, H, H, fc.sq, 1, 0, 1, fc.sq, 0))) return rc;
+        set_stage(kFireStages[f][1]);
+        if ((rc = blocked_conv(bufS, WP(c0 + 1), B(c0 + 1), nxt, N, fc.sq, H, H, fc.e, 1, 0, 1, 2 * fc.e, 0))) return rc;
+        set_stage(kFireStages[f][2]);
+        if ((rc = blocked_conv(bufS, WP(c0 + 2), B(c0 + 2), nxt, N, fc.sq, H, H, fc.e, 3, 1, 1, 2 * fc.e, fc.e))) return rc;
+        C = 2 * fc.e;
+        if ((rc = tap_out(tap++, nxt, C, H))) return rc;
+        { char *t = cur; cur = nxt; nxt = t; }
+        if (f == 2 || f == 6) {
+            set_stage(f == 2 ? "pool4" : "pool8");
+            if ((rc = blocked_maxpool(cur, nxt, N, C, H, H, 3, 2))) return rc;
+            H = (H - 3) / 2 + 1;
+            if ((rc = tap_out(tap++, nxt, C, H))) return rc;
+            { char *t = cur; cur = nxt; nxt = t; }
+        }
+    }
+    set_stage("conv10");
+    if ((rc = blocked_conv(cur, WP(25), B(25), nxt, N, 512, H, H, 1000, 1, 0, 1, 1000, 0))) return rc;
+    if ((rc = tap_out(12, nxt, 1000, H))) return rc;
+    set_stage("avgpool");
+    if ((rc = blocked_avgpool_global(nxt, means, N, 1000, H, H))) return rc;
     if ((rc = copy_tap(taps, 13, means, n * 1000))) return rc;
     set_stage("softmax");
     if ((rc = softmax(means, probs, N, 1000))) return rc;

@@ -1,0 +1,526 @@
+// Reduced-precision path: feature maps and kernels in bfloat16, sums in fp32 (the
+// counterpart of the paper's relaxed-precision mode, section "Imprecise computing"; its
+// layer-private vector layout, sections "Data Reordering" and "Zero-overhead
+// vectorization", is used here with vectors of eight layers).
+//
+// Layout ("blocked"): a feature map of C layers is stored as [N][ceil(C/8)][H][W][8]
+// bfloat16 -- the eight layers 8k..8k+7 of one pixel are one 16-byte element, which is
+// exactly the operand a lane feeds to v_mfma_f32_32x32x16_bf16 (8 consecutive k values).
+// Every layer of the network writes its output directly in this layout, so nothing is
+// ever re-ordered between layers.  Layers past C in the last block are zero.
+//
+// Kernels are packed once (offline in the paper's terms) into MFMA A-operand order:
+//   wp[ceil(Cout/32)][K*K][Cin/16][64 lanes][8]:  lane l holds output layer 32*mb + l%32,
+//   tap t, input layers 16*g + 8*(l/32) .. +7.
+//
+// Convolution kernel (K x K, stride 1, pad (K-1)/2).  D(32 layers x 32 pixels) +=
+// A(32 x 16) B(16 x 32) per MFMA, with A = packed kernels from LDS (one 16-byte read per
+// lane) and B = one 16-byte element per lane loaded straight from global memory into the
+// operand registers (pixel l%32 of the tile, shifted by the tap; layer block 2g + l/32).
+// A persistent workgroup of 8 wavefronts owns 32*CB output layers, keeps all their
+// kernels in LDS and walks over tiles of 32*PB pixels; the wavefronts are autonomous
+// after the one barrier.  Loads run D steps ahead of the MFMAs in a register ring.  Zero
+// padding comes from the buffer range check (an invalid tap gets an out-of-range
+// offset).  Results leave as 8-byte stores (four consecutive layers of one pixel), which
+// a wavefront lays down as 512 contiguous bytes per layer block.
+#include "conv_mfma_common.h"
+
+namespace sq {
+namespace blocked {
+
+using namespace mfma;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 512, kWaves = kThreads / 64;
+
+__device__ __forceinline__ uint32_t pack2(float a, float b) { return pack_bf16x2(a, b); }   // round to nearest even
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
+
+// ------------------------------------------------------------------------------- layout
+// NCHW (fp32 or bf16) -> blocked bf16.  One thread per 16-byte element.
+template <typename TIN>
+__global__ void pack_map_kernel(const TIN *in, u32x4 *out, int N, int C, int HW, int CB, FastDiv dHW, FastDiv dCB)
+{
+    const long long total = (long long)N * CB * HW;
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long long)gridDim.x * blockDim.x) {
+        const int ncb = fdiv((int)e, dHW), pix = (int)e - ncb * HW;
+        const int n = fdiv(ncb, dCB), cb = ncb - n * CB;
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int c = cb * 8 + k;
+            float x = 0.f;
+            if (c < C) {
+                const TIN raw = in[((size_t)n * C + c) * HW + pix];
+                if constexpr (sizeof(TIN) == 4) x = raw;
+                else x = __builtin_bit_cast(float, (uint32_t)raw << 16);
+            }
+            v[k] = x;
+        }
+        u32x4 o = {pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])};
+        out[e] = o;
+    }
+}
+
+// blocked bf16 -> NCHW fp32.  One thread per 16-byte element.
+__global__ void unpack_map_kernel(const u32x4 *in, float *out, int N, int C, int HW, int CB, FastDiv dHW, FastDiv dCB)
+{
+    const long long total = (long long)N * CB * HW;
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long long)gridDim.x * blockDim.x) {
+        const int ncb = fdiv((int)e, dHW), pix = (int)e - ncb * HW;
+        const int n = fdiv(ncb, dCB), cb = ncb - n * CB;
+        const u32x4 v = in[e];
+        const float f[8] = {bf_lo(v.x), bf_hi(v.x), bf_lo(v.y), bf_hi(v.y), bf_lo(v.z), bf_hi(v.z), bf_lo(v.w), bf_hi(v.w)};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int c = cb * 8 + k;
+            if (c < C) out[((size_t)n * C + c) * HW + pix] = f[k];
+        }
+    }
+}
+
+// fp32 -> bfloat16 (nearest even), same order.
+__global__ void convert_bf16_kernel(const float *in, uint16_t *out, int n)
+{
+    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < n; e += gridDim.x * blockDim.x)
+        out[e] = (uint16_t)(pack2(in[e], 0.f) & 0xffffu);
+}
+
+// [Cout][Cin][K][K] (fp32 or bf16) -> MFMA A-operand order (see the header of this file).
+template <typename TIN>
+__global__ void pack_kernels_kernel(const TIN *w, u32x4 *wp, int Cout, int Cin, int KK, int G, int total)
+{
+    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gridDim.x * blockDim.x) {
+        const int lane = e & 63;
+        int r = e >> 6;
+        const int g = r % G;
+        r /= G;
+        const int tap = r % KK, mb = r / KK;
+        const int m = mb * 32 + (lane & 31), c0 = g * 16 + 8 * (lane >> 5);
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int c = c0 + k;
+            float x = 0.f;
+            if (m < Cout && c < Cin) {
+                const TIN raw = w[((size_t)m * Cin + c) * KK + tap];
+                if constexpr (sizeof(TIN) == 4) x = raw;
+                else x = __builtin_bit_cast(float, (uint32_t)raw << 16);
+            }
+            v[k] = x;
+        }
+        u32x4 o = {pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])};
+        wp[e] = o;
+    }
+}
+
+// --------------------------------------------------------------------------- convolution
+struct ConvParams {
+    const void *in;      // blocked [N][Cin/8][H][W][8]
+    const void *wp;      // packed kernels
+    const float *b;      // [Cout] or nullptr
+    void *out;           // blocked [N][ldcb][H][W][8]
+    uint32_t in_bytes, out_bytes, wp_elems;   // wp_elems: 16-byte elements of wp
+    int N, Cin, H, W, HW, Cout, K, P, relu;
+    int G;               // Cin / 16
+    int steps;           // K*K*G, a multiple of the ring depth
+    int ldcb, coffb;     // layer blocks (of 8) per image in `out`, first block written
+    int PT;              // N*H*W
+    int tiles;           // pixel tiles of 32*PB
+    int ncblk;           // groups of 32*CB output layers = workgroups that share a pixel range
+    FastDiv dHW, dW, dG, dK, dNcblk;
+};
+
+template <int CB, int PB, int D>
+__global__ __launch_bounds__(kThreads, 2) void conv_blocked_kernel(const ConvParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    u32x4 *const wl = reinterpret_cast<u32x4 *>(smem);                 // [CB][steps][64] A operands
+    const int per_mb = p.steps * 64;                                      // 16-byte elements per 32 layers
+    float *const bl = reinterpret_cast<float *>(smem + (size_t)CB * per_mb * 16);   // [CB*32] bias
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int j = lane & 31, h = lane >> 5;
+    const int slot = fdiv((int)blockIdx.x, p.dNcblk), cblk = (int)blockIdx.x - slot * p.ncblk;
+    const int nslots = (int)gridDim.x / p.ncblk;          // the host launches a multiple of ncblk
+    const int mb0 = cblk * CB;                            // first block of 32 output layers
+
+    // ---- this workgroup's kernels and bias into LDS (a straight copy: they are packed) ----
+    {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(p.wp);
+        const uint32_t first = (uint32_t)mb0 * (uint32_t)per_mb;
+        for (int e = t; e < CB * per_mb; e += kThreads) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (first + (uint32_t)e < p.wp_elems) v = src[first + e];
+            wl[e] = v;
+        }
+        if (t < CB * 32) {
+            const int m = mb0 * 32 + t;
+            bl[t] = (p.b && m < p.Cout) ? p.b[m] : 0.f;
+        }
+    }
+    __syncthreads();   // the only barrier
+
+    const rsrc_t rin = make_rsrc(p.in, p.in_bytes);
+    const rsrc_t rout = make_rsrc(p.out, p.out_bytes);
+    const float lowest = p.relu ? 0.f : -__builtin_inff();
+    const uint32_t hw16 = (uint32_t)p.HW * 16u;
+    const int KK = p.K * p.K;
+
+    for (int tile = slot * kWaves + wv; tile < p.tiles; tile += nslots * kWaves) {
+        // ---- this lane's pixels: input offset (layer block h of a pair), output offset, tap validity
+        uint32_t ibase[PB], obase[PB], vmask[PB];
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            const int gp = (tile * PB + pb) * 32 + j;
+            const bool ok = gp < p.PT;
+            const int gq = ok ? gp : 0;
+            const int n = fdiv(gq, p.dHW), pix = gq - n * p.HW;
+            const int y = fdiv(pix, p.dW), x = pix - y * p.W;
+            ibase[pb] = (uint32_t)((n * (p.Cin >> 3) + h) * p.HW + pix) * 16u;
+            obase[pb] = ok ? (uint32_t)((n * p.ldcb + p.coffb) * p.HW + pix) * 16u + 8u * (uint32_t)h : kOob;
+            uint32_t m = 0;
+            for (int tap = 0; tap < KK; ++tap) {
+                const int ky = fdiv(tap, p.dK), kx = tap - ky * p.K;
+                const bool v = ok && (unsigned)(y + ky - p.P) < (unsigned)p.H && (unsigned)(x + kx - p.P) < (unsigned)p.W;
+                m |= (v ? 1u : 0u) << tap;
+            }
+            vmask[pb] = m;
+        }
+
+        // input of step s = (tap, pair of layer blocks g): one 16-byte element per lane and pixel block,
+        // loaded as four adjacent dwords the compiler merges
+        float bx[D][PB][4];
+        auto issue = [&](int ring, int s_) {
+            const int s = __builtin_amdgcn_readfirstlane(s_);
+            const int tap = fdiv(s, p.dG), g = s - tap * p.G;
+            const int ky = fdiv(tap, p.dK), kx = tap - ky * p.K;
+            const int shift = ((ky - p.P) * p.W + (kx - p.P)) * 16;
+            const uint32_t so = (uint32_t)g * 2u * hw16;
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb) {
+                uint32_t off = ((vmask[pb] >> tap) & 1u) ? ibase[pb] + (uint32_t)shift : kOob;
+                asm volatile("" : "+v"(off));   // keeps +4, +8, +12 as immediates so that the four loads merge
+#pragma unroll
+                for (int q = 0; q < 4; ++q) bx[ring][pb][q] = buf_ld(rin, off + 4u * q, so);
+            }
+        };
+#pragma unroll
+        for (int r = 0; r < D; ++r) issue(r, r);
+
+        // ---- accumulators start from the bias: registers 4q..4q+3 = layers 8q + 4h .. +3 of the block
+        f32x16 acc[CB][PB];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 bv = *reinterpret_cast<const f32x4 *>(bl + cb * 32 + 8 * q + 4 * h);
+#pragma unroll
+                for (int pb = 0; pb < PB; ++pb) {
+                    acc[cb][pb][4 * q + 0] = bv.x; acc[cb][pb][4 * q + 1] = bv.y;
+                    acc[cb][pb][4 * q + 2] = bv.z; acc[cb][pb][4 * q + 3] = bv.w;
+                }
+            }
+
+        auto compute = [&](int ring, int s) {
+            bf16x8 a[CB];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) a[cb] = __builtin_bit_cast(bf16x8, wl[(cb * p.steps + s) * 64 + lane]);
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb) {
+                f32x4 raw = {bx[ring][pb][0], bx[ring][pb][1], bx[ring][pb][2], bx[ring][pb][3]};
+                const bf16x8 b = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    acc[cb][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cb], b, acc[cb][pb], 0, 0, 0);
+            }
+        };
+        int s0 = 0;
+        for (; s0 < p.steps - D; s0 += D) {
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                compute(r, s0 + r);
+                issue(r, s0 + r + D);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < D; ++r) compute(r, s0 + r);
+
+        // ---- ReLU, round to bfloat16, 8-byte stores
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int lb = (mb0 + cb) * 4 + q;              // layer block (of 8) inside this convolution
+                if (lb * 8 < p.Cout) {                            // uniform
+                    const uint32_t so = (uint32_t)lb * hw16;
+#pragma unroll
+                    for (int pb = 0; pb < PB; ++pb) {
+                        const float v0 = fmaxf(acc[cb][pb][4 * q + 0], lowest), v1 = fmaxf(acc[cb][pb][4 * q + 1], lowest);
+                        const float v2 = fmaxf(acc[cb][pb][4 * q + 2], lowest), v3 = fmaxf(acc[cb][pb][4 * q + 3], lowest);
+                        buf_st2(rout, obase[pb], so, __builtin_bit_cast(float, pack2(v0, v1)),
+                                __builtin_bit_cast(float, pack2(v2, v3)));
+                    }
+                }
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------- pooling
+// Max pooling K x K stride S (floor mode, no padding) on blocked maps: one thread per
+// 16-byte output element (eight layers of one pixel).
+__global__ void maxpool_blocked_kernel(const u32x4 *in, u32x4 *out, int planes, int H, int W, int Ho, int Wo, int K, int S,
+                                       FastDiv dWo, FastDiv dHoWo)
+{
+    const long long total = (long long)planes * Ho * Wo;
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long long)gridDim.x * blockDim.x) {
+        const int pl = fdiv((int)e, dHoWo), rem = (int)e - pl * Ho * Wo;
+        const int oh = fdiv(rem, dWo), ow = rem - oh * Wo;
+        const u32x4 *src = in + ((size_t)pl * H + oh * S) * W + ow * S;
+        float m[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) m[k] = -__builtin_inff();
+        for (int i = 0; i < K; ++i)
+            for (int jx = 0; jx < K; ++jx) {
+                const u32x4 v = src[i * W + jx];
+                m[0] = fmaxf(m[0], bf_lo(v.x)); m[1] = fmaxf(m[1], bf_hi(v.x));
+                m[2] = fmaxf(m[2], bf_lo(v.y)); m[3] = fmaxf(m[3], bf_hi(v.y));
+                m[4] = fmaxf(m[4], bf_lo(v.z)); m[5] = fmaxf(m[5], bf_hi(v.z));
+                m[6] = fmaxf(m[6], bf_lo(v.w)); m[7] = fmaxf(m[7], bf_hi(v.w));
+            }
+        // the maxima are bfloat16 values already: keeping the upper halves is exact
+        u32x4 o;
+        o.x = (__builtin_bit_cast(uint32_t, m[0]) >> 16) | (__builtin_bit_cast(uint32_t, m[1]) & 0xffff0000u);
+        o.y = (__builtin_bit_cast(uint32_t, m[2]) >> 16) | (__builtin_bit_cast(uint32_t, m[3]) & 0xffff0000u);
+        o.z = (__builtin_bit_cast(uint32_t, m[4]) >> 16) | (__builtin_bit_cast(uint32_t, m[5]) & 0xffff0000u);
+        o.w = (__builtin_bit_cast(uint32_t, m[6]) >> 16) | (__builtin_bit_cast(uint32_t, m[7]) & 0xffff0000u);
+        out[e] = o;
+    }
+}
+
+// Global average pooling of a blocked map into fp32 [N][C]: one wavefront per (image, layer block).
+__global__ __launch_bounds__(256) void avgpool_blocked_kernel(const u32x4 *in, float *out, int planes, int C, int CB, int HW,
+                                                              FastDiv dCB)
+{
+    const int lane = threadIdx.x & 63;
+    const int pl = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (pl >= planes) return;
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int pix = lane; pix < HW; pix += 64) {
+        const u32x4 v = in[(size_t)pl * HW + pix];
+        s[0] += bf_lo(v.x); s[1] += bf_hi(v.x); s[2] += bf_lo(v.y); s[3] += bf_hi(v.y);
+        s[4] += bf_lo(v.z); s[5] += bf_hi(v.z); s[6] += bf_lo(v.w); s[7] += bf_hi(v.w);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) s[k] += __shfl_xor(s[k], d, 64);
+    if (lane < 8) {
+        const int n = fdiv(pl, dCB), cb = pl - n * CB, c = cb * 8 + lane;
+        float v = s[0];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) v = lane == k ? s[k] : v;
+        if (c < C) out[(size_t)n * C + c] = v / (float)HW;
+    }
+}
+
+}  // namespace blocked
+
+// ------------------------------------------------------------------------------ host side
+using namespace blocked;
+
+namespace {
+
+int grid_for(long long total, int threads)
+{
+    long long b = (total + threads - 1) / threads;
+    const long long cap = 256ll * 32;
+    if (b > cap) b = cap;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+int num_cus_blocked()
+{
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+        (void)hipGetLastError();
+    }
+    return cus;
+}
+
+typedef void (*BlockedConvFn)(const ConvParams);
+template <int CB, int PB> BlockedConvFn conv_fn(int D)
+{
+    switch (D) {
+        case 4: return conv_blocked_kernel<CB, PB, 4>;
+        case 3: return conv_blocked_kernel<CB, PB, 3>;
+        case 2: return conv_blocked_kernel<CB, PB, 2>;
+        default: return conv_blocked_kernel<CB, PB, 1>;
+    }
+}
+
+bool allow_lds(BlockedConvFn fn)
+{
+    static BlockedConvFn done[16];
+    static int ndone = 0;
+    for (int i = 0; i < ndone; ++i)
+        if (done[i] == fn) return true;
+    if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, mfma::kLdsBytes) != hipSuccess) return false;
+    if (ndone < 16) done[ndone++] = fn;
+    return true;
+}
+
+}  // namespace
+
+// Tuning hook (not part of the public interface): ring depth to use where it divides the step count.
+int g_force_depth = 0;
+extern "C" void sq_internal_blocked_force_depth(int d) { g_force_depth = d; }
+
+size_t blocked_map_bytes(int N, int C, int H, int W) { return (size_t)N * ((C + 7) / 8) * H * W * 16; }
+
+size_t blocked_packed_kernel_bytes(int Cout, int Cin, int K)
+{
+    return (size_t)((Cout + 31) / 32) * K * K * ((Cin + 15) / 16) * 64 * 16;
+}
+
+int blocked_pack_map(const void *in, int dtype, void *out, int N, int C, int H, int W)
+{
+    const int CB = (C + 7) / 8, HW = H * W;
+    const long long total = (long long)N * CB * HW;
+    if (total >= (1ll << 31)) return SQ_ERR_UNSUPPORTED;
+    LaunchScope scope("pack_map", 0.0, (dtype == SQ_BF16 ? 2.0 : 4.0) * N * C * HW + 16.0 * total);
+    if (dtype == SQ_BF16)
+        hipLaunchKernelGGL(pack_map_kernel<uint16_t>, dim3(grid_for(total, 256)), dim3(256), 0, current_stream(),
+                           (const uint16_t *)in, (u32x4 *)out, N, C, HW, CB, make_fastdiv(HW), make_fastdiv(CB));
+    else
+        hipLaunchKernelGGL(pack_map_kernel<float>, dim3(grid_for(total, 256)), dim3(256), 0, current_stream(),
+                           (const float *)in, (u32x4 *)out, N, C, HW, CB, make_fastdiv(HW), make_fastdiv(CB));
+    return check_launch();
+}
+
+int blocked_unpack_map(const void *in, float *out, int N, int C, int H, int W)
+{
+    const int CB = (C + 7) / 8, HW = H * W;
+    const long long total = (long long)N * CB * HW;
+    if (total >= (1ll << 31)) return SQ_ERR_UNSUPPORTED;
+    LaunchScope scope("unpack_map", 0.0, 4.0 * N * C * HW + 16.0 * total);
+    hipLaunchKernelGGL(unpack_map_kernel, dim3(grid_for(total, 256)), dim3(256), 0, current_stream(), (const u32x4 *)in, out, N,
+                       C, HW, CB, make_fastdiv(HW), make_fastdiv(CB));
+    return check_launch();
+}
+
+int blocked_convert_bf16(const float *in, void *out, int n)
+{
+    LaunchScope scope("convert_bf16", 0.0, 6.0 * n);
+    hipLaunchKernelGGL(convert_bf16_kernel, dim3(grid_for(n, 256)), dim3(256), 0, current_stream(), in, (uint16_t *)out, n);
+    return check_launch();
+}
+
+int blocked_pack_kernels(const void *w, int dtype, void *packed, int Cout, int Cin, int K)
+{
+    const int G = (Cin + 15) / 16, KK = K * K;
+    const long long total = (long long)((Cout + 31) / 32) * KK * G * 64;
+    if (total >= (1ll << 31)) return SQ_ERR_UNSUPPORTED;
+    LaunchScope scope("pack_kernels", 0.0, (dtype == SQ_BF16 ? 2.0 : 4.0) * Cout * Cin * KK + 16.0 * total);
+    if (dtype == SQ_BF16)
+        hipLaunchKernelGGL(pack_kernels_kernel<uint16_t>, dim3(grid_for(total, 256)), dim3(256), 0, current_stream(),
+                           (const uint16_t *)w, (u32x4 *)packed, Cout, Cin, KK, G, (int)total);
+    else
+        hipLaunchKernelGGL(pack_kernels_kernel<float>, dim3(grid_for(total, 256)), dim3(256), 0, current_stream(),
+                           (const float *)w, (u32x4 *)packed, Cout, Cin, KK, G, (int)total);
+    return check_launch();
+}
+
+// Whether the blocked convolution kernel covers this shape (the checks need no GPU).
+bool blocked_conv_supported(int Cin, int Cout, int K, int P)
+{
+    if (K < 1 || K > 5 || (K & 1) == 0 || P != (K - 1) / 2) return false;
+    if (Cin % 16 != 0 || Cout % 8 != 0) return false;
+    // kernels of 32 output layers must fit LDS with room for a second workgroup
+    const size_t per_mb = (size_t)K * K * (Cin / 16) * 64 * 16;
+    return per_mb + 256 <= (size_t)mfma::kLdsBytes / 2;
+}
+
+int blocked_conv(const void *in, const void *wp, const float *b, void *out, int N, int Cin, int H, int W, int Cout, int K, int P,
+                 int relu, int ldc_channels, int c_offset)
+{
+    if (!blocked_conv_supported(Cin, Cout, K, P) || ldc_channels % 8 != 0 || c_offset % 8 != 0) return SQ_ERR_UNSUPPORTED;
+    const long long in_bytes = (long long)blocked_map_bytes(N, Cin, H, W);
+    const long long out_bytes = (long long)blocked_map_bytes(N, ldc_channels, H, W);
+    const long long PT = (long long)N * H * W;
+    if (in_bytes >= (1ll << 31) || out_bytes >= (1ll << 31) || PT >= (1ll << 30)) return SQ_ERR_UNSUPPORTED;
+
+    ConvParams p;
+    p.in = in; p.wp = wp; p.b = b; p.out = out;
+    p.in_bytes = (uint32_t)in_bytes; p.out_bytes = (uint32_t)out_bytes;
+    p.wp_elems = (uint32_t)(blocked_packed_kernel_bytes(Cout, Cin, K) / 16);
+    p.N = N; p.Cin = Cin; p.H = H; p.W = W; p.HW = H * W; p.Cout = Cout; p.K = K; p.P = P; p.relu = relu;
+    p.G = Cin / 16;
+    p.steps = K * K * p.G;
+    p.ldcb = ldc_channels / 8; p.coffb = c_offset / 8;
+    p.PT = (int)PT;
+    p.dHW = make_fastdiv(p.HW); p.dW = make_fastdiv(W); p.dG = make_fastdiv(p.G); p.dK = make_fastdiv(K);
+
+    // 64 output layers per workgroup when their kernels fit half the LDS, else 32
+    const size_t per_mb = (size_t)p.steps * 64 * 16;
+    const int CB = (Cout > 32 && 2 * per_mb + 512 <= (size_t)mfma::kLdsBytes / 2) ? 2 : 1;
+    constexpr int PB = 2;
+    p.tiles = (int)((PT + 32 * PB - 1) / (32 * PB));
+    p.ncblk = (Cout + 32 * CB - 1) / (32 * CB);
+    p.dNcblk = make_fastdiv(p.ncblk);
+    int D = p.steps % 4 == 0 ? 4 : p.steps % 3 == 0 ? 3 : p.steps % 2 == 0 ? 2 : 1;
+    if (g_force_depth > 0 && p.steps % g_force_depth == 0) D = g_force_depth;
+    BlockedConvFn fn = CB == 2 ? conv_fn<2, PB>(D) : conv_fn<1, PB>(D);
+    if (!allow_lds(fn)) {
+        const int rc = check_launch();
+        return rc ? rc : SQ_ERR_HIP;
+    }
+    // persistent: at most two workgroups per CU, and no more than there are tiles to hand out
+    long long slots = (2ll * num_cus_blocked()) / p.ncblk;
+    const long long need = (p.tiles + kWaves - 1) / kWaves;
+    if (slots > need) slots = need;
+    if (slots < 1) slots = 1;
+    const size_t lds = (size_t)CB * per_mb + (size_t)CB * 32 * sizeof(float);
+    // the profiler keeps the pointer: one permanent string per (K, CB, D)
+    static char names[6][3][5][24];
+    char *name = names[K][CB][D];
+    if (!name[0]) snprintf(name, sizeof names[0][0][0], "k%db_%dx%d_d%d", K, 32 * CB, 32 * PB, D);
+    LaunchScope scope(name, 2.0 * N * Cout * H * W * (double)Cin * K * K,
+                      2.0 * ((double)N * Cin * H * W + (double)Cout * Cin * K * K + (double)N * Cout * H * W) + 4.0 * Cout);
+    hipLaunchKernelGGL(fn, dim3((unsigned)(slots * p.ncblk)), dim3(kThreads), lds, current_stream(), p);
+    return check_launch();
+}
+
+int blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S)
+{
+    const int Ho = (H - K) / S + 1, Wo = (W - K) / S + 1, planes = N * ((C + 7) / 8);
+    const long long total = (long long)planes * Ho * Wo;
+    if (total >= (1ll << 31) || (long long)planes * H * W >= (1ll << 31)) return SQ_ERR_UNSUPPORTED;
+    LaunchScope scope("maxpool_blocked", 0.0, 16.0 * ((double)planes * H * W + (double)total));
+    hipLaunchKernelGGL(maxpool_blocked_kernel, dim3(grid_for(total, 256)), dim3(256), 0, current_stream(), (const u32x4 *)in,
+                       (u32x4 *)out, planes, H, W, Ho, Wo, K, S, make_fastdiv(Wo), make_fastdiv(Ho * Wo));
+    return check_launch();
+}
+
+int blocked_avgpool_global(const void *in, float *out, int N, int C, int H, int W)
+{
+    const int CB = (C + 7) / 8, planes = N * CB;
+    if ((long long)planes * H * W >= (1ll << 31)) return SQ_ERR_UNSUPPORTED;
+    LaunchScope scope("avgpool_blocked", 0.0, 16.0 * (double)planes * H * W + 4.0 * N * C);
+    hipLaunchKernelGGL(avgpool_blocked_kernel, dim3((planes + 3) / 4), dim3(256), 0, current_stream(), (const u32x4 *)in, out,
+                       planes, C, CB, H * W, make_fastdiv(CB));
+    return check_launch();
+}
+
+}  // namespace sq

@@ -142,27 +142,27 @@ __device__ __forceinline__ void buf_st(rsrc_t r, uint32_t lane_off, uint32_t uni
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)lane_off, (int)uni_off, 0);
 }
 
-// 8-byte store through a buffer resource.  The compiler's builtins for buffer accesses wider
-// than four bytes are not used in this library (the ROCm 7.2 compiler lowers the wide loads to
-// a single dword), so the instruction is written out; a store returns nothing the compiler
-// would have to wait for, and the data registers are read when it issues.
-typedef int rsrc_words_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ rsrc_words_t make_rsrc_words(const void *base, uint32_t bytes)
+// 8-byte store through a buffer resource, written as two adjacent 4-byte stores with the same
+// lane offset register, which the compiler merges into one buffer_store_dwordx2.  (Its builtins
+// for buffer accesses wider than four bytes are not used in this library: the ROCm 7.2 compiler
+// lowers the wide loads to a single dword.  Writing the instruction out as inline assembly is
+// not safe either: the compiler does not see which scalar registers the statement reads, so it
+// leaves out the wait states the hardware needs between a vector instruction that writes a
+// scalar register -- such as the re-load of a spilled one -- and a memory instruction that reads
+// it, and the store then goes to a stale address.)
+__device__ __forceinline__ void buf_st2(rsrc_t r, uint32_t lane_off, uint32_t uni_off, float v0, float v1)
 {
-    const uint64_t a = (uint64_t)base;
-    rsrc_words_t r;
-    r.x = (int)(uint32_t)a;
-    r.y = (int)((uint32_t)(a >> 32) & 0xffffu);   // stride 0: raw buffer
-    r.z = (int)bytes;
-    r.w = 0x00020000;
-    return r;
+    asm volatile("" : "+v"(lane_off));   // keeps the +4 an immediate of the second store
+    buf_st(r, lane_off, uni_off, v0);
+    buf_st(r, lane_off + 4u, uni_off, v1);
 }
-__device__ __forceinline__ void buf_st2(rsrc_words_t r, uint32_t lane_off, uint32_t uni_off, float v0, float v1)
+
+// Two fp32 values rounded to bfloat16 (nearest even), first in the low half of the word.
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
 {
-    typedef float f32x2 __attribute__((ext_vector_type(2)));
-    f32x2 v;
-    v.x = v0; v.y = v1;
-    asm volatile("buffer_store_dwordx2 %0, %1, %2, %3 offen" : : "v"(v), "v"(lane_off), "s"(r), "s"(uni_off) : "memory");
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 v = {(__bf16)a, (__bf16)b};
+    return __builtin_bit_cast(uint32_t, v);
 }
 
 // Input element of type TIN as fp32: float as is, uint16_t = bfloat16 (upper half of binary32).
@@ -196,7 +196,8 @@ struct KernelSet {
     KernelFn plain, tail, fused_e1;
 };
 extern const KernelSet conv_mfma_kernels_f32[], conv_mfma_kernels_bf16[];
-KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers, bool bf16_inputs);
+// blocked_out: the result is written as bfloat16 in the layout [N][layers/8][Ho][Wo][8] (NW = 8 only).
+KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers, bool bf16_inputs, bool blocked_out);
 
 // Minimal-filtering F(2x2, 3x3) kernel: workgroup tile (output layers x tiles of 2x2 pixels),
 // input layers per chunk, and the floats of the kernel image [16 positions][2][64][4] of one chunk.

@@ -307,7 +307,6 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
     if (mw >= p.Cout) continue;
     const float sg = pr ? -1.f : 1.f;
     const rsrc_t rout = make_rsrc(p.out, p.out_bytes);
-    const rsrc_words_t rout2 = make_rsrc_words(p.out, p.out_bytes);
     const uint32_t hs = (uint32_t)p.HoWo * 4u;
     // this wavefront writes output row pr of its tiles: pixels (2ty + pr, 2tx) and (.., 2tx + 1)
     uint32_t o2, o1;   // lane offsets for a tile with both columns inside the image / only the first
@@ -342,7 +341,7 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
         const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(mw + M::row_reg(q)) * hs;
-        buf_st2(rout2, o2, so, zin[0][q], zin[1][q]);
+        buf_st2(rout, o2, so, zin[0][q], zin[1][q]);
         buf_st(rout, o1, so, zin[0][q]);   // tiles cut by the right edge (odd widths); dropped otherwise
     }
     }   // tiles of this workgroup

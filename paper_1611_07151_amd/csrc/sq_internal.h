@@ -28,6 +28,7 @@ struct ConvArgs {
     void *ws;         // caller scratch some algorithms need (16-byte aligned), or nullptr
     size_t ws_bytes;
     bool ws_ready;    // ws already holds this layer's transformed kernels (conv_prepare_kernels)
+    bool out_blocked; // `out` is a bfloat16 tensor [N][out_channels/8][Ho][Wo][8] (conv1-type kernel only)
 };
 
 inline double conv_flops(const ConvArgs &a)
@@ -63,6 +64,19 @@ int conv_prepare_kernels(const KernelPrepJob *jobs, int n, int dtype);
 bool conv_wants_prepared_kernels(const ConvArgs &a);
 int conv_mfma_variant_count();
 const char *conv_mfma_variant_name(int i);
+
+// Reduced-precision path on blocked bfloat16 maps [N][ceil(C/8)][H][W][8] (blocked_bf16.hip).
+size_t blocked_map_bytes(int N, int C, int H, int W);
+size_t blocked_packed_kernel_bytes(int Cout, int Cin, int K);
+bool blocked_conv_supported(int Cin, int Cout, int K, int P);
+int blocked_pack_map(const void *in, int dtype, void *out, int N, int C, int H, int W);
+int blocked_unpack_map(const void *in, float *out, int N, int C, int H, int W);
+int blocked_convert_bf16(const float *in, void *out, int n);
+int blocked_pack_kernels(const void *w, int dtype, void *packed, int Cout, int Cin, int K);
+int blocked_conv(const void *in, const void *wp, const float *b, void *out, int N, int Cin, int H, int W, int Cout, int K, int P,
+                 int relu, int ldc_channels, int c_offset);
+int blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S);
+int blocked_avgpool_global(const void *in, float *out, int N, int C, int H, int W);
 
 int maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int S);
 int avgpool_global(const float *in, float *out, int N, int C, int H, int W);

@@ -16,6 +16,10 @@ durations behind `roofline` and `layers`, and its own step time is reported as
 launch, so it is a little slower).  `cpu_baseline` is the CPU oracle timed on the host
 cores on a bounded sample of the same workload.
 
+`reduced_precision` times the same network through sq_squeezenet_forward_bf16 (bfloat16
+feature maps and kernels, fp32 sums: the counterpart of the paper's relaxed-precision mode)
+on the same images, and reports how often it predicts the class the fp32 network predicts.
+
 `energy` is the analogue of the paper's power table (section "Power Consumption"): the GPU's
 own power sensor is sampled while idle (before any kernel runs) and while forward passes run
 back to back for --energy-seconds; energy per image = power x time per image, given both for
@@ -88,6 +92,7 @@ def main() -> int:
                          "(11x11 stride 4, 5x5, 3x3)")
     ap.add_argument("--energy-seconds", type=float, default=3.0,
                     help="length of each power-sampling window (0 = leave the energy measurement out)")
+    ap.add_argument("--skip-reduced", action="store_true", help="leave the reduced-precision (bf16) network out")
     ap.add_argument("--skip-batch1", action="store_true", help="leave the batch-1 timing out (for profiler runs)")
     ap.add_argument("--cpu-sample", type=int, default=32,
                     help="images of the workload the CPU oracle is timed on (0 = skip)")
@@ -249,6 +254,62 @@ def main() -> int:
         torch.cuda.synchronize()
         dt1g = time.perf_counter() - t0
 
+    # ---------------------------------------------------------------- reduced precision (bf16 maps and kernels)
+    # the same network through sq_squeezenet_forward_bf16: kernels re-ordered once ahead of time, fp32 image in
+    reduced = None
+    if not args.skip_reduced:
+        packed = sq.sq_squeezenet_bf16_pack_params(params)
+        ws16 = torch.empty(sq.sq_squeezenet_bf16_workspace_bytes(B), device="cuda", dtype=torch.uint8)
+        probs16 = torch.empty((B, 1000), device="cuda")
+
+        def timed16(xx, pp, pk, ww, oo, steps, profile):
+            if profile:
+                sq.sq_profile_begin(steps * 48)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                sq.sq_squeezenet_forward_bf16(xx, pp, pk, workspace=ww, probs=oo)
+            torch.cuda.synchronize()
+            dt_ = time.perf_counter() - t0
+            return dt_, (sq.sq_profile_end() if profile else None)
+
+        for _ in range(W):
+            sq.sq_squeezenet_forward_bf16(x, params, packed, workspace=ws16, probs=probs16)
+        dt16, _ = timed16(x, params, packed, ws16, probs16, K, False)
+        _, recs16 = timed16(x, params, packed, ws16, probs16, K, True)
+        layers16 = {}
+        for r in recs16:
+            st = r["name"].split("|")[0]
+            e = layers16.setdefault(st, dict(us=0.0, flops=0.0, bytes=0.0, kernel=r["name"].split("|")[1]))
+            e["us"] += r["ms"] / K * 1e3
+            e["flops"] += r["flops"] / K
+            e["bytes"] += r["bytes"] / K
+        for e in layers16.values():
+            e["tflops"] = round(e.pop("flops") / e["us"] / 1e6, 1)
+            e["gbs"] = round(e.pop("bytes") / e["us"] / 1e3)
+            e["us"] = round(e["us"], 1)
+        # agreement with the fp32 network on the images of this batch (class means decide the prediction)
+        _, t32 = sq.sq_squeezenet_forward(x, params, workspace=ws, want_taps=True)
+        _, t16 = sq.sq_squeezenet_forward_bf16(x, params, packed, workspace=ws16, want_taps=True)
+        m32, m16 = t32["means"].double(), t16["means"].double()
+        rel = ((m16 - m32).abs() / m32.std(dim=1, keepdim=True))
+        reduced = dict(images_per_s=round(B * K / dt16, 1), ms_per_step=round(dt16 / K * 1e3, 4),
+                       speedup_vs_fp32=round(dt / dt16, 3), dtype="bf16 maps and kernels, fp32 accumulate",
+                       top1_agreement_with_fp32=round(float((m16.argmax(1) == m32.argmax(1)).double().mean()), 4),
+                       class_mean_error_over_spread=dict(max=round(float(rel.max()), 4),
+                                                         rms=round(float((rel ** 2).mean().sqrt()), 5)),
+                       conv_tflops=round(B * FLOP_PER_IMAGE / (sum(e["us"] for e in layers16.values() if e["tflops"]) * 1e-6) / 1e12, 1),
+                       layers=layers16)
+        del t32, t16
+        if not args.skip_batch1:
+            packed1 = sq.sq_squeezenet_bf16_pack_params(params1)
+            ws161 = torch.empty(sq.sq_squeezenet_bf16_workspace_bytes(1), device="cuda", dtype=torch.uint8)
+            for _ in range(20):
+                sq.sq_squeezenet_forward_bf16(x1, params1, packed1, workspace=ws161, probs=probs1)
+            d1, _ = timed16(x1, params1, packed1, ws161, probs1, k1, False)
+            reduced["batch1_ms"] = round(d1 / k1 * 1e3, 4)
+            reduced["batch1_images_per_s"] = round(k1 / d1, 1)
+
     # ---------------------------------------------------------------- energy per image
     energy = None
     if idle_w is not None:
@@ -303,7 +364,7 @@ def main() -> int:
         "batch1_graph_images_per_sec": None if args.skip_batch1 else round(k1 / dt1g, 1),
         "batch1_graph_matches_eager": graph_ok,
         "ms_per_step_with_events": round(dt_events / K * 1e3, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "energy": energy, "layers": layers,
+        "roofline": roofline, "cpu_baseline": cpu, "energy": energy, "reduced_precision": reduced, "layers": layers,
     }
     print(json.dumps(out))
     return 0

@@ -234,6 +234,13 @@ size_t sq_squeezenet_workspace_bytes(int N);
  * multiple of 16; Cout, ldc_channels and c_offset multiples of 8; the kernels of 32
  * output layers (K*K*Cin*64 bytes) must fit half the LDS -- otherwise
  * SQ_ERR_UNSUPPORTED.  in and out must not overlap.
+ * sq_blocked_conv7s2_forward(): the conv1-type layer -- 7 x 7 kernels, stride 2, zero
+ * padding P, exactly three input layers -- reading an NCHW image (in_dtype SQ_F32 or
+ * SQ_BF16; fp32 pixels are rounded to bfloat16 as they are staged) and writing layers
+ * [c_offset, c_offset+Cout) of a blocked map [N][ldc_channels/8][Ho][Wo][8],
+ * Ho = (H + 2P - 7)/2 + 1.  Cout <= 96 and a multiple of 8.  Its kernels
+ * [Cout][3][7][7] are packed by sq_blocked_pack_kernels7() into a buffer of
+ * sq_blocked_kernel7_bytes() bytes.
  * sq_blocked_maxpool(): K x K window, stride S, floor mode, no padding.
  * sq_blocked_avgpool_global(): mean over H x W of each layer, fp32 [N][C] out.
  * Errors: SQ_ERR_NULL, SQ_ERR_SHAPE, SQ_ERR_UNSUPPORTED, SQ_ERR_HIP.
@@ -246,6 +253,11 @@ int sq_blocked_pack_kernels(const void *w, sq_dtype w_dtype, void *packed, int C
 int sq_blocked_conv2d_forward(const void *in, const void *packed_w, const float *b, void *out,
                               int N, int Cin, int H, int W, int Cout, int K, int P, int relu,
                               int ldc_channels, int c_offset);
+size_t sq_blocked_kernel7_bytes(void);
+int sq_blocked_pack_kernels7(const void *w, sq_dtype w_dtype, void *packed, int Cout);
+int sq_blocked_conv7s2_forward(const void *in, sq_dtype in_dtype, const void *packed_w, const float *b,
+                               void *out, int N, int H, int W, int Cout, int P, int relu,
+                               int ldc_channels, int c_offset);
 int sq_blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S);
 int sq_blocked_avgpool_global(const void *in, float *out, int N, int C, int H, int W);
 
@@ -253,7 +265,8 @@ int sq_blocked_avgpool_global(const void *in, float *out, int N, int C, int H, i
  * SqueezeNet v1.0 forward in reduced precision: the network of sq_squeezenet_forward
  * with bfloat16 feature maps and kernels (fp32 sums, fp32 biases, fp32 class means
  * and probabilities).  conv1 reads the NCHW image (in_dtype SQ_F32, or SQ_BF16 for a
- * bfloat16 image) and writes a blocked map; everything after it stays blocked.
+ * bfloat16 image; fp32 pixels are rounded to bfloat16 as they are staged) and writes a
+ * blocked map; everything after it stays blocked.
  *   params  as for sq_squeezenet_forward (fp32; only the biases are read here).
  *   packed  device buffer of sq_squeezenet_bf16_packed_bytes() bytes, 256-byte
  *           aligned, filled once by sq_squeezenet_bf16_pack_params(params, packed,

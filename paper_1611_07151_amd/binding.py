@@ -50,6 +50,10 @@ lib.sq_blocked_kernel_bytes.restype = _sz
 lib.sq_blocked_kernel_bytes.argtypes = [_i] * 3
 lib.sq_blocked_pack_kernels.argtypes = [_vp, _i, _vp] + [_i] * 3
 lib.sq_blocked_conv2d_forward.argtypes = [_vp] * 4 + [_i] * 10
+lib.sq_blocked_kernel7_bytes.restype = _sz
+lib.sq_blocked_kernel7_bytes.argtypes = []
+lib.sq_blocked_pack_kernels7.argtypes = [_vp, _i, _vp, _i]
+lib.sq_blocked_conv7s2_forward.argtypes = [_vp, _i, _vp, _vp, _vp] + [_i] * 8
 lib.sq_blocked_maxpool.argtypes = [_vp, _vp] + [_i] * 6
 lib.sq_blocked_avgpool_global.argtypes = [_vp, _vp] + [_i] * 4
 lib.sq_squeezenet_bf16_packed_bytes.restype = _sz
@@ -332,6 +336,39 @@ def sq_blocked_conv2d_forward(m, packed_w, b, Cin, Cout, K, pad, relu=False, out
                                        _dev(b, torch.float32, "b"), _dev(out, torch.bfloat16, "out"), N, Cin, H, W,
                                        Cout, int(K), int(pad), 1 if relu else 0, out.shape[1] * 8, int(c_offset))
     _check(rc, "sq_blocked_conv2d_forward")
+    return out
+
+
+def sq_blocked_kernel7_bytes() -> int:
+    return int(lib.sq_blocked_kernel7_bytes())
+
+
+def sq_blocked_pack_kernels7(w):
+    """conv1-type kernels [Cout][3][7][7] (float32 / bfloat16) -> packed buffer (uint8 tensor)."""
+    if tuple(w.shape[1:]) != (3, 7, 7):
+        raise ValueError("expects [Cout][3][7][7]")
+    out = torch.empty(sq_blocked_kernel7_bytes(), device=w.device, dtype=torch.uint8)
+    _use_current_stream()
+    _check(lib.sq_blocked_pack_kernels7(_dev(w, None, "w"), _dtype_code(w, "w"), _dev(out), w.shape[0]),
+           "sq_blocked_pack_kernels7")
+    return out
+
+
+def sq_blocked_conv7s2_forward(x, packed_w, b, Cout, pad, relu=False, out=None, c_offset=0):
+    """x: NCHW image [N][3][H][W], float32 or bfloat16; out: blocked map (default: a new one of Cout layers)."""
+    N, C, H, W = x.shape
+    if C != 3:
+        raise ValueError("three input layers")
+    if H + 2 * pad < 7 or W + 2 * pad < 7:
+        _check(-2, "sq_blocked_conv7s2_forward")
+    Ho, Wo = (H + 2 * pad - 7) // 2 + 1, (W + 2 * pad - 7) // 2 + 1
+    if out is None:
+        out = _new_map(N, Cout, Ho, Wo, x.device)
+    _use_current_stream()
+    rc = lib.sq_blocked_conv7s2_forward(_dev(x, None, "x"), _dtype_code(x, "x"), _dev(packed_w, torch.uint8, "packed_w"),
+                                        _dev(b, torch.float32, "b"), _dev(out, torch.bfloat16, "out"), N, H, W, Cout,
+                                        int(pad), 1 if relu else 0, out.shape[1] * 8, int(c_offset))
+    _check(rc, "sq_blocked_conv7s2_forward")
     return out
 
 

@@ -99,7 +99,7 @@ ConvArgs make_args(const void *in, const void *w, const float *b, float *out, in
     a.out_channels = out_channels;
     a.c_offset = c_offset;
     a.dtype = dtype;
-    a.ws = nullptr; a.ws_bytes = 0; a.ws_ready = false; a.out_blocked = false;
+    a.ws = nullptr; a.ws_bytes = 0; a.ws_ready = false;
     return a;
 }
 
@@ -488,6 +488,28 @@ int sq_blocked_conv2d_forward(const void *in, const void *packed_w, const float 
     return blocked_conv(in, packed_w, b, out, N, Cin, H, W, Cout, K, P, relu ? 1 : 0, ldc_channels, c_offset);
 }
 
+size_t sq_blocked_kernel7_bytes(void) { return blocked_packed_kernel7_bytes(); }
+
+int sq_blocked_pack_kernels7(const void *w, sq_dtype w_dtype, void *packed, int Cout)
+{
+    if (!w || !packed) return SQ_ERR_NULL;
+    if (Cout <= 0) return SQ_ERR_SHAPE;
+    if (w_dtype != SQ_F32 && w_dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if ((uintptr_t)packed & 15) return SQ_ERR_UNSUPPORTED;
+    return blocked_pack_kernels7(w, w_dtype, packed, Cout);
+}
+
+int sq_blocked_conv7s2_forward(const void *in, sq_dtype in_dtype, const void *packed_w, const float *b, void *out, int N,
+                               int H, int W, int Cout, int P, int relu, int ldc_channels, int c_offset)
+{
+    if (!in || !packed_w || !out) return SQ_ERR_NULL;
+    if (N <= 0 || H <= 0 || W <= 0 || Cout <= 0 || P < 0 || H + 2 * P < 7 || W + 2 * P < 7) return SQ_ERR_SHAPE;
+    if (c_offset < 0 || ldc_channels < c_offset + Cout) return SQ_ERR_SHAPE;
+    if (in_dtype != SQ_F32 && in_dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)out & 15) || ((uintptr_t)packed_w & 15)) return SQ_ERR_UNSUPPORTED;
+    return blocked_conv7s2(in, in_dtype, packed_w, b, out, N, H, W, Cout, P, relu ? 1 : 0, ldc_channels, c_offset);
+}
+
 int sq_blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S)
 {
     if (!in || !out) return SQ_ERR_NULL;
@@ -513,15 +535,14 @@ void net_conv_shape(int i, int &cout, int &cin, int &k)
     if (part == 0) { cout = fc.sq; cin = fc.cin; k = 1; }
     else { cout = fc.e; cin = fc.sq; k = part == 1 ? 1 : 3; }
 }
-// byte offset of convolution i's packed kernels inside the packed buffer (conv1: its kernels as plain
-// bfloat16 [96][3][7][7], which the conv1 kernel stages itself)
+// byte offset of convolution i's packed kernels inside the packed buffer
 size_t net_packed_offset(int i)
 {
     size_t off = 0;
     for (int q = 0; q < i; ++q) {
         int cout, cin, k;
         net_conv_shape(q, cout, cin, k);
-        off += align_up(q == 0 ? (size_t)96 * 3 * 49 * 2 : blocked_packed_kernel_bytes(cout, cin, k), 256);
+        off += align_up(q == 0 ? blocked_packed_kernel7_bytes() : blocked_packed_kernel_bytes(cout, cin, k), 256);
     }
     return off;
 }
@@ -535,8 +556,7 @@ int sq_squeezenet_bf16_pack_params(const void *const *params, void *packed, size
     for (int i = 0; i < 52; ++i)
         if (!params[i]) return SQ_ERR_NULL;
     if (((uintptr_t)packed & 255) || packed_bytes < sq_squeezenet_bf16_packed_bytes()) return SQ_ERR_WORKSPACE;
-    // conv1: [96][3][7][7] -> bfloat16, same order
-    int rc = blocked_convert_bf16((const float *)params[0], packed, 96 * 3 * 49);
+    int rc = blocked_pack_kernels7(params[0], SQ_F32, packed, 96);
     if (rc) return rc;
     for (int i = 1; i < 26; ++i) {
         int cout, cin, k;
@@ -584,14 +604,7 @@ int sq_squeezenet_forward_bf16(const void *in, sq_dtype in_dtype, const void *co
 
     int rc = SQ_OK;
     set_stage("conv1");
-    {
-        // the conv1 kernel reads image and kernels in one type: fp32 image with the fp32 kernels, bfloat16
-        // image with the bfloat16 copy of the kernels
-        ConvArgs a = make_args(in, in_dtype == SQ_BF16 ? WP(0) : params[0], B(0), (float *)bufA, N, 3, 224, 224, 96, 7, 2, 2,
-                               1, 96, 0, in_dtype);
-        a.out_blocked = true;
-        if ((rc = conv_mfma(a, -1))) return rc;
-    }
+    if ((rc = blocked_conv7s2(in, in_dtype, WP(0), B(0), bufA, N, 224, 224, 96, 2, 1, 96, 0))) return rc;
     if ((rc = tap_out(0, bufA, 96, 111))) return rc;
     set_stage("pool1");
     if ((rc = blocked_maxpool(bufA, bufB, N, 96, 111, 111, 3, 2))) return rc;

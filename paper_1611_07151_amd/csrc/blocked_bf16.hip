@@ -82,13 +82,6 @@ __global__ void unpack_map_kernel(const u32x4 *in, float *out, int N, int C, int
     }
 }
 
-// fp32 -> bfloat16 (nearest even), same order.
-__global__ void convert_bf16_kernel(const float *in, uint16_t *out, int n)
-{
-    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < n; e += gridDim.x * blockDim.x)
-        out[e] = (uint16_t)(pack2(in[e], 0.f) & 0xffffu);
-}
-
 // [Cout][Cin][K][K] (fp32 or bf16) -> MFMA A-operand order (see the header of this file).
 template <typename TIN>
 __global__ void pack_kernels_kernel(const TIN *w, u32x4 *wp, int Cout, int Cin, int KK, int G, int total)
@@ -417,13 +410,6 @@ int blocked_unpack_map(const void *in, float *out, int N, int C, int H, int W)
     LaunchScope scope("unpack_map", 0.0, 4.0 * N * C * HW + 16.0 * total);
     hipLaunchKernelGGL(unpack_map_kernel, dim3(grid_for(total, 256)), dim3(256), 0, current_stream(), (const u32x4 *)in, out, N,
                        C, HW, CB, make_fastdiv(HW), make_fastdiv(CB));
-    return check_launch();
-}
-
-int blocked_convert_bf16(const float *in, void *out, int n)
-{
-    LaunchScope scope("convert_bf16", 0.0, 6.0 * n);
-    hipLaunchKernelGGL(convert_bf16_kernel, dim3(grid_for(n, 256)), dim3(256), 0, current_stream(), in, (uint16_t *)out, n);
     return check_launch();
 }
 

@@ -77,10 +77,7 @@ __host__ __device__ constexpr int step_offset(int s)
 
 // FULL: the layer has exactly 96 output layers, so no store needs a layer test.
 // TIN: float, or uint16_t = bfloat16 input and kernels, widened to fp32 while staged.
-// OUTB: results leave as bfloat16 in the blocked layout [N][layers/8][Ho][Wo][8]: registers
-// 4q..4q+3 of an accumulator are four consecutive layers of one pixel = one 8-byte store
-// (twelve stores per tile instead of 48); p.ldc and p.coff still count layers.
-template <typename TIN, int NW, bool FULL, int MINW, bool OUTB = false>
+template <typename TIN, int NW, bool FULL, int MINW>
 __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams p)
 {
     constexpr int ESZ = (int)sizeof(TIN);
@@ -152,7 +149,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
     };
 
     const rsrc_t rin = make_rsrc(p.in, p.in_bytes), rout = make_rsrc(p.out, p.out_bytes);
-    const uint32_t hs16 = (uint32_t)(p.HoWo * 16);
 
     float xreg[3 * kPR];
     auto load_patch = [&](int tile) {
@@ -190,9 +186,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
         int n, oh0, ow0;
         decode(tile, n, oh0, ow0);
         const int oh = oh0 + prow, ow = ow0 + pcol;
-        const uint32_t off =
-            OUTB ? (uint32_t)((((n * p.ldc + p.coff) >> 3) * p.HoWo + oh * p.Wo + ow) * 16 + 8 * kk)
-                 : (uint32_t)(((n * p.ldc + p.coff + M::row_lane(lane)) * p.HoWo + oh * p.Wo + ow) * 4);
+        const uint32_t off = (uint32_t)(((n * p.ldc + p.coff + M::row_lane(lane)) * p.HoWo + oh * p.Wo + ow) * 4);
         return (oh < p.Ho && ow < p.Wo) ? off : kOob;
     };
 
@@ -227,15 +221,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
                     acc[x] = M::run(av[s & 1][x], bv[s & 1], acc[x]);
                 }
             }
-            if (OUTB) {
-                if (s < 12) {
-                    const int x = s / 4, q = s % 4;     // layer block 4x + q: layers 8(4x+q) + 4kk .. +3
-                    if (FULL || (4 * x + q) * 8 < p.Cout)
-                        buf_st2(rout, prev_off, (uint32_t)(4 * x + q) * hs16,
-                                __builtin_bit_cast(float, pack_bf16x2(prev[x][4 * q], prev[x][4 * q + 1])),
-                                __builtin_bit_cast(float, pack_bf16x2(prev[x][4 * q + 2], prev[x][4 * q + 3])));
-                }
-            } else if (s < 48) {
+            if (s < 48) {
                 // layers come in groups of 8 (rows mu..mu+3 in the lower half-wave, +4 in the
                 // upper), and Cout is a multiple of 8, so the layer test is uniform
                 const int x = s / 16, r = s % 16;
@@ -301,20 +287,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
         }
     }
     // results of the last tile
-    if (OUTB) {
-#pragma unroll
-        for (int x = 0; x < kTM; ++x)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (!(FULL || (4 * x + q) * 8 < p.Cout)) continue;
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = lastA ? accA[x][4 * q + e] : accB[x][4 * q + e];
-                buf_st2(rout, lastA ? offA : offB, (uint32_t)(4 * x + q) * hs16,
-                        __builtin_bit_cast(float, pack_bf16x2(v[0], v[1])), __builtin_bit_cast(float, pack_bf16x2(v[2], v[3])));
-            }
-        return;
-    }
 #pragma unroll
     for (int x = 0; x < kTM; ++x)
 #pragma unroll
@@ -326,13 +298,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
 
 }  // namespace
 
-KernelFn conv7s2c3_kernel_for(int NW, bool full, bool bf16, bool blocked_out)
+KernelFn conv7s2c3_kernel_for(int NW, bool full, bool bf16)
 {
-    if (blocked_out) {
-        if (NW != 8) return nullptr;
-        if (bf16) return full ? conv7s2c3_kernel<uint16_t, 8, true, 1, true> : conv7s2c3_kernel<uint16_t, 8, false, 1, true>;
-        return full ? conv7s2c3_kernel<float, 8, true, 1, true> : conv7s2c3_kernel<float, 8, false, 1, true>;
-    }
     if (bf16) {
         if (NW == 8) return full ? conv7s2c3_kernel<uint16_t, 8, true, 1> : conv7s2c3_kernel<uint16_t, 8, false, 1>;
         if (NW == 4) return full ? conv7s2c3_kernel<uint16_t, 4, true, 1> : conv7s2c3_kernel<uint16_t, 4, false, 1>;

@@ -49,7 +49,6 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(
 
 int conv_direct(const ConvArgs &a)
 {
-    if (a.out_blocked) return SQ_ERR_UNSUPPORTED;   // this kernel writes fp32 NCHW only
     const size_t total = (size_t)a.N * a.Cout * a.Ho * a.Wo;
     size_t blocks = (total + 255) / 256;
     if (blocks > (1u << 20)) blocks = 1u << 20;

@@ -110,7 +110,6 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
         pixels + v.BN >= kMaxBufferElems)
         return false;
     if (v.conv1_type && (a.Cin != 3 || a.Cout > 96 || a.Cout % 8 != 0)) return false;
-    if (a.out_blocked && (!v.conv1_type || v.NT != 512 || a.out_channels % 8 != 0 || a.c_offset % 8 != 0)) return false;
     if (v.wino && (a.P != 1 || a.Cin % v.CC != 0 || a.Cout % 32 != 0 || !a.ws || ((uintptr_t)a.ws & 15) ||
                    a.ws_bytes < wino_transformed_bytes(a.Cout, a.Cin)))
         return false;
@@ -161,7 +160,7 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
     k.dVH = make_fastdiv(k.VH); k.dHW = make_fastdiv(k.HW); k.dHoWo = make_fastdiv(k.HoWo);
     k.dMtiles = make_fastdiv(k.mtiles);
     const long long esz = a.dtype == SQ_BF16 ? 2 : 4;
-    k.in_bytes = (uint32_t)(in_elems * esz); k.out_bytes = (uint32_t)(out_elems * (a.out_blocked ? 2 : 4)); k.w_bytes = (uint32_t)(w_elems * esz);
+    k.in_bytes = (uint32_t)(in_elems * esz); k.out_bytes = (uint32_t)(out_elems * 4); k.w_bytes = (uint32_t)(w_elems * esz);
     long long blocks = (long long)k.mtiles * k.ntiles;
     if (v.conv1_type) {
         // autonomous wavefronts: tiles of 2 x 16 output pixels, NW = NT/64 wavefronts per
@@ -208,7 +207,7 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
     const Variant &v = kVariants[vi];
     const KernelSet &ks = kernel_set(v, a.dtype);
     KernelFn fn = e1 ? ks.fused_e1 : ks.plain;
-    if (v.conv1_type) fn = conv7s2c3_kernel_for(v.NT / 64, a.Cout == 96, a.dtype == SQ_BF16, a.out_blocked);
+    if (v.conv1_type) fn = conv7s2c3_kernel_for(v.NT / 64, a.Cout == 96, a.dtype == SQ_BF16);
     if (!v.conv1_type && !v.wino && !e1 && a.Cin % v.CC != 0) fn = ks.tail;
     if (!allow_big_lds(fn)) {
         const int rc = check_launch();

@@ -196,8 +196,7 @@ struct KernelSet {
     KernelFn plain, tail, fused_e1;
 };
 extern const KernelSet conv_mfma_kernels_f32[], conv_mfma_kernels_bf16[];
-// blocked_out: the result is written as bfloat16 in the layout [N][layers/8][Ho][Wo][8] (NW = 8 only).
-KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers, bool bf16_inputs, bool blocked_out);
+KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers, bool bf16_inputs);
 
 // Minimal-filtering F(2x2, 3x3) kernel: workgroup tile (output layers x tiles of 2x2 pixels),
 // input layers per chunk, and the floats of the kernel image [16 positions][2][64][4] of one chunk.

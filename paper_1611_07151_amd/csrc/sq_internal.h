@@ -28,7 +28,6 @@ struct ConvArgs {
     void *ws;         // caller scratch some algorithms need (16-byte aligned), or nullptr
     size_t ws_bytes;
     bool ws_ready;    // ws already holds this layer's transformed kernels (conv_prepare_kernels)
-    bool out_blocked; // `out` is a bfloat16 tensor [N][out_channels/8][Ho][Wo][8] (conv1-type kernel only)
 };
 
 inline double conv_flops(const ConvArgs &a)
@@ -71,10 +70,13 @@ size_t blocked_packed_kernel_bytes(int Cout, int Cin, int K);
 bool blocked_conv_supported(int Cin, int Cout, int K, int P);
 int blocked_pack_map(const void *in, int dtype, void *out, int N, int C, int H, int W);
 int blocked_unpack_map(const void *in, float *out, int N, int C, int H, int W);
-int blocked_convert_bf16(const float *in, void *out, int n);
 int blocked_pack_kernels(const void *w, int dtype, void *packed, int Cout, int Cin, int K);
 int blocked_conv(const void *in, const void *wp, const float *b, void *out, int N, int Cin, int H, int W, int Cout, int K, int P,
                  int relu, int ldc_channels, int c_offset);
+size_t blocked_packed_kernel7_bytes();
+int blocked_pack_kernels7(const void *w, int dtype, void *packed, int Cout);
+int blocked_conv7s2(const void *in, int dtype, const void *wp, const float *b, void *out, int N, int H, int W, int Cout, int P,
+                    int relu, int ldc_channels, int c_offset);
 int blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S);
 int blocked_avgpool_global(const void *in, float *out, int N, int C, int H, int W);
 

@@ -123,6 +123,38 @@ def test_blocked_conv_matches_oracle(sq, case, relu):
     assert_close(from_blocked(out0, Cout), oracle.conv2d(rounded(x), rounded(w), None, 1, P, relu), TIGHT_TOL, "no bias")
 
 
+CONV7_CASES = [
+    # N, H,   W,   Cout, P
+    (1, 224, 224, 96, 2),       # conv1 at full size
+    (1, 227, 227, 96, 0),       # the other reading of conv1 (227, no padding)
+    (2, 37, 41, 96, 2),         # odd sizes, ragged tiles
+    (3, 21, 19, 40, 3),         # fewer layers, wide padding
+    (1, 7, 7, 8, 0),            # a single output pixel
+]
+
+
+@pytest.mark.parametrize("case", CONV7_CASES, ids=lambda c: "x".join(map(str, c)))
+@pytest.mark.parametrize("relu", [True, False])
+def test_blocked_conv7s2_matches_oracle(sq, case, relu):
+    N, H, W, Cout, P = case
+    rng = np.random.default_rng(300 + H + Cout)
+    x = synth.uniform01(rng, (N, 3, H, W))
+    w, b = synth.conv_params(rng, Cout, 3, 7)
+    ref = oracle.conv2d(x, w, b, 2, P, relu)
+    ref_r = oracle.conv2d(rounded(x), rounded(w), b, 2, P, relu)
+    for xd in (dev(x), dev(x, torch.bfloat16)):
+        for wd in (dev(w), dev(w, torch.bfloat16)):
+            out = sq.sq_blocked_conv7s2_forward(xd, sq.sq_blocked_pack_kernels7(wd), dev(b), Cout, P, relu)
+            got = from_blocked(out, Cout)
+            assert_close(got, ref, BF16_TOL, "stated tolerance")
+            assert_close(got, ref_r, TIGHT_TOL, "same rounded operands")
+    out = torch.full((N, 13, ref.shape[2], ref.shape[3], 8), -7.0, device="cuda", dtype=torch.bfloat16)   # 104 layers
+    sq.sq_blocked_conv7s2_forward(dev(x), sq.sq_blocked_pack_kernels7(dev(w)), None, Cout, P, relu, out=out, c_offset=8)
+    full = from_blocked(out, 104)
+    assert_close(full[:, 8:8 + Cout], oracle.conv2d(rounded(x), rounded(w), None, 2, P, relu), TIGHT_TOL, "offset, no bias")
+    assert (full[:, :8] == -7.0).all() and (full[:, 8 + Cout:] == -7.0).all()
+
+
 @pytest.mark.parametrize("k", [1, 3])
 def test_blocked_conv_channel_offset_leaves_other_layers_untouched(sq, k):
     rng = np.random.default_rng(9)

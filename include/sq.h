@@ -241,6 +241,12 @@ size_t sq_squeezenet_workspace_bytes(int N);
  * Ho = (H + 2P - 7)/2 + 1.  Cout <= 96 and a multiple of 8.  Its kernels
  * [Cout][3][7][7] are packed by sq_blocked_pack_kernels7() into a buffer of
  * sq_blocked_kernel7_bytes() bytes.
+ * sq_blocked_fire_forward(): the fire layer of sq_fire_forward on blocked maps, with
+ * packed kernels (squeeze [Csq][Cin][1][1], expand [Ce1][Csq][1][1] and [Ce3][Csq][3][3]);
+ * the squeeze map is rounded to bfloat16, both expands run in one launch and write
+ * layers [0, Ce1) and [Ce1, Ce1+Ce3) of out.  workspace: device scratch of at least
+ * sq_blocked_map_bytes(N, Csq, H, W) bytes, 256-byte aligned (the squeeze map).
+ * Cin and Csq multiples of 16, Ce1 and Ce3 multiples of 8.
  * sq_blocked_maxpool(): K x K window, stride S, floor mode, no padding.
  * sq_blocked_avgpool_global(): mean over H x W of each layer, fp32 [N][C] out.
  * Errors: SQ_ERR_NULL, SQ_ERR_SHAPE, SQ_ERR_UNSUPPORTED, SQ_ERR_HIP.
@@ -258,6 +264,10 @@ int sq_blocked_pack_kernels7(const void *w, sq_dtype w_dtype, void *packed, int 
 int sq_blocked_conv7s2_forward(const void *in, sq_dtype in_dtype, const void *packed_w, const float *b,
                                void *out, int N, int H, int W, int Cout, int P, int relu,
                                int ldc_channels, int c_offset);
+int sq_blocked_fire_forward(const void *in, const void *packed_sq, const float *b_sq,
+                            const void *packed_e1, const float *b_e1, const void *packed_e3,
+                            const float *b_e3, void *out, int N, int Cin, int H, int W,
+                            int Csq, int Ce1, int Ce3, void *workspace, size_t workspace_bytes);
 int sq_blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S);
 int sq_blocked_avgpool_global(const void *in, float *out, int N, int C, int H, int W);
 

@@ -54,6 +54,7 @@ lib.sq_blocked_kernel7_bytes.restype = _sz
 lib.sq_blocked_kernel7_bytes.argtypes = []
 lib.sq_blocked_pack_kernels7.argtypes = [_vp, _i, _vp, _i]
 lib.sq_blocked_conv7s2_forward.argtypes = [_vp, _i, _vp, _vp, _vp] + [_i] * 8
+lib.sq_blocked_fire_forward.argtypes = [_vp] * 8 + [_i] * 7 + [_vp, _sz]
 lib.sq_blocked_maxpool.argtypes = [_vp, _vp] + [_i] * 6
 lib.sq_blocked_avgpool_global.argtypes = [_vp, _vp] + [_i] * 4
 lib.sq_squeezenet_bf16_packed_bytes.restype = _sz
@@ -369,6 +370,24 @@ def sq_blocked_conv7s2_forward(x, packed_w, b, Cout, pad, relu=False, out=None, 
                                         _dev(b, torch.float32, "b"), _dev(out, torch.bfloat16, "out"), N, H, W, Cout,
                                         int(pad), 1 if relu else 0, out.shape[1] * 8, int(c_offset))
     _check(rc, "sq_blocked_conv7s2_forward")
+    return out
+
+
+def sq_blocked_fire_forward(m, Cin, packed_sq, b_sq, packed_e1, b_e1, packed_e3, b_e3, Csq, Ce1, Ce3, workspace=None):
+    """Fire layer on a blocked map of Cin layers; returns the blocked map of Ce1 + Ce3 layers."""
+    N, CB, H, W, _ = m.shape
+    if m.shape[4] != 8 or (Cin + 7) // 8 != CB:
+        raise ValueError("not a blocked map of Cin layers")
+    if workspace is None:
+        workspace = torch.empty(sq_blocked_map_bytes(N, Csq, H, W), device=m.device, dtype=torch.uint8)
+    out = _new_map(N, Ce1 + Ce3, H, W, m.device)
+    u8, f32 = torch.uint8, torch.float32
+    _use_current_stream()
+    rc = lib.sq_blocked_fire_forward(_dev(m, torch.bfloat16, "m"), _dev(packed_sq, u8, "packed_sq"), _dev(b_sq, f32, "b_sq"),
+                                     _dev(packed_e1, u8, "packed_e1"), _dev(b_e1, f32, "b_e1"),
+                                     _dev(packed_e3, u8, "packed_e3"), _dev(b_e3, f32, "b_e3"), _dev(out), N, Cin, H, W,
+                                     Csq, Ce1, Ce3, _dev(workspace), workspace.numel() * workspace.element_size())
+    _check(rc, "sq_blocked_fire_forward")
     return out
 
 

@@ -510,6 +510,26 @@ int sq_blocked_conv7s2_forward(const void *in, sq_dtype in_dtype, const void *pa
     return blocked_conv7s2(in, in_dtype, packed_w, b, out, N, H, W, Cout, P, relu ? 1 : 0, ldc_channels, c_offset);
 }
 
+int sq_blocked_fire_forward(const void *in, const void *packed_sq, const float *b_sq, const void *packed_e1,
+                            const float *b_e1, const void *packed_e3, const float *b_e3, void *out, int N, int Cin, int H,
+                            int W, int Csq, int Ce1, int Ce3, void *workspace, size_t workspace_bytes)
+{
+    if (!in || !packed_sq || !packed_e1 || !packed_e3 || !out) return SQ_ERR_NULL;
+    if (N <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Csq <= 0 || Ce1 <= 0 || Ce3 <= 0) return SQ_ERR_SHAPE;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < blocked_map_bytes(N, Csq, H, W)) return SQ_ERR_WORKSPACE;
+    if (((uintptr_t)in & 15) || ((uintptr_t)out & 15) || ((uintptr_t)packed_sq & 15) || ((uintptr_t)packed_e1 & 15) ||
+        ((uintptr_t)packed_e3 & 15) || Ce1 % 8 != 0)
+        return SQ_ERR_UNSUPPORTED;
+    set_stage(kFireAlone[0]);
+    int rc = blocked_conv(in, packed_sq, b_sq, workspace, N, Cin, H, W, Csq, 1, 0, 1, Csq, 0);
+    if (!rc) {
+        set_stage(kFireAlone[3]);
+        rc = blocked_conv_pair(workspace, packed_e1, b_e1, Ce1, 0, packed_e3, b_e3, Ce3, Ce1, 3, out, N, Csq, H, W, 1, Ce1 + Ce3);
+    }
+    set_stage("");
+    return rc;
+}
+
 int sq_blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S)
 {
     if (!in || !out) return SQ_ERR_NULL;
@@ -617,10 +637,11 @@ int sq_squeezenet_forward_bf16(const void *in, sq_dtype in_dtype, const void *co
         const int c0 = 1 + 3 * f;
         set_stage(kFireStages[f][0]);
         if ((rc = blocked_conv(cur, WP(c0), B(c0), bufS, N, C, H, H, fc.sq, 1, 0, 1, fc.sq, 0))) return rc;
-        set_stage(kFireStages[f][1]);
-        if ((rc = blocked_conv(bufS, WP(c0 + 1), B(c0 + 1), nxt, N, fc.sq, H, H, fc.e, 1, 0, 1, 2 * fc.e, 0))) return rc;
-        set_stage(kFireStages[f][2]);
-        if ((rc = blocked_conv(bufS, WP(c0 + 2), B(c0 + 2), nxt, N, fc.sq, H, H, fc.e, 3, 1, 1, 2 * fc.e, fc.e))) return rc;
+        // both expands in one launch
+        set_stage(kFireStages[f][3]);
+        if ((rc = blocked_conv_pair(bufS, WP(c0 + 1), B(c0 + 1), fc.e, 0, WP(c0 + 2), B(c0 + 2), fc.e, fc.e, 3, nxt, N, fc.sq, H,
+                                    H, 1, 2 * fc.e)))
+            return rc;
         C = 2 * fc.e;
         if ((rc = tap_out(tap++, nxt, C, H))) return rc;
         { char *t = cur; cur = nxt; nxt = t; }

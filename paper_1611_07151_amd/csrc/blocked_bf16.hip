@@ -127,9 +127,16 @@ struct ConvParams {
     FastDiv dHW, dW, dG, dK, dNcblk;
 };
 
+// Two convolutions of the same input and the same CB/PB/D may share a launch (the two expands of
+// a fire layer): workgroups [0, split) run pa, the rest run pb.  A single convolution passes
+// split = gridDim.x.
 template <int CB, int PB, int D>
-__global__ __launch_bounds__(kThreads, 2) void conv_blocked_kernel(const ConvParams p)
+__global__ __launch_bounds__(kThreads, 2) void conv_blocked_kernel(const ConvParams pa, const ConvParams pb, const int split)
 {
+    const bool second = (int)blockIdx.x >= split;
+    const ConvParams p = second ? pb : pa;   // by value: every field becomes a scalar select
+    const int wg = second ? (int)blockIdx.x - split : (int)blockIdx.x;
+    const int nwg = second ? (int)gridDim.x - split : split;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     u32x4 *const wl = reinterpret_cast<u32x4 *>(smem);                 // [CB][steps][64] A operands
     const int per_mb = p.steps * 64;                                      // 16-byte elements per 32 layers
@@ -138,8 +145,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_blocked_kernel(const ConvPar
     const int t = threadIdx.x, lane = t & 63;
     const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
     const int j = lane & 31, h = lane >> 5;
-    const int slot = fdiv((int)blockIdx.x, p.dNcblk), cblk = (int)blockIdx.x - slot * p.ncblk;
-    const int nslots = (int)gridDim.x / p.ncblk;          // the host launches a multiple of ncblk
+    const int slot = fdiv(wg, p.dNcblk), cblk = wg - slot * p.ncblk;
+    const int nslots = nwg / p.ncblk;                     // the host launches a multiple of ncblk
     const int mb0 = cblk * CB;                            // first block of 32 output layers
 
     // ---- this workgroup's kernels and bias into LDS (a straight copy: they are packed) ----
@@ -352,7 +359,7 @@ int num_cus_blocked()
     return cus;
 }
 
-typedef void (*BlockedConvFn)(const ConvParams);
+typedef void (*BlockedConvFn)(const ConvParams, const ConvParams, int);
 template <int CB, int PB> BlockedConvFn conv_fn(int D)
 {
     switch (D) {
@@ -376,9 +383,11 @@ bool allow_lds(BlockedConvFn fn)
 
 }  // namespace
 
-// Tuning hook (not part of the public interface): ring depth to use where it divides the step count.
-int g_force_depth = 0;
+// Tuning hooks (not part of the public interface): ring depth to use where it divides the step count;
+// blocks of 32 output layers per workgroup and of 32 pixels per wavefront tile (0 = automatic).
+int g_force_depth = 0, g_force_cb = 0, g_force_pb = 0;
 extern "C" void sq_internal_blocked_force_depth(int d) { g_force_depth = d; }
+extern "C" void sq_internal_blocked_force_tile(int cb, int pb) { g_force_cb = cb; g_force_pb = pb; }
 
 size_t blocked_map_bytes(int N, int C, int H, int W) { return (size_t)N * ((C + 7) / 8) * H * W * 16; }
 
@@ -438,8 +447,18 @@ bool blocked_conv_supported(int Cin, int Cout, int K, int P)
     return per_mb + 256 <= (size_t)mfma::kLdsBytes / 2;
 }
 
-int blocked_conv(const void *in, const void *wp, const float *b, void *out, int N, int Cin, int H, int W, int Cout, int K, int P,
-                 int relu, int ldc_channels, int c_offset)
+namespace {
+
+struct ConvPlan {
+    ConvParams p;
+    int CB, PB, D;
+    size_t per_mb;     // bytes of packed kernels per 32 output layers
+    double flops, bytes;
+};
+
+// Fills the launch parameters of one convolution; CB/PB/D = 0 lets this function choose.
+int plan_conv(ConvPlan &pl, const void *in, const void *wp, const float *b, void *out, int N, int Cin, int H, int W, int Cout,
+              int K, int P, int relu, int ldc_channels, int c_offset, int CB, int PB, int D)
 {
     if (!blocked_conv_supported(Cin, Cout, K, P) || ldc_channels % 8 != 0 || c_offset % 8 != 0) return SQ_ERR_UNSUPPORTED;
     const long long in_bytes = (long long)blocked_map_bytes(N, Cin, H, W);
@@ -447,7 +466,7 @@ int blocked_conv(const void *in, const void *wp, const float *b, void *out, int 
     const long long PT = (long long)N * H * W;
     if (in_bytes >= (1ll << 31) || out_bytes >= (1ll << 31) || PT >= (1ll << 30)) return SQ_ERR_UNSUPPORTED;
 
-    ConvParams p;
+    ConvParams &p = pl.p;
     p.in = in; p.wp = wp; p.b = b; p.out = out;
     p.in_bytes = (uint32_t)in_bytes; p.out_bytes = (uint32_t)out_bytes;
     p.wp_elems = (uint32_t)(blocked_packed_kernel_bytes(Cout, Cin, K) / 16);
@@ -459,32 +478,102 @@ int blocked_conv(const void *in, const void *wp, const float *b, void *out, int 
     p.dHW = make_fastdiv(p.HW); p.dW = make_fastdiv(W); p.dG = make_fastdiv(p.G); p.dK = make_fastdiv(K);
 
     // 64 output layers per workgroup when their kernels fit half the LDS, else 32
-    const size_t per_mb = (size_t)p.steps * 64 * 16;
-    const int CB = (Cout > 32 && 2 * per_mb + 512 <= (size_t)mfma::kLdsBytes / 2) ? 2 : 1;
-    constexpr int PB = 2;
+    pl.per_mb = (size_t)p.steps * 64 * 16;
+    const bool two_fit = 2 * pl.per_mb + 512 <= (size_t)mfma::kLdsBytes / 2;
+    if (CB == 0) CB = (Cout > 32 && two_fit) ? 2 : 1;
+    if (CB == 2 && !two_fit) return SQ_ERR_UNSUPPORTED;
+    // wavefront tiles of 32 pixels: measured equal to or faster than 64 on every layer of the network
+    if (PB == 0) PB = 1;
+    if (g_force_cb == 1 || (g_force_cb == 2 && two_fit)) CB = g_force_cb;
+    if (g_force_pb == 1 || g_force_pb == 2) PB = g_force_pb;
+    if (D == 0) {
+        D = p.steps % 4 == 0 ? 4 : p.steps % 3 == 0 ? 3 : p.steps % 2 == 0 ? 2 : 1;
+        if (g_force_depth > 0 && p.steps % g_force_depth == 0) D = g_force_depth;
+    }
+    if (p.steps % D != 0) return SQ_ERR_UNSUPPORTED;
+    pl.CB = CB; pl.PB = PB; pl.D = D;
     p.tiles = (int)((PT + 32 * PB - 1) / (32 * PB));
     p.ncblk = (Cout + 32 * CB - 1) / (32 * CB);
     p.dNcblk = make_fastdiv(p.ncblk);
-    int D = p.steps % 4 == 0 ? 4 : p.steps % 3 == 0 ? 3 : p.steps % 2 == 0 ? 2 : 1;
-    if (g_force_depth > 0 && p.steps % g_force_depth == 0) D = g_force_depth;
-    BlockedConvFn fn = CB == 2 ? conv_fn<2, PB>(D) : conv_fn<1, PB>(D);
-    if (!allow_lds(fn)) {
-        const int rc = check_launch();
-        return rc ? rc : SQ_ERR_HIP;
-    }
-    // persistent: at most two workgroups per CU, and no more than there are tiles to hand out
-    long long slots = (2ll * num_cus_blocked()) / p.ncblk;
-    const long long need = (p.tiles + kWaves - 1) / kWaves;
+    pl.flops = 2.0 * N * Cout * H * W * (double)Cin * K * K;
+    pl.bytes = 2.0 * ((double)N * Cin * H * W + (double)Cout * Cin * K * K + (double)N * Cout * H * W) + 4.0 * Cout;
+    return SQ_OK;
+}
+
+BlockedConvFn kernel_for(int CB, int PB, int D)
+{
+    return CB == 2 ? (PB == 2 ? conv_fn<2, 2>(D) : conv_fn<2, 1>(D)) : (PB == 2 ? conv_fn<1, 2>(D) : conv_fn<1, 1>(D));
+}
+
+// workgroups a convolution can use: a multiple of its layer groups, at most `cap`, no more than its tiles need
+long long slots_for(const ConvPlan &pl, long long cap)
+{
+    long long slots = cap / pl.p.ncblk;
+    const long long need = (pl.p.tiles + kWaves - 1) / kWaves;
     if (slots > need) slots = need;
-    if (slots < 1) slots = 1;
-    const size_t lds = (size_t)CB * per_mb + (size_t)CB * 32 * sizeof(float);
-    // the profiler keeps the pointer: one permanent string per (K, CB, D)
-    static char names[6][3][5][24];
-    char *name = names[K][CB][D];
-    if (!name[0]) snprintf(name, sizeof names[0][0][0], "k%db_%dx%d_d%d", K, 32 * CB, 32 * PB, D);
-    LaunchScope scope(name, 2.0 * N * Cout * H * W * (double)Cin * K * K,
-                      2.0 * ((double)N * Cin * H * W + (double)Cout * Cin * K * K + (double)N * Cout * H * W) + 4.0 * Cout);
-    hipLaunchKernelGGL(fn, dim3((unsigned)(slots * p.ncblk)), dim3(kThreads), lds, current_stream(), p);
+    return slots < 1 ? 1 : slots;
+}
+
+// the profiler keeps the pointer: one permanent string per shape of launch
+const char *launch_name(int K, int CB, int PB, int D, bool pair)
+{
+    static char names[2][6][3][3][5][28];
+    char *name = names[pair][K][CB][PB][D];
+    if (!name[0]) snprintf(name, sizeof names[0][0][0][0][0], pair ? "k1b+k%db_%dx%d_d%d" : "k%db_%dx%d_d%d", K, 32 * CB, 32 * PB, D);
+    return name;
+}
+
+}  // namespace
+
+int blocked_conv(const void *in, const void *wp, const float *b, void *out, int N, int Cin, int H, int W, int Cout, int K, int P,
+                 int relu, int ldc_channels, int c_offset)
+{
+    ConvPlan pl;
+    const int rc = plan_conv(pl, in, wp, b, out, N, Cin, H, W, Cout, K, P, relu, ldc_channels, c_offset, 0, 0, 0);
+    if (rc) return rc;
+    BlockedConvFn fn = kernel_for(pl.CB, pl.PB, pl.D);
+    if (!allow_lds(fn)) {
+        const int e = check_launch();
+        return e ? e : SQ_ERR_HIP;
+    }
+    // persistent: at most two workgroups per CU
+    const long long wgs = slots_for(pl, 2ll * num_cus_blocked()) * pl.p.ncblk;
+    const size_t lds = (size_t)pl.CB * pl.per_mb + (size_t)pl.CB * 32 * sizeof(float);
+    LaunchScope scope(launch_name(K, pl.CB, pl.PB, pl.D, false), pl.flops, pl.bytes);
+    hipLaunchKernelGGL(fn, dim3((unsigned)wgs), dim3(kThreads), lds, current_stream(), pl.p, pl.p, (int)wgs);
+    return check_launch();
+}
+
+// The two expands of a fire layer in one launch: a 1x1 convolution (w1, b1 -> layers [c_offset1, +Cout1)) and a K x K
+// convolution (wk, bk -> layers [c_offsetk, +Coutk)) of the same input into the same output map.
+int blocked_conv_pair(const void *in, const void *wp1, const float *b1, int Cout1, int c_offset1, const void *wpk,
+                      const float *bk, int Coutk, int c_offsetk, int K, void *out, int N, int Cin, int H, int W, int relu,
+                      int ldc_channels)
+{
+    ConvPlan p1, pk;
+    int rc = plan_conv(pk, in, wpk, bk, out, N, Cin, H, W, Coutk, K, (K - 1) / 2, relu, ldc_channels, c_offsetk, 0, 0, 0);
+    if (rc) return rc;
+    // the ring depth must divide both step counts; the 1x1 has the fewer steps
+    const int G = Cin / 16;
+    const int D = G % 4 == 0 ? 4 : G % 3 == 0 ? 3 : G % 2 == 0 ? 2 : 1;
+    if ((rc = plan_conv(pk, in, wpk, bk, out, N, Cin, H, W, Coutk, K, (K - 1) / 2, relu, ldc_channels, c_offsetk, pk.CB, pk.PB, D)))
+        return rc;
+    if ((rc = plan_conv(p1, in, wp1, b1, out, N, Cin, H, W, Cout1, 1, 0, relu, ldc_channels, c_offset1, pk.CB, pk.PB, D))) return rc;
+    BlockedConvFn fn = kernel_for(pk.CB, pk.PB, D);
+    if (!allow_lds(fn)) {
+        const int e = check_launch();
+        return e ? e : SQ_ERR_HIP;
+    }
+    // workgroups are shared out in proportion to the work (the K x K part has K*K times the steps)
+    const long long cap = 2ll * num_cus_blocked();
+    long long cap1 = cap / (1 + K * K * (long long)Coutk / Cout1);
+    if (cap1 < p1.p.ncblk) cap1 = p1.p.ncblk;
+    const long long wg1 = slots_for(p1, cap1) * p1.p.ncblk;
+    const long long wgk = slots_for(pk, cap - wg1 > pk.p.ncblk ? cap - wg1 : pk.p.ncblk) * pk.p.ncblk;
+    const size_t ldsk = (size_t)pk.CB * pk.per_mb, lds1 = (size_t)p1.CB * p1.per_mb;
+    const size_t lds = (ldsk > lds1 ? ldsk : lds1) + (size_t)pk.CB * 32 * sizeof(float);
+    LaunchScope scope(launch_name(K, pk.CB, pk.PB, D, true), p1.flops + pk.flops, p1.bytes + pk.bytes - 2.0 * N * Cin * H * W);
+    hipLaunchKernelGGL(fn, dim3((unsigned)(wg1 + wgk)), dim3(kThreads), lds, current_stream(), p1.p, pk.p, (int)wg1);
     return check_launch();
 }
 

@@ -77,6 +77,9 @@ size_t blocked_packed_kernel7_bytes();
 int blocked_pack_kernels7(const void *w, int dtype, void *packed, int Cout);
 int blocked_conv7s2(const void *in, int dtype, const void *wp, const float *b, void *out, int N, int H, int W, int Cout, int P,
                     int relu, int ldc_channels, int c_offset);
+int blocked_conv_pair(const void *in, const void *wp1, const float *b1, int Cout1, int c_offset1, const void *wpk,
+                      const float *bk, int Coutk, int c_offsetk, int K, void *out, int N, int Cin, int H, int W, int relu,
+                      int ldc_channels);
 int blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S);
 int blocked_avgpool_global(const void *in, float *out, int N, int C, int H, int W);
 

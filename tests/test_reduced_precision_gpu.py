@@ -169,6 +169,41 @@ def test_blocked_conv_channel_offset_leaves_other_layers_untouched(sq, k):
     assert (full[:, :24] == -7.0).all() and (full[:, 88:] == -7.0).all()
 
 
+@pytest.mark.parametrize("shape", [(2, 96, 55, 16, 64), (2, 128, 55, 32, 128), (3, 256, 27, 48, 192), (2, 384, 27, 64, 256),
+                                   (5, 512, 13, 64, 256), (1, 32, 6, 16, 24)])
+def test_blocked_fire_matches_oracle(sq, shape):
+    """Squeeze, then both expands in one launch, against the oracle's fire layer; also with a large positive
+    squeeze bias, so that a padded tap that saw relu(bias) instead of zero would show."""
+    N, Cin, H, Csq, Ce = shape
+    rng = np.random.default_rng(400 + Cin + Ce)
+    x = synth.normal01(rng, (N, Cin, H, H))
+    (w_sq, b_sq), (w_e1, b_e1), (w_e3, b_e3) = (synth.conv_params(rng, Csq, Cin, 1), synth.conv_params(rng, Ce, Csq, 1),
+                                                synth.conv_params(rng, Ce, Csq, 3))
+    for bias_shift in (0.0, 3.0):
+        bs = (b_sq + bias_shift).astype(np.float32)
+        ref = oracle.fire(x, w_sq, bs, w_e1, b_e1, w_e3, b_e3)
+        ws = torch.empty(sq.sq_blocked_map_bytes(N, Csq, H, H), device="cuda", dtype=torch.uint8)
+        out = sq.sq_blocked_fire_forward(to_blocked(x).cuda(), Cin, sq.sq_blocked_pack_kernels(dev(w_sq)), dev(bs),
+                                         sq.sq_blocked_pack_kernels(dev(w_e1)), dev(b_e1),
+                                         sq.sq_blocked_pack_kernels(dev(w_e3)), dev(b_e3), Csq, Ce, Ce, workspace=ws)
+        got = from_blocked(out, 2 * Ce)
+        # the stated tolerance is per convolution: the squeeze map (left in the workspace) against the oracle,
+        # then the expands against the oracle applied to that squeeze map
+        s_gpu = from_blocked(ws.view(torch.bfloat16).view(N, Csq // 8, H, H, 8), Csq)
+        if bias_shift == 0.0:   # (a squeeze map with mean 3 is outside the value range the tolerance is stated for)
+            assert_close(s_gpu, oracle.conv2d(x, w_sq, bs, 1, 0, True), BF16_TOL, "squeeze")
+            ref_e = np.concatenate([oracle.conv2d(s_gpu, w_e1, b_e1, 1, 0, True), oracle.conv2d(s_gpu, w_e3, b_e3, 1, 1, True)],
+                                   axis=1)
+            assert_close(got, ref_e, BF16_TOL, "expands")
+            assert_close(got, ref, 2 * BF16_TOL, "whole fire layer (two roundings)")
+        # tight bar, convolution by convolution, each on exactly the operands the GPU had (the squeeze map is
+        # taken from the GPU: where the two sides' sums straddle a rounding boundary it differs by one ulp)
+        assert_close(s_gpu, oracle.conv2d(rounded(x), rounded(w_sq), bs, 1, 0, True), TIGHT_TOL, f"squeeze, shift {bias_shift}")
+        ref_r = np.concatenate([oracle.conv2d(s_gpu, rounded(w_e1), b_e1, 1, 0, True),
+                                oracle.conv2d(s_gpu, rounded(w_e3), b_e3, 1, 1, True)], axis=1)
+        assert_close(got, ref_r, TIGHT_TOL, f"expands, shift {bias_shift}")
+
+
 def test_blocked_conv_refuses_what_it_does_not_cover(sq):
     m = torch.zeros((1, 1, 4, 4, 8), device="cuda", dtype=torch.bfloat16)
     wp = torch.zeros(sq.sq_blocked_kernel_bytes(8, 8, 1), device="cuda", dtype=torch.uint8)

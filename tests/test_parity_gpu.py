@@ -186,6 +186,33 @@ def test_fire2_workload(sq, n):
     assert_close(got, ref, FP32_TOL, "fire2")
 
 
+@pytest.mark.parametrize("cin,sq_c,e,h,n", [(96, 16, 64, 55, 1), (256, 48, 192, 27, 2), (512, 64, 256, 13, 3), (24, 8, 40, 9, 2)])
+def test_fire_with_both_expands_in_one_launch(sq, cin, sq_c, e, h, n):
+    """Every tiling compiled with the fused 1x1 expand, forced through the library's tuning
+    switch, against the oracle's fire layer; and the separate-launch form beside it."""
+    rng = np.random.default_rng(cin + e + n)
+    x = synth.normal01(rng, (n, cin, h, h))
+    w_sq, b_sq = synth.conv_params(rng, sq_c, cin, 1)
+    b_sq = (b_sq + 1.0).astype(np.float32)            # relu(b_sq) != 0: the padding must still be zero
+    w_e1, b_e1 = synth.conv_params(rng, e, sq_c, 1)
+    w_e3, b_e3 = synth.conv_params(rng, e, sq_c, 3)
+    ref = oracle.fire(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3)
+    args = [dev(a) for a in (x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3)]
+    fused_ran = 0
+    try:
+        for v in [-3, -2, -1] + list(range(sq.sq_conv_variant_count())):
+            sq.lib.sq_internal_force_expand(v)
+            sq.sq_profile_begin(16)
+            got = sq.sq_fire_forward(*args)
+            stages = {r["name"].split("|")[0] for r in sq.sq_profile_end()}
+            assert_close(got, ref, FP32_TOL, f"expand mode {v}")
+            assert v != -3 or "fire/e1+e3" not in stages
+            fused_ran += v >= 0 and "fire/e1+e3" in stages
+    finally:
+        sq.lib.sq_internal_force_expand(-2)
+    assert fused_ran >= 3 or sq_c % 4        # several tilings took the fused form (input layers must fill their chunks)
+
+
 def test_fire_border_sees_zero_padding_not_relu_of_bias(sq):
     # large positive squeeze bias: relu(b_sq) != 0, so a halo filled with the
     # squeeze of zero-padded input (instead of zeros) would be visibly wrong

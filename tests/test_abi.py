@@ -164,3 +164,85 @@ def test_tuned_table_names_exist(lib):
     assert rows, "tuned table is empty"
     used = {n for row in rows for n in row}
     assert used <= names, used - names
+
+
+def test_reduced_precision_entry_points_validate_before_any_gpu_call(lib):
+    """Blocked bfloat16 maps: size queries, and every refusal that needs no GPU."""
+    sz = ctypes.c_size_t
+    for name in ("sq_blocked_map_bytes", "sq_blocked_kernel_bytes", "sq_blocked_kernel7_bytes",
+                 "sq_squeezenet_bf16_packed_bytes", "sq_squeezenet_bf16_workspace_bytes"):
+        getattr(lib, name).restype = sz
+    # [N][ceil(C/8)][H][W][8] two-byte elements; kernels [Cout/32][K*K][Cin/16][64][8]
+    assert lib.sq_blocked_map_bytes(2, 20, 5, 7) == 2 * 3 * 5 * 7 * 16
+    assert lib.sq_blocked_map_bytes(0, 8, 5, 7) == 0
+    assert lib.sq_blocked_kernel_bytes(48, 32, 3) == 2 * 9 * 2 * 64 * 16
+    assert lib.sq_blocked_kernel7_bytes() == 3 * 11 * 64 * 16
+    assert lib.sq_squeezenet_bf16_packed_bytes() % 256 == 0
+    assert lib.sq_squeezenet_bf16_packed_bytes() >= 2 * 1_248_424 - 2 * (96 * 147) - 2 * 1200   # all kernels, two bytes each
+    assert lib.sq_squeezenet_bf16_workspace_bytes(0) == 0
+    assert 2 * lib.sq_squeezenet_bf16_workspace_bytes(3) < lib.sq_squeezenet_workspace_bytes(3) + 4096 * 3 + 4 * 3000 * 2
+
+    conv = lib.sq_blocked_conv2d_forward
+    good = [1, 16, 8, 8, 32, 3, 1, 1, 32, 0]      # N Cin H W Cout K P relu ldc c_offset
+    assert conv(NULL, FAKE, FAKE, FAKE, *good) == -1
+    assert conv(FAKE, NULL, FAKE, FAKE, *good) == -1
+    assert conv(FAKE, FAKE, FAKE, NULL, *good) == -1
+    for idx, bad in [(0, 0), (1, 0), (2, 0), (3, -1), (4, 0), (5, 0), (6, -1)]:
+        args = list(good)
+        args[idx] = bad
+        assert conv(FAKE, FAKE, FAKE, FAKE, *args) == -2, (idx, bad)
+    assert conv(FAKE, FAKE, FAKE, FAKE, 1, 16, 8, 8, 32, 3, 1, 1, 24, 0) == -2     # output map too narrow
+    assert conv(FAKE, FAKE, FAKE, FAKE, 1, 16, 8, 8, 32, 3, 1, 1, 64, 40) == -2    # offset + Cout past the map
+    for args in ([1, 8, 8, 8, 32, 3, 1, 1, 32, 0],      # Cin not a multiple of 16
+                 [1, 16, 8, 8, 12, 3, 1, 1, 16, 0],     # Cout not a multiple of 8
+                 [1, 16, 8, 8, 32, 3, 0, 1, 32, 0],     # 3x3 without its padding
+                 [1, 16, 8, 8, 32, 2, 0, 1, 32, 0],     # even kernel size
+                 [1, 16, 8, 8, 32, 7, 3, 1, 32, 0],     # kernel size beyond 5
+                 [1, 16, 8, 8, 32, 3, 1, 1, 36, 4],     # offset not a multiple of 8
+                 [1, 4096, 8, 8, 32, 3, 1, 1, 32, 0]):  # kernels of 32 layers beyond half the LDS
+        assert conv(FAKE, FAKE, FAKE, FAKE, *args) == -3, args
+    assert conv(ctypes.c_void_p(0x1004), FAKE, FAKE, FAKE, *good) == -3             # maps are 16-byte aligned
+
+    c7 = lib.sq_blocked_conv7s2_forward
+    assert c7(NULL, 0, FAKE, FAKE, FAKE, 1, 224, 224, 96, 2, 1, 96, 0) == -1
+    assert c7(FAKE, 0, FAKE, FAKE, FAKE, 1, 4, 224, 96, 0, 1, 96, 0) == -2          # window larger than the image
+    assert c7(FAKE, 0, FAKE, FAKE, FAKE, 1, 224, 224, 96, 2, 1, 64, 0) == -2         # map too narrow
+    assert c7(FAKE, 5, FAKE, FAKE, FAKE, 1, 224, 224, 96, 2, 1, 96, 0) == -3         # unknown image type
+    assert c7(FAKE, 0, FAKE, FAKE, FAKE, 1, 224, 224, 104, 2, 1, 104, 0) == -3       # more than 96 layers
+    assert c7(FAKE, 0, FAKE, FAKE, FAKE, 1, 224, 224, 20, 2, 1, 24, 0) == -3         # not a multiple of 8
+
+    assert lib.sq_blocked_pack(NULL, 0, FAKE, 1, 8, 4, 4) == -1
+    assert lib.sq_blocked_pack(FAKE, 0, FAKE, 1, 0, 4, 4) == -2
+    assert lib.sq_blocked_pack(FAKE, 7, FAKE, 1, 8, 4, 4) == -3
+    assert lib.sq_blocked_unpack(FAKE, NULL, 1, 8, 4, 4) == -1
+    assert lib.sq_blocked_pack_kernels(FAKE, 0, ctypes.c_void_p(0x1008), 8, 16, 1) == -3
+    assert lib.sq_blocked_pack_kernels7(FAKE, 0, FAKE, 0) == -2
+    assert lib.sq_blocked_maxpool(FAKE, FAKE, 1, 8, 2, 9, 3, 2) == -2
+    assert lib.sq_blocked_avgpool_global(FAKE, NULL, 1, 8, 4, 4) == -1
+
+    fire = lib.sq_blocked_fire_forward
+    fire.argtypes = [ctypes.c_void_p] * 8 + [ctypes.c_int] * 7 + [ctypes.c_void_p, sz]
+    ws = ctypes.c_void_p(0x2000)
+    need = lib.sq_blocked_map_bytes(1, 16, 8, 8)
+    assert fire(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, NULL, 1, 96, 8, 8, 16, 64, 64, ws, need) == -1
+    assert fire(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 96, 8, 8, 16, 64, 64, ws, need - 1) == -4
+    assert fire(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 96, 8, 8, 16, 64, 64, ctypes.c_void_p(0x2010), need) == -4
+    assert fire(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 96, 8, 8, 0, 64, 64, ws, need) == -2
+    assert fire(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 100, 8, 8, 16, 64, 64, ws, need) == -3   # Cin % 16
+
+    net = lib.sq_squeezenet_forward_bf16
+    net.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p, ctypes.c_void_p,
+                    ctypes.c_int, ctypes.c_void_p, sz, ctypes.POINTER(ctypes.c_void_p)]
+    params = (ctypes.c_void_p * 52)(*([0x1000] * 52))
+    big = lib.sq_squeezenet_bf16_workspace_bytes(1)
+    assert net(NULL, 0, params, FAKE, FAKE, 1, ws, big, None) == -1
+    assert net(FAKE, 0, params, FAKE, FAKE, 0, ws, big, None) == -2
+    assert net(FAKE, 3, params, FAKE, FAKE, 1, ws, big, None) == -3
+    assert net(FAKE, 0, params, ctypes.c_void_p(0x1000), FAKE, 1, ws, big - 1, None) == -4
+    assert net(FAKE, 0, params, ctypes.c_void_p(0x1010), FAKE, 1, ws, big, None) == -4        # packed kernels 256-byte aligned
+    holes = (ctypes.c_void_p * 52)(*([0x1000] * 51 + [None]))
+    assert net(FAKE, 0, holes, FAKE, FAKE, 1, ws, big, None) == -1
+    pk = lib.sq_squeezenet_bf16_pack_params
+    pk.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p, sz]
+    assert pk(params, ctypes.c_void_p(0x1000), lib.sq_squeezenet_bf16_packed_bytes() - 1) == -4
+    assert pk(holes, ctypes.c_void_p(0x1000), lib.sq_squeezenet_bf16_packed_bytes()) == -1

@@ -247,6 +247,11 @@ size_t sq_squeezenet_workspace_bytes(int N);
  * layers [0, Ce1) and [Ce1, Ce1+Ce3) of out.  workspace: device scratch of at least
  * sq_blocked_map_bytes(N, Csq, H, W) bytes, 256-byte aligned (the squeeze map).
  * Cin and Csq multiples of 16, Ce1 and Ce3 multiples of 8.
+ * sq_blocked_pool_conv2d_forward(): max pooling (3 x 3 window, stride 2, floor mode) of a
+ * blocked map [N][Cin/8][Hin][Win][8] followed by a 1 x 1 convolution (+bias, optional
+ * ReLU) to Cout layers, in one launch; the pooled map is not written.  The result has
+ * extents H = (Hin-3)/2 + 1, W = (Win-3)/2 + 1 and equals sq_blocked_maxpool followed by
+ * sq_blocked_conv2d_forward bit for bit.  Same divisibility rules as the convolution.
  * sq_blocked_maxpool(): K x K window, stride S, floor mode, no padding.
  * sq_blocked_avgpool_global(): mean over H x W of each layer, fp32 [N][C] out.
  * Errors: SQ_ERR_NULL, SQ_ERR_SHAPE, SQ_ERR_UNSUPPORTED, SQ_ERR_HIP.
@@ -264,6 +269,9 @@ int sq_blocked_pack_kernels7(const void *w, sq_dtype w_dtype, void *packed, int 
 int sq_blocked_conv7s2_forward(const void *in, sq_dtype in_dtype, const void *packed_w, const float *b,
                                void *out, int N, int H, int W, int Cout, int P, int relu,
                                int ldc_channels, int c_offset);
+int sq_blocked_pool_conv2d_forward(const void *in, const void *packed_w, const float *b, void *out,
+                                   int N, int Cin, int Hin, int Win, int Cout, int relu,
+                                   int ldc_channels, int c_offset);
 int sq_blocked_fire_forward(const void *in, const void *packed_sq, const float *b_sq,
                             const void *packed_e1, const float *b_e1, const void *packed_e3,
                             const float *b_e3, void *out, int N, int Cin, int H, int W,

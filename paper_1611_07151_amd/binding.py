@@ -54,6 +54,7 @@ lib.sq_blocked_kernel7_bytes.restype = _sz
 lib.sq_blocked_kernel7_bytes.argtypes = []
 lib.sq_blocked_pack_kernels7.argtypes = [_vp, _i, _vp, _i]
 lib.sq_blocked_conv7s2_forward.argtypes = [_vp, _i, _vp, _vp, _vp] + [_i] * 8
+lib.sq_blocked_pool_conv2d_forward.argtypes = [_vp] * 4 + [_i] * 8
 lib.sq_blocked_fire_forward.argtypes = [_vp] * 8 + [_i] * 7 + [_vp, _sz]
 lib.sq_blocked_maxpool.argtypes = [_vp, _vp] + [_i] * 6
 lib.sq_blocked_avgpool_global.argtypes = [_vp, _vp] + [_i] * 4
@@ -370,6 +371,23 @@ def sq_blocked_conv7s2_forward(x, packed_w, b, Cout, pad, relu=False, out=None, 
                                         _dev(b, torch.float32, "b"), _dev(out, torch.bfloat16, "out"), N, H, W, Cout,
                                         int(pad), 1 if relu else 0, out.shape[1] * 8, int(c_offset))
     _check(rc, "sq_blocked_conv7s2_forward")
+    return out
+
+
+def sq_blocked_pool_conv2d_forward(m, packed_w, b, Cin, Cout, relu=False, out=None, c_offset=0):
+    """3x3 stride-2 max pooling of a blocked map of Cin layers, then a 1x1 convolution to Cout layers."""
+    N, CB, Hin, Win, _ = m.shape
+    if m.shape[4] != 8 or (Cin + 7) // 8 != CB:
+        raise ValueError("not a blocked map of Cin layers")
+    if Hin < 3 or Win < 3:
+        _check(-2, "sq_blocked_pool_conv2d_forward")
+    if out is None:
+        out = _new_map(N, Cout, (Hin - 3) // 2 + 1, (Win - 3) // 2 + 1, m.device)
+    _use_current_stream()
+    rc = lib.sq_blocked_pool_conv2d_forward(_dev(m, torch.bfloat16, "m"), _dev(packed_w, torch.uint8, "packed_w"),
+                                            _dev(b, torch.float32, "b"), _dev(out, torch.bfloat16, "out"), N, Cin, Hin, Win,
+                                            Cout, 1 if relu else 0, out.shape[1] * 8, int(c_offset))
+    _check(rc, "sq_blocked_pool_conv2d_forward")
     return out
 
 

@@ -510,6 +510,16 @@ int sq_blocked_conv7s2_forward(const void *in, sq_dtype in_dtype, const void *pa
     return blocked_conv7s2(in, in_dtype, packed_w, b, out, N, H, W, Cout, P, relu ? 1 : 0, ldc_channels, c_offset);
 }
 
+int sq_blocked_pool_conv2d_forward(const void *in, const void *packed_w, const float *b, void *out, int N, int Cin, int Hin,
+                                   int Win, int Cout, int relu, int ldc_channels, int c_offset)
+{
+    if (!in || !packed_w || !out) return SQ_ERR_NULL;
+    if (N <= 0 || Cin <= 0 || Hin < 3 || Win < 3 || Cout <= 0) return SQ_ERR_SHAPE;
+    if (c_offset < 0 || ldc_channels < c_offset + Cout) return SQ_ERR_SHAPE;
+    if (((uintptr_t)in & 15) || ((uintptr_t)out & 15) || ((uintptr_t)packed_w & 15)) return SQ_ERR_UNSUPPORTED;
+    return blocked_pool_conv(in, packed_w, b, out, N, Cin, Hin, Win, Cout, relu ? 1 : 0, ldc_channels, c_offset);
+}
+
 int sq_blocked_fire_forward(const void *in, const void *packed_sq, const float *b_sq, const void *packed_e1,
                             const float *b_e1, const void *packed_e3, const float *b_e3, void *out, int N, int Cin, int H,
                             int W, int Csq, int Ce1, int Ce3, void *workspace, size_t workspace_bytes)
@@ -543,6 +553,14 @@ int sq_blocked_avgpool_global(const void *in, float *out, int N, int C, int H, i
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return SQ_ERR_SHAPE;
     return blocked_avgpool_global(in, out, N, C, H, W);
 }
+
+// Which poolings of the reduced-precision network run inside the following squeeze launch (bit 0: pool1,
+// bit 1: pool4, bit 2: pool8); -1 = the default policy.  Measured on MI355X: pool4 pays at every batch
+// (4 % of the pass at batch 64), pool1 only up to batch 32 (beyond, both forms are bound by reading the
+// conv1 map), pool8 never (its squeeze has 512 input layers: 32 dependent steps of nine loads each on too
+// few pixels to hide them).  The setter is a tuning hook, not part of the public interface.
+int g_fuse_pools = -1;
+void sq_internal_fuse_pools(int mask) { g_fuse_pools = mask; }
 
 namespace {
 // (Cout, Cin, K) of convolution i of the network, i = 0 (conv1) .. 25 (conv10)
@@ -626,17 +644,34 @@ int sq_squeezenet_forward_bf16(const void *in, sq_dtype in_dtype, const void *co
     set_stage("conv1");
     if ((rc = blocked_conv7s2(in, in_dtype, WP(0), B(0), bufA, N, 224, 224, 96, 2, 1, 96, 0))) return rc;
     if ((rc = tap_out(0, bufA, 96, 111))) return rc;
-    set_stage("pool1");
-    if ((rc = blocked_maxpool(bufA, bufB, N, 96, 111, 111, 3, 2))) return rc;
-    if ((rc = tap_out(1, bufB, 96, 55))) return rc;
-
-    char *cur = bufB, *nxt = bufA;
-    int C = 96, H = 55, tap = 2;
+    // Each pooled map is read by exactly one squeeze layer, so pooling runs inside that layer's launch and the
+    // pooled map is never written -- unless the caller wants to see it (taps), then the two run separately
+    // (same results bit for bit).
+    const int fuse_pools = taps != nullptr ? 0 : g_fuse_pools >= 0 ? g_fuse_pools : (N <= 32 ? 3 : 2);
+    char *cur = bufA, *nxt = bufB;
+    int C = 96, H = 111, tap = 1;
+    bool pool_pending = true;       // `cur` still has to be pooled (3x3, stride 2) before the next squeeze
+    static const char *const kPoolSq[3] = {"pool1+fire2/sq", "pool4+fire5/sq", "pool8+fire9/sq"};
     for (int f = 0; f < 8; ++f) {
         const FireCfg &fc = kFires[f];
         const int c0 = 1 + 3 * f;
-        set_stage(kFireStages[f][0]);
-        if ((rc = blocked_conv(cur, WP(c0), B(c0), bufS, N, C, H, H, fc.sq, 1, 0, 1, fc.sq, 0))) return rc;
+        const int which_pool = f == 0 ? 0 : f == 3 ? 1 : 2;
+        if (pool_pending && ((fuse_pools >> which_pool) & 1)) {
+            set_stage(kPoolSq[which_pool]);
+            if ((rc = blocked_pool_conv(cur, WP(c0), B(c0), bufS, N, C, H, H, fc.sq, 1, fc.sq, 0))) return rc;
+            H = (H - 3) / 2 + 1;
+        } else {
+            if (pool_pending) {
+                set_stage(f == 0 ? "pool1" : f == 3 ? "pool4" : "pool8");
+                if ((rc = blocked_maxpool(cur, nxt, N, C, H, H, 3, 2))) return rc;
+                H = (H - 3) / 2 + 1;
+                if ((rc = tap_out(tap++, nxt, C, H))) return rc;
+                { char *t = cur; cur = nxt; nxt = t; }
+            }
+            set_stage(kFireStages[f][0]);
+            if ((rc = blocked_conv(cur, WP(c0), B(c0), bufS, N, C, H, H, fc.sq, 1, 0, 1, fc.sq, 0))) return rc;
+        }
+        pool_pending = false;
         // both expands in one launch
         set_stage(kFireStages[f][3]);
         if ((rc = blocked_conv_pair(bufS, WP(c0 + 1), B(c0 + 1), fc.e, 0, WP(c0 + 2), B(c0 + 2), fc.e, fc.e, 3, nxt, N, fc.sq, H,
@@ -645,13 +680,7 @@ int sq_squeezenet_forward_bf16(const void *in, sq_dtype in_dtype, const void *co
         C = 2 * fc.e;
         if ((rc = tap_out(tap++, nxt, C, H))) return rc;
         { char *t = cur; cur = nxt; nxt = t; }
-        if (f == 2 || f == 6) {
-            set_stage(f == 2 ? "pool4" : "pool8");
-            if ((rc = blocked_maxpool(cur, nxt, N, C, H, H, 3, 2))) return rc;
-            H = (H - 3) / 2 + 1;
-            if ((rc = tap_out(tap++, nxt, C, H))) return rc;
-            { char *t = cur; cur = nxt; nxt = t; }
-        }
+        pool_pending = f == 2 || f == 6;   // pooling follows fire4 and fire8
     }
     set_stage("conv10");
     if ((rc = blocked_conv(cur, WP(25), B(25), nxt, N, 512, H, H, 1000, 1, 0, 1, 1000, 0))) return rc;

@@ -124,6 +124,7 @@ struct ConvParams {
     int PT;              // N*H*W
     int tiles;           // pixel tiles of 32*PB
     int ncblk;           // groups of 32*CB output layers = workgroups that share a pixel range
+    int Hin, Win;        // pooled-input kernel: extents of the map before the 3x3 stride-2 max pooling (H, W = after)
     FastDiv dHW, dW, dG, dK, dNcblk;
 };
 
@@ -265,6 +266,140 @@ __global__ __launch_bounds__(kThreads, 2) void conv_blocked_kernel(const ConvPar
                         buf_st2(rout, obase[pb], so, __builtin_bit_cast(float, pack2(v0, v1)),
                                 __builtin_bit_cast(float, pack2(v2, v3)));
                     }
+                }
+            }
+    }
+}
+
+// Max pooling (3x3 window, stride 2, floor mode) fused into the 1x1 convolution that reads its
+// result -- in this network every pooled map is read by exactly one squeeze layer, so the pooled
+// map never exists in memory.  Same structure as conv_blocked_kernel with one pixel block per
+// wavefront tile; the B operand of a step is the maximum over the nine window elements, each a
+// 16-byte load of eight layers.  bfloat16 values are compared as 16-bit integers after the usual
+// order-preserving map (negative: all bits flipped, else sign bit flipped), two per 32-bit operation.
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t order_key(uint32_t x)
+{
+    const i16x2 sign = __builtin_bit_cast(i16x2, x) >> 15;                          // 0xffff where negative
+    return x ^ (__builtin_bit_cast(uint32_t, sign) | 0x80008000u);
+}
+__device__ __forceinline__ uint32_t order_key_inverse(uint32_t k)
+{
+    const i16x2 top = __builtin_bit_cast(i16x2, k) >> 15;                           // 0xffff where the value was not negative
+    return k ^ (~__builtin_bit_cast(uint32_t, top) | 0x80008000u);
+}
+__device__ __forceinline__ uint32_t max_u16x2(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
+}
+
+template <int CB, int D>
+__global__ __launch_bounds__(kThreads, 2) void pool_conv_blocked_kernel(const ConvParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    u32x4 *const wl = reinterpret_cast<u32x4 *>(smem);
+    const int per_mb = p.steps * 64;
+    float *const bl = reinterpret_cast<float *>(smem + (size_t)CB * per_mb * 16);
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int j = lane & 31, h = lane >> 5;
+    const int slot = fdiv((int)blockIdx.x, p.dNcblk), cblk = (int)blockIdx.x - slot * p.ncblk;
+    const int nslots = (int)gridDim.x / p.ncblk;
+    const int mb0 = cblk * CB;
+    {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(p.wp);
+        const uint32_t first = (uint32_t)mb0 * (uint32_t)per_mb;
+        for (int e = t; e < CB * per_mb; e += kThreads) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (first + (uint32_t)e < p.wp_elems) v = src[first + e];
+            wl[e] = v;
+        }
+        if (t < CB * 32) {
+            const int m = mb0 * 32 + t;
+            bl[t] = (p.b && m < p.Cout) ? p.b[m] : 0.f;
+        }
+    }
+    __syncthreads();
+
+    const rsrc_t rin = make_rsrc(p.in, p.in_bytes);
+    const rsrc_t rout = make_rsrc(p.out, p.out_bytes);
+    const float lowest = p.relu ? 0.f : -__builtin_inff();
+    const uint32_t hw16 = (uint32_t)p.HW * 16u, hwin16 = (uint32_t)(p.Hin * p.Win) * 16u, row16 = (uint32_t)p.Win * 16u;
+
+    for (int tile = slot * kWaves + wv; tile < p.tiles; tile += nslots * kWaves) {
+        const int gp = tile * 32 + j;
+        const bool ok = gp < p.PT;
+        const int gq = ok ? gp : 0;
+        const int n = fdiv(gq, p.dHW), pix = gq - n * p.HW;
+        const int y = fdiv(pix, p.dW), x = pix - y * p.W;
+        // first element of this pixel's window in layer block h of a pair; every window lies inside the map
+        const uint32_t ibase = ok ? (uint32_t)(((n * (p.Cin >> 3) + h) * p.Hin + 2 * y) * p.Win + 2 * x) * 16u : kOob;
+        const uint32_t obase = ok ? (uint32_t)((n * p.ldcb + p.coffb) * p.HW + pix) * 16u + 8u * (uint32_t)h : kOob;
+
+        float bx[D][9][4];
+        auto issue = [&](int ring, int s_) {
+            const int s = __builtin_amdgcn_readfirstlane(s_);
+            const uint32_t so = (uint32_t)s * 2u * hwin16;
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                uint32_t off = ok ? ibase + (uint32_t)i * row16 : kOob;
+                asm volatile("" : "+v"(off));   // the twelve loads of a window row differ by immediates only
+#pragma unroll
+                for (int jx = 0; jx < 3; ++jx)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) bx[ring][3 * i + jx][q] = buf_ld(rin, off + 16u * jx + 4u * q, so);
+            }
+        };
+#pragma unroll
+        for (int r = 0; r < D; ++r) issue(r, r);
+
+        f32x16 acc[CB];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 bv = *reinterpret_cast<const f32x4 *>(bl + cb * 32 + 8 * q + 4 * h);
+                acc[cb][4 * q + 0] = bv.x; acc[cb][4 * q + 1] = bv.y; acc[cb][4 * q + 2] = bv.z; acc[cb][4 * q + 3] = bv.w;
+            }
+        auto compute = [&](int ring, int s) {
+            u32x4 m;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t k = order_key(__builtin_bit_cast(uint32_t, bx[ring][0][q]));
+#pragma unroll
+                for (int e = 1; e < 9; ++e) k = max_u16x2(k, order_key(__builtin_bit_cast(uint32_t, bx[ring][e][q])));
+                m[q] = order_key_inverse(k);
+            }
+            const bf16x8 b = __builtin_bit_cast(bf16x8, m);
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, wl[(cb * p.steps + s) * 64 + lane]);
+                acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[cb], 0, 0, 0);
+            }
+        };
+        int s0 = 0;
+        for (; s0 < p.steps - D; s0 += D) {
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                compute(r, s0 + r);
+                issue(r, s0 + r + D);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < D; ++r) compute(r, s0 + r);
+
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int lb = (mb0 + cb) * 4 + q;
+                if (lb * 8 < p.Cout) {
+                    const float v0 = fmaxf(acc[cb][4 * q + 0], lowest), v1 = fmaxf(acc[cb][4 * q + 1], lowest);
+                    const float v2 = fmaxf(acc[cb][4 * q + 2], lowest), v3 = fmaxf(acc[cb][4 * q + 3], lowest);
+                    buf_st2(rout, obase, (uint32_t)lb * hw16, __builtin_bit_cast(float, pack2(v0, v1)),
+                            __builtin_bit_cast(float, pack2(v2, v3)));
                 }
             }
     }
@@ -471,6 +606,7 @@ int plan_conv(ConvPlan &pl, const void *in, const void *wp, const float *b, void
     p.in_bytes = (uint32_t)in_bytes; p.out_bytes = (uint32_t)out_bytes;
     p.wp_elems = (uint32_t)(blocked_packed_kernel_bytes(Cout, Cin, K) / 16);
     p.N = N; p.Cin = Cin; p.H = H; p.W = W; p.HW = H * W; p.Cout = Cout; p.K = K; p.P = P; p.relu = relu;
+    p.Hin = H; p.Win = W;
     p.G = Cin / 16;
     p.steps = K * K * p.G;
     p.ldcb = ldc_channels / 8; p.coffb = c_offset / 8;
@@ -574,6 +710,47 @@ int blocked_conv_pair(const void *in, const void *wp1, const float *b1, int Cout
     const size_t lds = (ldsk > lds1 ? ldsk : lds1) + (size_t)pk.CB * 32 * sizeof(float);
     LaunchScope scope(launch_name(K, pk.CB, pk.PB, D, true), p1.flops + pk.flops, p1.bytes + pk.bytes - 2.0 * N * Cin * H * W);
     hipLaunchKernelGGL(fn, dim3((unsigned)(wg1 + wgk)), dim3(kThreads), lds, current_stream(), p1.p, pk.p, (int)wg1);
+    return check_launch();
+}
+
+// 3x3 stride-2 max pooling of a blocked map of Cin layers (Hin x Win) followed by a 1x1 convolution to Cout layers,
+// in one launch; the pooled map is never written.
+int blocked_pool_conv(const void *in, const void *wp, const float *b, void *out, int N, int Cin, int Hin, int Win, int Cout,
+                      int relu, int ldc_channels, int c_offset)
+{
+    if (Hin < 3 || Win < 3) return SQ_ERR_SHAPE;
+    const int H = (Hin - 3) / 2 + 1, W = (Win - 3) / 2 + 1;
+    ConvPlan pl;
+    // planned on the pooled extents (they are the output's); the input side is patched afterwards
+    int rc = plan_conv(pl, in, wp, b, out, N, Cin, H, W, Cout, 1, 0, relu, ldc_channels, c_offset, 0, 1, 0);
+    if (rc) return rc;
+    const long long in_bytes = (long long)blocked_map_bytes(N, Cin, Hin, Win);
+    if (in_bytes >= (1ll << 31)) return SQ_ERR_UNSUPPORTED;
+    pl.p.in_bytes = (uint32_t)in_bytes;
+    pl.p.Hin = Hin; pl.p.Win = Win;
+    // nine 16-byte loads per lane and step: two steps in flight is what the registers hold
+    const int D = pl.p.steps % 2 == 0 ? 2 : 1;
+    typedef void (*PoolConvFn)(const ConvParams);
+    PoolConvFn fn = pl.CB == 2 ? (D == 2 ? pool_conv_blocked_kernel<2, 2> : pool_conv_blocked_kernel<2, 1>)
+                               : (D == 2 ? pool_conv_blocked_kernel<1, 2> : pool_conv_blocked_kernel<1, 1>);
+    static PoolConvFn allowed[4];
+    bool seen = false;
+    for (PoolConvFn f : allowed) seen |= f == fn;
+    if (!seen) {
+        if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, mfma::kLdsBytes) != hipSuccess) {
+            const int e = check_launch();
+            return e ? e : SQ_ERR_HIP;
+        }
+        for (PoolConvFn &f : allowed)
+            if (!f) { f = fn; break; }
+    }
+    const long long wgs = slots_for(pl, 2ll * num_cus_blocked()) * pl.p.ncblk;
+    const size_t lds = (size_t)pl.CB * pl.per_mb + (size_t)pl.CB * 32 * sizeof(float);
+    static char names[3][3][24];
+    char *name = names[pl.CB][D];
+    if (!name[0]) snprintf(name, sizeof names[0][0], "pool3s2+k1b_%dx32_d%d", 32 * pl.CB, D);
+    LaunchScope scope(name, pl.flops, 2.0 * ((double)N * Cin * Hin * Win + (double)Cout * Cin + (double)N * Cout * H * W) + 4.0 * Cout);
+    hipLaunchKernelGGL(fn, dim3((unsigned)wgs), dim3(kThreads), lds, current_stream(), pl.p);
     return check_launch();
 }
 

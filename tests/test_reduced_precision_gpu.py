@@ -228,6 +228,32 @@ def test_blocked_maxpool_is_exact(sq, shape, k, s):
     assert np.array_equal(got, ref)
 
 
+@pytest.mark.parametrize("case", [(2, 96, 111, 111, 16), (2, 256, 55, 55, 32), (3, 512, 27, 27, 64), (1, 16, 3, 3, 8),
+                                  (2, 48, 10, 7, 40), (1, 16, 4, 9, 72)])
+@pytest.mark.parametrize("relu", [True, False])
+def test_pooling_inside_the_convolution_launch(sq, case, relu):
+    """3x3 stride-2 max pooling fused into the 1x1 convolution that reads it: equal bit for bit to the two
+    separate launches, and to the oracle (pooling exact, convolution at the tight bar); inputs of both signs."""
+    N, Cin, Hin, Win, Cout = case
+    rng = np.random.default_rng(500 + Cin + Cout)
+    x = synth.normal01(rng, (N, Cin, Hin, Win))
+    w, b = synth.conv_params(rng, Cout, Cin, 1)
+    m = to_blocked(x).cuda()
+    wp = sq.sq_blocked_pack_kernels(dev(w))
+    fused = sq.sq_blocked_pool_conv2d_forward(m, wp, dev(b), Cin, Cout, relu)
+    two = sq.sq_blocked_conv2d_forward(sq.sq_blocked_maxpool(m, Cin, 3, 2), wp, dev(b), Cin, Cout, 1, 0, relu)
+    assert fused.shape == two.shape
+    assert torch.equal(fused.view(torch.int16), two.view(torch.int16))
+    pooled = oracle.maxpool(rounded(x), 3, 2)
+    assert_close(from_blocked(fused, Cout), oracle.conv2d(pooled, rounded(w), b, 1, 0, relu), TIGHT_TOL, "pool + 1x1")
+    assert_close(from_blocked(fused, Cout), oracle.conv2d(oracle.maxpool(x, 3, 2), w, b, 1, 0, relu), BF16_TOL, "stated tolerance")
+    # into a wider map at an offset
+    out = torch.full((N, Cout // 8 + 2, two.shape[2], two.shape[3], 8), -7.0, device="cuda", dtype=torch.bfloat16)
+    sq.sq_blocked_pool_conv2d_forward(m, wp, dev(b), Cin, Cout, relu, out=out, c_offset=8)
+    assert torch.equal(out[:, 1:-1].contiguous().view(torch.int16), two.view(torch.int16))
+    assert (out[:, 0] == -7.0).all() and (out[:, -1] == -7.0).all()
+
+
 @pytest.mark.parametrize("shape", [(2, 1000, 13, 13), (3, 20, 5, 4), (1, 8, 1, 1)])
 def test_blocked_avgpool_matches_oracle(sq, shape):
     rng = np.random.default_rng(6)
@@ -242,7 +268,7 @@ def _network(sq, cfg, x_dev):
     params = [dev(p) for p in cfg["params"]]
     packed = sq.sq_squeezenet_bf16_pack_params(params)
     probs, taps = sq.sq_squeezenet_forward_bf16(x_dev, params, packed, want_taps=True)
-    plain = sq.sq_squeezenet_forward_bf16(x_dev, params, packed)
+    plain = sq.sq_squeezenet_forward_bf16(x_dev, params, packed)     # without taps the pools run inside the squeeze launches
     assert torch.equal(plain, probs)
     return params, probs, taps
 

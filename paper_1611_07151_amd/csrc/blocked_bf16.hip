@@ -152,12 +152,24 @@ __global__ __launch_bounds__(kThreads, 2) void conv_blocked_kernel(const ConvPar
 
     // ---- this workgroup's kernels and bias into LDS (a straight copy: they are packed) ----
     {
+        // (all loads of a batch are issued before the first LDS write, so their latencies overlap: with up to
+        // 74 KB per workgroup a load-then-write loop would spend ten memory round trips before the first MFMA)
         const u32x4 *src = reinterpret_cast<const u32x4 *>(p.wp);
         const uint32_t first = (uint32_t)mb0 * (uint32_t)per_mb;
-        for (int e = t; e < CB * per_mb; e += kThreads) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (first + (uint32_t)e < p.wp_elems) v = src[first + e];
-            wl[e] = v;
+        constexpr int kBatch = 10;
+        for (int e0 = t; e0 < CB * per_mb; e0 += kBatch * kThreads) {
+            u32x4 v[kBatch];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const int e = e0 + k * kThreads;
+                v[k] = u32x4{0u, 0u, 0u, 0u};
+                if (e < CB * per_mb && first + (uint32_t)e < p.wp_elems) v[k] = src[first + e];
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const int e = e0 + k * kThreads;
+                if (e < CB * per_mb) wl[e] = v[k];
+            }
         }
         if (t < CB * 32) {
             const int m = mb0 * 32 + t;
@@ -309,12 +321,24 @@ __global__ __launch_bounds__(kThreads, 2) void pool_conv_blocked_kernel(const Co
     const int nslots = (int)gridDim.x / p.ncblk;
     const int mb0 = cblk * CB;
     {
+        // (all loads of a batch are issued before the first LDS write, so their latencies overlap: with up to
+        // 74 KB per workgroup a load-then-write loop would spend ten memory round trips before the first MFMA)
         const u32x4 *src = reinterpret_cast<const u32x4 *>(p.wp);
         const uint32_t first = (uint32_t)mb0 * (uint32_t)per_mb;
-        for (int e = t; e < CB * per_mb; e += kThreads) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (first + (uint32_t)e < p.wp_elems) v = src[first + e];
-            wl[e] = v;
+        constexpr int kBatch = 10;
+        for (int e0 = t; e0 < CB * per_mb; e0 += kBatch * kThreads) {
+            u32x4 v[kBatch];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const int e = e0 + k * kThreads;
+                v[k] = u32x4{0u, 0u, 0u, 0u};
+                if (e < CB * per_mb && first + (uint32_t)e < p.wp_elems) v[k] = src[first + e];
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const int e = e0 + k * kThreads;
+                if (e < CB * per_mb) wl[e] = v[k];
+            }
         }
         if (t < CB * 32) {
             const int m = mb0 * 32 + t;
@@ -507,12 +531,12 @@ template <int CB, int PB> BlockedConvFn conv_fn(int D)
 
 bool allow_lds(BlockedConvFn fn)
 {
-    static BlockedConvFn done[16];
+    static BlockedConvFn done[32];
     static int ndone = 0;
     for (int i = 0; i < ndone; ++i)
         if (done[i] == fn) return true;
     if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, mfma::kLdsBytes) != hipSuccess) return false;
-    if (ndone < 16) done[ndone++] = fn;
+    if (ndone < 32) done[ndone++] = fn;
     return true;
 }
 

@@ -313,10 +313,13 @@ def main() -> int:
     # ---------------------------------------------------------------- energy per image
     energy = None
     if idle_w is not None:
-        def run_for(xx, pp, ww, oo, n):
+        def run_for(xx, pp, ww, oo, n, packed_kernels=None):
             def burst():
                 for _ in range(8):
-                    sq.sq_squeezenet_forward(xx, pp, workspace=ww, probs=oo)
+                    if packed_kernels is None:
+                        sq.sq_squeezenet_forward(xx, pp, workspace=ww, probs=oo)
+                    else:
+                        sq.sq_squeezenet_forward_bf16(xx, pp, packed_kernels, workspace=ww, probs=oo)
                 torch.cuda.synchronize()
             load = sample_power(sensor, args.energy_seconds, burst, settle=0.5)
             t0, reps = time.perf_counter(), 0
@@ -333,6 +336,8 @@ def main() -> int:
         energy[f"batch{B}"] = run_for(x, params, ws, probs, B)
         if not args.skip_batch1:
             energy["batch1"] = run_for(x1, params1, ws1, probs1, 1)
+        if reduced is not None:
+            energy[f"batch{B}_reduced_precision"] = run_for(x, params, ws16, probs16, B, packed)
 
     # ---------------------------------------------------------------- CPU oracle baseline
     cpu = None

@@ -206,24 +206,42 @@ __global__ __launch_bounds__(kThreads, 2) void conv_blocked_kernel(const ConvPar
         }
 
         // input of step s = (tap, pair of layer blocks g): one 16-byte element per lane and pixel block,
-        // loaded as four adjacent dwords the compiler merges
+        // loaded as four adjacent dwords the compiler merges.  Steps are loaded in order, so the position
+        // (tap, g) of the next one is a cursor that is advanced after every load: one scalar add per step
+        // and the per-lane offsets of a tap only when the tap changes (the scalar unit of a SIMD is shared
+        // by its wavefronts; recomputing the position of every step from its index by divisions kept it
+        // busy 74 % of the kernel's time).
         float bx[D][PB][4];
-        auto issue = [&](int ring, int s_) {
-            const int s = __builtin_amdgcn_readfirstlane(s_);
-            const int tap = fdiv(s, p.dG), g = s - tap * p.G;
-            const int ky = fdiv(tap, p.dK), kx = tap - ky * p.K;
-            const int shift = ((ky - p.P) * p.W + (kx - p.P)) * 16;
-            const uint32_t so = (uint32_t)g * 2u * hw16;
+        int g_i = 0, tap_i = 0, ky_i = 0, kx_i = 0;
+        uint32_t so_i = 0, off_i[PB];
+        auto set_tap = [&]() {
+            const int shift = ((ky_i - p.P) * p.W + (kx_i - p.P)) * 16;
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb) off_i[pb] = ((vmask[pb] >> tap_i) & 1u) ? ibase[pb] + (uint32_t)shift : kOob;
+        };
+        set_tap();
+        auto issue = [&](int ring) {
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
-                uint32_t off = ((vmask[pb] >> tap) & 1u) ? ibase[pb] + (uint32_t)shift : kOob;
+                uint32_t off = off_i[pb];
                 asm volatile("" : "+v"(off));   // keeps +4, +8, +12 as immediates so that the four loads merge
 #pragma unroll
-                for (int q = 0; q < 4; ++q) bx[ring][pb][q] = buf_ld(rin, off + 4u * q, so);
+                for (int q = 0; q < 4; ++q) bx[ring][pb][q] = buf_ld(rin, off + 4u * q, so_i);
+            }
+            so_i += 2u * hw16;
+            if (++g_i == p.G) {      // uniform: next tap
+                g_i = 0;
+                so_i = 0;
+                ++tap_i;
+                if (++kx_i == p.K) {
+                    kx_i = 0;
+                    ++ky_i;
+                }
+                set_tap();
             }
         };
 #pragma unroll
-        for (int r = 0; r < D; ++r) issue(r, r);
+        for (int r = 0; r < D; ++r) issue(r);
 
         // ---- accumulators start from the bias: registers 4q..4q+3 = layers 8q + 4h .. +3 of the block
         f32x16 acc[CB][PB];
@@ -239,25 +257,34 @@ __global__ __launch_bounds__(kThreads, 2) void conv_blocked_kernel(const ConvPar
                 }
             }
 
-        auto compute = [&](int ring, int s) {
-            bf16x8 a[CB];
+        // A operands are read from LDS one step ahead of their MFMAs (the read of step s+1 is issued before the
+        // MFMAs of step s), so the LDS latency is not on the path from one step to the next
+        bf16x8 a_cur[CB], a_nxt[CB];
+        auto read_a = [&](bf16x8 (&a)[CB], int s) {
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) a[cb] = __builtin_bit_cast(bf16x8, wl[(cb * p.steps + s) * 64 + lane]);
+        };
+        auto compute = [&](int ring, int s) {
+            read_a(a_nxt, s + 1 < p.steps ? s + 1 : s);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
                 f32x4 raw = {bx[ring][pb][0], bx[ring][pb][1], bx[ring][pb][2], bx[ring][pb][3]};
                 const bf16x8 b = __builtin_bit_cast(bf16x8, raw);
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
-                    acc[cb][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cb], b, acc[cb][pb], 0, 0, 0);
+                    acc[cb][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[cb], b, acc[cb][pb], 0, 0, 0);
             }
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) a_cur[cb] = a_nxt[cb];
         };
+        read_a(a_cur, 0);
         int s0 = 0;
         for (; s0 < p.steps - D; s0 += D) {
 #pragma unroll
             for (int r = 0; r < D; ++r) {
                 compute(r, s0 + r);
-                issue(r, s0 + r + D);
+                issue(r);
             }
         }
 #pragma unroll

@@ -31,7 +31,7 @@ namespace sq {
 namespace mfma {
 namespace {
 
-constexpr int kKS = 7, kS = 2, kKK = 49, kK = 147, kLDK = 149, kBM = 96, kTM = 3;
+constexpr int kKS = 7, kS = 2, kKK = 49, kK = 147, kLDK = 149;
 constexpr int kTR = kConv7TileRows, kTC = kConv7TileCols;
 constexpr int kPR = (kTR - 1) * kS + kKS;      // 9 patch rows
 constexpr int kPC = (kTC - 1) * kS + kKS;      // 37 patch columns
@@ -40,7 +40,8 @@ constexpr int kLWs = 40;                       // LDS row stride: the two pixel 
 constexpr int kPlane = 416;                    // >= 9*40, = 32 (mod 64): the two k-halves on disjoint banks
 constexpr int kOne = 3 * kPlane;               // word holding 1.0 (multiplier of the bias slot)
 constexpr int kXbuf = 3 * kPlane + 32;         // floats per patch buffer
-constexpr int kWsFloats = kBM * kLDK + 32 - (kBM * kLDK) % 32;
+// LDS floats of the kernels of 32*TM output layers (padded: the tile counter lives in the padding)
+constexpr int ws_floats(int TM) { return 32 * TM * kLDK + 32 - (32 * TM * kLDK) % 32; }
 static_assert(kPR * kLWs <= kPlane && kPC <= kLWs, "patch plane");
 
 // position of patch column c inside a row: even columns, then odd columns
@@ -76,10 +77,15 @@ __host__ __device__ constexpr int step_offset(int s)
 }
 
 // FULL: the layer has exactly 96 output layers, so no store needs a layer test.
+// TM: blocks of 32 output layers a workgroup computes (3 = all 96; 1 = blockIdx.y picks one block, which
+// triples the number of wavefronts and cuts the MFMA chain of a tile to a third -- for small batches,
+// where there are too few tiles to fill the GPU and a pass is bound by the latency of each launch).
 // TIN: float, or uint16_t = bfloat16 input and kernels, widened to fp32 while staged.
-template <typename TIN, int NW, bool FULL, int MINW>
+template <typename TIN, int NW, bool FULL, int MINW, int TM>
 __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams p)
 {
+    constexpr int kTM = TM, kBM = 32 * TM, kWsFloats = ws_floats(TM);
+    const int m0 = (int)blockIdx.y * kBM;          // first output layer of this workgroup
     constexpr int ESZ = (int)sizeof(TIN);
     using M = Mfma<32>;
     using Acc = typename M::Acc;
@@ -101,7 +107,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
 #pragma unroll
         for (int r = 0; r < WR; ++r) {
             const int e = t + NT * r;
-            wv_[r] = buf_ld_in<TIN>(rw, e < kBM * kK ? (uint32_t)(e * ESZ) : kOob, 0);
+            wv_[r] = buf_ld_in<TIN>(rw, e < kBM * kK ? (uint32_t)((m0 * kK + e) * ESZ) : kOob, 0);
         }
 #pragma unroll
         for (int r = 0; r < WR; ++r) {
@@ -111,7 +117,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
         }
     }
     if (t < kBM) {
-        Ws[t * kLDK + 147] = (p.b && t < p.Cout) ? p.b[t] : 0.f;
+        Ws[t * kLDK + 147] = (p.b && m0 + t < p.Cout) ? p.b[m0 + t] : 0.f;
         Ws[t * kLDK + 148] = 0.f;
     }
     if (lane < 2) Xw[lane * kXbuf + kOne] = 1.0f;
@@ -221,11 +227,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
                     acc[x] = M::run(av[s & 1][x], bv[s & 1], acc[x]);
                 }
             }
-            if (s < 48) {
+            if (s < 16 * kTM) {
                 // layers come in groups of 8 (rows mu..mu+3 in the lower half-wave, +4 in the
                 // upper), and Cout is a multiple of 8, so the layer test is uniform
                 const int x = s / 16, r = s % 16;
-                const int mu = x * 32 + M::row_reg(r);
+                const int mu = m0 + x * 32 + M::row_reg(r);
                 if (FULL || mu < p.Cout) buf_st(rout, prev_off, (uint32_t)mu * hs1, prev[x][r]);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -291,26 +297,31 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
     for (int x = 0; x < kTM; ++x)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int mu = x * 32 + M::row_reg(r);
+            const int mu = m0 + x * 32 + M::row_reg(r);
             if (FULL || mu < p.Cout) buf_st(rout, lastA ? offA : offB, (uint32_t)mu * hs1, lastA ? accA[x][r] : accB[x][r]);
         }
 }
 
 }  // namespace
 
-KernelFn conv7s2c3_kernel_for(int NW, bool full, bool bf16)
+KernelFn conv7s2c3_kernel_for(int NW, bool full, bool bf16, int TM)
 {
+    if (TM == 1) {
+        if (NW != 4) return nullptr;
+        if (bf16) return full ? conv7s2c3_kernel<uint16_t, 4, true, 2, 1> : conv7s2c3_kernel<uint16_t, 4, false, 2, 1>;
+        return full ? conv7s2c3_kernel<float, 4, true, 2, 1> : conv7s2c3_kernel<float, 4, false, 2, 1>;
+    }
     if (bf16) {
-        if (NW == 8) return full ? conv7s2c3_kernel<uint16_t, 8, true, 1> : conv7s2c3_kernel<uint16_t, 8, false, 1>;
-        if (NW == 4) return full ? conv7s2c3_kernel<uint16_t, 4, true, 1> : conv7s2c3_kernel<uint16_t, 4, false, 1>;
+        if (NW == 8) return full ? conv7s2c3_kernel<uint16_t, 8, true, 1, 3> : conv7s2c3_kernel<uint16_t, 8, false, 1, 3>;
+        if (NW == 4) return full ? conv7s2c3_kernel<uint16_t, 4, true, 1, 3> : conv7s2c3_kernel<uint16_t, 4, false, 1, 3>;
         return nullptr;
     }
-    if (NW == 8) return full ? conv7s2c3_kernel<float, 8, true, 1> : conv7s2c3_kernel<float, 8, false, 1>;
-    if (NW == 4) return full ? conv7s2c3_kernel<float, 4, true, 1> : conv7s2c3_kernel<float, 4, false, 1>;
+    if (NW == 8) return full ? conv7s2c3_kernel<float, 8, true, 1, 3> : conv7s2c3_kernel<float, 8, false, 1, 3>;
+    if (NW == 4) return full ? conv7s2c3_kernel<float, 4, true, 1, 3> : conv7s2c3_kernel<float, 4, false, 1, 3>;
     return nullptr;
 }
 
-size_t conv7s2c3_lds_bytes(int NW) { return ((size_t)kWsFloats + (size_t)NW * 2 * kXbuf) * sizeof(float); }
+size_t conv7s2c3_lds_bytes(int NW, int TM) { return ((size_t)ws_floats(TM) + (size_t)NW * 2 * kXbuf) * sizeof(float); }
 
 }  // namespace mfma
 }  // namespace sq

@@ -51,18 +51,20 @@ struct Variant {
     {"k" #KS "s" #S "_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC "_o" #MINW, KS, S, BM, BN, MT, CC, PE, 2, \
      WM * WN * 64, false, false},
 #define SQ_C(NW) {"k7s2c3_waves" #NW, 7, 2, 96, 32 * NW, 32, 3, 64, 2, 64 * NW, true, false},
+#define SQ_C1(NW) {"k7s2c3_waves" #NW "_m32", 7, 2, 32, 32 * NW, 32, 3, 64, 2, 64 * NW, true, false},
 #define SQ_W(BM, BT, CC) {"k3s1_f2x2_" #BM "x" #BT "_c" #CC, 3, 1, BM, BT, 32, CC, 0, 2, 256, false, true},
 static_assert(kWinoBM == 64 && kWinoBT == 32 && kWinoCC == 8, "the W() entry of the variant list names these");
-const Variant kVariants[] = {SQ_VARIANT_LIST(SQ_V, SQ_V, SQ_C, SQ_W)};
+const Variant kVariants[] = {SQ_VARIANT_LIST(SQ_V, SQ_V, SQ_C, SQ_W, SQ_C1)};
 #undef SQ_V
 #undef SQ_C
+#undef SQ_C1
 #undef SQ_W
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 struct Plan {
     KParams kp;
     size_t lds_bytes;
-    unsigned blocks;
+    unsigned blocks, blocks_y;
 };
 
 int num_cus()
@@ -114,6 +116,7 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
                    a.ws_bytes < wino_transformed_bytes(a.Cout, a.Cin)))
         return false;
 
+    pl.blocks_y = 1;
     KParams &k = pl.kp;
     k.in = (const float *)a.in; k.w = (const float *)a.w; k.b = a.b; k.out = a.out;
     k.N = a.N; k.Cin = a.Cin; k.H = a.H; k.W = a.W; k.Cout = a.Cout; k.P = a.P; k.relu = a.relu;
@@ -173,9 +176,10 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
         k.dRG = make_fastdiv(k.RG); k.dCB = make_fastdiv(k.CB);
         k.dMtiles = make_fastdiv(k.RG * k.CB);
         k.ntiles = (int)tiles;
-        pl.lds_bytes = conv7s2c3_lds_bytes(NW);
+        pl.lds_bytes = conv7s2c3_lds_bytes(NW, v.BM / 32);
         blocks = (tiles + NW - 1) / NW;
         if (blocks > num_cus()) blocks = num_cus();
+        if (v.BM == 32) pl.blocks_y = (unsigned)k.mtiles;   // one workgroup per block of 32 output layers
     } else if (v.wino) {
         blocks = std::min<long long>(blocks, 2ll * num_cus());   // persistent: two workgroups per CU
         pl.lds_bytes = (size_t)(kWinoImage + 16 * 2 * kWinoBT * 4) * sizeof(float);
@@ -207,7 +211,7 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
     const Variant &v = kVariants[vi];
     const KernelSet &ks = kernel_set(v, a.dtype);
     KernelFn fn = e1 ? ks.fused_e1 : ks.plain;
-    if (v.conv1_type) fn = conv7s2c3_kernel_for(v.NT / 64, a.Cout == 96, a.dtype == SQ_BF16);
+    if (v.conv1_type) fn = conv7s2c3_kernel_for(v.NT / 64, a.Cout == 96, a.dtype == SQ_BF16, v.BM / 32);
     if (!v.conv1_type && !v.wino && !e1 && a.Cin % v.CC != 0) fn = ks.tail;
     if (!allow_big_lds(fn)) {
         const int rc = check_launch();
@@ -224,7 +228,7 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
         if (rc) return rc;
     }
     LaunchScope scope(v.name, flops, bytes);
-    hipLaunchKernelGGL(fn, dim3(pl.blocks), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
+    hipLaunchKernelGGL(fn, dim3(pl.blocks, pl.blocks_y), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
     return check_launch();
 }
 
@@ -311,8 +315,8 @@ int conv_mfma_variant_count() { return kNumVariants; }
 const char *conv_mfma_variant_name(int i) { return kVariants[i].name; }
 
 // Which tiling runs the fused expand: -3 = never fuse, -2 = the default policy (fuse at batches of at
-// most four images, where a fire layer is bound by its launches: measured 14 % / 10 % / 5 % faster
-// network passes at batch 1 / 2 / 4, even at 8, slower from 32 on, where the fused kernel's lower
+// most 16 images, where a fire layer is bound by its launches: measured 14 % / 10 % / 5 % / 3 % / 4 %
+// faster network passes at batch 1 / 2 / 4 / 8 / 16, slower from 32 on, where the fused kernel's lower
 // occupancy costs more than the launch it saves), -1 = always, automatic choice of tiling,
 // i >= 0 = tiling i.  The setter is a tuning hook, not part of the public interface.
 int g_force_expand = -2;
@@ -325,7 +329,7 @@ int conv_expand_fused(const ConvArgs &a3, const void *w1, const float *b1, int C
     if (a3.K != 3 || a3.S != 1 || a3.P != 1 || a3.dtype != SQ_F32) return SQ_ERR_UNSUPPORTED;
     const FusedE1 e1{w1, b1, Cout1, coff1};
     Plan pl;
-    if (g_force_expand == -3 || (g_force_expand == -2 && a3.N > 4)) return SQ_ERR_UNSUPPORTED;
+    if (g_force_expand == -3 || (g_force_expand == -2 && a3.N > 16)) return SQ_ERR_UNSUPPORTED;
     if (g_force_expand >= 0) {
         if (g_force_expand >= kNumVariants || !plan(kVariants[g_force_expand], a3, pl, &e1)) return SQ_ERR_UNSUPPORTED;
         return launch(g_force_expand, pl, a3, &e1);

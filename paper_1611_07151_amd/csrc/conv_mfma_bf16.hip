@@ -15,7 +15,7 @@ namespace mfma {
      nullptr},
 #define SQ_C(NW) {nullptr, nullptr, nullptr},
 #define SQ_W(BM, BT, CC) {conv_wino_kernel<uint16_t>, nullptr, nullptr},
-const KernelSet conv_mfma_kernels_bf16[] = {SQ_VARIANT_LIST(SQ_V, SQ_E, SQ_C, SQ_W)};
+const KernelSet conv_mfma_kernels_bf16[] = {SQ_VARIANT_LIST(SQ_V, SQ_E, SQ_C, SQ_W, SQ_C)};
 
 }  // namespace mfma
 }  // namespace sq

@@ -196,7 +196,8 @@ struct KernelSet {
     KernelFn plain, tail, fused_e1;
 };
 extern const KernelSet conv_mfma_kernels_f32[], conv_mfma_kernels_bf16[];
-KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers, bool bf16_inputs);
+// TM = blocks of 32 output layers per workgroup: 3 (all 96), or 1 with the block chosen by blockIdx.y (NW = 4 only).
+KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers, bool bf16_inputs, int TM);
 
 // Minimal-filtering F(2x2, 3x3) kernel: workgroup tile (output layers x tiles of 2x2 pixels),
 // input layers per chunk, and the floats of the kernel image [16 positions][2][64][4] of one chunk.
@@ -205,7 +206,7 @@ constexpr int kWinoImage = 16 * 2 * 64 * 4;
 constexpr int kWinoMaxJobs = 8;
 
 constexpr int kConv7TileRows = 2, kConv7TileCols = 16;   // output pixels per wavefront tile
-size_t conv7s2c3_lds_bytes(int NW);
+size_t conv7s2c3_lds_bytes(int NW, int TM);
 
 }  // namespace mfma
 }  // namespace sq

@@ -15,7 +15,7 @@ namespace mfma {
      conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false, true>},
 #define SQ_C(NW) {nullptr, nullptr, nullptr},
 #define SQ_W(BM, BT, CC) {conv_wino_kernel<float>, nullptr, nullptr},
-const KernelSet conv_mfma_kernels_f32[] = {SQ_VARIANT_LIST(SQ_V, SQ_E, SQ_C, SQ_W)};
+const KernelSet conv_mfma_kernels_f32[] = {SQ_VARIANT_LIST(SQ_V, SQ_E, SQ_C, SQ_W, SQ_C)};
 
 }  // namespace mfma
 }  // namespace sq

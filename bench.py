@@ -84,9 +84,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--calibrate-copy", action="store_true")
-    ap.add_argument("--layer-sweep", choices=["f32", "bf16"], default=None,
+    ap.add_argument("--layer-sweep", choices=["f32", "bf16", "blocked"], default=None,
                     help="instead of the network: time every convolution shape on its own at --batch "
-                         "(workload 5 is --layer-sweep bf16 --batch 256) and print one JSON line")
+                         "(workload 5 is --layer-sweep bf16 --batch 256) and print one JSON line; "
+                         "'blocked' = the reduced-precision kernels on blocked bfloat16 maps")
+    ap.add_argument("--only", default=None, help="with --layer-sweep: only the layers whose name contains this")
     ap.add_argument("--net", choices=["squeezenet", "second"], default="squeezenet",
                     help="layer list of --layer-sweep: SqueezeNet's 26 convolutions, or the five of a second CNN "
                          "(11x11 stride 4, 5x5, 3x3)")
@@ -135,11 +137,47 @@ def main() -> int:
     if args.layer_sweep:
         dt_in = torch.bfloat16 if args.layer_sweep == "bf16" else torch.float32
         esz = 2 if args.layer_sweep == "bf16" else 4
+        out_note = "bfloat16 maps and kernels, fp32 accumulate" if args.layer_sweep == "blocked" else \
+            f"{args.layer_sweep} inputs, fp32 accumulate/output"
         gen = torch.Generator(device="cuda").manual_seed(4)
         layers, total_flop, total_us = {}, 0.0, 0.0
         net_layers = synth.conv_layers() if args.net == "squeezenet" else synth.second_network_layers()
+        if args.only:
+            net_layers = [l for l in net_layers if args.only in l[0]]
         for name, cin, cout, k, s_, p_, h in net_layers:
             ho = (h + 2 * p_ - k) // s_ + 1
+            if args.layer_sweep == "blocked":
+                # the same shape through the reduced-precision kernels: blocked bfloat16 in and out, kernels packed ahead
+                xf = torch.randn((B, cin, h, h), device="cuda", generator=gen)
+                wf = torch.randn((cout, cin, k, k), device="cuda", generator=gen) * (2.0 / (cin * k * k)) ** 0.5
+                b = torch.rand(cout, device="cuda", generator=gen) * 0.2 - 0.1
+                if k == 7:
+                    wp = sq.sq_blocked_pack_kernels7(wf)
+                    run = lambda: sq.sq_blocked_conv7s2_forward(xf, wp, b, cout, p_, True, out=outm)
+                    in_bytes = 4.0 * B * cin * h * h
+                elif sq.lib.sq_blocked_kernel_bytes(cout, cin, k) and cin % 16 == 0 and k in (1, 3, 5) and s_ == 1 and p_ == k // 2:
+                    xm = sq.sq_blocked_pack(xf)
+                    wp = sq.sq_blocked_pack_kernels(wf)
+                    run = lambda: sq.sq_blocked_conv2d_forward(xm, wp, b, cin, cout, k, p_, True, out=outm)
+                    in_bytes = 2.0 * B * cin * h * h
+                else:
+                    continue                      # a shape the blocked kernels do not cover
+                outm = torch.empty((B, (cout + 7) // 8, ho, ho, 8), device="cuda", dtype=torch.bfloat16)
+                for _ in range(3):
+                    run()
+                sq.sq_profile_begin(64)
+                for _ in range(10):
+                    run()
+                recs = sq.sq_profile_end()
+                us = sum(r["ms"] for r in recs) / 10 * 1e3
+                flop = 2.0 * B * cout * ho * ho * cin * k * k
+                byts = in_bytes + 2.0 * cout * cin * k * k + 2.0 * B * cout * ho * ho
+                layers[name] = dict(us=round(us, 1), tflops=round(flop / us / 1e6, 1), gbs=round(byts / us / 1e3),
+                                    kernel=recs[0]["name"].split("|")[1])
+                total_flop += flop
+                total_us += us
+                del xf, wf, outm
+                continue
             x = torch.randn((B, cin, h, h), device="cuda", generator=gen).to(dt_in)
             w = (torch.randn((cout, cin, k, k), device="cuda", generator=gen) * (2.0 / (cin * k * k)) ** 0.5).to(dt_in)
             b = torch.rand(cout, device="cuda", generator=gen) * 0.2 - 0.1
@@ -160,9 +198,9 @@ def main() -> int:
             total_flop += flop
             total_us += us
             del x, w, out
-        print(json.dumps({"metric": f"per-layer convolution sweep, batch {B}, {args.layer_sweep} inputs, fp32 accumulate/output",
+        print(json.dumps({"metric": f"per-layer convolution sweep, batch {B}, {out_note}",
                           "value": round(total_flop / total_us / 1e6, 2), "unit": "TFLOP/s (all layers)",
-                          "n_gpus": 1, "dtype": args.layer_sweep, "data": "synthetic",
+                          "n_gpus": 1, "dtype": "bf16" if args.layer_sweep == "blocked" else args.layer_sweep, "data": "synthetic",
                           "config": {"workload": f"{len(net_layers)} convolution shapes ({args.net}) at batch {B}"},
                           "total_us": round(total_us, 1), "layers": layers}))
         return 0

@@ -96,7 +96,7 @@ def main() -> int:
                     help="length of each power-sampling window (0 = leave the energy measurement out)")
     ap.add_argument("--skip-reduced", action="store_true", help="leave the reduced-precision (bf16) network out")
     ap.add_argument("--skip-batch1", action="store_true", help="leave the batch-1 timing out (for profiler runs)")
-    ap.add_argument("--cpu-sample", type=int, default=32,
+    ap.add_argument("--cpu-sample", type=int, default=64,
                     help="images of the workload the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:

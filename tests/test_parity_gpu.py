@@ -50,6 +50,8 @@ CONV_CASES = [
     (2, 3, 37, 41, 96, 7, 2, 2),      # conv1-like, odd sizes
     (1, 3, 224, 224, 96, 7, 2, 2),    # conv1 at full size
     (1, 3, 227, 227, 96, 7, 2, 0),    # the other reading of conv1 (227, no pad)
+    (2, 3, 30, 33, 40, 7, 2, 2),      # conv1-type with fewer than 96 output layers (partial layer blocks)
+    (1, 3, 19, 64, 72, 7, 2, 3),
     (3, 16, 13, 13, 64, 3, 1, 1),     # expand3x3, several images per tile
     (2, 16, 55, 55, 64, 3, 1, 1),
     (1, 48, 27, 27, 192, 3, 1, 1),

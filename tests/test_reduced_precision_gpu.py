@@ -329,3 +329,23 @@ def test_network_end_to_end_against_the_fp32_oracle_and_fp32_gpu(sq):
     pb = sq.sq_squeezenet_forward_bf16(xb, params, packed)
     pf = sq.sq_squeezenet_forward_bf16(xb.float(), params, packed)
     assert_close(pb.cpu().numpy(), pf.cpu().numpy(), 2e-2, "bfloat16 image vs its fp32 widening")
+
+
+@pytest.mark.parametrize("n", [3, 33])
+def test_networks_at_odd_batch_sizes(sq, n):
+    """Batches that fill no tile evenly (and sit on both sides of the fusion policies): the fp32 network
+    against the oracle on the first and last image, the reduced-precision network against the fp32 one."""
+    cfg = synth.config_squeezenet(seed=7, n=n)
+    x = dev(cfg["x"])
+    params = [dev(p) for p in cfg["params"]]
+    probs32, taps32 = sq.sq_squeezenet_forward(x, params, want_taps=True)
+    assert torch.equal(sq.sq_squeezenet_forward(x, params), probs32)
+    for i in (0, n - 1):
+        ref_p, ref_t = oracle.squeezenet(cfg["x"][i:i + 1], cfg["params"], want_taps=True)
+        assert_close(taps32["means"][i:i + 1].cpu().numpy(), ref_t["means"], 1e-4, f"fp32 class means, image {i}")
+        assert_close(probs32[i:i + 1].cpu().numpy(), ref_p, 1e-4, f"fp32 probabilities, image {i}")
+    _, probs16, taps16 = _network(sq, cfg, x)
+    m16, m32 = taps16["means"].cpu().numpy().astype(np.float64), taps32["means"].cpu().numpy().astype(np.float64)
+    rel = np.abs(m16 - m32) / m32.std(axis=1, keepdims=True)
+    assert rel.max() < 0.25 and np.sqrt((rel ** 2).mean()) < 0.05, (rel.max(), np.sqrt((rel ** 2).mean()))
+    assert abs(float(probs16.sum()) - n) < 1e-3

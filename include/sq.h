@@ -244,8 +244,9 @@ size_t sq_squeezenet_workspace_bytes(int N);
  * sq_blocked_fire_forward(): the fire layer of sq_fire_forward on blocked maps, with
  * packed kernels (squeeze [Csq][Cin][1][1], expand [Ce1][Csq][1][1] and [Ce3][Csq][3][3]);
  * the squeeze map is rounded to bfloat16, both expands run in one launch and write
- * layers [0, Ce1) and [Ce1, Ce1+Ce3) of out.  workspace: device scratch of at least
- * sq_blocked_map_bytes(N, Csq, H, W) bytes, 256-byte aligned (the squeeze map).
+ * layers [0, Ce1) and [Ce1, Ce1+Ce3) of out.  workspace:
+ * device scratch of at least sq_blocked_map_bytes(N, Csq, H, W) bytes, 256-byte aligned
+ * (room for the squeeze map; contents on return are unspecified).
  * Cin and Csq multiples of 16, Ce1 and Ce3 multiples of 8.
  * sq_blocked_pool_conv2d_forward(): max pooling (3 x 3 window, stride 2, floor mode) of a
  * blocked map [N][Cin/8][Hin][Win][8] followed by a 1 x 1 convolution (+bias, optional

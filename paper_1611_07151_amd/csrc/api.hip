@@ -520,6 +520,17 @@ int sq_blocked_pool_conv2d_forward(const void *in, const void *packed_w, const f
     return blocked_pool_conv(in, packed_w, b, out, N, Cin, Hin, Win, Cout, relu ? 1 : 0, ldc_channels, c_offset);
 }
 
+// Whether a reduced-precision fire layer runs as one launch (squeeze map kept in LDS): 1 = always where the
+// shape is covered, 0 = never, -1 = the default policy by batch size.  Tuning hook, not part of the interface.
+// Measured on MI355X the one launch is slower than squeeze + paired expands at every batch (network pass at
+// batch 1 / 2 / 4 / 8 / 16: 0.133 / 0.143 / 0.154 / 0.185 / 0.261 ms against 0.124 / 0.129 / 0.140 / 0.156 /
+// 0.179 ms): with a band of a few rows per workgroup only two or three of its eight wavefronts have a pixel
+// block in each phase, and each walks its 6 to 36 dependent steps alone.  So the policy never picks it; it
+// stays selectable, with its parity test, as the measured form of "a fire layer in one launch".
+int g_fire_one_launch = -1;
+void sq_internal_fire_one_launch(int mode) { g_fire_one_launch = mode; }
+constexpr int kFireOneLaunchMaxBatch = 0;
+
 int sq_blocked_fire_forward(const void *in, const void *packed_sq, const float *b_sq, const void *packed_e1,
                             const float *b_e1, const void *packed_e3, const float *b_e3, void *out, int N, int Cin, int H,
                             int W, int Csq, int Ce1, int Ce3, void *workspace, size_t workspace_bytes)
@@ -530,6 +541,12 @@ int sq_blocked_fire_forward(const void *in, const void *packed_sq, const float *
     if (((uintptr_t)in & 15) || ((uintptr_t)out & 15) || ((uintptr_t)packed_sq & 15) || ((uintptr_t)packed_e1 & 15) ||
         ((uintptr_t)packed_e3 & 15) || Ce1 % 8 != 0)
         return SQ_ERR_UNSUPPORTED;
+    if (g_fire_one_launch == 1 || (g_fire_one_launch == -1 && N <= kFireOneLaunchMaxBatch)) {
+        set_stage("fire");
+        const int rc1 = blocked_fire_fused(in, packed_sq, b_sq, packed_e1, b_e1, packed_e3, b_e3, out, N, Cin, H, W, Csq, Ce1, Ce3);
+        set_stage("");
+        if (rc1 != SQ_ERR_UNSUPPORTED) return rc1;
+    }
     set_stage(kFireAlone[0]);
     int rc = blocked_conv(in, packed_sq, b_sq, workspace, N, Cin, H, W, Csq, 1, 0, 1, Csq, 0);
     if (!rc) {
@@ -657,27 +674,38 @@ int sq_squeezenet_forward_bf16(const void *in, sq_dtype in_dtype, const void *co
         const FireCfg &fc = kFires[f];
         const int c0 = 1 + 3 * f;
         const int which_pool = f == 0 ? 0 : f == 3 ? 1 : 2;
-        if (pool_pending && ((fuse_pools >> which_pool) & 1)) {
-            set_stage(kPoolSq[which_pool]);
-            if ((rc = blocked_pool_conv(cur, WP(c0), B(c0), bufS, N, C, H, H, fc.sq, 1, fc.sq, 0))) return rc;
+        // small batches: the whole fire layer in one launch (then its pooling, if any, runs on its own)
+        const bool one_launch = (g_fire_one_launch == 1 || (g_fire_one_launch == -1 && N <= kFireOneLaunchMaxBatch)) &&
+                                blocked_fire_fused_supported(C, fc.sq, fc.e, fc.e, pool_pending ? (H - 3) / 2 + 1 : H);
+        if (pool_pending && (one_launch || !((fuse_pools >> which_pool) & 1))) {
+            set_stage(f == 0 ? "pool1" : f == 3 ? "pool4" : "pool8");
+            if ((rc = blocked_maxpool(cur, nxt, N, C, H, H, 3, 2))) return rc;
             H = (H - 3) / 2 + 1;
+            if ((rc = tap_out(tap++, nxt, C, H))) return rc;
+            { char *t = cur; cur = nxt; nxt = t; }
+            pool_pending = false;
+        }
+        if (one_launch) {
+            set_stage(kFireStages[f][3]);
+            if ((rc = blocked_fire_fused(cur, WP(c0), B(c0), WP(c0 + 1), B(c0 + 1), WP(c0 + 2), B(c0 + 2), nxt, N, C, H, H, fc.sq,
+                                         fc.e, fc.e)))
+                return rc;
         } else {
             if (pool_pending) {
-                set_stage(f == 0 ? "pool1" : f == 3 ? "pool4" : "pool8");
-                if ((rc = blocked_maxpool(cur, nxt, N, C, H, H, 3, 2))) return rc;
+                set_stage(kPoolSq[which_pool]);
+                if ((rc = blocked_pool_conv(cur, WP(c0), B(c0), bufS, N, C, H, H, fc.sq, 1, fc.sq, 0))) return rc;
                 H = (H - 3) / 2 + 1;
-                if ((rc = tap_out(tap++, nxt, C, H))) return rc;
-                { char *t = cur; cur = nxt; nxt = t; }
+                pool_pending = false;
+            } else {
+                set_stage(kFireStages[f][0]);
+                if ((rc = blocked_conv(cur, WP(c0), B(c0), bufS, N, C, H, H, fc.sq, 1, 0, 1, fc.sq, 0))) return rc;
             }
-            set_stage(kFireStages[f][0]);
-            if ((rc = blocked_conv(cur, WP(c0), B(c0), bufS, N, C, H, H, fc.sq, 1, 0, 1, fc.sq, 0))) return rc;
+            // both expands in one launch
+            set_stage(kFireStages[f][3]);
+            if ((rc = blocked_conv_pair(bufS, WP(c0 + 1), B(c0 + 1), fc.e, 0, WP(c0 + 2), B(c0 + 2), fc.e, fc.e, 3, nxt, N, fc.sq, H,
+                                        H, 1, 2 * fc.e)))
+                return rc;
         }
-        pool_pending = false;
-        // both expands in one launch
-        set_stage(kFireStages[f][3]);
-        if ((rc = blocked_conv_pair(bufS, WP(c0 + 1), B(c0 + 1), fc.e, 0, WP(c0 + 2), B(c0 + 2), fc.e, fc.e, 3, nxt, N, fc.sq, H,
-                                    H, 1, 2 * fc.e)))
-            return rc;
         C = 2 * fc.e;
         if ((rc = tap_out(tap++, nxt, C, H))) return rc;
         { char *t = cur; cur = nxt; nxt = t; }

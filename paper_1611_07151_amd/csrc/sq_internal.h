@@ -80,6 +80,10 @@ int blocked_conv7s2(const void *in, int dtype, const void *wp, const float *b, v
 int blocked_conv_pair(const void *in, const void *wp1, const float *b1, int Cout1, int c_offset1, const void *wpk,
                       const float *bk, int Coutk, int c_offsetk, int K, void *out, int N, int Cin, int H, int W, int relu,
                       int ldc_channels);
+bool blocked_fire_fused_supported(int Cin, int Csq, int Ce1, int Ce3, int W);
+int blocked_fire_fused(const void *in, const void *wp_sq, const float *b_sq, const void *wp_e1, const float *b_e1,
+                       const void *wp_e3, const float *b_e3, void *out, int N, int Cin, int H, int W, int Csq, int Ce1,
+                       int Ce3);
 int blocked_pool_conv(const void *in, const void *wp, const float *b, void *out, int N, int Cin, int Hin, int Win, int Cout,
                       int relu, int ldc_channels, int c_offset);
 int blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S);

@@ -172,24 +172,38 @@ def test_blocked_conv_channel_offset_leaves_other_layers_untouched(sq, k):
 @pytest.mark.parametrize("shape", [(2, 96, 55, 16, 64), (2, 128, 55, 32, 128), (3, 256, 27, 48, 192), (2, 384, 27, 64, 256),
                                    (5, 512, 13, 64, 256), (1, 32, 6, 16, 24)])
 def test_blocked_fire_matches_oracle(sq, shape):
-    """Squeeze, then both expands in one launch, against the oracle's fire layer; also with a large positive
-    squeeze bias, so that a padded tap that saw relu(bias) instead of zero would show."""
+    """Squeeze, then both expands in one launch -- and the whole layer in one launch -- against the oracle's fire
+    layer; also with a large positive squeeze bias, so that a padded tap that saw relu(bias) instead of zero
+    would show."""
     N, Cin, H, Csq, Ce = shape
     rng = np.random.default_rng(400 + Cin + Ce)
     x = synth.normal01(rng, (N, Cin, H, H))
     (w_sq, b_sq), (w_e1, b_e1), (w_e3, b_e3) = (synth.conv_params(rng, Csq, Cin, 1), synth.conv_params(rng, Ce, Csq, 1),
                                                 synth.conv_params(rng, Ce, Csq, 3))
+    packed = [sq.sq_blocked_pack_kernels(dev(w)) for w in (w_sq, w_e1, w_e3)]
     for bias_shift in (0.0, 3.0):
         bs = (b_sq + bias_shift).astype(np.float32)
         ref = oracle.fire(x, w_sq, bs, w_e1, b_e1, w_e3, b_e3)
         ws = torch.empty(sq.sq_blocked_map_bytes(N, Csq, H, H), device="cuda", dtype=torch.uint8)
-        out = sq.sq_blocked_fire_forward(to_blocked(x).cuda(), Cin, sq.sq_blocked_pack_kernels(dev(w_sq)), dev(bs),
-                                         sq.sq_blocked_pack_kernels(dev(w_e1)), dev(b_e1),
-                                         sq.sq_blocked_pack_kernels(dev(w_e3)), dev(b_e3), Csq, Ce, Ce, workspace=ws)
+
+        def run():
+            return sq.sq_blocked_fire_forward(to_blocked(x).cuda(), Cin, packed[0], dev(bs), packed[1], dev(b_e1), packed[2],
+                                              dev(b_e3), Csq, Ce, Ce, workspace=ws)
+        try:
+            sq.lib.sq_internal_fire_one_launch(0)          # squeeze into the workspace, then both expands in one launch
+            out = run()
+            s_gpu = from_blocked(ws.view(torch.bfloat16).view(N, Csq // 8, H, H, 8), Csq)
+            sq.lib.sq_internal_fire_one_launch(1)          # the whole layer in one launch, squeeze map in LDS
+            sq.sq_profile_begin(8)
+            out1 = run()
+            stages = [r["name"] for r in sq.sq_profile_end()]
+        finally:
+            sq.lib.sq_internal_fire_one_launch(-1)
+        assert len(stages) == 1 and stages[0].startswith("fire|fire1_bf16"), stages
+        assert torch.equal(out.view(torch.int16), out1.view(torch.int16)), "one launch and two launches differ"
         got = from_blocked(out, 2 * Ce)
         # the stated tolerance is per convolution: the squeeze map (left in the workspace) against the oracle,
         # then the expands against the oracle applied to that squeeze map
-        s_gpu = from_blocked(ws.view(torch.bfloat16).view(N, Csq // 8, H, H, 8), Csq)
         if bias_shift == 0.0:   # (a squeeze map with mean 3 is outside the value range the tolerance is stated for)
             assert_close(s_gpu, oracle.conv2d(x, w_sq, bs, 1, 0, True), BF16_TOL, "squeeze")
             ref_e = np.concatenate([oracle.conv2d(s_gpu, w_e1, b_e1, 1, 0, True), oracle.conv2d(s_gpu, w_e3, b_e3, 1, 1, True)],

@@ -13,6 +13,21 @@ thread_local int g_last_hip = 0;
 
 hipStream_t current_stream() { return g_stream; }
 
+int num_cus()
+{
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+        (void)hipGetLastError();
+    }
+    return cus;
+}
+
 // ---- per-launch profiler --------------------------------------------------------------
 namespace {
 struct ProfRecord {

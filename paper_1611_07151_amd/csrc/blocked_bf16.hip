@@ -530,21 +530,6 @@ int grid_for(long long total, int threads)
     return (int)b;
 }
 
-int num_cus_blocked()
-{
-    static int cus = 0;
-    if (!cus) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
-        (void)hipGetLastError();
-    }
-    return cus;
-}
-
 typedef void (*BlockedConvFn)(const ConvParams, const ConvParams, int);
 template <int CB, int PB> BlockedConvFn conv_fn(int D)
 {
@@ -724,7 +709,7 @@ int blocked_conv(const void *in, const void *wp, const float *b, void *out, int 
         return e ? e : SQ_ERR_HIP;
     }
     // persistent: at most two workgroups per CU
-    const long long wgs = slots_for(pl, 2ll * num_cus_blocked()) * pl.p.ncblk;
+    const long long wgs = slots_for(pl, 2ll * num_cus()) * pl.p.ncblk;
     const size_t lds = (size_t)pl.CB * pl.per_mb + (size_t)pl.CB * 32 * sizeof(float);
     LaunchScope scope(launch_name(K, pl.CB, pl.PB, pl.D, false), pl.flops, pl.bytes);
     hipLaunchKernelGGL(fn, dim3((unsigned)wgs), dim3(kThreads), lds, current_stream(), pl.p, pl.p, (int)wgs);
@@ -752,7 +737,7 @@ int blocked_conv_pair(const void *in, const void *wp1, const float *b1, int Cout
         return e ? e : SQ_ERR_HIP;
     }
     // workgroups are shared out in proportion to the work (the K x K part has K*K times the steps)
-    const long long cap = 2ll * num_cus_blocked();
+    const long long cap = 2ll * num_cus();
     long long cap1 = cap / (1 + K * K * (long long)Coutk / Cout1);
     if (cap1 < p1.p.ncblk) cap1 = p1.p.ncblk;
     const long long wg1 = slots_for(p1, cap1) * p1.p.ncblk;
@@ -795,7 +780,7 @@ int blocked_pool_conv(const void *in, const void *wp, const float *b, void *out,
         for (PoolConvFn &f : allowed)
             if (!f) { f = fn; break; }
     }
-    const long long wgs = slots_for(pl, 2ll * num_cus_blocked()) * pl.p.ncblk;
+    const long long wgs = slots_for(pl, 2ll * num_cus()) * pl.p.ncblk;
     const size_t lds = (size_t)pl.CB * pl.per_mb + (size_t)pl.CB * 32 * sizeof(float);
     static char names[3][3][24];
     char *name = names[pl.CB][D];

@@ -200,21 +200,6 @@ __global__ __launch_bounds__(kThreads7, 3) void conv7s2c3_blocked_kernel(const C
     }
 }
 
-int cus7()
-{
-    static int cus = 0;
-    if (!cus) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
-        (void)hipGetLastError();
-    }
-    return cus;
-}
-
 }  // namespace
 }  // namespace blocked
 
@@ -257,7 +242,7 @@ int blocked_conv7s2(const void *in, int dtype, const void *wp, const float *b, v
     p.ldcb = ldc_channels / 8; p.coffb = c_offset / 8;
     p.tiles = (int)tiles;
     p.dCG = make_fastdiv(p.CG); p.dTilesPerImage = make_fastdiv(p.RG * p.CG);
-    long long blocks = 3ll * cus7();
+    long long blocks = 3ll * num_cus();
     if (blocks > tiles) blocks = tiles;
     LaunchScope scope("k7s2c3_bf16_8x16", 2.0 * N * Cout * Ho * Wo * 147.0,
                       (dtype == SQ_BF16 ? 2.0 : 4.0) * N * 3 * H * W + 2.0 * Cout * 147 + 2.0 * N * Cout * Ho * Wo + 4.0 * Cout);

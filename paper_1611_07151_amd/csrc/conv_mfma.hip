@@ -67,22 +67,6 @@ struct Plan {
     unsigned blocks, blocks_y;
 };
 
-int num_cus()
-{
-    static int cus = 0;
-    if (!cus) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
-        (void)hipGetLastError();
-    }
-    return cus;
-}
-
-// Fills the launch parameters of variant v for this call; false if v cannot run it.
 // kernels of tiling v for the given input type
 const KernelSet &kernel_set(const Variant &v, int dtype)
 {
@@ -96,6 +80,7 @@ struct FusedE1 {
     int Cout1, coff1;
 };
 
+// Fills the launch parameters of variant v for this call; false if v cannot run it.
 bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nullptr)
 {
     const KernelSet &ks = kernel_set(v, a.dtype);

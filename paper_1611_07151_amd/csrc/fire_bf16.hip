@@ -227,21 +227,6 @@ __global__ __launch_bounds__(kFireThreads, 1) void fire_blocked_kernel(const Fir
     }
 }
 
-int fire_cus()
-{
-    static int cus = 0;
-    if (!cus) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
-        (void)hipGetLastError();
-    }
-    return cus;
-}
-
 }  // namespace
 }  // namespace blocked
 
@@ -278,7 +263,7 @@ int blocked_fire_fused(const void *in, const void *wp_sq, const float *b_sq, con
     int TH = (int)((size_t)mfma::kLdsBytes / 2 / row_bytes) - 2;
     if (TH < 1) TH = 1;
     p.nsl1 = (Ce1 + 63) / 64; p.nsl3 = (Ce3 + 63) / 64;
-    const int want_bands = (fire_cus() + N * (p.nsl1 + p.nsl3) - 1) / (N * (p.nsl1 + p.nsl3));
+    const int want_bands = (num_cus() + N * (p.nsl1 + p.nsl3) - 1) / (N * (p.nsl1 + p.nsl3));
     int th_par = (H + want_bands - 1) / want_bands;
     if (th_par < 4) th_par = 4;                       // two halo rows per band: keep the recomputation under a half
     if (TH > th_par) TH = th_par;

@@ -12,6 +12,9 @@ namespace sq {
 // Stream of the calling host thread (set by sq_set_stream).
 hipStream_t current_stream();
 
+// Compute units of the current device (256 if the query fails); cached after the first call.
+int num_cus();
+
 // Folds the sticky launch error into a status code and records it.
 int check_launch();
 

@@ -144,6 +144,27 @@ size_t sq_conv2d_workspace_bytes(int Cin, int Cout, int K, int S, int P);
 int sq_maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int S);
 
 /*
+ * The network's max pooling (3 x 3 window, stride 2; section "Pooling and
+ * Softmax") and the 1 x 1 convolution that reads its result (the squeeze of a
+ * fire layer, section "Convolutional Neural Networks"), as one operation: the
+ * pooled map is formed while the convolution stages its input and is never
+ * written to memory.  The result equals sq_maxpool(in, K=3, S=2) followed by
+ * sq_conv2d_forward_ex(K=1, S=1, P=0) with the same algorithm, bit for bit
+ * (the maximum is exact and the contraction runs in the same order).
+ *   in:  [N][Cin][H][W] fp32, H >= 3 and W >= 3 (else SQ_ERR_SHAPE)
+ *   w:   [Cout][Cin] fp32;  b: [Cout] fp32 or NULL
+ *   out: [N][out_channels][Hp][Wp] fp32 with Hp = floor((H-3)/2)+1, likewise Wp;
+ *        layers [c_offset, c_offset+Cout) are written
+ *   algo: SQ_ALGO_AUTO or SQ_ALGO_VARIANT0 + i for a 1 x 1 tiling of the fp32
+ *        matrix-core kernel whose input-layer chunk divides Cin; anything else
+ *        returns SQ_ERR_UNSUPPORTED (there is no other implementation).
+ * All pointers are device pointers owned by the caller.
+ */
+int sq_maxpool_conv2d_forward(const float *in, const float *w, const float *b, float *out,
+                              int N, int Cin, int H, int W, int Cout, int relu,
+                              int out_channels, int c_offset, int algo);
+
+/*
  * Average pooling over the whole plane (section "Pooling and Softmax"; the
  * network applies it to the 13 x 13 classifier maps):
  * out[n][c] = mean over h,w of in[n][c][h][w].  in [N][C][H][W], out [N][C].

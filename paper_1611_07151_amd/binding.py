@@ -33,6 +33,7 @@ lib.sq_conv2d_forward_ws.argtypes = [_vp] * 4 + [_i] * 13 + [_vp, _sz]
 lib.sq_conv2d_workspace_bytes.restype = _sz
 lib.sq_conv2d_workspace_bytes.argtypes = [_i] * 5
 lib.sq_maxpool.argtypes = [_vp, _vp] + [_i] * 6
+lib.sq_maxpool_conv2d_forward.argtypes = [_vp] * 4 + [_i] * 9
 lib.sq_avgpool_global.argtypes = [_vp, _vp] + [_i] * 4
 lib.sq_softmax.argtypes = [_vp, _vp, _i, _i]
 lib.sq_fire_forward.argtypes = [_vp] * 8 + [_i] * 7 + [_vp, _sz]
@@ -198,6 +199,22 @@ def sq_maxpool(x, k=3, stride=2):
     _use_current_stream()
     _check(lib.sq_maxpool(_dev(x, torch.float32, "x"), _dev(out), N, C, H, W, int(k), int(stride)),
            "sq_maxpool")
+    return out
+
+
+def sq_maxpool_conv2d_forward(x, w, b=None, relu=True, out=None, c_offset=0, algo=SQ_ALGO_AUTO):
+    N, Cin, H, W = x.shape
+    Cout = w.shape[0]
+    if H < 3 or W < 3:
+        _check(-2, "sq_maxpool_conv2d_forward")
+    Hp, Wp = (H - 3) // 2 + 1, (W - 3) // 2 + 1
+    if out is None:
+        out = torch.empty((N, Cout, Hp, Wp), device=x.device, dtype=torch.float32)
+    _use_current_stream()
+    _check(lib.sq_maxpool_conv2d_forward(_dev(x, torch.float32, "x"), _dev(w, torch.float32, "w"),
+                                         _dev(b, torch.float32, "b") if b is not None else None, _dev(out),
+                                         N, Cin, H, W, Cout, int(bool(relu)), out.shape[1], int(c_offset), int(algo)),
+           "sq_maxpool_conv2d_forward")
     return out
 
 

@@ -90,10 +90,11 @@ int validate_conv(const void *in, const void *w, const float *out, int N, int Ci
 
 int run_conv(const ConvArgs &a, int algo)
 {
+    if (a.pool_H && (algo == SQ_ALGO_DIRECT || a.K != 1 || a.S != 1 || a.P != 0)) return SQ_ERR_UNSUPPORTED;
     if (algo == SQ_ALGO_DIRECT) return conv_direct(a);
     if (algo == SQ_ALGO_AUTO) {
         const int rc = conv_mfma(a, -1);
-        if (rc != SQ_ERR_UNSUPPORTED) return rc;
+        if (rc != SQ_ERR_UNSUPPORTED || a.pool_H) return rc;   // only the tiled kernels pool on the way in
         return conv_direct(a);
     }
     const int v = algo - SQ_ALGO_VARIANT0;
@@ -115,18 +116,21 @@ ConvArgs make_args(const void *in, const void *w, const float *b, float *out, in
     a.c_offset = c_offset;
     a.dtype = dtype;
     a.ws = nullptr; a.ws_bytes = 0; a.ws_ready = false;
+    a.pool_H = a.pool_W = 0;
     return a;
 }
 
-// Unchecked fire layer: squeeze into `sq_map`, then both expands into `out`.
+// Unchecked fire layer: squeeze into `sq_map`, then both expands into `out`.  With pool_H != 0 `in` is a
+// map of pool_H x pool_W pixels that the squeeze max-pools (3x3, stride 2) down to H x W while it reads it.
 int fire_impl(const void *in, const void *w_sq, const float *b_sq, const void *w_e1,
               const float *b_e1, const void *w_e3, const float *b_e3, float *out, int N, int Cin,
               int H, int W, int Csq, int Ce1, int Ce3, float *sq_map, void *conv_ws, size_t conv_ws_bytes,
-              bool conv_ws_ready, const char *const *stages)
+              bool conv_ws_ready, const char *const *stages, int pool_H = 0, int pool_W = 0, int sq_algo = SQ_ALGO_AUTO)
 {
     set_stage(stages[0]);
-    int rc = run_conv(make_args(in, w_sq, b_sq, sq_map, N, Cin, H, W, Csq, 1, 1, 0, 1, Csq, 0, SQ_F32),
-                      SQ_ALGO_AUTO);
+    ConvArgs asq = make_args(in, w_sq, b_sq, sq_map, N, Cin, H, W, Csq, 1, 1, 0, 1, Csq, 0, SQ_F32);
+    asq.pool_H = pool_H; asq.pool_W = pool_W;
+    int rc = run_conv(asq, sq_algo);
     if (rc) return rc;
     // both expands in one launch when a fused tiling exists for this shape
     set_stage(stages[3]);
@@ -316,6 +320,19 @@ int sq_conv2d_forward(const void *in, const void *w, const float *b, float *out,
                                 SQ_ALGO_AUTO);
 }
 
+int sq_maxpool_conv2d_forward(const float *in, const float *w, const float *b, float *out, int N, int Cin, int H,
+                              int W, int Cout, int relu, int out_channels, int c_offset, int algo)
+{
+    if (!in || !w || !out) return SQ_ERR_NULL;
+    if (N <= 0 || Cin <= 0 || Cout <= 0 || H < 3 || W < 3) return SQ_ERR_SHAPE;
+    if (c_offset < 0 || out_channels <= 0 || (long long)c_offset + Cout > out_channels) return SQ_ERR_SHAPE;
+    if (algo < 0 || algo == SQ_ALGO_DIRECT) return SQ_ERR_UNSUPPORTED;
+    const int Hp = (H - 3) / 2 + 1, Wp = (W - 3) / 2 + 1;
+    ConvArgs a = make_args(in, w, b, out, N, Cin, Hp, Wp, Cout, 1, 1, 0, relu, out_channels, c_offset, SQ_F32);
+    a.pool_H = H; a.pool_W = W;
+    return run_conv(a, algo);
+}
+
 int sq_maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int S)
 {
     if (!in || !out) return SQ_ERR_NULL;
@@ -366,6 +383,16 @@ size_t sq_squeezenet_workspace_bytes(int N)
     return align_up(n * kBufA * 4, 256) + align_up(n * kBufB * 4, 256) + align_up(n * kBufS * 4, 256) +
            align_up(n * 1000 * 4, 256) + conv_ws;
 }
+
+// Which max-pooling layers of the fp32 network run inside the squeeze layer that reads them: bit 0 = pool1,
+// bit 1 = pool4, bit 2 = pool8; -1 = the default policy: what made the whole pass faster when measured at
+// batches 1 to 256 (pool1 everywhere; pool4 from batch 4 on, below that the squeeze of fire5 has too few
+// workgroups to hide nine loads per element; pool8 from batch 64 on).  A call with taps keeps every pooled
+// map, but runs the squeeze with the tiling the fused form would use, so the results are the same bit for bit.
+// The setter is a tuning hook, not part of the public interface.
+int g_fuse_pools_f32 = -1;
+extern "C" void sq_internal_fuse_pools_f32(int mask) { g_fuse_pools_f32 = mask; }
+int fuse_pools_f32_policy(int N) { return 1 | (N >= 4 ? 2 : 0) | (N >= 64 ? 4 : 0); }
 
 int sq_squeezenet_forward(const void *in, const void *const *params, float *probs, int N,
                           void *workspace, size_t workspace_bytes, float *const *taps)
@@ -419,22 +446,55 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
                       SQ_ALGO_AUTO);
     if (rc) return rc;
     if ((rc = copy_tap(taps, 0, bufA, n * 96 * 111 * 111))) return rc;
-    set_stage("pool1");
-    if ((rc = maxpool(bufA, bufB, N, 96, 111, 111, 3, 2))) return rc;
-    if ((rc = copy_tap(taps, 1, bufB, n * 96 * 55 * 55))) return rc;
+    const int pools_in_squeeze = g_fuse_pools_f32 >= 0 ? g_fuse_pools_f32 : fuse_pools_f32_policy(N);
+    const int fuse_pools = taps ? 0 : pools_in_squeeze;
+    // tiling of the squeeze behind pool `bit` when the pooled map is kept although the policy would not keep it
+    auto squeeze_algo = [&](int bit, int f, int C, int H_in) {
+        if (!(pools_in_squeeze & bit) || (fuse_pools & bit)) return (int)SQ_ALGO_AUTO;
+        const int Hp = (H_in - 3) / 2 + 1;
+        ConvArgs a = make_args(bufA, params[2 + 6 * f], nullptr, bufS, N, C, Hp, Hp, kFires[f].sq, 1, 1, 0, 1, kFires[f].sq, 0, SQ_F32);
+        a.pool_H = a.pool_W = H_in;
+        const int v = conv_mfma_choice(a);
+        return v >= 0 ? SQ_ALGO_VARIANT0 + v : (int)SQ_ALGO_AUTO;
+    };
+    float *cur = bufA, *nxt = bufB;
+    int pooled_from = 0;   // extent of the map `cur` before the pooling that the next squeeze is to do, or 0
+    int sq_algo = squeeze_algo(1, 0, 96, 111);
+    if (fuse_pools & 1) {
+        pooled_from = 111;
+    } else {
+        set_stage("pool1");
+        if ((rc = maxpool(bufA, bufB, N, 96, 111, 111, 3, 2))) return rc;
+        if ((rc = copy_tap(taps, 1, bufB, n * 96 * 55 * 55))) return rc;
+        cur = bufB; nxt = bufA;
+    }
 
-    float *cur = bufB, *nxt = bufA;
     int C = 96, H = 55, tap = 2, p = 2;
     for (int f = 0; f < 8; ++f) {
         const FireCfg &fc = kFires[f];
-        rc = fire_impl(cur, params[p], P(p + 1), params[p + 2], P(p + 3), params[p + 4], P(p + 5), nxt,
-                       N, C, H, H, fc.sq, fc.e, fc.e, bufS, conv_ws[f], conv_ws_bytes[f], conv_ws_ready[f], kFireStages[f]);
+        // Only the squeeze reads a fire layer's input, and it has finished before the expands start.  A layer
+        // that pools on the way in therefore writes over its own input: every later layer then finds its
+        // input and output in the same buffer as without the fusion (with the roles exchanged instead, conv1
+        // and several later layers ran measurably slower at batch 32).
+        float *dst = pooled_from ? cur : nxt;
+        rc = fire_impl(cur, params[p], P(p + 1), params[p + 2], P(p + 3), params[p + 4], P(p + 5), dst,
+                       N, C, H, H, fc.sq, fc.e, fc.e, bufS, conv_ws[f], conv_ws_bytes[f], conv_ws_ready[f], kFireStages[f],
+                       pooled_from, pooled_from, sq_algo);
+        sq_algo = SQ_ALGO_AUTO;
         if (rc) return rc;
         p += 6;
         C = 2 * fc.e;
-        if ((rc = copy_tap(taps, tap++, nxt, n * C * H * H))) return rc;
-        { float *t = cur; cur = nxt; nxt = t; }
+        if ((rc = copy_tap(taps, tap++, dst, n * C * H * H))) return rc;
+        if (!pooled_from) { float *t = cur; cur = nxt; nxt = t; }
+        pooled_from = 0;
         if (f == 2 || f == 6) {  // pooling follows fire4 and fire8
+            sq_algo = squeeze_algo(f == 2 ? 2 : 4, f + 1, C, H);
+            if (fuse_pools & (f == 2 ? 2 : 4)) {
+                pooled_from = H;
+                H = (H - 3) / 2 + 1;
+                ++tap;
+                continue;
+            }
             set_stage(f == 2 ? "pool4" : "pool8");
             if ((rc = maxpool(cur, nxt, N, C, H, H, 3, 2))) return rc;
             H = (H - 3) / 2 + 1;

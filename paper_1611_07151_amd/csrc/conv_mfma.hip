@@ -85,10 +85,11 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
 {
     const KernelSet &ks = kernel_set(v, a.dtype);
     if (e1 && (!ks.fused_e1 || a.Cin % v.CC != 0)) return false;
+    if (a.pool_H && (!ks.pooled || e1 || a.Cin % v.CC != 0)) return false;
     if (a.K != v.KS || a.S != v.S) return false;
     if (!v.conv1_type && !ks.plain) return false;
     if (a.W + 2 * a.P < a.K) return false;
-    const long long in_elems = (long long)a.N * a.Cin * a.H * a.W;
+    const long long in_elems = (long long)a.N * a.Cin * (a.pool_H ? (long long)a.pool_H * a.pool_W : (long long)a.H * a.W);
     const long long out_elems = (long long)a.N * a.out_channels * a.Ho * a.Wo;
     const long long pixels = (long long)a.N * a.Ho * a.Wo;
     // per-lane addresses are 32-bit byte offsets from a uniform base
@@ -107,6 +108,7 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
     k.N = a.N; k.Cin = a.Cin; k.H = a.H; k.W = a.W; k.Cout = a.Cout; k.P = a.P; k.relu = a.relu;
     k.Ho = a.Ho; k.Wo = a.Wo; k.HoWo = a.Ho * a.Wo; k.HW = a.H * a.W;
     k.ldc = a.out_channels; k.coff = a.c_offset;
+    k.Win = a.pool_W; k.HWin = a.pool_H * a.pool_W;
     k.PT = (int)pixels;
     k.mtiles = ((e1 && e1->Cout1 > a.Cout ? e1->Cout1 : a.Cout) + v.BM - 1) / v.BM;
     k.w1 = e1 ? (const float *)e1->w1 : nullptr; k.b1 = e1 ? e1->b1 : nullptr;
@@ -181,7 +183,7 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
 // Dynamic LDS above the default limit must be opted into once per kernel function.
 bool allow_big_lds(KernelFn fn)
 {
-    static KernelFn done[2 * kNumVariants + 4];
+    static KernelFn done[4 * kNumVariants + 4];
     static int ndone = 0;
     for (int i = 0; i < ndone; ++i)
         if (done[i] == fn) return true;
@@ -198,6 +200,7 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
     KernelFn fn = e1 ? ks.fused_e1 : ks.plain;
     if (v.conv1_type) fn = conv7s2c3_kernel_for(v.NT / 64, a.Cout == 96, a.dtype == SQ_BF16, v.BM / 32);
     if (!v.conv1_type && !v.wino && !e1 && a.Cin % v.CC != 0) fn = ks.tail;
+    if (a.pool_H) fn = ks.pooled;
     if (!allow_big_lds(fn)) {
         const int rc = check_launch();
         return rc ? rc : SQ_ERR_HIP;
@@ -218,7 +221,8 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
 }
 
 // Measured winners (written by tune.py).  An entry applies to its exact layer shape and to
-// the batch sizes nearest to the one it was measured at.
+// the batch sizes nearest to the one it was measured at.  P = -1 marks a 1x1 layer that pools
+// on the way in (H, W are then the pooled extents).
 struct Tuned {
     int K, S, P, Cin, Cout, H, W, N;
     const char *variant;        // fastest of all
@@ -233,7 +237,7 @@ int tuned_variant(const ConvArgs &a)
     const Tuned *best = nullptr;
     double best_dist = 0;
     for (const Tuned *e = kTuned; e->K; ++e) {
-        if (e->K != a.K || e->S != a.S || e->P != a.P || e->Cin != a.Cin || e->Cout != a.Cout || e->H != a.H ||
+        if (e->K != a.K || e->S != a.S || e->P != (a.pool_H ? -1 : a.P) || e->Cin != a.Cin || e->Cout != a.Cout || e->H != a.H ||
             e->W != a.W)
             continue;
         const double d = fabs(log((double)a.N / e->N));
@@ -335,6 +339,31 @@ int conv_expand_fused(const ConvArgs &a3, const void *w1, const float *b1, int C
     return launch(best, best_plan, a3, &e1);
 }
 
+// The tiling the automatic choice runs for this call (the measured winner where the table has the shape,
+// else the lowest estimate), its plan in pl; -1 if no tiling can run it.
+static int choose_variant(const ConvArgs &a, Plan &pl)
+{
+    const int tv = tuned_variant(a);
+    if (tv >= 0 && plan(kVariants[tv], a, pl)) return tv;
+    int best = -1;
+    double best_cost = 0;
+    Plan cand;
+    for (int i = 0; i < kNumVariants; ++i) {
+        if (!plan(kVariants[i], a, cand)) continue;
+        const double c = estimate(kVariants[i], cand, a);
+        if (best < 0 || c < best_cost) {
+            best = i; best_cost = c; pl = cand;
+        }
+    }
+    return best;
+}
+
+int conv_mfma_choice(const ConvArgs &a)
+{
+    Plan pl;
+    return choose_variant(a, pl);
+}
+
 int conv_mfma(const ConvArgs &a, int variant)
 {
     Plan pl;
@@ -342,20 +371,9 @@ int conv_mfma(const ConvArgs &a, int variant)
         if (variant >= kNumVariants || !plan(kVariants[variant], a, pl)) return SQ_ERR_UNSUPPORTED;
         return launch(variant, pl, a);
     }
-    const int tv = tuned_variant(a);
-    if (tv >= 0 && plan(kVariants[tv], a, pl)) return launch(tv, pl, a);
-    int best = -1;
-    double best_cost = 0;
-    Plan best_plan;
-    for (int i = 0; i < kNumVariants; ++i) {
-        if (!plan(kVariants[i], a, pl)) continue;
-        const double c = estimate(kVariants[i], pl, a);
-        if (best < 0 || c < best_cost) {
-            best = i; best_cost = c; best_plan = pl;
-        }
-    }
+    const int best = choose_variant(a, pl);
     if (best < 0) return SQ_ERR_UNSUPPORTED;
-    return launch(best, best_plan, a);
+    return launch(best, pl, a);
 }
 
 }  // namespace sq

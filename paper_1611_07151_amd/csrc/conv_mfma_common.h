@@ -83,6 +83,7 @@ struct KParams {
     FastDiv dTX, dTXY;
     const float *wu;     // its transformed kernels (written by wino_kernel_transform)
     uint32_t wu_bytes;
+    int Win, HWin;       // 1x1 kernels with pooling on the way in: row length and plane size of the map in memory
 };
 
 template <int MT> struct Mfma;
@@ -191,9 +192,10 @@ __device__ __forceinline__ void st_f32(float *base, uint32_t byte_off, float v)
 // their own persistent kernel with NW autonomous wavefronts per workgroup (8 or 4).
 typedef void (*KernelFn)(const KParams);
 
-// Kernels of one tiling: plain, input layers not a multiple of CC, fused 1x1 expand.
+// Kernels of one tiling: plain, input layers not a multiple of CC, fused 1x1 expand, 1x1 with 3x3 stride-2
+// max pooling on the way in.
 struct KernelSet {
-    KernelFn plain, tail, fused_e1;
+    KernelFn plain, tail, fused_e1, pooled;
 };
 extern const KernelSet conv_mfma_kernels_f32[], conv_mfma_kernels_bf16[];
 // TM = blocks of 32 output layers per workgroup: 3 (all 96), or 1 with the block chosen by blockIdx.y (NW = 4 only).

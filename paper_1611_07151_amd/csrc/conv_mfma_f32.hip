@@ -6,15 +6,25 @@
 namespace sq {
 namespace mfma {
 
+// The pooled-input form exists for those 1x1 tilings that can keep nine values per staged element in registers
+// beside their accumulators without spilling (checked with -Rpass-analysis=kernel-resource-usage).
+template <int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW> constexpr KernelFn pooled_kernel()
+{
+    constexpr int XREG = CC * BN / (WM * WN * 64);
+    if constexpr (KS == 1 && S == 1 && MINW <= 2 && (XREG <= 8 || BM == 16 || (BM == 32 && CC == 16))) return conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false, false, true>;
+    else return nullptr;
+}
+
 #define SQ_V(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                                 \
     {conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false>,                       \
-     conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, true>, nullptr},
+     conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, true>, nullptr,               \
+     pooled_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW>()},
 #define SQ_E(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                                 \
     {conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false>,                       \
      conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, true>,                        \
-     conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false, true>},
-#define SQ_C(NW) {nullptr, nullptr, nullptr},
-#define SQ_W(BM, BT, CC) {conv_wino_kernel<float>, nullptr, nullptr},
+     conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false, true>, nullptr},
+#define SQ_C(NW) {nullptr, nullptr, nullptr, nullptr},
+#define SQ_W(BM, BT, CC) {conv_wino_kernel<float>, nullptr, nullptr, nullptr},
 const KernelSet conv_mfma_kernels_f32[] = {SQ_VARIANT_LIST(SQ_V, SQ_E, SQ_C, SQ_W, SQ_C)};
 
 }  // namespace mfma

@@ -43,7 +43,12 @@ namespace mfma {
 // TIN: element type of the input and the kernels in memory, float or uint16_t (bfloat16).
 // bfloat16 values are widened to fp32 while they are staged (a shift), so LDS and the MFMAs
 // are the same as for fp32 inputs; products of two bfloat16 values are exact in fp32.
-template <typename TIN, int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW, bool TAIL, bool E1 = false>
+// POOL (1x1 kernels only): the input is max-pooled (3x3 window, stride 2, floor mode) on the way
+// in -- in this network every pooled map is read by exactly one squeeze layer, so it need not
+// exist in memory.  p.H, p.W are the pooled extents, p.Win / p.HWin those of the map in memory; a
+// staged element is the maximum of nine loads (per window row one 8-byte and one 4-byte load).
+template <typename TIN, int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW, bool TAIL, bool E1 = false,
+          bool POOL = false>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KParams p)
 {
     using M = Mfma<MT>;
@@ -62,6 +67,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KPa
     static_assert(CC % KQ == 0, "chunk must hold whole MFMA k-groups");
     static_assert(!POINTWISE || (NT % BN == 0 && BN % 64 == 0 && (CC * BN) % NT == 0), "pointwise staging split");
     static_assert(!E1 || (KS % 2 == 1 && S == 1 && !TAIL), "fused expand needs a centre tap");
+    static_assert(!POOL || (POINTWISE && !TAIL && !E1), "pooling on the way in is for plain 1x1 kernels");
     constexpr int ESZ = (int)sizeof(TIN);
     constexpr int LD1 = CC + 1;                       // LDS row stride of the 1x1 kernels
     constexpr int W1BUF = E1 ? BM * LD1 : 0;
@@ -149,7 +155,13 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KPa
     if constexpr (POINTWISE) {
         const int pl = t % BN, pp = P0 + pl;
         const int n = fdiv(pp, p.dHW);
-        xsrc[0] = pp < p.PT ? (uint32_t)((n * p.Cin * p.HW + (pp - n * p.HW)) * ESZ) : kOob;
+        if constexpr (POOL) {
+            // first element of this pixel's window in the map before pooling
+            const int pix = pp - n * p.HW, y = fdiv(pix, p.dWo), x = pix - y * p.Wo;
+            xsrc[0] = pp < p.PT ? (uint32_t)((n * p.Cin * p.HWin + 2 * y * p.Win + 2 * x) * ESZ) : kOob;
+        } else {
+            xsrc[0] = pp < p.PT ? (uint32_t)((n * p.Cin * p.HW + (pp - n * p.HW)) * ESZ) : kOob;
+        }
         xdst[0] = pl;
     } else {
 #pragma unroll
@@ -166,7 +178,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KPa
     }
     const int cpart = POINTWISE ? __builtin_amdgcn_readfirstlane(t / BN) : 0;
 
-    float wreg[WREG], xreg[XREG], w1reg[W1REG];
+    float wreg[WREG], xreg[XREG], w1reg[W1REG], xwin[POOL ? XREG : 1][9];
 
     // Global loads of one chunk through buffer addressing: the per-lane offsets were fixed
     // above (kOob where the value is padding, which the hardware turns into zero), the chunk
@@ -203,6 +215,22 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KPa
 #pragma unroll
             for (int r = 0; r < W1REG; ++r) w1reg[r] = buf_ld_in<TIN>(rw1, w1src[r], (uint32_t)(c0 * ESZ));
         }
+        if constexpr (POOL) {
+            // the nine values of every window stay in registers until store_chunk takes their maximum, so that
+            // the loads are in flight during the MFMAs of the chunk before (an out-of-range pixel reads zeros)
+#pragma unroll
+            for (int r = 0; r < XREG; ++r) {
+                const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane((c0 + cpart + (NT / BN) * r) * p.HWin * ESZ);
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    uint32_t off = xsrc[0] + (uint32_t)(i * p.Win * ESZ);   // an offset turned away stays beyond the range
+                    asm volatile("" : "+v"(off));   // the loads of a window row differ by immediates: two of them merge
+#pragma unroll
+                    for (int jx = 0; jx < 3; ++jx) xwin[r][3 * i + jx] = buf_ld_in<TIN>(rin, off + (uint32_t)(jx * ESZ), so);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int r = 0; r < XREG; ++r) {
             const int c = POINTWISE ? cpart + (NT / BN) * r : r / XMAP;       // uniform
@@ -223,7 +251,15 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KPa
             for (int r = 0; r < W1REG; ++r)
                 if (w1dst[r] >= 0) w1s[w1dst[r]] = w1reg[r];
         }
-        if constexpr (POINTWISE) {
+        if constexpr (POOL) {
+#pragma unroll
+            for (int r = 0; r < XREG; ++r) {
+                float m = xwin[r][0];
+#pragma unroll
+                for (int e = 1; e < 9; ++e) m = fmaxf(m, xwin[r][e]);
+                xs[(cpart + (NT / BN) * r) * plane + xdst[0]] = m;
+            }
+        } else if constexpr (POINTWISE) {
 #pragma unroll
             for (int r = 0; r < XREG; ++r) xs[(cpart + (NT / BN) * r) * plane + xdst[0]] = xreg[r];
         } else {

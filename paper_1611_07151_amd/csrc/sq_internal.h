@@ -31,6 +31,9 @@ struct ConvArgs {
     void *ws;         // caller scratch some algorithms need (16-byte aligned), or nullptr
     size_t ws_bytes;
     bool ws_ready;    // ws already holds this layer's transformed kernels (conv_prepare_kernels)
+    // 1x1 convolution of a map that is max-pooled (3x3 window, stride 2, no padding) on the way in: extents of
+    // the map in memory; H and W are then the pooled extents.  0 = the input is read as it is.
+    int pool_H, pool_W;
 };
 
 inline double conv_flops(const ConvArgs &a)
@@ -40,7 +43,8 @@ inline double conv_flops(const ConvArgs &a)
 inline double conv_bytes(const ConvArgs &a)
 {
     const double esz = a.dtype == SQ_BF16 ? 2.0 : 4.0;
-    return esz * ((double)a.N * a.Cin * a.H * a.W + (double)a.Cout * a.Cin * a.K * a.K) +
+    const double in_plane = a.pool_H ? (double)a.pool_H * a.pool_W : (double)a.H * a.W;
+    return esz * ((double)a.N * a.Cin * in_plane + (double)a.Cout * a.Cin * a.K * a.K) +
            4.0 * ((double)a.N * a.Cout * a.Ho * a.Wo + a.Cout);
 }
 
@@ -49,6 +53,8 @@ int conv_direct(const ConvArgs &a);
 // Matrix-core family.  variant < 0 = pick by shape; returns SQ_ERR_UNSUPPORTED when
 // the (variant, shape, dtype) combination has no kernel.
 int conv_mfma(const ConvArgs &a, int variant);
+// The tiling conv_mfma(a, -1) runs, or -1.
+int conv_mfma_choice(const ConvArgs &a);
 // Fused expand of a fire layer: the 3x3 convolution a3 and a 1x1 convolution of the same
 // input in one launch; SQ_ERR_UNSUPPORTED if no compiled tiling fits.
 int conv_expand_fused(const ConvArgs &a3, const void *w1, const float *b1, int Cout1, int coff1);

@@ -7,6 +7,10 @@ granularity g (section "Optimizing Thread Granularity" and its table of optimal
 granularities): here the searched quantity is the workgroup / wavefront tile shape.
 Run on the GPU:  python paper_1611_07151_amd/tune.py [out.inc] [--batches 1,8,64,256]
 then copy the file to paper_1611_07151_amd/csrc/tuned_table.inc and rebuild.
+
+The three squeeze layers that follow a max-pooling layer are also timed with the pooling done
+inside the convolution (sq_maxpool_conv2d_forward); those rows carry P = -1 and the pooled
+extents.  --pooled-only keeps the other rows of an existing table and renews only these.
 """
 from __future__ import annotations
 
@@ -23,6 +27,7 @@ def main() -> int:
     ap.add_argument("out", nargs="?", default=os.path.join(ROOT, "paper_1611_07151_amd", "csrc", "tuned_table.inc"))
     ap.add_argument("--batches", default="1,8,64,256")
     ap.add_argument("--reps", type=int, default=20)
+    ap.add_argument("--pooled-only", action="store_true")
     args = ap.parse_args()
 
     import torch
@@ -33,7 +38,42 @@ def main() -> int:
     nv = sq.sq_conv_variant_count()
     names = [sq.sq_conv_variant_name(i) for i in range(nv)]
     rows, report = [], []
+
+    def gpu_us(call):
+        # GPU time of the launches themselves (the library's per-launch events)
+        call()
+        torch.cuda.synchronize()
+        sq.sq_profile_begin(4 * args.reps + 4)
+        for _ in range(args.reps):
+            call()
+        torch.cuda.synchronize()
+        return sum(r["ms"] for r in sq.sq_profile_end()) / args.reps * 1e3
+
     for N in [int(b) for b in args.batches.split(",")]:
+        # squeeze layers behind a pooling layer: (name, Cin, Cout, extent before pooling)
+        for name, cin, cout, h in (("pool1+fire2/sq", 96, 16, 111), ("pool4+fire5/sq", 256, 32, 55), ("pool8+fire9/sq", 512, 64, 27)):
+            hp = (h - 3) // 2 + 1
+            x = torch.rand((N, cin, h, h), device="cuda")
+            w = torch.randn((cout, cin, 1, 1), device="cuda") * (2.0 / cin) ** 0.5
+            b = torch.rand(cout, device="cuda") * 0.2 - 0.1
+            out = torch.empty((N, cout, hp, hp), device="cuda")
+            timings = []
+            for v in range(nv):
+                try:
+                    us = gpu_us(lambda: sq.sq_maxpool_conv2d_forward(x, w, b, True, out=out, algo=sq.SQ_ALGO_VARIANT0 + v))
+                except sq.SqError:
+                    continue
+                timings.append((us, names[v]))
+            timings.sort()
+            pooled = sq.sq_maxpool(x)
+            two_us = gpu_us(lambda: (sq.sq_maxpool(x), sq.sq_conv2d_forward_ex(pooled, w, b, 1, 0, True, out=out)))
+            rows.append((1, 1, -1, cin, cout, hp, hp, N, timings[0][1], timings[0][1]))
+            report.append(f"// N={N:3d} {name:14s} {cin:4d}->{cout:4d} k1 {hp:3d}x{hp:<3d}: best {timings[0][1]} {timings[0][0]:8.1f} us; "
+                          f"worst {timings[-1][1]} {timings[-1][0]:8.1f} us; two launches {two_us:8.1f} us")
+            print(report[-1], flush=True)
+            del x, w, b, out, pooled
+        if args.pooled_only:
+            continue
         seen = set()
         for name, cin, cout, k, s, p, h in synth.conv_layers():
             key = (k, s, p, cin, cout, h)
@@ -80,10 +120,16 @@ def main() -> int:
                           f"{flop / best_us / 1e6:6.1f} TFLOP/s; worst {worst} {worst_us:8.1f} us ({worst_us / best_us:.2f}x)")
             print(report[-1], flush=True)
             del x, w, b, out
+    kept = []
+    if args.pooled_only:
+        with open(args.out) as f:
+            kept = [ln for ln in f.read().splitlines()[2:] if ln and " pool" not in ln and not ln.startswith("{1, 1, -1,")]
     with open(args.out, "w") as f:
         f.write("// Generated by paper_1611_07151_amd/tune.py on an MI355X: fastest tiling per layer shape and batch.\n")
         f.write("// {K, S, P, Cin, Cout, H, W, N, fastest tiling, fastest tiling that needs no scratch}\n")
-        for line in report:
+        for line in [ln for ln in kept if ln.startswith("//")] + report:
+            f.write(line + "\n")
+        for line in [ln for ln in kept if not ln.startswith("//")]:
             f.write(line + "\n")
         for r in rows:
             f.write("{%d, %d, %d, %d, %d, %d, %d, %d, \"%s\", \"%s\"},\n" % r)

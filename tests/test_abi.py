@@ -94,6 +94,12 @@ def test_pool_and_softmax_reject_bad_arguments(lib):
     assert lib.sq_maxpool(NULL, FAKE, 1, 1, 8, 8, 3, 2) == -1
     assert lib.sq_maxpool(FAKE, FAKE, 1, 1, 2, 8, 3, 2) == -2
     assert lib.sq_maxpool(FAKE, FAKE, 1, 1, 8, 8, 3, 0) == -2
+    f = lib.sq_maxpool_conv2d_forward     # in, w, b, out, N, Cin, H, W, Cout, relu, out_channels, c_offset, algo
+    assert f(NULL, FAKE, FAKE, FAKE, 1, 16, 9, 9, 8, 1, 8, 0, 0) == -1
+    assert f(FAKE, FAKE, NULL, FAKE, 1, 16, 2, 9, 8, 1, 8, 0, 0) == -2      # no 3x3 window fits
+    assert f(FAKE, FAKE, NULL, FAKE, 1, 16, 9, 9, 8, 1, 8, 1, 0) == -2      # layers past the end of out
+    assert f(FAKE, FAKE, NULL, FAKE, 1, 16, 9, 9, 8, 1, 8, 0, 1) == -3      # the one-thread-per-output kernel cannot
+    assert f(FAKE, FAKE, NULL, FAKE, 1, 24, 9, 9, 8, 1, 8, 0, 0) == -3      # no tiling's input-layer chunk divides 24
     assert lib.sq_avgpool_global(FAKE, NULL, 1, 1, 8, 8) == -1
     assert lib.sq_avgpool_global(FAKE, FAKE, 1, 0, 8, 8) == -2
     assert lib.sq_softmax(NULL, FAKE, 1, 10) == -1

@@ -155,6 +155,74 @@ def test_maxpool_exact(sq, shape, k, s):
     np.testing.assert_array_equal(got, oracle.maxpool(x, k, s))
 
 
+# N, Cin, H, W, Cout: the three pooled maps of the network with the squeeze that reads them, then ragged cases
+# (even extents whose last row and column no window reaches, one window, a partial layer tile, Cin = 16 only).
+POOL_CONV_CASES = [(2, 96, 111, 111, 16), (2, 256, 55, 55, 32), (3, 512, 27, 27, 64), (2, 32, 12, 10, 40),
+                   (1, 16, 3, 3, 8), (3, 64, 9, 30, 16), (1, 128, 8, 7, 100)]
+
+
+@pytest.mark.parametrize("case", POOL_CONV_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_maxpool_inside_the_squeeze_is_bit_identical_to_two_calls(sq, case):
+    N, Cin, H, W, Cout = case
+    rng = np.random.default_rng(7 * Cin + H)
+    x = synth.normal01(rng, (N, Cin, H, W))
+    w, b = synth.conv_params(rng, Cout, Cin, 1)
+    ref = oracle.conv2d(oracle.maxpool(x, 3, 2), w, b, 1, 0, True)
+    xd, wd, bd = dev(x), dev(w), dev(b)
+    pooled = sq.sq_maxpool(xd, 3, 2)
+    ran = 0
+    for algo in [sq.SQ_ALGO_AUTO] + [sq.SQ_ALGO_VARIANT0 + i for i in range(sq.sq_conv_variant_count())]:
+        try:
+            got = sq.sq_maxpool_conv2d_forward(xd, wd, bd, True, algo=algo)
+        except sq.SqError as e:
+            assert e.status == -3 and algo >= sq.SQ_ALGO_VARIANT0, (algo, str(e))
+            continue
+        ran += 1
+        assert_close(got, ref, FP32_TOL, f"algo {algo}")
+        if algo >= sq.SQ_ALGO_VARIANT0:   # the same tiling on the pooled map: same contraction order
+            two = sq.sq_conv2d_forward_ex(pooled, wd, bd, 1, 0, True, algo=algo)
+            assert torch.equal(got, two), f"algo {algo}"
+    assert ran >= 5
+    # channel offset into a wider tensor, no bias, no relu
+    out = torch.full((N, Cout + 5, (H - 3) // 2 + 1, (W - 3) // 2 + 1), -7.0, device="cuda")
+    sq.sq_maxpool_conv2d_forward(xd, wd, None, False, out=out, c_offset=3)
+    assert_close(out[:, 3:3 + Cout], oracle.conv2d(oracle.maxpool(x, 3, 2), w, None, 1, 0, False), FP32_TOL, "offset")
+    assert bool((out[:, :3] == -7).all()) and bool((out[:, 3 + Cout:] == -7).all())
+
+
+def test_maxpool_inside_the_squeeze_rejects_what_it_cannot_run(sq):
+    x, w = torch.zeros((1, 24, 9, 9), device="cuda"), torch.zeros((8, 24, 1, 1), device="cuda")
+    with pytest.raises(sq.SqError) as e:      # no tiling has an input-layer chunk that divides 24
+        sq.sq_maxpool_conv2d_forward(x, w)
+    assert e.value.status == -3
+    with pytest.raises(sq.SqError) as e:
+        sq.sq_maxpool_conv2d_forward(x, w, algo=sq.SQ_ALGO_DIRECT)
+    assert e.value.status == -3
+    with pytest.raises(sq.SqError) as e:
+        sq.sq_maxpool_conv2d_forward(torch.zeros((1, 16, 2, 9), device="cuda"), torch.zeros((8, 16, 1, 1), device="cuda"))
+    assert e.value.status == -2
+
+
+def test_network_with_pooling_inside_the_squeeze_layers(sq):
+    cfg = synth.config_squeezenet(seed=5, n=3)
+    params = [dev(p) for p in cfg["params"]]
+    x = dev(cfg["x"])
+    by_policy, taps = sq.sq_squeezenet_forward(x, params, want_taps=True)
+    assert torch.equal(by_policy, sq.sq_squeezenet_forward(x, params))   # pooled maps kept or not: same bits
+    assert taps["pool1"].shape == (3, 96, 55, 55) and bool((taps["pool4"] >= 0).all())
+    sq.lib.sq_internal_fuse_pools_f32(0)
+    try:
+        separate = sq.sq_squeezenet_forward(x, params)
+        for mask in (1, 2, 4, 7):
+            sq.lib.sq_internal_fuse_pools_f32(mask)
+            fused = sq.sq_squeezenet_forward(x, params)
+            assert_close(fused, separate.cpu().numpy(), FP32_TOL, f"mask {mask}")
+    finally:
+        sq.lib.sq_internal_fuse_pools_f32(-1)
+    ref = oracle.squeezenet(cfg["x"], cfg["params"])
+    assert_close(fused, ref, FP32_TOL, "all pools fused")
+
+
 @pytest.mark.parametrize("shape", [(2, 1000, 13, 13), (1, 7, 5, 3), (3, 2, 1, 1), (1, 1, 30, 30)])
 def test_avgpool(sq, shape):
     rng = np.random.default_rng(12)
@@ -314,7 +382,9 @@ def test_benchmark_configuration_runs_the_kernels_it_reports(sq):
     assert any(n.startswith("fire4/e3|k3s1_f2x2_") for n in names), names
     assert "kernel transform|f2x2_kernel_transform" in names
     assert not any("direct" in k for k in kernels), kernels
-    assert len(names) == 32          # 26 convolutions, 3 + 1 pools, softmax, kernel transform
+    # 26 convolutions, global average pooling, softmax, kernel transform; the three max-pooling layers run
+    # inside the squeeze layers that read them
+    assert len(names) == 29 and not any("maxpool" in k for k in kernels), names
 
 
 # ----------------------------------------------------------------- workload 5

@@ -30,6 +30,7 @@
 #include "conv_mfma_variants.h"
 
 #include <math.h>
+#include <stdio.h>
 #include <algorithm>
 #include <string.h>
 
@@ -215,7 +216,10 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
         const int rc = conv_prepare_kernels(&job, 1, a.dtype);
         if (rc) return rc;
     }
-    LaunchScope scope(v.name, flops, bytes);
+    // a launch that pools on the way in is reported under a name of its own ("pool3s2+<tiling>")
+    static char pooled_names[kNumVariants][64];
+    if (a.pool_H && !pooled_names[vi][0]) snprintf(pooled_names[vi], sizeof(pooled_names[vi]), "pool3s2+%s", v.name);
+    LaunchScope scope(a.pool_H ? pooled_names[vi] : v.name, flops, bytes);
     hipLaunchKernelGGL(fn, dim3(pl.blocks, pl.blocks_y), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
     return check_launch();
 }

@@ -132,21 +132,22 @@ int fire_impl(const void *in, const void *w_sq, const float *b_sq, const void *w
     asq.pool_H = pool_H; asq.pool_W = pool_W;
     int rc = run_conv(asq, sq_algo);
     if (rc) return rc;
-    // both expands in one launch when a fused tiling exists for this shape
+    const ConvArgs a1 = make_args(sq_map, w_e1, b_e1, out, N, Csq, H, W, Ce1, 1, 1, 0, 1, Ce1 + Ce3, 0, SQ_F32);
+    ConvArgs a3 = make_args(sq_map, w_e3, b_e3, out, N, Csq, H, W, Ce3, 3, 1, 1, 1, Ce1 + Ce3, Ce1, SQ_F32);
+    a3.ws = conv_ws; a3.ws_bytes = conv_ws_bytes; a3.ws_ready = conv_ws_ready;
+    // Both expands in one launch: the expand1x1 tiles behind the persistent workgroups of a minimal-filtering
+    // expand3x3 (batches of three images and more), else both in the tiles of one direct 3x3 kernel (small
+    // batches, where a fused tiling exists for the shape), else two launches.
     set_stage(stages[3]);
-    rc = conv_expand_fused(make_args(sq_map, w_e3, b_e3, out, N, Csq, H, W, Ce3, 3, 1, 1, 1, Ce1 + Ce3, Ce1, SQ_F32),
-                           w_e1, b_e1, Ce1, 0);
+    rc = conv_expand_pair(a3, a1);
+    if (rc == SQ_ERR_UNSUPPORTED) rc = conv_expand_fused(a3, w_e1, b_e1, Ce1, 0);
     if (rc != SQ_ERR_UNSUPPORTED) {
         set_stage("");
         return rc;
     }
     set_stage(stages[1]);
-    rc = run_conv(make_args(sq_map, w_e1, b_e1, out, N, Csq, H, W, Ce1, 1, 1, 0, 1, Ce1 + Ce3, 0, SQ_F32),
-                  SQ_ALGO_AUTO);
-    if (rc) return rc;
+    if ((rc = run_conv(a1, SQ_ALGO_AUTO))) return rc;
     set_stage(stages[2]);
-    ConvArgs a3 = make_args(sq_map, w_e3, b_e3, out, N, Csq, H, W, Ce3, 3, 1, 1, 1, Ce1 + Ce3, Ce1, SQ_F32);
-    a3.ws = conv_ws; a3.ws_bytes = conv_ws_bytes; a3.ws_ready = conv_ws_ready;
     rc = run_conv(a3, SQ_ALGO_AUTO);
     set_stage("");
     return rc;
@@ -430,7 +431,7 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
             ConvArgs a3 = make_args(bufS, params[2 + 6 * f + 4], nullptr, bufA, N, fc.sq, h, h, fc.e, 3, 1, 1, 1,
                                     2 * fc.e, fc.e, SQ_F32);
             a3.ws = conv_ws[f]; a3.ws_bytes = conv_ws_bytes[f];
-            conv_ws_ready[f] = conv_wants_prepared_kernels(a3);
+            conv_ws_ready[f] = conv_wants_prepared_kernels(a3, true);
             if (conv_ws_ready[f]) prep[nprep++] = KernelPrepJob{params[2 + 6 * f + 4], conv_ws[f], fc.sq, fc.e};
             if (f == 2) h = 27;
             if (f == 6) h = 13;

@@ -182,13 +182,13 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
 }
 
 // Dynamic LDS above the default limit must be opted into once per kernel function.
-bool allow_big_lds(KernelFn fn)
+bool allow_big_lds(const void *fn)
 {
-    static KernelFn done[4 * kNumVariants + 4];
+    static const void *done[4 * kNumVariants + 8];
     static int ndone = 0;
     for (int i = 0; i < ndone; ++i)
         if (done[i] == fn) return true;
-    if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
         return false;
     if (ndone < (int)(sizeof(done) / sizeof(done[0]))) done[ndone++] = fn;
     return true;
@@ -202,7 +202,7 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
     if (v.conv1_type) fn = conv7s2c3_kernel_for(v.NT / 64, a.Cout == 96, a.dtype == SQ_BF16, v.BM / 32);
     if (!v.conv1_type && !v.wino && !e1 && a.Cin % v.CC != 0) fn = ks.tail;
     if (a.pool_H) fn = ks.pooled;
-    if (!allow_big_lds(fn)) {
+    if (!allow_big_lds((const void *)fn)) {
         const int rc = check_launch();
         return rc ? rc : SQ_ERR_HIP;
     }
@@ -297,11 +297,37 @@ size_t conv_workspace_bytes(int Cin, int Cout, int K, int S, int P)
     return 0;
 }
 
-bool conv_wants_prepared_kernels(const ConvArgs &a)
+// Whether the two expands of a fire layer share a launch (expand_pair_kernel): -1 = from kExpandPairMinBatch images
+// on (the default), 0 = never, 1 + i = like -1 with the i-th compiled expand1x1 tiling.  A tuning hook, not part of
+// the public interface.  Measured on whole fp32 passes: with the pair on every fire layer 4 % / 10 % / 9 % / 11 % /
+// 6 % / 3 % faster at batch 4 / 8 / 16 / 32 / 64 / 256 than the best of the other forms (both expands in the tiles
+// of one direct 3x3 kernel up to batch 16, separate launches above), slower only at batches 1 and 2.
+int g_expand_pair = -1;
+extern "C" void sq_internal_expand_pair(int v) { g_expand_pair = v; }
+constexpr int kExpandPairMinBatch = 3;
+
+static bool expand_pair_wanted(const ConvArgs &a3)
+{
+    return g_expand_pair != 0 && a3.N >= kExpandPairMinBatch && a3.dtype == SQ_F32 && a3.K == 3 && a3.S == 1 && a3.P == 1;
+}
+
+// The minimal-filtering tiling if this layer is to run in it -- because it is the measured choice for the layer
+// on its own, or (pair = true) as the first part of an expand pair, which takes it wherever it fits; -1 otherwise.
+static int wino_choice(const ConvArgs &a, Plan &pl, bool pair)
 {
     const int tv = tuned_variant(a);
+    if (tv >= 0 && kVariants[tv].wino) return plan(kVariants[tv], a, pl) ? tv : -1;
+    if (pair)
+        for (int i = 0; i < kNumVariants; ++i)
+            if (kVariants[i].wino && plan(kVariants[i], a, pl)) return i;
+    return -1;
+}
+
+// fire_expand: this is the expand3x3 of a fire layer (it may run as part of an expand pair)
+bool conv_wants_prepared_kernels(const ConvArgs &a, bool fire_expand)
+{
     Plan pl;
-    return tv >= 0 && kVariants[tv].wino && plan(kVariants[tv], a, pl);
+    return wino_choice(a, pl, fire_expand && expand_pair_wanted(a)) >= 0;
 }
 
 int conv_mfma_variant_count() { return kNumVariants; }
@@ -366,6 +392,48 @@ int conv_mfma_choice(const ConvArgs &a)
 {
     Plan pl;
     return choose_variant(a, pl);
+}
+
+int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1)
+{
+    if (!expand_pair_wanted(a3) || a1.dtype != SQ_F32) return SQ_ERR_UNSUPPORTED;
+    if (a1.K != 1 || a1.S != 1 || a1.P != 0 || a1.pool_H || a1.in != a3.in || a1.out != a3.out || a1.N != a3.N) return SQ_ERR_UNSUPPORTED;
+    Plan p3, p1;
+    const int v3 = wino_choice(a3, p3, true);
+    if (v3 < 0 || kVariants[v3].NT != 256) return SQ_ERR_UNSUPPORTED;
+    // The expand1x1 tiling.  Measured inside the pair on whole passes at batches 32 to 256 (the stand-alone winners
+    // 64x64 and 48x64 lose here, 128x128 too): 64x128 first, 64x256 first from batch 128 on.
+    auto variant_of = [](const PairKernel &pk) {
+        for (int i = 0; i < kNumVariants; ++i)
+            if (!strcmp(kVariants[i].name, pk.e1_variant)) return i;
+        return -1;
+    };
+    const int prefer = g_expand_pair > 0 ? g_expand_pair - 1 : (a1.N >= 128 ? 1 : 0);
+    if (prefer >= num_expand_pair_kernels) return SQ_ERR_UNSUPPORTED;
+    int pair = -1;
+    for (int k = 0; k < num_expand_pair_kernels && pair < 0; ++k) {
+        if (g_expand_pair > 0 && k > 0) break;                    // a forced tiling has no substitute
+        const int i = (prefer + k) % num_expand_pair_kernels;     // the preferred one first, then the others
+        const int v = variant_of(expand_pair_kernels[i]);
+        if (v >= 0 && a1.Cin % kVariants[v].CC == 0 && plan(kVariants[v], a1, p1)) pair = i;
+    }
+    if (pair < 0) return SQ_ERR_UNSUPPORTED;
+    const long long blocks = (long long)p3.blocks + p1.blocks;
+    if (blocks >= (1ll << 31) || p1.blocks_y != 1) return SQ_ERR_UNSUPPORTED;
+    const PairKernel &pk = expand_pair_kernels[pair];
+    if (!allow_big_lds((const void *)pk.fn)) {
+        const int rc = check_launch();
+        return rc ? rc : SQ_ERR_HIP;
+    }
+    if (!a3.ws_ready) {
+        const KernelPrepJob job{a3.w, a3.ws, a3.Cin, a3.Cout};
+        const int rc = conv_prepare_kernels(&job, 1, a3.dtype);
+        if (rc) return rc;
+    }
+    LaunchScope scope(pk.name, conv_flops(a3) + conv_flops(a1), conv_bytes(a3) + conv_bytes(a1));
+    hipLaunchKernelGGL(pk.fn, dim3((unsigned)blocks), dim3(256), std::max(p3.lds_bytes, p1.lds_bytes), current_stream(), p3.kp,
+                       p1.kp, (int)p3.blocks);
+    return check_launch();
 }
 
 int conv_mfma(const ConvArgs &a, int variant)

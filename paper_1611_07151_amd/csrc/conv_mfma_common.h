@@ -198,6 +198,16 @@ struct KernelSet {
     KernelFn plain, tail, fused_e1, pooled;
 };
 extern const KernelSet conv_mfma_kernels_f32[], conv_mfma_kernels_bf16[];
+// Both expands of a fire layer in one launch (expand_pair_kernel): the compiled expand1x1 tilings, each named
+// like the stand-alone tiling it is.
+typedef void (*PairFn)(const KParams, const KParams, int);
+struct PairKernel {
+    const char *e1_variant;   // name of the 1x1 tiling in the variant list
+    const char *name;         // name of the pair in profiles
+    PairFn fn;
+};
+extern const PairKernel expand_pair_kernels[];
+extern const int num_expand_pair_kernels;
 // TM = blocks of 32 output layers per workgroup: 3 (all 96), or 1 with the block chosen by blockIdx.y (NW = 4 only).
 KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers, bool bf16_inputs, int TM);
 

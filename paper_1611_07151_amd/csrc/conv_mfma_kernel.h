@@ -47,9 +47,13 @@ namespace mfma {
 // in -- in this network every pooled map is read by exactly one squeeze layer, so it need not
 // exist in memory.  p.H, p.W are the pooled extents, p.Win / p.HWin those of the map in memory; a
 // staged element is the maximum of nine loads (per window row one 8-byte and one 4-byte load).
-template <typename TIN, int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW, bool TAIL, bool E1 = false,
+//
+// conv_mfma_tile is the work of one workgroup (tile number `block` of the launch), conv_mfma_kernel the
+// kernel that consists of nothing else; the expand pair kernel (conv_wino_kernel.h) runs the same tiles
+// behind its own.
+template <typename TIN, int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, bool TAIL, bool E1 = false,
           bool POOL = false>
-__global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KParams p)
+__device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block)
 {
     using M = Mfma<MT>;
     using Acc = typename M::Acc;
@@ -85,7 +89,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KPa
     const int wm = wv / WN, wn = wv % WN;
     const int li = lane % MT, kk = lane / MT;
 
-    const int tile = xcd_remap(blockIdx.x, p.mtiles * p.ntiles);
+    const int tile = xcd_remap(block, p.mtiles * p.ntiles);
     const int pt = fdiv(tile, p.dMtiles), mt = tile - pt * p.mtiles;
     const int P0 = pt * BN, m0 = mt * BM;
     const bool full_m = m0 + BM <= p.Cout && (!E1 || m0 + BM <= p.Cout1);
@@ -414,6 +418,13 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KPa
             if (m0 < p.Cout1) write_out(acc1, p.Cout1, p.coff1, std::false_type{});
         }
     }
+}
+
+template <typename TIN, int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW, bool TAIL, bool E1 = false,
+          bool POOL = false>
+__global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KParams p)
+{
+    conv_mfma_tile<TIN, KS, S, BM, BN, WM, WN, MT, CC, PE, TAIL, E1, POOL>(p, (int)blockIdx.x);
 }
 
 }  // namespace mfma

@@ -38,6 +38,7 @@
 #include <type_traits>
 
 #include "conv_mfma_common.h"
+#include "conv_mfma_kernel.h"
 
 namespace sq {
 namespace mfma {
@@ -93,8 +94,9 @@ __global__ __launch_bounds__(256) void wino_kernel_transform(const WinoJobs jobs
     }
 }
 
+// conv_wino_tiles: what one persistent workgroup does -- tile blocks first, first + stride, ... of the layer.
 template <typename TIN>
-__global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
+__device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int first, const int stride)
 {
     constexpr int BM = kWinoBM, BT = kWinoBT, CC = kWinoCC;
     static_assert(BM == 64 && BT == 32 && CC == 8, "thread roles below are written for this tile");
@@ -113,8 +115,8 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
     // Persistent workgroups (two per CU): a workgroup that retires keeps its registers and LDS
     // until its last stores have drained; looping over tiles lets the next tile start behind them.
     const int ntile_blocks = p.mtiles * p.ntiles;
-    for (int bid_raw = blockIdx.x; bid_raw < ntile_blocks; bid_raw += gridDim.x) {
-    if (bid_raw != (int)blockIdx.x) __syncthreads();   // the exchange area of the previous tile has been read out
+    for (int bid_raw = first; bid_raw < ntile_blocks; bid_raw += stride) {
+    if (bid_raw != first) __syncthreads();   // the exchange area of the previous tile has been read out
     const int bid = xcd_remap(bid_raw, ntile_blocks);
     const int tb = fdiv(bid, p.dMtiles);
     const int mt = bid - tb * p.mtiles, m0 = mt * BM, t0 = tb * BT;
@@ -345,6 +347,27 @@ __global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
         buf_st(rout, o1, so, zin[0][q]);   // tiles cut by the right edge (odd widths); dropped otherwise
     }
     }   // tiles of this workgroup
+}
+
+template <typename TIN>
+__global__ __launch_bounds__(256, 2) void conv_wino_kernel(const KParams p)
+{
+    conv_wino_tiles<TIN>(p, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// Both expands of a fire layer in one launch at large batches: the first wino_blocks workgroups are the
+// persistent workgroups of the minimal-filtering expand3x3 (p3), the others one tile each of the expand1x1 (p1)
+// in the tiling <BM, BN, WM, WN, MT, CC>.  The two write different layers of one tensor and read the same map.
+// expand3x3 is bound by the matrix cores and its persistent workgroups finish at different times (at batch 64
+// the layers of this network give a CU 6.1 tile blocks on average, so some CUs take seven and most six);
+// expand1x1 is bound by its stores.  Its workgroups come last in the grid, so they are placed as the others
+// retire and fill the CUs that would idle until the launch ends -- without the cost of a second stream.
+template <int BM, int BN, int WM, int WN, int MT, int CC>
+__global__ __launch_bounds__(256, 2) void expand_pair_kernel(const KParams p3, const KParams p1, const int wino_blocks)
+{
+    static_assert(WM * WN == 4, "both parts run with four wavefronts");
+    if ((int)blockIdx.x < wino_blocks) conv_wino_tiles<float>(p3, (int)blockIdx.x, wino_blocks);
+    else conv_mfma_tile<float, 1, 1, BM, BN, WM, WN, MT, CC, 0, false>(p1, (int)blockIdx.x - wino_blocks);
 }
 
 }  // namespace mfma

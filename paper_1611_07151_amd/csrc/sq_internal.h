@@ -53,6 +53,10 @@ int conv_direct(const ConvArgs &a);
 // Matrix-core family.  variant < 0 = pick by shape; returns SQ_ERR_UNSUPPORTED when
 // the (variant, shape, dtype) combination has no kernel.
 int conv_mfma(const ConvArgs &a, int variant);
+// Both expands of a fire layer (a3: 3x3 pad 1, a1: 1x1, same input map and output tensor) in one launch, where the
+// measured choice for a3 is the minimal-filtering kernel and a compiled expand1x1 tiling fits; SQ_ERR_UNSUPPORTED
+// otherwise.
+int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1);
 // The tiling conv_mfma(a, -1) runs, or -1.
 int conv_mfma_choice(const ConvArgs &a);
 // Fused expand of a fire layer: the 3x3 convolution a3 and a 1x1 convolution of the same
@@ -68,8 +72,9 @@ struct KernelPrepJob {
     int Cin, Cout;
 };
 int conv_prepare_kernels(const KernelPrepJob *jobs, int n, int dtype);
-// Whether the automatic choice for this call is an algorithm that runs on transformed kernels.
-bool conv_wants_prepared_kernels(const ConvArgs &a);
+// Whether this call will run an algorithm that works on transformed kernels; fire_expand says that it is the
+// expand3x3 of a fire layer, which may share a launch with the expand1x1 (conv_expand_pair).
+bool conv_wants_prepared_kernels(const ConvArgs &a, bool fire_expand);
 int conv_mfma_variant_count();
 const char *conv_mfma_variant_name(int i);
 

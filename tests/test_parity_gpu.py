@@ -270,6 +270,7 @@ def test_fire_with_both_expands_in_one_launch(sq, cin, sq_c, e, h, n):
     args = [dev(a) for a in (x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3)]
     fused_ran = 0
     try:
+        sq.lib.sq_internal_expand_pair(0)          # the other one-launch form would take these layers first
         for v in [-3, -2, -1] + list(range(sq.sq_conv_variant_count())):
             sq.lib.sq_internal_force_expand(v)
             sq.sq_profile_begin(16)
@@ -280,7 +281,48 @@ def test_fire_with_both_expands_in_one_launch(sq, cin, sq_c, e, h, n):
             fused_ran += v >= 0 and "fire/e1+e3" in stages
     finally:
         sq.lib.sq_internal_force_expand(-2)
+        sq.lib.sq_internal_expand_pair(-1)
     assert fused_ran >= 3 or sq_c % 4        # several tilings took the fused form (input layers must fill their chunks)
+
+
+@pytest.mark.parametrize("cin,sq_c,e,h,n", [(96, 16, 64, 55, 3), (256, 32, 128, 27, 5), (384, 48, 192, 27, 4), (512, 64, 256, 13, 9),
+                                            (40, 8, 32, 10, 3), (64, 16, 96, 7, 130)])
+def test_fire_expand_pair_is_bit_identical_to_its_two_parts(sq, cin, sq_c, e, h, n):
+    """From three images on the two expands share a launch: the persistent workgroups of the minimal-filtering
+    expand3x3 and, behind them in the grid, the tiles of the expand1x1.  Each part must give what its kernel gives
+    on its own; the whole must match the oracle."""
+    rng = np.random.default_rng(cin + e + n)
+    x = synth.normal01(rng, (n, cin, h, h))
+    w_sq, b_sq = synth.conv_params(rng, sq_c, cin, 1)
+    b_sq = (b_sq + 1.0).astype(np.float32)
+    w_e1, b_e1 = synth.conv_params(rng, e, sq_c, 1)
+    w_e3, b_e3 = synth.conv_params(rng, e, sq_c, 3)
+    args = [dev(a) for a in (x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3)]
+    names = [sq.sq_conv_variant_name(i) for i in range(sq.sq_conv_variant_count())]
+    sq_map = sq.sq_conv2d_forward(args[0], args[1], args[2], 1, 0, True)
+    ran = 0
+    try:
+        for i, e1_name in enumerate(["k1s1_64x128_w2x2_m32_c16_o2", "k1s1_64x256_w1x4_m32_c16_o2"]):
+            sq.lib.sq_internal_expand_pair(1 + i)
+            sq.sq_profile_begin(16)
+            got = sq.sq_fire_forward(*args)
+            recs = [r["name"] for r in sq.sq_profile_end()]
+            if sq_c % 16:                    # the pair's expand1x1 tilings take 16 input layers at a time
+                assert not any("+k1s1" in r for r in recs), recs
+                continue
+            assert any(r == f"fire/e1+e3|k3s1_f2x2_64x32_c8+{e1_name[:-3]}" for r in recs), recs
+            ran += 1
+            e3 = sq.sq_conv2d_forward_ws(sq_map, args[5], args[6], 1, 1, True, algo=sq.SQ_ALGO_VARIANT0 + names.index("k3s1_f2x2_64x32_c8"))
+            e1 = sq.sq_conv2d_forward_ex(sq_map, args[3], args[4], 1, 0, True, algo=sq.SQ_ALGO_VARIANT0 + names.index(e1_name))
+            assert torch.equal(got[:, :e], e1) and torch.equal(got[:, e:], e3), e1_name
+            assert_close(got, oracle.fire(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3), FP32_TOL, e1_name)
+        sq.lib.sq_internal_expand_pair(0)
+        sq.sq_profile_begin(16)
+        assert_close(sq.sq_fire_forward(*args), oracle.fire(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3), FP32_TOL, "pair off")
+        assert not any("+k1s1" in r["name"] for r in sq.sq_profile_end())
+    finally:
+        sq.lib.sq_internal_expand_pair(-1)
+    assert ran == (0 if sq_c % 16 else 2)
 
 
 def test_fire_border_sees_zero_padding_not_relu_of_bias(sq):
@@ -379,12 +421,12 @@ def test_benchmark_configuration_runs_the_kernels_it_reports(sq):
     names = [r["name"] for r in sq.sq_profile_end()]
     kernels = {n.split("|")[1] for n in names}
     assert "conv1|k7s2c3_waves8" in names
-    assert any(n.startswith("fire4/e3|k3s1_f2x2_") for n in names), names
+    assert sum(n.endswith("/e1+e3|k3s1_f2x2_64x32_c8+k1s1_64x128_w2x2_m32_c16") for n in names) == 8, names
     assert "kernel transform|f2x2_kernel_transform" in names
     assert not any("direct" in k for k in kernels), kernels
-    # 26 convolutions, global average pooling, softmax, kernel transform; the three max-pooling layers run
-    # inside the squeeze layers that read them
-    assert len(names) == 29 and not any("maxpool" in k for k in kernels), names
+    # conv1, eight fire layers of two launches (squeeze; both expands), conv10, global average pooling, softmax,
+    # kernel transform; the three max-pooling layers run inside the squeeze layers that read them
+    assert len(names) == 21 and not any("maxpool" in k for k in kernels), names
 
 
 # ----------------------------------------------------------------- workload 5

@@ -128,6 +128,7 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
         k.dTX = make_fastdiv(k.TX); k.dTXY = make_fastdiv(k.TXY);
         k.ntiles = (int)((tiles + v.BN - 1) / v.BN);
         k.VH = a.Ho; k.LW = a.Wo; k.LWs = a.Wo; k.PRcap = 0; k.plane = 0;
+        if (wino_transformed_bytes(a.Cout, a.Cin) >= (size_t)kMaxBufferElems * 4) return false;   // read through a buffer
         k.wu = (const float *)a.ws;
         k.wu_bytes = (uint32_t)wino_transformed_bytes(a.Cout, a.Cin);
     } else if (v.KS == 1 && v.S == 1) {

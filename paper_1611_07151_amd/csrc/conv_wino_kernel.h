@@ -154,6 +154,8 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
 
     float dpatch[16];
     f32x4 ucopy[8];
+    const rsrc_t ru = make_rsrc(p.wu, p.wu_bytes);
+    uint32_t ulane = (uint32_t)(t * 16);
     auto load_chunk = [&](int ch) {
         const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(ch * CC * p.HW) * ESZ;
 #pragma unroll
@@ -163,10 +165,17 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
 #pragma unroll
             for (int b = 1; b < 4; ++b) dpatch[4 * a + b] = buf_ld_in<TIN>(rx, xrow[a] + (b - 1) * ESZ, so);
         }
-        // U image of this (layer block, chunk): uniform 64-bit base + 32-bit lane offset
-        const char *ub = (const char *)p.wu + (size_t)__builtin_amdgcn_readfirstlane(mt * p.nchunks + ch) * (US * 4);
+        // U image of this (layer block, chunk): its offset and the piece number go into the uniform offset, the
+        // lane offset t * 16 never changes -- no vector arithmetic per load
+        const uint32_t ub = (uint32_t)__builtin_amdgcn_readfirstlane(mt * p.nchunks + ch) * (uint32_t)(US * 4);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) ucopy[i] = *(const f32x4 *)(ub + i * 4096 + (size_t)(uint32_t)(t * 16));
+        for (int i = 0; i < 8; ++i) {
+            asm volatile("" : "+v"(ulane));   // four adjacent dword loads from one lane offset merge into one of 16 bytes
+            ucopy[i].x = buf_ld(ru, ulane, ub + i * 4096);
+            ucopy[i].y = buf_ld(ru, ulane + 4, ub + i * 4096);
+            ucopy[i].z = buf_ld(ru, ulane + 8, ub + i * 4096);
+            ucopy[i].w = buf_ld(ru, ulane + 12, ub + i * 4096);
+        }
     };
     auto store_chunk = [&]() {
 #pragma unroll
@@ -206,9 +215,15 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
         for (int q = 0; q < 16; ++q) start11[q] = 0.f;
     }
 
-    // per-lane operand addresses: A = U[xi][kk][32 wx + li][0..3], B = V[xi][kk][li][0..3]
-    const float *ua = lds + 8 * pr * 512 + kk * 256 + (32 * wx + li) * 4;
-    const float *vb = lds + US + 8 * pr * (2 * BT * 4) + kk * (BT * 4) + li * 4;
+    // per-lane operand addresses: A = U[xi][kk][32 wx + li][0..3], B = V[xi][kk][li][0..3].  The wavefront's two
+    // grid rows are taken in the order (0, 1) for pr = 0 and (3, 2) for pr = 1, so that the row the partner needs
+    // (1 or 2) is the second one in both and the output transform has no per-wavefront choice of registers.
+    // [g]: base such that accumulator s (row g = s / 4 of the wavefront's order) reads at base[g] + s * stride.
+    const float *ua[2], *vb[2];
+    ua[0] = lds + 12 * pr * 512 + kk * 256 + (32 * wx + li) * 4;
+    ua[1] = ua[0] - 8 * pr * 512;
+    vb[0] = lds + US + 12 * pr * (2 * BT * 4) + kk * (BT * 4) + li * 4;
+    vb[1] = vb[0] - 8 * pr * (2 * BT * 4);
     auto compute_chunk = [&](auto first_chunk) {
         constexpr bool FIRST = decltype(first_chunk)::value;
         // two grid positions at a time, their MFMAs interleaved: consecutive MFMAs never
@@ -216,8 +231,8 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
         f32x4 a[4], b[4];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-            a[e] = *(const f32x4 *)(ua + e * 512);
-            b[e] = *(const f32x4 *)(vb + e * (2 * BT * 4));
+            a[e] = *(const f32x4 *)(ua[0] + e * 512);
+            b[e] = *(const f32x4 *)(vb[0] + e * (2 * BT * 4));
         }
 #pragma unroll
         for (int s = 0; s < 8; s += 2) {
@@ -225,8 +240,8 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
             if (s + 2 < 8) {
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
-                    a[nxt2 + e] = *(const f32x4 *)(ua + (s + 2 + e) * 512);
-                    b[nxt2 + e] = *(const f32x4 *)(vb + (s + 2 + e) * (2 * BT * 4));
+                    a[nxt2 + e] = *(const f32x4 *)(ua[(s + 2 + e) / 4] + (s + 2 + e) * 512);
+                    b[nxt2 + e] = *(const f32x4 *)(vb[(s + 2 + e) / 4] + (s + 2 + e) * (2 * BT * 4));
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -269,11 +284,12 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
     }
 
     // ---- output transform -------------------------------------------------------------------
-    // acc[4i + s] is grid position (row 2pr+i, column s).  Folding a row with A gives
+    // acc[4g + s] is column s of the wavefront's g-th grid row (rows 0, 1 for pr = 0; rows 3, 2 for pr = 1).
+    // Folding a row with A gives
     //   z(row)[0] = m0 + m1 + m2,   z(row)[1] = m1 - m2 - m3,
     // and the output rows are  Y[0] = z(0) + z(1) + z(2),  Y[1] = z(1) - z(2) - z(3).
-    // pr = 0 holds rows 0, 1: keeps z(0) + z(1) for Y[0] and hands z(1) to its partner;
-    // pr = 1 holds rows 2, 3: keeps -z(2) - z(3) for Y[1] and hands z(2) over.
+    // pr = 0 keeps z(0) + z(1) for Y[0] and hands z(1), its second row, to its partner;
+    // pr = 1 keeps -z(3) - z(2) for Y[1] and hands z(2), its second row, over.
     // Exchange area: [wavefront][zz][register][lane]; the images are free by now.
     constexpr int ZQ = 16 * 64;
     static_assert(4 * 2 * ZQ <= US + VS, "exchange area must fit the staging images");
@@ -289,20 +305,8 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
             const float z0b = acc[4][q] + acc[5][q] + acc[6][q], z1b = acc[5][q] - acc[6][q] - acc[7][q];
             keep[0][q] = z0a + z0b;
             keep[1][q] = z1a + z1b;
-            acc[0][q] = z0a; acc[1][q] = z1a; acc[2][q] = z0b; acc[3][q] = z1b;
-        }
-        if (pr) {   // hand over grid row 2 (first of this wavefront's rows) ...
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                z[q * 64] = acc[0][q];
-                z[ZQ + q * 64] = acc[1][q];
-            }
-        } else {    // ... or grid row 1 (second of them)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                z[q * 64] = acc[2][q];
-                z[ZQ + q * 64] = acc[3][q];
-            }
+            z[q * 64] = z0b;
+            z[ZQ + q * 64] = z1b;
         }
     }
     __syncthreads();

@@ -171,7 +171,7 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
         if (v.BM == 32) pl.blocks_y = (unsigned)k.mtiles;   // one workgroup per block of 32 output layers
     } else if (v.wino) {
         blocks = std::min<long long>(blocks, 2ll * num_cus());   // persistent: two workgroups per CU
-        pl.lds_bytes = (size_t)(kWinoImage + 16 * 2 * kWinoBT * 4) * sizeof(float);
+        pl.lds_bytes = (size_t)(2 * 16 * 2 * kWinoBT * 4) * sizeof(float);   // two V images
     } else {
         pl.lds_bytes = ((size_t)v.NBUF * v.BM * LDK + (size_t)v.NBUF * v.CC * k.plane +
                         (e1 ? (size_t)2 * v.BM * (v.CC + 1) : 0)) * sizeof(float);

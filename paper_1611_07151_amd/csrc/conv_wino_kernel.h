@@ -16,21 +16,22 @@
 //         | 0  1  0 -1 |       | 0    0    1  |
 //
 // Two kernels.  wino_kernel_transform writes U for all (m, c) once per call (for several
-// layers at once when the caller has several), already in
-// the order the main kernel keeps it in LDS, so the main kernel copies it with 16-byte
-// loads and spends no arithmetic on it.  conv_wino_kernel: a workgroup owns 64 output
+// layers at once when the caller has several), already in the order in which the lanes of
+// the main kernel take it as MFMA operands, so the main kernel loads it with 16-byte loads
+// and spends no arithmetic on it.  conv_wino_kernel: a workgroup owns 64 output
 // layers x 32 tiles and has 4 wavefronts (pr, x): wavefront (pr, x) accumulates the eight
-// positions of grid rows 2pr and 2pr+1 for layers 32x..32x+31 and all 32 tiles in eight
+// positions of two grid rows for layers 32x..32x+31 and all 32 tiles in eight
 // accumulators of v_mfma_f32_32x32x2_f32 (A operand = output layers, B operand = tiles).
-// Input layers are taken eight at a time; both LDS images hold, per position and per lane
-// half kk, the four values c = kk, kk+2, kk+4, kk+6 of a layer (tile) side by side, so one
-// 16-byte LDS read feeds four MFMAs.  Every thread transforms the patch of one (tile, input
-// layer) and copies eight 16-byte pieces of U per chunk: the global loads of chunk c+1 are
-// issued before the MFMAs of chunk c and their results go to LDS between two barriers
-// afterwards.  Two persistent workgroups share a CU (256 registers per wavefront) and loop
-// over tiles.  At the end a wavefront folds its two grid
-// rows with A and half of A^T, swaps the other half with its partner (pr ^ 1) through LDS,
-// and writes output row pr of its tiles.
+// Input layers are taken eight at a time; U in memory and the V image in LDS hold, per
+// position and per lane half kk, the four values c = kk, kk+2, kk+4, kk+6 of a layer (tile)
+// side by side, so one 16-byte read feeds four MFMAs.  A wavefront needs exactly a quarter
+// of the U of a chunk, and no other wavefront needs that quarter: it goes from memory (L2)
+// straight into the wavefront's registers, one chunk ahead of its use.  Every thread
+// transforms the patch of one (tile, input layer) per chunk and writes it into one of two V
+// images in LDS while the other one is being multiplied: one barrier per chunk.  Two
+// persistent workgroups share a CU (256 registers per wavefront) and loop over tiles.  At the
+// end a wavefront folds its two grid rows with A and half of A^T, swaps the other half with
+// its partner (pr ^ 1) through LDS, and writes output row pr of its tiles.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -100,8 +101,8 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
 {
     constexpr int BM = kWinoBM, BT = kWinoBT, CC = kWinoCC;
     static_assert(BM == 64 && BT == 32 && CC == 8, "thread roles below are written for this tile");
-    constexpr int US = kWinoImage;             // floats of the U image [16][2][64][4]
-    constexpr int VS = 16 * 2 * BT * 4;        // floats of the V image [16][2][32][4]
+    constexpr int US = kWinoImage;             // floats of the U image [16][2][64][4] of one (layer block, chunk) in memory
+    constexpr int VS = 16 * 2 * BT * 4;        // floats of the V image [16][2][32][4]; LDS holds two of them
     constexpr uint32_t ESZ = sizeof(TIN);
     using M = Mfma<32>;
     using Acc = M::Acc;
@@ -150,13 +151,30 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
         mc3 = iw0 + 3 < p.W ? 1.f : 0.f;
     }
     // V image position of (tile vt, layer vc): lane half vc & 1, slot vc >> 1
-    const int vdst = US + (vc & 1) * (BT * 4) + vt * 4 + (vc >> 1);
+    const int vdst = (vc & 1) * (BT * 4) + vt * 4 + (vc >> 1);
+
+    // The wavefront's two grid rows are taken in the order (0, 1) for pr = 0 and (3, 2) for pr = 1, so that the
+    // row the partner needs (1 or 2) is the second one in both and the output transform has no per-wavefront
+    // choice of registers: accumulator s belongs to grid position gpos(s).
+    auto gpos = [&](int s) { return (s < 4 ? 12 * pr : 4 * pr) + s; };   // uniform
 
     float dpatch[16];
-    f32x4 ucopy[8];
+    // A operands.  Of the U image of a (layer block, chunk), wavefront (pr, x) needs exactly the quarter
+    // [its 8 positions][kk][32x..32x+31][4]: lane (li, kk) takes its 16 bytes of every position straight from
+    // memory (L2) into registers -- the image never passes through LDS.  The uniform offset carries layer block,
+    // chunk and position, the lane offset never changes.
+    f32x4 A[8];
     const rsrc_t ru = make_rsrc(p.wu, p.wu_bytes);
-    uint32_t ulane = (uint32_t)(t * 16);
-    auto load_chunk = [&](int ch) {
+    uint32_t ulane = (uint32_t)((kk * 64 + 32 * wx + li) * 16);
+    auto load_A = [&](int ch, int s_) {
+        const uint32_t ub = (uint32_t)__builtin_amdgcn_readfirstlane((mt * p.nchunks + ch) * (US * 4) + gpos(s_) * 2048);
+        asm volatile("" : "+v"(ulane));   // four adjacent dword loads from one lane offset merge into one of 16 bytes
+        A[s_].x = buf_ld(ru, ulane, ub);
+        A[s_].y = buf_ld(ru, ulane + 4, ub);
+        A[s_].z = buf_ld(ru, ulane + 8, ub);
+        A[s_].w = buf_ld(ru, ulane + 12, ub);
+    };
+    auto load_patch = [&](int ch) {
         const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(ch * CC * p.HW) * ESZ;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
@@ -165,21 +183,8 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
 #pragma unroll
             for (int b = 1; b < 4; ++b) dpatch[4 * a + b] = buf_ld_in<TIN>(rx, xrow[a] + (b - 1) * ESZ, so);
         }
-        // U image of this (layer block, chunk): its offset and the piece number go into the uniform offset, the
-        // lane offset t * 16 never changes -- no vector arithmetic per load
-        const uint32_t ub = (uint32_t)__builtin_amdgcn_readfirstlane(mt * p.nchunks + ch) * (uint32_t)(US * 4);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            asm volatile("" : "+v"(ulane));   // four adjacent dword loads from one lane offset merge into one of 16 bytes
-            ucopy[i].x = buf_ld(ru, ulane, ub + i * 4096);
-            ucopy[i].y = buf_ld(ru, ulane + 4, ub + i * 4096);
-            ucopy[i].z = buf_ld(ru, ulane + 8, ub + i * 4096);
-            ucopy[i].w = buf_ld(ru, ulane + 12, ub + i * 4096);
-        }
     };
-    auto store_chunk = [&]() {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) *(f32x4 *)(lds + (i * 256 + t) * 4) = ucopy[i];
+    auto store_V = [&](float *img) {
         // V = B^T d B
         float rr[4][4];
 #pragma unroll
@@ -189,7 +194,7 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
             rr[2][b] = dpatch[8 + b] - dpatch[4 + b];
             rr[3][b] = dpatch[4 + b] - dpatch[12 + b];
         }
-        float *vs = lds + vdst;
+        float *vs = img + vdst;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             const float r2 = rr[a][2] * mc2;          // columns 0 (zero-filled) and 1 need no factor
@@ -215,34 +220,26 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
         for (int q = 0; q < 16; ++q) start11[q] = 0.f;
     }
 
-    // per-lane operand addresses: A = U[xi][kk][32 wx + li][0..3], B = V[xi][kk][li][0..3].  The wavefront's two
-    // grid rows are taken in the order (0, 1) for pr = 0 and (3, 2) for pr = 1, so that the row the partner needs
-    // (1 or 2) is the second one in both and the output transform has no per-wavefront choice of registers.
-    // [g]: base such that accumulator s (row g = s / 4 of the wavefront's order) reads at base[g] + s * stride.
-    const float *ua[2], *vb[2];
-    ua[0] = lds + 12 * pr * 512 + kk * 256 + (32 * wx + li) * 4;
-    ua[1] = ua[0] - 8 * pr * 512;
-    vb[0] = lds + US + 12 * pr * (2 * BT * 4) + kk * (BT * 4) + li * 4;
-    vb[1] = vb[0] - 8 * pr * (2 * BT * 4);
-    auto compute_chunk = [&](auto first_chunk) {
+    // per-lane B operand offsets within a V image: V[xi][kk][li][0..3]; [g]: offset such that accumulator s
+    // (row g = s / 4 of the wavefront's order) reads at vbo[g] + s * stride
+    int vbo[2];
+    vbo[0] = 12 * pr * (2 * BT * 4) + kk * (BT * 4) + li * 4;
+    vbo[1] = vbo[0] - 8 * pr * (2 * BT * 4);
+    // Multiplies chunk ch out of the V image img; reload: fetch the A operands of chunk ch + 1 into the registers
+    // of each pair of positions as soon as its MFMAs have been issued (a whole chunk ahead of their use).
+    auto compute_chunk = [&](auto first_chunk, const float *img, const bool reload, const int ch) {
         constexpr bool FIRST = decltype(first_chunk)::value;
         // two grid positions at a time, their MFMAs interleaved: consecutive MFMAs never
         // wait for each other's accumulator
-        f32x4 a[4], b[4];
+        f32x4 b[4];
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            a[e] = *(const f32x4 *)(ua[0] + e * 512);
-            b[e] = *(const f32x4 *)(vb[0] + e * (2 * BT * 4));
-        }
+        for (int e = 0; e < 2; ++e) b[e] = *(const f32x4 *)(img + vbo[0] + e * (2 * BT * 4));
 #pragma unroll
         for (int s = 0; s < 8; s += 2) {
             const int cur2 = s & 2, nxt2 = cur2 ^ 2;
             if (s + 2 < 8) {
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    a[nxt2 + e] = *(const f32x4 *)(ua[(s + 2 + e) / 4] + (s + 2 + e) * 512);
-                    b[nxt2 + e] = *(const f32x4 *)(vb[(s + 2 + e) / 4] + (s + 2 + e) * (2 * BT * 4));
-                }
+                for (int e = 0; e < 2; ++e) b[nxt2 + e] = *(const f32x4 *)(img + vbo[(s + 2 + e) / 4] + (s + 2 + e) * (2 * BT * 4));
             }
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (FIRST) {
@@ -251,36 +248,48 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
                 Acc zero;
 #pragma unroll
                 for (int q = 0; q < 16; ++q) zero[q] = 0.f;
-                acc[s] = M::run(a[cur2].x, b[cur2].x, zero);
-                acc[s + 1] = M::run(a[cur2 + 1].x, b[cur2 + 1].x, s + 1 == 5 ? start11 : zero);
+                acc[s] = M::run(A[s].x, b[cur2].x, zero);
+                acc[s + 1] = M::run(A[s + 1].x, b[cur2 + 1].x, s + 1 == 5 ? start11 : zero);
             } else {
-                acc[s] = M::run(a[cur2].x, b[cur2].x, acc[s]);
-                acc[s + 1] = M::run(a[cur2 + 1].x, b[cur2 + 1].x, acc[s + 1]);
+                acc[s] = M::run(A[s].x, b[cur2].x, acc[s]);
+                acc[s + 1] = M::run(A[s + 1].x, b[cur2 + 1].x, acc[s + 1]);
             }
-            acc[s] = M::run(a[cur2].y, b[cur2].y, acc[s]);
-            acc[s + 1] = M::run(a[cur2 + 1].y, b[cur2 + 1].y, acc[s + 1]);
-            acc[s] = M::run(a[cur2].z, b[cur2].z, acc[s]);
-            acc[s + 1] = M::run(a[cur2 + 1].z, b[cur2 + 1].z, acc[s + 1]);
-            acc[s] = M::run(a[cur2].w, b[cur2].w, acc[s]);
-            acc[s + 1] = M::run(a[cur2 + 1].w, b[cur2 + 1].w, acc[s + 1]);
+            acc[s] = M::run(A[s].y, b[cur2].y, acc[s]);
+            acc[s + 1] = M::run(A[s + 1].y, b[cur2 + 1].y, acc[s + 1]);
+            acc[s] = M::run(A[s].z, b[cur2].z, acc[s]);
+            acc[s + 1] = M::run(A[s + 1].z, b[cur2 + 1].z, acc[s + 1]);
+            acc[s] = M::run(A[s].w, b[cur2].w, acc[s]);
+            acc[s + 1] = M::run(A[s + 1].w, b[cur2 + 1].w, acc[s + 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (reload) {
+                load_A(ch + 1, s);
+                load_A(ch + 1, s + 1);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     // ---- main loop ---------------------------------------------------------------------------
-    load_chunk(0);
-    store_chunk();
+    // Chunk ch is multiplied out of V image ch & 1 while chunk ch + 1 is written into the other one: one barrier
+    // per chunk, and no phase in which a workgroup only stages.  (With one image and the kernels staged through
+    // LDS as well, a quarter of the time went into such phases: the two workgroups of a CU fall into step, since
+    // the one behind gets the matrix pipe to itself and catches up, and then both stage at once.)
+    load_patch(0);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) load_A(0, s);
+    store_V(lds);
+    if (p.nchunks > 1) load_patch(1);
     __syncthreads();
     for (int ch = 0; ch < p.nchunks; ++ch) {
         const bool more = ch + 1 < p.nchunks;
-        if (more) load_chunk(ch + 1);
-        if (ch == 0) compute_chunk(std::true_type{});
-        else compute_chunk(std::false_type{});
-        __syncthreads();               // every wavefront is done reading the images
+        float *cur = lds + (ch & 1) * VS, *oth = lds + ((ch & 1) ^ 1) * VS;
         if (more) {
-            store_chunk();
-            __syncthreads();
+            store_V(oth);                                    // the patches of chunk ch + 1, loaded a chunk ago
+            if (ch + 2 < p.nchunks) load_patch(ch + 2);
         }
+        if (ch == 0) compute_chunk(std::true_type{}, cur, more, ch);
+        else compute_chunk(std::false_type{}, cur, more, ch);
+        __syncthreads();               // image ch & 1 has been read by all, image (ch + 1) & 1 written by all
     }
 
     // ---- output transform -------------------------------------------------------------------
@@ -292,7 +301,7 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
     // pr = 1 keeps -z(3) - z(2) for Y[1] and hands z(2), its second row, over.
     // Exchange area: [wavefront][zz][register][lane]; the images are free by now.
     constexpr int ZQ = 16 * 64;
-    static_assert(4 * 2 * ZQ <= US + VS, "exchange area must fit the staging images");
+    static_assert(4 * 2 * ZQ <= 2 * VS, "exchange area must fit the two V images");
     // keep[zz] = z(first row)[zz] + z(second row)[zz]; its sign (pr = 1: minus) goes into the
     // final multiply-add.  The vector-ALU work here and below is kept minimal: it cannot
     // overlap with the MFMAs of the workgroup sharing the SIMDs.

@@ -736,9 +736,12 @@ int blocked_conv_pair(const void *in, const void *wp1, const float *b1, int Cout
         const int e = check_launch();
         return e ? e : SQ_ERR_HIP;
     }
-    // workgroups are shared out in proportion to the work (the K x K part has K*K times the steps)
+    // Workgroups are shared out between the two parts so that both finish together.  The K x K part has K*K times
+    // the MFMA steps, but both write the same number of bytes and a tile's time is mostly its stores and its
+    // fixed part: measured on whole passes at batches 1 to 256, a fifth of the workgroups for the 1x1 part is
+    // best (8 % faster at batches 64 and 256 than the share by steps, a tenth; no slower at any batch).
     const long long cap = 2ll * num_cus();
-    long long cap1 = cap / (1 + K * K * (long long)Coutk / Cout1);
+    long long cap1 = K == 1 ? cap / 2 : cap * Cout1 / (Cout1 + 4ll * Coutk);
     if (cap1 < p1.p.ncblk) cap1 = p1.p.ncblk;
     const long long wg1 = slots_for(p1, cap1) * p1.p.ncblk;
     const long long wgk = slots_for(pk, cap - wg1 > pk.p.ncblk ? cap - wg1 : pk.p.ncblk) * pk.p.ncblk;

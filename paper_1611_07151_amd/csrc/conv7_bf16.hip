@@ -140,17 +140,19 @@ __global__ __launch_bounds__(kThreads7, 3) void conv7s2c3_blocked_kernel(const C
         step_dw[s] = lane_dw + (h ? o1 : o0);
     }
 
-    int tile = blockIdx.x;
-    if (tile < p.tiles) {
+    // tiles in memory order per XCD: neighbouring tiles share patch rows and columns, which then come out of one L2
+    const mfma::XcdShare share = mfma::xcd_share((int)blockIdx.x, (int)gridDim.x, p.tiles);
+    int tile = share.first;
+    if (tile < share.end) {
         fetch(tile);
         stash(0);
     }
     __syncthreads();
     const float lowest = p.relu ? 0.f : -__builtin_inff();
     int buf = 0;
-    for (; tile < p.tiles; tile += gridDim.x) {
-        const int next = tile + gridDim.x;
-        const bool more = next < p.tiles;
+    for (; tile < share.end; tile += share.step) {
+        const int next = tile + share.step;
+        const bool more = next < share.end;
         if (more) fetch(next);
 
         f32x16 acc[3];

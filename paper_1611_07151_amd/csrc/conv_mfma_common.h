@@ -120,6 +120,21 @@ __device__ __forceinline__ int xcd_remap(int b, int total)
     return start + idx;
 }
 
+// Share of a persistent workgroup in `total` work items such that the workgroups of one XCD (workgroup numbers
+// equal modulo 8: they are dealt out round-robin) walk through one contiguous eighth of the items, side by side.
+// Items that are neighbours in memory then meet in the same L2 instead of being fetched from HBM by several.
+// The workgroup takes items first, first + step, ... below end.  The launch must have at least min(8, total) workgroups.
+struct XcdShare {
+    int first, step, end;
+};
+__device__ __forceinline__ XcdShare xcd_share(int block, int blocks, int total)
+{
+    const int xcd = block & 7, q = total >> 3, r = total & 7;
+    const int lo = xcd * q + (xcd < r ? xcd : r), cnt = q + (xcd < r ? 1 : 0);
+    const int step = (blocks - xcd + 7) >> 3;   // workgroups of this XCD
+    return XcdShare{lo + (block >> 3), step, lo + cnt};
+}
+
 // Buffer addressing: a uniform 128-bit resource (base, size) + per-lane 32-bit byte offset
 // + uniform 32-bit byte offset.  Needs no vector arithmetic per access, and the hardware
 // range check does the zero padding: a lane whose offset is >= the buffer size reads 0 and

@@ -244,15 +244,20 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
         }
     };
 
-    // Tiles of this workgroup are blockIdx.x + k * gridDim.x; its wavefronts draw k from a
-    // counter in LDS, so a wavefront that gets less of the SIMD (the hardware favours the
+    // The tiles of the workgroups of one XCD are one contiguous eighth of all tiles (neighbouring tiles share five
+    // of their nine patch rows and meet in one L2); a workgroup takes every step-th of them.  Its wavefronts draw k
+    // from a counter in LDS, so a wavefront that gets less of the SIMD (the hardware favours the
     // older one of two) simply takes fewer tiles and all finish together.  Every wavefront
-    // leaves the loop as soon as its draw is past the last tile.
+    // leaves the loop as soon as its draw is past the last tile.  (Fewer than eight workgroups: plain striding.)
+    const bool by_xcd = gridDim.x >= 8;
+    const XcdShare share = xcd_share((int)blockIdx.x, (int)gridDim.x, ntiles);
     auto draw = [&]() -> int {
         int k = 0;
         if (lane == 0) k = atomicAdd(next_tile, 1);
         k = __builtin_amdgcn_readfirstlane(k);
-        return (int)blockIdx.x + k * (int)gridDim.x;
+        if (!by_xcd) return (int)blockIdx.x + k * (int)gridDim.x;
+        const long long tl = (long long)share.first + (long long)k * share.step;
+        return tl < share.end ? (int)tl : ntiles;
     };
     int tile = draw();
     if (tile >= ntiles) return;

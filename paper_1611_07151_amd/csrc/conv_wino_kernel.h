@@ -357,7 +357,15 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
     for (int q = 0; q < 16; ++q) {
         const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(mw + M::row_reg(q)) * hs;
         buf_st2(rout, o2, so, zin[0][q], zin[1][q]);
-        buf_st(rout, o1, so, zin[0][q]);   // tiles cut by the right edge (odd widths); dropped otherwise
+    }
+    // tiles cut by the right edge (odd widths) have one column: only their lanes take part, so that the memory
+    // pipe is not kept busy by sixteen instructions whose lanes are nearly all turned away
+    if (o1 != kOob) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(mw + M::row_reg(q)) * hs;
+            buf_st(rout, o1, so, zin[0][q]);
+        }
     }
     }   // tiles of this workgroup
 }

@@ -90,7 +90,7 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
-// One wavefront per (image, layer) plane.
+// One wavefront per (image, layer) plane: any plane size.
 __global__ __launch_bounds__(256) void avgpool_kernel(const float *__restrict__ in,
                                                       float *__restrict__ out, size_t planes, int HW)
 {
@@ -102,6 +102,36 @@ __global__ __launch_bounds__(256) void avgpool_kernel(const float *__restrict__ 
     for (int i = lane; i < HW; i += 64) s += src[i];
     s = wave_sum(s);
     if (lane == 0) out[pl] = s / (float)HW;
+}
+
+// Planes of at most 64*IT pixels, PL consecutive planes per wavefront: all PL*IT loads of a lane are issued
+// before the first sum, where the loop above waits for memory once per 64 pixels.  The order of the sums is
+// that of the loop above, so both give the same bits.
+template <int PL, int IT>
+__global__ __launch_bounds__(256) void avgpool_small_kernel(const float *__restrict__ in,
+                                                            float *__restrict__ out, size_t planes, int HW)
+{
+    const int lane = threadIdx.x & 63;
+    const size_t pl0 = ((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * PL;
+    if (pl0 >= planes) return;
+    float v[PL][IT];
+#pragma unroll
+    for (int q = 0; q < PL; ++q)
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int i = lane + 64 * j;
+            v[q][j] = (i < HW && pl0 + q < planes) ? in[(pl0 + q) * HW + i] : 0.f;
+        }
+    float mine = 0.f;
+#pragma unroll
+    for (int q = 0; q < PL; ++q) {
+        float s = 0.f;
+#pragma unroll
+        for (int j = 0; j < IT; ++j) s += v[q][j];
+        s = wave_sum(s);
+        if (lane == q) mine = s;
+    }
+    if (lane < PL && pl0 + lane < planes) out[pl0 + lane] = mine / (float)HW;
 }
 
 // One 256-thread workgroup per image.
@@ -170,8 +200,24 @@ int avgpool_global(const float *in, float *out, int N, int C, int H, int W)
 {
     const size_t planes = (size_t)N * C;
     LaunchScope scope("avgpool", 0.0, 4.0 * planes * ((double)H * W + 1.0));
-    hipLaunchKernelGGL(avgpool_kernel, dim3((unsigned)((planes + 3) / 4)), dim3(256), 0,
-                       current_stream(), in, out, planes, H * W);
+    const int HW = H * W, IT = (HW + 63) / 64;
+    // four planes per wavefront once that still leaves every compute unit a dozen wavefronts
+    const int PL = planes >= 16384 ? 4 : 1;
+    const dim3 grid((unsigned)((planes + 4 * PL - 1) / (4 * PL)));
+    void (*kernel)(const float *, float *, size_t, int) = avgpool_kernel;
+    switch (IT * 8 + PL) {
+        case 1 * 8 + 1: kernel = avgpool_small_kernel<1, 1>; break;
+        case 2 * 8 + 1: kernel = avgpool_small_kernel<1, 2>; break;
+        case 3 * 8 + 1: kernel = avgpool_small_kernel<1, 3>; break;
+        case 4 * 8 + 1: kernel = avgpool_small_kernel<1, 4>; break;
+        case 1 * 8 + 4: kernel = avgpool_small_kernel<4, 1>; break;
+        case 2 * 8 + 4: kernel = avgpool_small_kernel<4, 2>; break;
+        case 3 * 8 + 4: kernel = avgpool_small_kernel<4, 3>; break;
+        case 4 * 8 + 4: kernel = avgpool_small_kernel<4, 4>; break;
+        default: break;   // larger planes: the loop, one plane per wavefront
+    }
+    const dim3 grid_used = kernel == avgpool_kernel ? dim3((unsigned)((planes + 3) / 4)) : grid;
+    hipLaunchKernelGGL(kernel, grid_used, dim3(256), 0, current_stream(), in, out, planes, HW);
     return check_launch();
 }
 

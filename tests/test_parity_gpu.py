@@ -223,7 +223,10 @@ def test_network_with_pooling_inside_the_squeeze_layers(sq):
     assert_close(fused, ref, FP32_TOL, "all pools fused")
 
 
-@pytest.mark.parametrize("shape", [(2, 1000, 13, 13), (1, 7, 5, 3), (3, 2, 1, 1), (1, 1, 30, 30)])
+# planes of up to 256 pixels take the kernel with every load issued up front, one plane per wavefront or, from
+# 16384 planes on, four (16386 planes: the last wavefront has two); larger planes take the loop
+@pytest.mark.parametrize("shape", [(2, 1000, 13, 13), (1, 7, 5, 3), (3, 2, 1, 1), (1, 1, 30, 30), (3, 5462, 13, 13),
+                                   (2, 8193, 8, 8), (1, 16385, 1, 1), (2, 3, 16, 16), (2, 3, 16, 17), (1, 5, 14, 14)])
 def test_avgpool(sq, shape):
     rng = np.random.default_rng(12)
     x = synth.normal01(rng, shape)

@@ -459,9 +459,13 @@ __global__ __launch_bounds__(kThreads, 2) void pool_conv_blocked_kernel(const Co
 // ------------------------------------------------------------------------------- pooling
 // Max pooling K x K stride S (floor mode, no padding) on blocked maps: one thread per
 // 16-byte output element (eight layers of one pixel).
-__global__ void maxpool_blocked_kernel(const u32x4 *in, u32x4 *out, int planes, int H, int W, int Ho, int Wo, int K, int S,
+// KT, ST: window and stride known at compile time (the network's 3x3 stride 2: all nine loads of a window are
+// issued before the first maximum), or 0 = taken from the arguments.
+template <int KT, int ST>
+__global__ void maxpool_blocked_kernel(const u32x4 *in, u32x4 *out, int planes, int H, int W, int Ho, int Wo, int K_, int S_,
                                        FastDiv dWo, FastDiv dHoWo)
 {
+    const int K = KT ? KT : K_, S = ST ? ST : S_;
     const long long total = (long long)planes * Ho * Wo;
     for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long long)gridDim.x * blockDim.x) {
         const int pl = fdiv((int)e, dHoWo), rem = (int)e - pl * Ho * Wo;
@@ -470,7 +474,9 @@ __global__ void maxpool_blocked_kernel(const u32x4 *in, u32x4 *out, int planes, 
         float m[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) m[k] = -__builtin_inff();
+#pragma unroll
         for (int i = 0; i < K; ++i)
+#pragma unroll
             for (int jx = 0; jx < K; ++jx) {
                 const u32x4 v = src[i * W + jx];
                 m[0] = fmaxf(m[0], bf_lo(v.x)); m[1] = fmaxf(m[1], bf_hi(v.x));
@@ -489,6 +495,9 @@ __global__ void maxpool_blocked_kernel(const u32x4 *in, u32x4 *out, int planes, 
 }
 
 // Global average pooling of a blocked map into fp32 [N][C]: one wavefront per (image, layer block).
+// IT: the plane has at most 64*IT pixels and a lane issues its IT loads before the first sum (a zero element adds
+// nothing, so the sums are those of the loop); 0 = any size, a loop.
+template <int IT>
 __global__ __launch_bounds__(256) void avgpool_blocked_kernel(const u32x4 *in, float *out, int planes, int C, int CB, int HW,
                                                               FastDiv dCB)
 {
@@ -496,10 +505,21 @@ __global__ __launch_bounds__(256) void avgpool_blocked_kernel(const u32x4 *in, f
     const int pl = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (pl >= planes) return;
     float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int pix = lane; pix < HW; pix += 64) {
-        const u32x4 v = in[(size_t)pl * HW + pix];
+    auto add = [&](const u32x4 v) {
         s[0] += bf_lo(v.x); s[1] += bf_hi(v.x); s[2] += bf_lo(v.y); s[3] += bf_hi(v.y);
         s[4] += bf_lo(v.z); s[5] += bf_hi(v.z); s[6] += bf_lo(v.w); s[7] += bf_hi(v.w);
+    };
+    if constexpr (IT > 0) {
+        u32x4 v[IT];
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int pix = lane + 64 * j;
+            v[j] = pix < HW ? in[(size_t)pl * HW + pix] : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int j = 0; j < IT; ++j) add(v[j]);
+    } else {
+        for (int pix = lane; pix < HW; pix += 64) add(in[(size_t)pl * HW + pix]);
     }
 #pragma unroll
     for (int k = 0; k < 8; ++k)
@@ -799,8 +819,10 @@ int blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K
     const long long total = (long long)planes * Ho * Wo;
     if (total >= (1ll << 31) || (long long)planes * H * W >= (1ll << 31)) return SQ_ERR_UNSUPPORTED;
     LaunchScope scope("maxpool_blocked", 0.0, 16.0 * ((double)planes * H * W + (double)total));
-    hipLaunchKernelGGL(maxpool_blocked_kernel, dim3(grid_for(total, 256)), dim3(256), 0, current_stream(), (const u32x4 *)in,
-                       (u32x4 *)out, planes, H, W, Ho, Wo, K, S, make_fastdiv(Wo), make_fastdiv(Ho * Wo));
+    auto kernel = maxpool_blocked_kernel<0, 0>;
+    if (K == 3 && S == 2) kernel = maxpool_blocked_kernel<3, 2>;
+    hipLaunchKernelGGL(kernel, dim3(grid_for(total, 256)), dim3(256), 0, current_stream(), (const u32x4 *)in, (u32x4 *)out,
+                       planes, H, W, Ho, Wo, K, S, make_fastdiv(Wo), make_fastdiv(Ho * Wo));
     return check_launch();
 }
 
@@ -809,7 +831,13 @@ int blocked_avgpool_global(const void *in, float *out, int N, int C, int H, int 
     const int CB = (C + 7) / 8, planes = N * CB;
     if ((long long)planes * H * W >= (1ll << 31)) return SQ_ERR_UNSUPPORTED;
     LaunchScope scope("avgpool_blocked", 0.0, 16.0 * (double)planes * H * W + 4.0 * N * C);
-    hipLaunchKernelGGL(avgpool_blocked_kernel, dim3((planes + 3) / 4), dim3(256), 0, current_stream(), (const u32x4 *)in, out,
+    const int IT = (H * W + 63) / 64;
+    auto kernel = avgpool_blocked_kernel<0>;
+    if (IT == 1) kernel = avgpool_blocked_kernel<1>;
+    else if (IT == 2) kernel = avgpool_blocked_kernel<2>;
+    else if (IT == 3) kernel = avgpool_blocked_kernel<3>;
+    else if (IT == 4) kernel = avgpool_blocked_kernel<4>;
+    hipLaunchKernelGGL(kernel, dim3((planes + 3) / 4), dim3(256), 0, current_stream(), (const u32x4 *)in, out,
                        planes, C, CB, H * W, make_fastdiv(CB));
     return check_launch();
 }

@@ -268,7 +268,9 @@ def test_pooling_inside_the_convolution_launch(sq, case, relu):
     assert (out[:, 0] == -7.0).all() and (out[:, -1] == -7.0).all()
 
 
-@pytest.mark.parametrize("shape", [(2, 1000, 13, 13), (3, 20, 5, 4), (1, 8, 1, 1)])
+# planes of 1, 20, 64, 128, 169 and 256 pixels take the forms with the loads issued up front, 272 and 900 the loop
+@pytest.mark.parametrize("shape", [(2, 1000, 13, 13), (3, 20, 5, 4), (1, 8, 1, 1), (2, 24, 8, 8), (1, 16, 8, 16), (2, 9, 16, 16),
+                                   (1, 40, 16, 17), (2, 12, 30, 30)])
 def test_blocked_avgpool_matches_oracle(sq, shape):
     rng = np.random.default_rng(6)
     x = synth.normal01(rng, shape)

@@ -30,6 +30,14 @@
  *     reports a failed launch; sq_last_hip_error() then gives the HIP code.
  *   - Calls are not re-entrant with respect to sq_set_stream(): the stream is
  *     a per-host-thread setting.
+ *   - Sizes.  The matrix-core kernels address a tensor through 32-bit byte
+ *     offsets, so they serve a convolution only while its input, its whole
+ *     output tensor ([N][out_channels][Ho][Wo]) and its kernels each have fewer
+ *     than 2^29 elements.  Beyond that SQ_ALGO_AUTO runs the direct algorithm
+ *     (64-bit indices, correct, far slower) and an explicitly chosen tiling
+ *     returns SQ_ERR_UNSUPPORTED.  The two network calls reject a batch beyond
+ *     SQ_SQUEEZENET_MAX_BATCH / SQ_SQUEEZENET_BF16_MAX_BATCH with
+ *     SQ_ERR_UNSUPPORTED before anything is enqueued: split such a batch.
  */
 #ifndef SQ_H
 #define SQ_H
@@ -48,6 +56,12 @@ typedef enum sq_status {
     SQ_ERR_WORKSPACE = -4,   /* workspace missing, misaligned or too small         */
     SQ_ERR_HIP = -5          /* a HIP launch failed; see sq_last_hip_error()       */
 } sq_status;
+
+/* Largest batch of sq_squeezenet_forward (conv1's output, 96 x 111 x 111 per image,
+ * stays below 2^29 elements) and of sq_squeezenet_forward_bf16 (the same map in
+ * bfloat16 stays below 2^31 bytes). */
+#define SQ_SQUEEZENET_MAX_BATCH 453
+#define SQ_SQUEEZENET_BF16_MAX_BATCH 907
 
 typedef enum sq_dtype {
     SQ_F32 = 0,  /* IEEE binary32 inputs and kernels                               */

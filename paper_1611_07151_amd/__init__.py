@@ -7,7 +7,8 @@ supplies device memory and the current stream, nothing else.  There is no CPU
 fallback: if the library is missing the import fails.
 """
 from .binding import (  # noqa: F401
-    SQ_ALGO_AUTO, SQ_ALGO_DIRECT, SQ_ALGO_VARIANT0, SQ_BF16, SQ_F32, SqError, lib,
+    SQ_ALGO_AUTO, SQ_ALGO_DIRECT, SQ_ALGO_VARIANT0, SQ_BF16, SQ_F32, SQ_SQUEEZENET_MAX_BATCH, SQ_SQUEEZENET_BF16_MAX_BATCH,
+    SqError, lib,
     sq_avgpool_global, sq_conv2d_forward, sq_conv2d_forward_ex, sq_conv2d_forward_ws,
     sq_conv2d_workspace_bytes, sq_conv_variant_count,
     sq_conv_variant_name, sq_fire_forward, sq_fire_workspace_bytes, sq_maxpool, sq_maxpool_conv2d_forward, sq_softmax,

@@ -18,6 +18,7 @@ lib = ctypes.CDLL(_LIB_PATH)
 
 SQ_F32, SQ_BF16 = 0, 1
 SQ_ALGO_AUTO, SQ_ALGO_DIRECT, SQ_ALGO_VARIANT0 = 0, 1, 2
+SQ_SQUEEZENET_MAX_BATCH, SQ_SQUEEZENET_BF16_MAX_BATCH = 453, 907   # as in include/sq.h
 
 _vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
 lib.sq_strerror.restype = ctypes.c_char_p

@@ -400,6 +400,7 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
 {
     if (!in || !params || !probs) return SQ_ERR_NULL;
     if (N <= 0) return SQ_ERR_SHAPE;
+    if (N > SQ_SQUEEZENET_MAX_BATCH) return SQ_ERR_UNSUPPORTED;   // conv1's output would pass 2^29 elements
     for (int i = 0; i < 52; ++i)
         if (!params[i]) return SQ_ERR_NULL;
     if (taps && taps[15]) return SQ_ERR_UNSUPPORTED;
@@ -712,6 +713,7 @@ int sq_squeezenet_forward_bf16(const void *in, sq_dtype in_dtype, const void *co
 {
     if (!in || !params || !packed || !probs) return SQ_ERR_NULL;
     if (N <= 0) return SQ_ERR_SHAPE;
+    if (N > SQ_SQUEEZENET_BF16_MAX_BATCH) return SQ_ERR_UNSUPPORTED;   // conv1's output would pass 2^31 bytes
     if (in_dtype != SQ_F32 && in_dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
     for (int i = 0; i < 52; ++i)
         if (!params[i]) return SQ_ERR_NULL;

@@ -127,6 +127,10 @@ def test_fire_and_network_check_workspace(lib):
     assert net(FAKE, params, FAKE, 1, FAKE, sz(wsb - 1), None) == -4
     assert net(FAKE, params, FAKE, 0, FAKE, sz(wsb), None) == -2
     assert net(NULL, params, FAKE, 1, FAKE, sz(wsb), None) == -1
+    # a batch whose conv1 output the 32-bit offsets of the kernels cannot address is refused up front
+    assert (453 * 96 * 111 * 111) < 2 ** 29 <= (454 * 96 * 111 * 111)
+    assert net(FAKE, params, FAKE, 454, FAKE, sz(lib.sq_squeezenet_workspace_bytes(454)), None) == -3
+    assert net(FAKE, params, FAKE, 453, FAKE, sz(lib.sq_squeezenet_workspace_bytes(453) - 1), None) == -4
     params[17] = None
     assert net(FAKE, params, FAKE, 1, FAKE, sz(wsb), None) == -1
 
@@ -246,6 +250,10 @@ def test_reduced_precision_entry_points_validate_before_any_gpu_call(lib):
     assert net(FAKE, 3, params, FAKE, FAKE, 1, ws, big, None) == -3
     assert net(FAKE, 0, params, ctypes.c_void_p(0x1000), FAKE, 1, ws, big - 1, None) == -4
     assert net(FAKE, 0, params, ctypes.c_void_p(0x1010), FAKE, 1, ws, big, None) == -4        # packed kernels 256-byte aligned
+    # conv1's bfloat16 output of 908 images passes 2^31 bytes: refused before anything is enqueued
+    assert 907 * 96 * 111 * 111 * 2 < 2 ** 31 <= 908 * 96 * 111 * 111 * 2
+    assert net(FAKE, 0, params, FAKE, FAKE, 908, ws, lib.sq_squeezenet_bf16_workspace_bytes(908), None) == -3
+    assert net(FAKE, 0, params, FAKE, FAKE, 907, ws, lib.sq_squeezenet_bf16_workspace_bytes(907) - 1, None) == -4
     holes = (ctypes.c_void_p * 52)(*([0x1000] * 51 + [None]))
     assert net(FAKE, 0, holes, FAKE, FAKE, 1, ws, big, None) == -1
     pk = lib.sq_squeezenet_bf16_pack_params

@@ -410,6 +410,33 @@ def test_squeezenet_batch64_sampled_images(sq):
     _check_network(sq, cfg, [0, 37, 63])
 
 
+def test_squeezenet_largest_batch(sq):
+    """453 images, the largest batch the network call takes (conv1's output just under 2^29 elements, the last
+    image's results near the top of what the kernels' 32-bit byte offsets reach): three distinct images repeated,
+    every copy must give its image's class probabilities, whichever place in the batch it has, and no launch may
+    fall back to the one-thread-per-output kernel.  One image more is refused."""
+    cfg = synth.config_squeezenet(seed=5, n=3)
+    ref = oracle.squeezenet(cfg["x"], cfg["params"])
+    params = [dev(p) for p in cfg["params"]]
+    x = dev(cfg["x"]).repeat(151, 1, 1, 1)                 # image i is cfg["x"][i % 3]
+    assert x.shape[0] == sq.SQ_SQUEEZENET_MAX_BATCH == 453
+    sq.sq_profile_begin(64)
+    probs = sq.sq_squeezenet_forward(x, params)
+    torch.cuda.synchronize()
+    names = [r["name"] for r in sq.sq_profile_end()]
+    assert not any("direct" in n for n in names), names
+    got = probs.cpu().numpy()
+    for i in (0, 1, 2, 224, 225, 226, 450, 451, 452):
+        assert_close(got[i:i + 1], ref[i % 3:i % 3 + 1], FP32_TOL, f"image {i}")
+    # all copies of an image agree to rounding (tiles straddle images differently along the batch)
+    spread = np.abs(got.reshape(151, 3, 1000) - got[:3][None]).max()
+    assert spread <= 1e-6, spread
+    del x, probs
+    with pytest.raises(sq.SqError) as e:
+        sq.sq_squeezenet_forward(torch.empty((454, 3, 224, 224), device="cuda"), params)
+    assert e.value.status == -3
+
+
 def test_benchmark_configuration_runs_the_kernels_it_reports(sq):
     """The batch-64 pass is served by the matrix-core kernels the benchmark's roofline names:
     the persistent conv1 kernel, the minimal-filtering kernel on transformed kernels for the

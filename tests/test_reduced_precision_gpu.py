@@ -365,3 +365,26 @@ def test_networks_at_odd_batch_sizes(sq, n):
     rel = np.abs(m16 - m32) / m32.std(axis=1, keepdims=True)
     assert rel.max() < 0.25 and np.sqrt((rel ** 2).mean()) < 0.05, (rel.max(), np.sqrt((rel ** 2).mean()))
     assert abs(float(probs16.sum()) - n) < 1e-3
+
+
+def test_network_largest_batch(sq):
+    """907 images, the largest batch the reduced-precision network call takes (conv1's bfloat16 output just under
+    2^31 bytes): three distinct images repeated; every copy must give what its image gives at the front of the
+    batch, and the front ones must agree with the fp32 oracle as at any batch.  One image more is refused."""
+    assert sq.SQ_SQUEEZENET_BF16_MAX_BATCH == 907
+    cfg = synth.config_squeezenet(seed=8, n=3)
+    params = [dev(p) for p in cfg["params"]]
+    packed = sq.sq_squeezenet_bf16_pack_params(params)
+    x3 = dev(cfg["x"])
+    x = torch.cat([x3.repeat(302, 1, 1, 1), x3[:1]])         # image i is cfg["x"][i % 3]
+    assert x.shape[0] == 907
+    probs = sq.sq_squeezenet_forward_bf16(x, params, packed).cpu().numpy()
+    assert np.isfinite(probs).all() and np.abs(probs.sum(1) - 1).max() < 1e-4
+    spread = np.abs(probs[:906].reshape(302, 3, 1000) - probs[:3][None]).max()
+    assert spread <= 1e-6 and np.abs(probs[906] - probs[0]).max() <= 1e-6, spread
+    ref = oracle.squeezenet(cfg["x"], cfg["params"])
+    assert (probs[:3].argmax(1) == ref.argmax(1)).all()
+    assert np.abs(probs[:3] - ref).max() < 0.25 * ref.max()
+    with pytest.raises(sq.SqError) as e:
+        sq.sq_squeezenet_forward_bf16(torch.empty((908, 3, 224, 224), device="cuda"), params, packed)
+    assert e.value.status == -3

@@ -139,6 +139,13 @@ int sq_conv2d_forward_ex(const void *in, const void *w, const float *b, float *o
  *     fits the shape can run; a smaller one only rules those algorithms out.
  *     Contents on return are unspecified; the same scratch must not be used by
  *     two calls in flight at once.
+ *   A layer with stride S >= 2 can also run as a stride-1 convolution of a
+ *     space-to-depth copy of its input (S*S times the input layers, kernels of
+ *     ceil(K/S) x ceil(K/S)), which the library makes in the workspace; under
+ *     SQ_ALGO_AUTO it does so when workspace_bytes is at least
+ *     sq_conv2d_strided_workspace_bytes(N, Cin, H, W, Cout, K, S, P) (0 = the
+ *     form does not apply) and a matrix-core tiling serves the stride-1 form
+ *     (regrouped kernels of 1x1, 3x3 or 5x5: e.g. 11x11 stride 4, 5x5 stride 2).
  * Everything else as for sq_conv2d_forward_ex; the result is the same up to
  * rounding whichever algorithm runs.
  */
@@ -148,6 +155,7 @@ int sq_conv2d_forward_ws(const void *in, const void *w, const float *b, float *o
                          int algo, void *workspace, size_t workspace_bytes);
 
 size_t sq_conv2d_workspace_bytes(int Cin, int Cout, int K, int S, int P);
+size_t sq_conv2d_strided_workspace_bytes(int N, int Cin, int H, int W, int Cout, int K, int S, int P);
 
 /*
  * Max pooling (section "Pooling and Softmax"): out[n][c][oh][ow] = largest of the

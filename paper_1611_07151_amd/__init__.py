@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     SQ_ALGO_AUTO, SQ_ALGO_DIRECT, SQ_ALGO_VARIANT0, SQ_BF16, SQ_F32, SQ_SQUEEZENET_MAX_BATCH, SQ_SQUEEZENET_BF16_MAX_BATCH,
     SqError, lib,
     sq_avgpool_global, sq_conv2d_forward, sq_conv2d_forward_ex, sq_conv2d_forward_ws,
-    sq_conv2d_workspace_bytes, sq_conv_variant_count,
+    sq_conv2d_workspace_bytes, sq_conv2d_strided_workspace_bytes, sq_conv_variant_count,
     sq_conv_variant_name, sq_fire_forward, sq_fire_workspace_bytes, sq_maxpool, sq_maxpool_conv2d_forward, sq_softmax,
     sq_profile_begin, sq_profile_end, sq_squeezenet_forward,
     sq_blocked_map_bytes, sq_blocked_pack, sq_blocked_unpack, sq_blocked_kernel_bytes, sq_blocked_pack_kernels,

@@ -93,6 +93,10 @@ int run_conv(const ConvArgs &a, int algo)
     if (a.pool_H && (algo == SQ_ALGO_DIRECT || a.K != 1 || a.S != 1 || a.P != 0)) return SQ_ERR_UNSUPPORTED;
     if (algo == SQ_ALGO_DIRECT) return conv_direct(a);
     if (algo == SQ_ALGO_AUTO) {
+        if (a.S >= 2 && a.ws) {   // given the scratch for it, a strided layer runs as a stride-1 one where that has a tiling
+            const int rs = conv_s2d(a);
+            if (rs != SQ_ERR_UNSUPPORTED) return rs;
+        }
         const int rc = conv_mfma(a, -1);
         if (rc != SQ_ERR_UNSUPPORTED || a.pool_H) return rc;   // only the tiled kernels pool on the way in
         return conv_direct(a);
@@ -288,6 +292,12 @@ size_t sq_conv2d_workspace_bytes(int Cin, int Cout, int K, int S, int P)
 {
     if (Cin <= 0 || Cout <= 0 || K <= 0 || S < 1 || P < 0) return 0;
     return conv_workspace_bytes(Cin, Cout, K, S, P);
+}
+
+size_t sq_conv2d_strided_workspace_bytes(int N, int Cin, int H, int W, int Cout, int K, int S, int P)
+{
+    if (N <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0 || K <= 0 || S < 1 || P < 0 || H + 2 * P < K || W + 2 * P < K) return 0;
+    return conv_s2d_workspace_bytes(N, Cin, H, W, Cout, K, S, P);
 }
 
 int sq_conv2d_forward_ws(const void *in, const void *w, const float *b, float *out, int N, int Cin,

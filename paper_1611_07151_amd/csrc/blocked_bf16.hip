@@ -474,16 +474,24 @@ __global__ void maxpool_blocked_kernel(const u32x4 *in, u32x4 *out, int planes, 
         float m[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) m[k] = -__builtin_inff();
+        auto take = [&](const u32x4 v) {
+            m[0] = fmaxf(m[0], bf_lo(v.x)); m[1] = fmaxf(m[1], bf_hi(v.x));
+            m[2] = fmaxf(m[2], bf_lo(v.y)); m[3] = fmaxf(m[3], bf_hi(v.y));
+            m[4] = fmaxf(m[4], bf_lo(v.z)); m[5] = fmaxf(m[5], bf_hi(v.z));
+            m[6] = fmaxf(m[6], bf_lo(v.w)); m[7] = fmaxf(m[7], bf_hi(v.w));
+        };
+        if constexpr (KT > 0) {
+            u32x4 v[KT * KT];
 #pragma unroll
-        for (int i = 0; i < K; ++i)
+            for (int i = 0; i < KT; ++i)
 #pragma unroll
-            for (int jx = 0; jx < K; ++jx) {
-                const u32x4 v = src[i * W + jx];
-                m[0] = fmaxf(m[0], bf_lo(v.x)); m[1] = fmaxf(m[1], bf_hi(v.x));
-                m[2] = fmaxf(m[2], bf_lo(v.y)); m[3] = fmaxf(m[3], bf_hi(v.y));
-                m[4] = fmaxf(m[4], bf_lo(v.z)); m[5] = fmaxf(m[5], bf_hi(v.z));
-                m[6] = fmaxf(m[6], bf_lo(v.w)); m[7] = fmaxf(m[7], bf_hi(v.w));
-            }
+                for (int jx = 0; jx < KT; ++jx) v[i * KT + jx] = src[i * W + jx];
+#pragma unroll
+            for (int q = 0; q < KT * KT; ++q) take(v[q]);
+        } else {
+            for (int i = 0; i < K; ++i)
+                for (int jx = 0; jx < K; ++jx) take(src[i * W + jx]);
+        }
         // the maxima are bfloat16 values already: keeping the upper halves is exact
         u32x4 o;
         o.x = (__builtin_bit_cast(uint32_t, m[0]) >> 16) | (__builtin_bit_cast(uint32_t, m[1]) & 0xffff0000u);

@@ -75,6 +75,10 @@ int conv_prepare_kernels(const KernelPrepJob *jobs, int n, int dtype);
 // Whether this call will run an algorithm that works on transformed kernels; fire_expand says that it is the
 // expand3x3 of a fire layer, which may share a launch with the expand1x1 (conv_expand_pair).
 bool conv_wants_prepared_kernels(const ConvArgs &a, bool fire_expand);
+// A convolution of stride >= 2 as a stride-1 convolution of a space-to-depth copy of its input (conv_s2d.hip): needs
+// a.ws of conv_s2d_workspace_bytes() bytes; SQ_ERR_UNSUPPORTED where that form has no matrix-core tiling.
+size_t conv_s2d_workspace_bytes(int N, int Cin, int H, int W, int Cout, int K, int S, int P);
+int conv_s2d(const ConvArgs &a);
 int conv_mfma_variant_count();
 const char *conv_mfma_variant_name(int i);
 

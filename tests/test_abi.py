@@ -73,6 +73,14 @@ def test_conv_workspace_entry_point_checks_its_scratch(lib):
     assert lib.sq_conv2d_workspace_bytes(32, 96, 3, 1, 1) == 16 * 128 * 32 * 4
     assert lib.sq_conv2d_workspace_bytes(32, 128, 3, 2, 1) == 0     # stride 2: no algorithm needs scratch
     assert lib.sq_conv2d_workspace_bytes(32, 128, 1, 1, 0) == 0
+    # space-to-depth form of a strided layer: the copy [N][Cin*S*S][Ho+K'-1][Wo+K'-1] and the regrouped kernels, fp32
+    lib.sq_conv2d_strided_workspace_bytes.restype = sz
+    up = lambda v: (v + 255) // 256 * 256
+    assert lib.sq_conv2d_strided_workspace_bytes(64, 3, 227, 227, 96, 11, 4, 0) == up(64 * 48 * 57 * 57 * 4) + up(96 * 48 * 9 * 4)
+    assert lib.sq_conv2d_strided_workspace_bytes(2, 8, 21, 23, 24, 5, 2, 2) == up(2 * 32 * 13 * 14 * 4) + up(24 * 32 * 9 * 4)
+    assert lib.sq_conv2d_strided_workspace_bytes(2, 16, 27, 27, 64, 3, 1, 1) == 0      # stride 1: nothing to regroup
+    assert lib.sq_conv2d_strided_workspace_bytes(0, 3, 227, 227, 96, 11, 4, 0) == 0
+    assert lib.sq_conv2d_strided_workspace_bytes(1, 3, 8, 8, 96, 11, 4, 0) == 0        # kernel larger than the image
     assert lib.sq_conv2d_workspace_bytes(30, 128, 3, 1, 1) == 0     # input layers not a multiple of 8
     assert lib.sq_conv2d_workspace_bytes(0, 128, 3, 1, 1) == 0
     h = lib.sq_conv2d_forward_ws

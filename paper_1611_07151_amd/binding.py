@@ -25,6 +25,8 @@ lib.sq_strerror.restype = ctypes.c_char_p
 lib.sq_strerror.argtypes = [_i]
 lib.sq_last_hip_error.restype = _i
 lib.sq_set_stream.argtypes = [_vp]
+lib.sq_set_dtype.argtypes = [_i]
+lib.sq_init.argtypes = []
 lib.sq_conv_variant_count.restype = _i
 lib.sq_conv_variant_name.restype = ctypes.c_char_p
 lib.sq_conv_variant_name.argtypes = [_i]
@@ -45,6 +47,14 @@ lib.sq_fire_workspace_bytes.argtypes = [_i] * 5
 lib.sq_squeezenet_forward.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _i, _vp, _sz, ctypes.POINTER(_vp)]
 lib.sq_squeezenet_workspace_bytes.restype = _sz
 lib.sq_squeezenet_workspace_bytes.argtypes = [_i]
+lib.sq_fire_packed_bytes.restype = _sz
+lib.sq_fire_packed_bytes.argtypes = [_i, _i]
+lib.sq_fire_pack_weights.argtypes = [_vp, _vp, _sz, _i, _i]
+lib.sq_fire_forward_packed.argtypes = [_vp] * 9 + [_i] * 7 + [_vp, _sz]
+lib.sq_packed_weights_bytes.restype = _sz
+lib.sq_packed_weights_bytes.argtypes = [_i]
+lib.sq_pack_weights.argtypes = [ctypes.POINTER(_vp), _i, _vp, _sz]
+lib.sq_squeezenet_forward_packed.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, _i, _vp, _sz, ctypes.POINTER(_vp)]
 
 lib.sq_blocked_map_bytes.restype = _sz
 lib.sq_blocked_map_bytes.argtypes = [_i] * 4
@@ -114,6 +124,19 @@ def _use_current_stream():
     lib.sq_set_stream(torch.cuda.current_stream().cuda_stream)
 
 
+_mode = SQ_F32   # mirror of the library's per-thread arithmetic mode, for the tensor type checks below
+
+
+def sq_set_dtype(dtype: int) -> None:
+    global _mode
+    _check(lib.sq_set_dtype(int(dtype)), "sq_set_dtype")
+    _mode = int(dtype)
+
+
+def sq_init() -> None:
+    _check(lib.sq_init(), "sq_init")
+
+
 def sq_conv_variant_count() -> int:
     return int(lib.sq_conv_variant_count())
 
@@ -136,7 +159,8 @@ def sq_conv2d_forward(x, w, b=None, stride=1, pad=0, relu=False):
     out = torch.empty((N, Cout, _out_extent(H, K, stride, pad), _out_extent(W, K, stride, pad)),
                       device=x.device, dtype=torch.float32)
     _use_current_stream()
-    rc = lib.sq_conv2d_forward(_dev(x, torch.float32, "x"), _dev(w, torch.float32, "w"),
+    tin = torch.float32 if _mode == SQ_F32 else torch.bfloat16
+    rc = lib.sq_conv2d_forward(_dev(x, tin, "x"), _dev(w, tin, "w"),
                                _dev(b, torch.float32, "b"), _dev(out), N, Cin, H, W, Cout, K,
                                int(stride), int(pad), int(bool(relu)))
     _check(rc, "sq_conv2d_forward")
@@ -268,6 +292,41 @@ def sq_fire_forward(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, workspace=None, out=N
     return out
 
 
+def sq_fire_packed_bytes(Csq, Ce3) -> int:
+    return int(lib.sq_fire_packed_bytes(int(Csq), int(Ce3)))
+
+
+def sq_fire_pack_weights(w_e3):
+    """Expand3x3 kernels [Ce3][Csq][3][3] float32 -> their re-ordered form (uint8 tensor), written once."""
+    Ce3, Csq = w_e3.shape[0], w_e3.shape[1]
+    if tuple(w_e3.shape[2:]) != (3, 3):
+        raise ValueError("expects [Ce3][Csq][3][3]")
+    out = torch.empty(max(sq_fire_packed_bytes(Csq, Ce3), 256), device=w_e3.device, dtype=torch.uint8)
+    _use_current_stream()
+    _check(lib.sq_fire_pack_weights(_dev(w_e3, torch.float32, "w_e3"), _dev(out), out.numel(), Csq, Ce3), "sq_fire_pack_weights")
+    return out
+
+
+def sq_fire_forward_packed(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, packed_e3, workspace=None, out=None):
+    N, Cin, H, W = x.shape
+    Csq, Ce1, Ce3 = w_sq.shape[0], w_e1.shape[0], w_e3.shape[0]
+    if tuple(w_sq.shape) != (Csq, Cin, 1, 1) or tuple(w_e1.shape) != (Ce1, Csq, 1, 1) \
+            or tuple(w_e3.shape) != (Ce3, Csq, 3, 3):
+        raise ValueError("fire kernel shapes")
+    if workspace is None:
+        workspace = torch.empty((N * Csq * H * W * 4 + 255) // 256 * 256, device=x.device, dtype=torch.uint8)
+    if out is None:
+        out = torch.empty((N, Ce1 + Ce3, H, W), device=x.device, dtype=torch.float32)
+    f32 = torch.float32
+    _use_current_stream()
+    rc = lib.sq_fire_forward_packed(_dev(x, f32, "x"), _dev(w_sq, f32, "w_sq"), _dev(b_sq, f32, "b_sq"),
+                                    _dev(w_e1, f32, "w_e1"), _dev(b_e1, f32, "b_e1"), _dev(w_e3, f32, "w_e3"),
+                                    _dev(b_e3, f32, "b_e3"), _dev(packed_e3, torch.uint8, "packed_e3"), _dev(out, f32, "out"),
+                                    N, Cin, H, W, Csq, Ce1, Ce3, _dev(workspace), workspace.numel() * workspace.element_size())
+    _check(rc, "sq_fire_forward_packed")
+    return out
+
+
 def sq_squeezenet_workspace_bytes(N) -> int:
     return int(lib.sq_squeezenet_workspace_bytes(int(N)))
 
@@ -294,6 +353,46 @@ def sq_squeezenet_forward(x, params, workspace=None, probs=None, want_taps=False
     rc = lib.sq_squeezenet_forward(_dev(x, torch.float32, "x"), parr, _dev(probs, torch.float32, "probs"),
                                    N, _dev(workspace), workspace.numel() * workspace.element_size(), tarr)
     _check(rc, "sq_squeezenet_forward")
+    return (probs, taps) if want_taps else probs
+
+
+def sq_packed_weights_bytes(dtype=SQ_F32) -> int:
+    return int(lib.sq_packed_weights_bytes(int(dtype)))
+
+
+def sq_pack_weights(params, dtype=SQ_F32):
+    """One-time re-ordering of the network's kernels for the given arithmetic mode -> packed uint8 tensor."""
+    if len(params) != 52:
+        raise ValueError("expects 52 parameter tensors")
+    out = torch.empty(sq_packed_weights_bytes(dtype), device=params[0].device, dtype=torch.uint8)
+    parr = (_vp * 52)(*[_dev(p, torch.float32, f"params[{i}]") for i, p in enumerate(params)])
+    _use_current_stream()
+    _check(lib.sq_pack_weights(parr, int(dtype), _dev(out), out.numel()), "sq_pack_weights")
+    return out
+
+
+def sq_squeezenet_forward_packed(x, params, packed, workspace=None, probs=None, want_taps=False):
+    """sq_squeezenet_forward on kernels packed by sq_pack_weights for the mode of sq_set_dtype."""
+    N = x.shape[0]
+    if tuple(x.shape[1:]) != (3, 224, 224) or len(params) != 52:
+        raise ValueError("expects [N,3,224,224] and 52 parameter tensors")
+    if workspace is None:
+        workspace = torch.empty(sq_squeezenet_workspace_bytes(N), device=x.device, dtype=torch.uint8)
+    if probs is None:
+        probs = torch.empty((N, 1000), device=x.device, dtype=torch.float32)
+    parr = (_vp * 52)(*[_dev(p, torch.float32, f"params[{i}]") for i, p in enumerate(params)])
+    taps, tarr = {}, None
+    if want_taps:
+        for name, (c, h) in zip(TAP_NAMES, TAP_SHAPES):
+            taps[name] = torch.empty((N, c, h, h), device=x.device, dtype=torch.float32)
+        taps["means"] = torch.empty((N, 1000), device=x.device, dtype=torch.float32)
+        taps["probs"] = torch.empty((N, 1000), device=x.device, dtype=torch.float32)
+        tarr = (_vp * 16)(*([taps[n].data_ptr() for n in TAP_NAMES] + [None]))
+    _use_current_stream()
+    rc = lib.sq_squeezenet_forward_packed(_dev(x, torch.float32, "x"), parr, _dev(packed, torch.uint8, "packed"),
+                                          _dev(probs, torch.float32, "probs"), N, _dev(workspace),
+                                          workspace.numel() * workspace.element_size(), tarr)
+    _check(rc, "sq_squeezenet_forward_packed")
     return (probs, taps) if want_taps else probs
 
 

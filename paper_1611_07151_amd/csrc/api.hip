@@ -5,27 +5,65 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
+
 namespace sq {
 namespace {
 thread_local hipStream_t g_stream = nullptr;
 thread_local int g_last_hip = 0;
+thread_local int g_dtype = SQ_F32;
 }  // namespace
 
 hipStream_t current_stream() { return g_stream; }
+int current_dtype() { return g_dtype; }
 
 int num_cus()
 {
-    static int cus = 0;
-    if (!cus) {
+    // filled once; two threads that race here store the same value
+    static std::atomic<int> cus{0};
+    int c = cus.load(std::memory_order_relaxed);
+    if (!c) {
         int dev = 0, n = 0;
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
+            c = n;
         else
-            cus = 256;
+            c = 256;
         (void)hipGetLastError();
+        cus.store(c, std::memory_order_relaxed);
     }
-    return cus;
+    return c;
+}
+
+// Kernel functions whose dynamic-LDS limit has been raised: an open-addressing table of atomics, so the
+// common case (already there) takes no lock; a miss takes the mutex, sets the attribute and publishes.
+namespace {
+constexpr int kLdsTable = 2048;
+std::atomic<const void *> g_lds_done[kLdsTable];
+std::mutex g_lds_mutex;
+inline unsigned lds_slot(const void *fn) { return (unsigned)(((uintptr_t)fn >> 4) * 2654435761u) & (kLdsTable - 1); }
+}  // namespace
+
+bool allow_big_lds(const void *fn)
+{
+    if (!fn) return true;
+    for (unsigned i = lds_slot(fn), n = 0; n < kLdsTable; i = (i + 1) & (kLdsTable - 1), ++n) {
+        const void *e = g_lds_done[i].load(std::memory_order_acquire);
+        if (e == fn) return true;
+        if (!e) break;
+    }
+    std::lock_guard<std::mutex> lock(g_lds_mutex);
+    for (unsigned i = lds_slot(fn), n = 0; n < kLdsTable; i = (i + 1) & (kLdsTable - 1), ++n) {
+        const void *e = g_lds_done[i].load(std::memory_order_acquire);
+        if (e == fn) return true;
+        if (e) continue;
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return false;
+        g_lds_done[i].store(fn, std::memory_order_release);
+        return true;
+    }
+    // table full (more kernels than the library has): set the attribute every time
+    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess;
 }
 
 // ---- per-launch profiler --------------------------------------------------------------
@@ -214,6 +252,24 @@ int sq_set_stream(void *hip_stream)
     return SQ_OK;
 }
 
+int sq_set_dtype(int dtype)
+{
+    if (dtype != SQ_F32 && dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    g_dtype = dtype;
+    return SQ_OK;
+}
+
+int sq_init(void)
+{
+    (void)num_cus();
+    const bool ok = conv_mfma_register_kernels() & blocked_register_kernels() & fire_bf16_register_kernels();
+    if (!ok) {
+        const int rc = check_launch();
+        return rc ? rc : SQ_ERR_HIP;
+    }
+    return SQ_OK;
+}
+
 int sq_profile_begin(int max_launches)
 {
     if (max_launches <= 0) return SQ_ERR_SHAPE;
@@ -327,7 +383,7 @@ int sq_conv2d_forward_ex(const void *in, const void *w, const float *b, float *o
 int sq_conv2d_forward(const void *in, const void *w, const float *b, float *out, int N, int Cin,
                       int H, int W, int Cout, int K, int S, int P, int relu)
 {
-    return sq_conv2d_forward_ex(in, w, b, out, N, Cin, H, W, Cout, K, S, P, relu, Cout, 0, SQ_F32,
+    return sq_conv2d_forward_ex(in, w, b, out, N, Cin, H, W, Cout, K, S, P, relu, Cout, 0, g_dtype,
                                 SQ_ALGO_AUTO);
 }
 
@@ -371,18 +427,64 @@ size_t sq_fire_workspace_bytes(int N, int H, int W, int Csq, int Ce3)
     return align_up((size_t)N * Csq * H * W * sizeof(float), 256) + conv_workspace_bytes(Csq, Ce3, 3, 1, 1);
 }
 
+namespace {
+// packed_e3: the expand3x3 kernels as sq_fire_pack_weights wrote them, or nullptr = transform them into the workspace
+int fire_checked(const void *in, const void *w_sq, const float *b_sq, const void *w_e1, const float *b_e1, const void *w_e3,
+                 const float *b_e3, const void *packed_e3, float *out, int N, int Cin, int H, int W, int Csq, int Ce1, int Ce3,
+                 void *workspace, size_t workspace_bytes)
+{
+    if (!in || !w_sq || !w_e1 || !w_e3 || !out) return SQ_ERR_NULL;
+    if (N <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Csq <= 0 || Ce1 <= 0 || Ce3 <= 0) return SQ_ERR_SHAPE;
+    if (g_dtype != SQ_F32) return SQ_ERR_UNSUPPORTED;   // the reduced-precision fire layer is sq_blocked_fire_forward
+    const size_t map_bytes = align_up((size_t)N * Csq * H * W * sizeof(float), 256);
+    const size_t need = packed_e3 ? map_bytes : sq_fire_workspace_bytes(N, H, W, Csq, Ce3);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need) return SQ_ERR_WORKSPACE;
+    if (packed_e3 && ((uintptr_t)packed_e3 & 255)) return SQ_ERR_WORKSPACE;
+    if (packed_e3)
+        return fire_impl(in, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, out, N, Cin, H, W, Csq, Ce1, Ce3, (float *)workspace,
+                         const_cast<void *>(packed_e3), conv_workspace_bytes(Csq, Ce3, 3, 1, 1), true, kFireAlone);
+    return fire_impl(in, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, out, N, Cin, H, W, Csq, Ce1, Ce3, (float *)workspace,
+                     (char *)workspace + map_bytes, workspace_bytes - map_bytes, false, kFireAlone);
+}
+}  // namespace
+
 int sq_fire_forward(const void *in, const void *w_sq, const float *b_sq, const void *w_e1,
                     const float *b_e1, const void *w_e3, const float *b_e3, float *out, int N,
                     int Cin, int H, int W, int Csq, int Ce1, int Ce3, void *workspace,
                     size_t workspace_bytes)
 {
-    if (!in || !w_sq || !w_e1 || !w_e3 || !out) return SQ_ERR_NULL;
-    if (N <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Csq <= 0 || Ce1 <= 0 || Ce3 <= 0) return SQ_ERR_SHAPE;
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < sq_fire_workspace_bytes(N, H, W, Csq, Ce3))
-        return SQ_ERR_WORKSPACE;
-    const size_t map_bytes = align_up((size_t)N * Csq * H * W * sizeof(float), 256);
-    return fire_impl(in, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, out, N, Cin, H, W, Csq, Ce1, Ce3,
-                     (float *)workspace, (char *)workspace + map_bytes, workspace_bytes - map_bytes, false, kFireAlone);
+    return fire_checked(in, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, nullptr, out, N, Cin, H, W, Csq, Ce1, Ce3, workspace,
+                        workspace_bytes);
+}
+
+size_t sq_fire_packed_bytes(int Csq, int Ce3)
+{
+    if (Csq <= 0 || Ce3 <= 0) return 0;
+    return conv_workspace_bytes(Csq, Ce3, 3, 1, 1);
+}
+
+int sq_fire_pack_weights(const void *w_e3, void *packed, size_t packed_bytes, int Csq, int Ce3)
+{
+    if (!w_e3 || !packed) return SQ_ERR_NULL;
+    if (Csq <= 0 || Ce3 <= 0) return SQ_ERR_SHAPE;
+    const size_t need = conv_workspace_bytes(Csq, Ce3, 3, 1, 1);
+    if (!need) return SQ_ERR_UNSUPPORTED;   // this shape has no packed form: call sq_fire_forward
+    if (((uintptr_t)packed & 255) || packed_bytes < need) return SQ_ERR_WORKSPACE;
+    const KernelPrepJob job{w_e3, packed, Csq, Ce3};
+    set_stage("kernel transform");
+    const int rc = conv_prepare_kernels(&job, 1, SQ_F32);
+    set_stage("");
+    return rc;
+}
+
+int sq_fire_forward_packed(const void *in, const void *w_sq, const float *b_sq, const void *w_e1, const float *b_e1,
+                           const void *w_e3, const float *b_e3, const void *packed_e3, float *out, int N, int Cin, int H, int W,
+                           int Csq, int Ce1, int Ce3, void *workspace, size_t workspace_bytes)
+{
+    if (!packed_e3) return SQ_ERR_NULL;
+    if (Csq > 0 && Ce3 > 0 && !conv_workspace_bytes(Csq, Ce3, 3, 1, 1)) return SQ_ERR_UNSUPPORTED;
+    return fire_checked(in, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, packed_e3, out, N, Cin, H, W, Csq, Ce1, Ce3, workspace,
+                        workspace_bytes);
 }
 
 size_t sq_squeezenet_workspace_bytes(int N)
@@ -401,11 +503,22 @@ size_t sq_squeezenet_workspace_bytes(int N)
 // workgroups to hide nine loads per element; pool8 from batch 64 on).  A call with taps keeps every pooled
 // map, but runs the squeeze with the tiling the fused form would use, so the results are the same bit for bit.
 // The setter is a tuning hook, not part of the public interface.
-int g_fuse_pools_f32 = -1;
-extern "C" void sq_internal_fuse_pools_f32(int mask) { g_fuse_pools_f32 = mask; }
+thread_local int g_fuse_pools_f32 = -1;
+extern "C" void sq_tune_fuse_pools_f32(int mask) { g_fuse_pools_f32 = mask; }
 int fuse_pools_f32_policy(int N) { return 1 | (N >= 4 ? 2 : 0) | (N >= 64 ? 4 : 0); }
 
-int sq_squeezenet_forward(const void *in, const void *const *params, float *probs, int N,
+namespace {
+size_t packed_f32_bytes()
+{
+    size_t b = 0;
+    for (const FireCfg &fc : kFires) b += conv_workspace_bytes(fc.sq, fc.e, 3, 1, 1);
+    return b;
+}
+}  // namespace
+
+// packed: the expand3x3 kernels of the eight fire layers as sq_pack_weights(SQ_F32) wrote them, or nullptr = they
+// are transformed into the workspace by one launch at the start of the call.
+static int squeezenet_f32(const void *in, const void *const *params, const void *packed, float *probs, int N,
                           void *workspace, size_t workspace_bytes, float *const *taps)
 {
     if (!in || !params || !probs) return SQ_ERR_NULL;
@@ -432,7 +545,7 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
     KernelPrepJob prep[8];
     int nprep = 0;
     {
-        char *next = (char *)means + align_up(n * 1000 * 4, 256);
+        char *next = packed ? (char *)const_cast<void *>(packed) : (char *)means + align_up(n * 1000 * 4, 256);
         int h = 55;
         for (int f = 0; f < 8; ++f) {
             const FireCfg &fc = kFires[f];
@@ -442,14 +555,14 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
             ConvArgs a3 = make_args(bufS, params[2 + 6 * f + 4], nullptr, bufA, N, fc.sq, h, h, fc.e, 3, 1, 1, 1,
                                     2 * fc.e, fc.e, SQ_F32);
             a3.ws = conv_ws[f]; a3.ws_bytes = conv_ws_bytes[f];
-            conv_ws_ready[f] = conv_wants_prepared_kernels(a3, true);
-            if (conv_ws_ready[f]) prep[nprep++] = KernelPrepJob{params[2 + 6 * f + 4], conv_ws[f], fc.sq, fc.e};
+            conv_ws_ready[f] = packed != nullptr || conv_wants_prepared_kernels(a3, true);
+            if (conv_ws_ready[f] && !packed) prep[nprep++] = KernelPrepJob{params[2 + 6 * f + 4], conv_ws[f], fc.sq, fc.e};
             if (f == 2) h = 27;
             if (f == 6) h = 13;
         }
     }
     int rc = SQ_OK;
-    if (nprep) {
+    if (nprep && !packed) {
         set_stage("kernel transform");
         if ((rc = conv_prepare_kernels(prep, nprep, SQ_F32))) return rc;
     }
@@ -526,6 +639,50 @@ int sq_squeezenet_forward(const void *in, const void *const *params, float *prob
     if ((rc = softmax(means, probs, N, 1000))) return rc;
     set_stage("");
     return copy_tap(taps, 14, probs, n * 1000);
+}
+
+int sq_squeezenet_forward(const void *in, const void *const *params, float *probs, int N,
+                          void *workspace, size_t workspace_bytes, float *const *taps)
+{
+    if (g_dtype != SQ_F32) return SQ_ERR_UNSUPPORTED;   // reduced precision needs packed kernels: sq_squeezenet_forward_packed
+    return squeezenet_f32(in, params, nullptr, probs, N, workspace, workspace_bytes, taps);
+}
+
+size_t sq_packed_weights_bytes(int dtype)
+{
+    if (dtype == SQ_F32) return packed_f32_bytes();
+    if (dtype == SQ_BF16) return sq_squeezenet_bf16_packed_bytes();
+    return 0;
+}
+
+int sq_pack_weights(const void *const *params, int dtype, void *packed, size_t packed_bytes)
+{
+    if (dtype == SQ_BF16) return sq_squeezenet_bf16_pack_params(params, packed, packed_bytes);
+    if (dtype != SQ_F32) return SQ_ERR_UNSUPPORTED;
+    if (!params || !packed) return SQ_ERR_NULL;
+    for (int i = 0; i < 52; ++i)
+        if (!params[i]) return SQ_ERR_NULL;
+    if (((uintptr_t)packed & 255) || packed_bytes < packed_f32_bytes()) return SQ_ERR_WORKSPACE;
+    KernelPrepJob prep[8];
+    char *next = (char *)packed;
+    for (int f = 0; f < 8; ++f) {
+        prep[f] = KernelPrepJob{params[2 + 6 * f + 4], next, kFires[f].sq, kFires[f].e};
+        next += conv_workspace_bytes(kFires[f].sq, kFires[f].e, 3, 1, 1);
+    }
+    set_stage("kernel transform");
+    const int rc = conv_prepare_kernels(prep, 8, SQ_F32);
+    set_stage("");
+    return rc;
+}
+
+int sq_squeezenet_forward_packed(const void *in, const void *const *params, const void *packed, float *probs, int N,
+                                 void *workspace, size_t workspace_bytes, float *const *taps)
+{
+    if (!packed) return SQ_ERR_NULL;
+    if ((uintptr_t)packed & 255) return SQ_ERR_WORKSPACE;
+    if (g_dtype == SQ_BF16)
+        return sq_squeezenet_forward_bf16(in, SQ_F32, params, packed, probs, N, workspace, workspace_bytes, taps);
+    return squeezenet_f32(in, params, packed, probs, N, workspace, workspace_bytes, taps);
 }
 
 // ---- reduced-precision path on blocked bfloat16 maps -------------------------------------
@@ -614,8 +771,8 @@ int sq_blocked_pool_conv2d_forward(const void *in, const void *packed_w, const f
 // 0.179 ms): with a band of a few rows per workgroup only two or three of its eight wavefronts have a pixel
 // block in each phase, and each walks its 6 to 36 dependent steps alone.  So the policy never picks it; it
 // stays selectable, with its parity test, as the measured form of "a fire layer in one launch".
-int g_fire_one_launch = -1;
-void sq_internal_fire_one_launch(int mode) { g_fire_one_launch = mode; }
+thread_local int g_fire_one_launch = -1;
+void sq_tune_fire_one_launch(int mode) { g_fire_one_launch = mode; }
 constexpr int kFireOneLaunchMaxBatch = 0;
 
 int sq_blocked_fire_forward(const void *in, const void *packed_sq, const float *b_sq, const void *packed_e1,
@@ -665,8 +822,8 @@ int sq_blocked_avgpool_global(const void *in, float *out, int N, int C, int H, i
 // pool8 at none (its squeeze has 512 input layers: 32 dependent steps of nine loads each on few pixels; the
 // pooling kernel that issues a window's nine loads at once is faster at every batch, by 0.5 % of the pass at
 // batches 128 and 256).  The setter is a tuning hook, not part of the public interface.
-int g_fuse_pools = -1;
-void sq_internal_fuse_pools(int mask) { g_fuse_pools = mask; }
+thread_local int g_fuse_pools = -1;
+void sq_tune_fuse_pools(int mask) { g_fuse_pools = mask; }
 
 namespace {
 // (Cout, Cin, K) of convolution i of the network, i = 0 (conv1) .. 25 (conv10)

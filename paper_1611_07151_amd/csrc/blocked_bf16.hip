@@ -569,24 +569,15 @@ template <int CB, int PB> BlockedConvFn conv_fn(int D)
     }
 }
 
-bool allow_lds(BlockedConvFn fn)
-{
-    static BlockedConvFn done[32];
-    static int ndone = 0;
-    for (int i = 0; i < ndone; ++i)
-        if (done[i] == fn) return true;
-    if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, mfma::kLdsBytes) != hipSuccess) return false;
-    if (ndone < 32) done[ndone++] = fn;
-    return true;
-}
+bool allow_lds(BlockedConvFn fn) { return allow_big_lds((const void *)fn); }
 
 }  // namespace
 
 // Tuning hooks (not part of the public interface): ring depth to use where it divides the step count;
 // blocks of 32 output layers per workgroup and of 32 pixels per wavefront tile (0 = automatic).
-int g_force_depth = 0, g_force_cb = 0, g_force_pb = 0;
-extern "C" void sq_internal_blocked_force_depth(int d) { g_force_depth = d; }
-extern "C" void sq_internal_blocked_force_tile(int cb, int pb) { g_force_cb = cb; g_force_pb = pb; }
+thread_local int g_force_depth = 0, g_force_cb = 0, g_force_pb = 0;
+extern "C" void sq_tune_blocked_force_depth(int d) { g_force_depth = d; }
+extern "C" void sq_tune_blocked_force_tile(int cb, int pb) { g_force_cb = cb; g_force_pb = pb; }
 
 size_t blocked_map_bytes(int N, int C, int H, int W) { return (size_t)N * ((C + 7) / 8) * H * W * 16; }
 
@@ -717,10 +708,21 @@ long long slots_for(const ConvPlan &pl, long long cap)
 // the profiler keeps the pointer: one permanent string per shape of launch
 const char *launch_name(int K, int CB, int PB, int D, bool pair)
 {
-    static char names[2][6][3][3][5][28];
-    char *name = names[pair][K][CB][PB][D];
-    if (!name[0]) snprintf(name, sizeof names[0][0][0][0][0], pair ? "k1b+k%db_%dx%d_d%d" : "k%db_%dx%d_d%d", K, 32 * CB, 32 * PB, D);
-    return name;
+    // filled once (function-local statics are initialised under a lock), read-only afterwards
+    struct Names {
+        char n[2][6][3][3][5][28];
+        Names()
+        {
+            for (int pr = 0; pr < 2; ++pr)
+                for (int k = 0; k < 6; ++k)
+                    for (int cb = 0; cb < 3; ++cb)
+                        for (int pb = 0; pb < 3; ++pb)
+                            for (int d = 0; d < 5; ++d)
+                                snprintf(n[pr][k][cb][pb][d], sizeof n[0][0][0][0][0], pr ? "k1b+k%db_%dx%d_d%d" : "k%db_%dx%d_d%d", k, 32 * cb, 32 * pb, d);
+        }
+    };
+    static const Names names;
+    return names.n[pair][K][CB][PB][D];
 }
 
 }  // namespace
@@ -800,25 +802,30 @@ int blocked_pool_conv(const void *in, const void *wp, const float *b, void *out,
     typedef void (*PoolConvFn)(const ConvParams);
     PoolConvFn fn = pl.CB == 2 ? (D == 2 ? pool_conv_blocked_kernel<2, 2> : pool_conv_blocked_kernel<2, 1>)
                                : (D == 2 ? pool_conv_blocked_kernel<1, 2> : pool_conv_blocked_kernel<1, 1>);
-    static PoolConvFn allowed[4];
-    bool seen = false;
-    for (PoolConvFn f : allowed) seen |= f == fn;
-    if (!seen) {
-        if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, mfma::kLdsBytes) != hipSuccess) {
-            const int e = check_launch();
-            return e ? e : SQ_ERR_HIP;
-        }
-        for (PoolConvFn &f : allowed)
-            if (!f) { f = fn; break; }
+    if (!allow_big_lds((const void *)fn)) {
+        const int e = check_launch();
+        return e ? e : SQ_ERR_HIP;
     }
     const long long wgs = slots_for(pl, 2ll * num_cus()) * pl.p.ncblk;
     const size_t lds = (size_t)pl.CB * pl.per_mb + (size_t)pl.CB * 32 * sizeof(float);
-    static char names[3][3][24];
-    char *name = names[pl.CB][D];
-    if (!name[0]) snprintf(name, sizeof names[0][0], "pool3s2+k1b_%dx32_d%d", 32 * pl.CB, D);
-    LaunchScope scope(name, pl.flops, 2.0 * ((double)N * Cin * Hin * Win + (double)Cout * Cin + (double)N * Cout * H * W) + 4.0 * Cout);
+    static const char *const names[3][3] = {{"", "", ""},
+                                            {"", "pool3s2+k1b_32x32_d1", "pool3s2+k1b_32x32_d2"},
+                                            {"", "pool3s2+k1b_64x32_d1", "pool3s2+k1b_64x32_d2"}};
+    LaunchScope scope(names[pl.CB][D], pl.flops, 2.0 * ((double)N * Cin * Hin * Win + (double)Cout * Cin + (double)N * Cout * H * W) + 4.0 * Cout);
     hipLaunchKernelGGL(fn, dim3((unsigned)wgs), dim3(kThreads), lds, current_stream(), pl.p);
     return check_launch();
+}
+
+// Every kernel of this file whose launch may ask for more dynamic LDS than the default limit.
+bool blocked_register_kernels()
+{
+    bool ok = true;
+    for (int cb = 1; cb <= 2; ++cb)
+        for (int pb = 1; pb <= 2; ++pb)
+            for (int d = 1; d <= 4; ++d) ok &= allow_big_lds((const void *)kernel_for(cb, pb, d));
+    ok &= allow_big_lds((const void *)pool_conv_blocked_kernel<1, 1>) && allow_big_lds((const void *)pool_conv_blocked_kernel<1, 2>) &&
+          allow_big_lds((const void *)pool_conv_blocked_kernel<2, 1>) && allow_big_lds((const void *)pool_conv_blocked_kernel<2, 2>);
+    return ok;
 }
 
 int blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S)

@@ -182,18 +182,16 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
     return true;
 }
 
-// Dynamic LDS above the default limit must be opted into once per kernel function.
-bool allow_big_lds(const void *fn)
-{
-    static const void *done[4 * kNumVariants + 8];
-    static int ndone = 0;
-    for (int i = 0; i < ndone; ++i)
-        if (done[i] == fn) return true;
-    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
-        return false;
-    if (ndone < (int)(sizeof(done) / sizeof(done[0]))) done[ndone++] = fn;
-    return true;
-}
+// a launch that pools on the way in is reported under a name of its own ("pool3s2+<tiling>"); the table is
+// filled during static initialisation, so concurrent launches only read it
+struct PooledNames {
+    char name[kNumVariants][64];
+    PooledNames()
+    {
+        for (int i = 0; i < kNumVariants; ++i) snprintf(name[i], sizeof(name[i]), "pool3s2+%s", kVariants[i].name);
+    }
+};
+const PooledNames kPooledNames;
 
 int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullptr)
 {
@@ -217,10 +215,7 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
         const int rc = conv_prepare_kernels(&job, 1, a.dtype);
         if (rc) return rc;
     }
-    // a launch that pools on the way in is reported under a name of its own ("pool3s2+<tiling>")
-    static char pooled_names[kNumVariants][64];
-    if (a.pool_H && !pooled_names[vi][0]) snprintf(pooled_names[vi], sizeof(pooled_names[vi]), "pool3s2+%s", v.name);
-    LaunchScope scope(a.pool_H ? pooled_names[vi] : v.name, flops, bytes);
+    LaunchScope scope(a.pool_H ? kPooledNames.name[vi] : v.name, flops, bytes);
     hipLaunchKernelGGL(fn, dim3(pl.blocks, pl.blocks_y), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
     return check_launch();
 }
@@ -283,7 +278,7 @@ double estimate(const Variant &v, const Plan &pl, const ConvArgs &a)
 // Host-side self check of the division-by-multiplication used in the kernels: number of
 // x in [0, x_max] for which it disagrees with x / d (exported for the tests, not part of
 // the public interface).
-extern "C" long long sq_internal_fastdiv_mismatches(unsigned d, unsigned x_max)
+extern "C" long long sq_tune_fastdiv_mismatches(unsigned d, unsigned x_max)
 {
     const mfma::FastDiv f = mfma::make_fastdiv(d);
     long long bad = 0;
@@ -303,8 +298,8 @@ size_t conv_workspace_bytes(int Cin, int Cout, int K, int S, int P)
 // the public interface.  Measured on whole fp32 passes: with the pair on every fire layer 4 % / 10 % / 9 % / 11 % /
 // 6 % / 3 % faster at batch 4 / 8 / 16 / 32 / 64 / 256 than the best of the other forms (both expands in the tiles
 // of one direct 3x3 kernel up to batch 16, separate launches above), slower only at batches 1 and 2.
-int g_expand_pair = -1;
-extern "C" void sq_internal_expand_pair(int v) { g_expand_pair = v; }
+thread_local int g_expand_pair = -1;
+extern "C" void sq_tune_expand_pair(int v) { g_expand_pair = v; }
 constexpr int kExpandPairMinBatch = 3;
 
 static bool expand_pair_wanted(const ConvArgs &a3)
@@ -331,6 +326,21 @@ bool conv_wants_prepared_kernels(const ConvArgs &a, bool fire_expand)
     return wino_choice(a, pl, fire_expand && expand_pair_wanted(a)) >= 0;
 }
 
+// Every kernel of this family whose launch may ask for more dynamic LDS than the default limit.
+bool conv_mfma_register_kernels()
+{
+    bool ok = true;
+    for (int i = 0; i < kNumVariants; ++i)
+        for (const KernelSet *ks : {&conv_mfma_kernels_f32[i], &conv_mfma_kernels_bf16[i]})
+            for (KernelFn fn : {ks->plain, ks->tail, ks->fused_e1, ks->pooled}) ok &= allow_big_lds((const void *)fn);
+    for (int nw : {4, 8})
+        for (int full = 0; full < 2; ++full)
+            for (int bf = 0; bf < 2; ++bf)
+                for (int tm : {1, 3}) ok &= allow_big_lds((const void *)conv7s2c3_kernel_for(nw, full, bf, tm));
+    for (int i = 0; i < num_expand_pair_kernels; ++i) ok &= allow_big_lds((const void *)expand_pair_kernels[i].fn);
+    return ok;
+}
+
 int conv_mfma_variant_count() { return kNumVariants; }
 const char *conv_mfma_variant_name(int i) { return kVariants[i].name; }
 
@@ -339,8 +349,8 @@ const char *conv_mfma_variant_name(int i) { return kVariants[i].name; }
 // faster network passes at batch 1 / 2 / 4 / 8 / 16, slower from 32 on, where the fused kernel's lower
 // occupancy costs more than the launch it saves), -1 = always, automatic choice of tiling,
 // i >= 0 = tiling i.  The setter is a tuning hook, not part of the public interface.
-int g_force_expand = -2;
-extern "C" void sq_internal_force_expand(int v) { g_force_expand = v; }
+thread_local int g_force_expand = -2;
+extern "C" void sq_tune_force_expand(int v) { g_force_expand = v; }
 
 // 3x3 (pad 1, stride 1) convolution a3 plus the 1x1 convolution (w1, b1, Cout1 layers) of the
 // same input, results in layers [a3.c_offset, +a3.Cout) and [coff1, +Cout1) of one tensor.

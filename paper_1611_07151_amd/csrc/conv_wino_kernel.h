@@ -122,19 +122,19 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
     const int tb = fdiv(bid, p.dMtiles);
     const int mt = bid - tb * p.mtiles, m0 = mt * BM, t0 = tb * BT;
 
-    const rsrc_t rx = make_rsrc(p.in, p.in_bytes);
-
     // ---- staging maps ----------------------------------------------------------------------
     // patches: thread -> (tile vt = t % 32, input layer vc = t / 32 of the chunk).
     // Per patch row two lane offsets: the first column on its own (rows outside the image, a
     // tile past the end, or column -1 get the top bit, which the buffer range check turns
     // into zeros) and columns 2, 3, 4 of the patch as one 12-byte run.  Offsets of real
     // elements are never negative.  Columns 3 and 4 may lie right of the image; there the
-    // run reads valid addresses of the next row and the factors mc2, mc3 (0 or 1) cancel
-    // them inside the column transform.
+    // run reads addresses of the next row, or past the last row of the last input layer whatever
+    // lies behind the tensor, and the column transform replaces what it read by zero with a
+    // select (c2ok, c3ok) -- not with a factor of zero, which would let a NaN or an infinity
+    // among those bytes through.
     const int vt = t & 31, vc = t >> 5;
     uint32_t xrow[4], xcol0[4];
-    float mc2, mc3;
+    bool c2ok, c3ok;
     {
         const int tg = t0 + vt, tgc = min(tg, p.T - 1);
         const int n = fdiv(tgc, p.dTXY), rem = tgc - n * p.TXY;
@@ -147,8 +147,8 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
             xrow[a] = (base + (uint32_t)(a * p.W) * ESZ) | bad;
             xcol0[a] = (base + (uint32_t)(a * p.W) * ESZ - ESZ) | bad | (iw0 >= 0 ? 0u : kOob);
         }
-        mc2 = iw0 + 2 < p.W ? 1.f : 0.f;
-        mc3 = iw0 + 3 < p.W ? 1.f : 0.f;
+        c2ok = iw0 + 2 < p.W;
+        c3ok = iw0 + 3 < p.W;
     }
     // V image position of (tile vt, layer vc): lane half vc & 1, slot vc >> 1
     const int vdst = (vc & 1) * (BT * 4) + vt * 4 + (vc >> 1);
@@ -175,13 +175,17 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
         A[s_].w = buf_ld(ru, ulane + 12, ub);
     };
     auto load_patch = [&](int ch) {
+        // The chunk's first input layer goes into the base of the resource (scalar arithmetic), not into the
+        // uniform offset of the loads: the hardware checks only the lane offset against the size, so a run that
+        // ends past the last row of the last input layer of the last image is cut off exactly at the end of `in`.
         const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(ch * CC * p.HW) * ESZ;
+        const rsrc_t rxc = make_rsrc((const char *)p.in + so, p.in_bytes - so);
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             asm volatile("" : "+v"(xrow[a]));   // keeps the column steps immediates, so the run is one load
-            dpatch[4 * a] = buf_ld_in<TIN>(rx, xcol0[a], so);
+            dpatch[4 * a] = buf_ld_in<TIN>(rxc, xcol0[a], 0u);
 #pragma unroll
-            for (int b = 1; b < 4; ++b) dpatch[4 * a + b] = buf_ld_in<TIN>(rx, xrow[a] + (b - 1) * ESZ, so);
+            for (int b = 1; b < 4; ++b) dpatch[4 * a + b] = buf_ld_in<TIN>(rxc, xrow[a] + (b - 1) * ESZ, 0u);
         }
     };
     auto store_V = [&](float *img) {
@@ -197,11 +201,12 @@ __device__ __forceinline__ void conv_wino_tiles(const KParams &p, const int firs
         float *vs = img + vdst;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-            const float r2 = rr[a][2] * mc2;          // columns 0 (zero-filled) and 1 need no factor
+            const float r2 = c2ok ? rr[a][2] : 0.f;   // columns 0 (zero-filled by the range check) and 1 are always real
+            const float r3 = c3ok ? rr[a][3] : 0.f;
             vs[(4 * a + 0) * (2 * BT * 4)] = rr[a][0] - r2;
             vs[(4 * a + 1) * (2 * BT * 4)] = rr[a][1] + r2;
             vs[(4 * a + 2) * (2 * BT * 4)] = r2 - rr[a][1];
-            vs[(4 * a + 3) * (2 * BT * 4)] = __builtin_fmaf(-rr[a][3], mc3, rr[a][1]);
+            vs[(4 * a + 3) * (2 * BT * 4)] = rr[a][1] - r3;
         }
     };
 

@@ -279,19 +279,20 @@ int blocked_fire_fused(const void *in, const void *wp_sq, const float *b_sq, con
     if (wgs >= (1ll << 31)) return SQ_ERR_UNSUPPORTED;
     typedef void (*FireFn)(const FireParams);
     FireFn fn = Csq > 32 ? fire_blocked_kernel<2> : fire_blocked_kernel<1>;
-    static bool allowed[2] = {false, false};
-    if (!allowed[Csq > 32]) {
-        if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, mfma::kLdsBytes) != hipSuccess) {
-            const int e = check_launch();
-            return e ? e : SQ_ERR_HIP;
-        }
-        allowed[Csq > 32] = true;
+    if (!allow_big_lds((const void *)fn)) {
+        const int e = check_launch();
+        return e ? e : SQ_ERR_HIP;
     }
     const double px = (double)N * H * W;
     LaunchScope scope(Csq > 32 ? "fire1_bf16_sq64" : "fire1_bf16_sq32", 2.0 * px * ((double)Cin * Csq + (double)Csq * Ce1 + 9.0 * Csq * Ce3),
                       2.0 * (px * (Cin + Ce1 + Ce3) + (double)Cin * Csq + (double)Csq * Ce1 + 9.0 * Csq * Ce3));
     hipLaunchKernelGGL(fn, dim3((unsigned)wgs), dim3(kFireThreads), lds, current_stream(), p);
     return check_launch();
+}
+
+bool fire_bf16_register_kernels()
+{
+    return allow_big_lds((const void *)fire_blocked_kernel<1>) && allow_big_lds((const void *)fire_blocked_kernel<2>);
 }
 
 }  // namespace sq

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "sq.h"
+#include "sq_tuning.h"
 
 namespace sq {
 
@@ -17,6 +18,17 @@ int num_cus();
 
 // Folds the sticky launch error into a status code and records it.
 int check_launch();
+
+// Arithmetic mode of the calling host thread (set by sq_set_dtype).
+int current_dtype();
+
+// Raises the dynamic-LDS limit of a kernel function to the hardware's 160 KB the first time it is asked for
+// that function; safe to call from several host threads.  sq_init() asks for every kernel of the library, so
+// that no later call issues anything but launches.
+bool allow_big_lds(const void *fn);
+bool conv_mfma_register_kernels();
+bool blocked_register_kernels();
+bool fire_bf16_register_kernels();
 
 // One convolution call after validation.  Ho/Wo are precomputed; the result goes
 // to layers [c_offset, c_offset+Cout) of an [N][out_channels][Ho][Wo] tensor.

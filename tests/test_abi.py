@@ -8,6 +8,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "sq.h")
+TUNING_HEADER = os.path.join(ROOT, "include", "sq_tuning.h")
 LIB = os.path.join(ROOT, "paper_1611_07151_amd", "libsq.so")
 
 
@@ -22,17 +23,31 @@ def lib():
     return l
 
 
-def _declared():
-    text = open(HEADER).read()
+def _declared(header=HEADER):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(sq_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared()
-    assert {"sq_conv2d_forward", "sq_maxpool", "sq_fire_forward", "sq_squeezenet_forward"} <= set(names)
-    for n in names:
+    assert {"sq_conv2d_forward", "sq_maxpool", "sq_fire_forward", "sq_squeezenet_forward", "sq_set_dtype",
+            "sq_pack_weights", "sq_set_stream", "sq_strerror"} <= set(names)
+    for n in names + _declared(TUNING_HEADER):
         assert hasattr(lib, n), n
+
+
+def test_every_exported_symbol_is_declared_in_a_header():
+    """No undeclared entry points: what the shared library exports under the sq_ prefix is exactly what the
+    two headers under include/ declare."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", LIB], capture_output=True, text=True, check=True).stdout
+    exported = {line.split()[-1] for line in out.splitlines() if line.split() and line.split()[-1].startswith("sq_")}
+    declared = set(_declared()) | set(_declared(TUNING_HEADER))
+    assert exported - declared == set(), sorted(exported - declared)
+    assert declared - exported == set(), sorted(declared - exported)
+    assert all(n.startswith("sq_tune_") for n in _declared(TUNING_HEADER))
+    assert not any(n.startswith("sq_tune_") for n in _declared())
 
 
 def test_strerror_covers_all_codes(lib):
@@ -166,7 +181,7 @@ def test_product_package_does_not_touch_the_oracle():
 def test_division_by_multiplication_is_exact(lib):
     """The kernels divide by runtime constants with a precomputed multiplier; the host
     twin of that routine must agree with integer division over the ranges in use."""
-    f = lib.sq_internal_fastdiv_mismatches
+    f = lib.sq_tune_fastdiv_mismatches
     f.restype = ctypes.c_longlong
     f.argtypes = [ctypes.c_uint, ctypes.c_uint]
     for d in (1, 2, 3, 5, 7, 13, 15, 16, 27, 29, 55, 57, 111, 169, 227, 392, 729, 3025, 12321, 65536, 1000003):
@@ -268,3 +283,102 @@ def test_reduced_precision_entry_points_validate_before_any_gpu_call(lib):
     pk.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p, sz]
     assert pk(params, ctypes.c_void_p(0x1000), lib.sq_squeezenet_bf16_packed_bytes() - 1) == -4
     assert pk(holes, ctypes.c_void_p(0x1000), lib.sq_squeezenet_bf16_packed_bytes()) == -1
+
+
+def test_dtype_setter_and_packed_entry_points_validate_before_any_gpu_call(lib):
+    sz = ctypes.c_size_t
+    lib.sq_packed_weights_bytes.restype = sz
+    lib.sq_fire_packed_bytes.restype = sz
+    lib.sq_squeezenet_bf16_packed_bytes.restype = sz
+    assert lib.sq_set_dtype(0) == 0 and lib.sq_set_dtype(7) == -3
+    # fp32: the sixteen-value transforms of the eight expand3x3 kernel sets (output layers in blocks of 64)
+    fires = [(16, 64), (16, 64), (32, 128), (32, 128), (48, 192), (48, 192), (64, 256), (64, 256)]
+    assert lib.sq_packed_weights_bytes(0) == sum(16 * 4 * sq * ((e + 63) // 64 * 64) for sq, e in fires)
+    assert lib.sq_packed_weights_bytes(1) == lib.sq_squeezenet_bf16_packed_bytes()
+    assert lib.sq_packed_weights_bytes(5) == 0
+    assert lib.sq_fire_packed_bytes(16, 64) == 16 * 4 * 16 * 64
+    assert lib.sq_fire_packed_bytes(12, 64) == 0 and lib.sq_fire_packed_bytes(16, 0) == 0
+    params = (ctypes.c_void_p * 52)(*([0x1000] * 52))
+    pk = lib.sq_pack_weights
+    pk.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, sz]
+    need = lib.sq_packed_weights_bytes(0)
+    assert pk(params, 0, NULL, need) == -1
+    assert pk(params, 0, ctypes.c_void_p(0x1010), need) == -4
+    assert pk(params, 0, FAKE, need - 1) == -4
+    assert pk(params, 9, FAKE, need) == -3
+    holes = (ctypes.c_void_p * 52)(*([0x1000] * 30 + [None] + [0x1000] * 21))
+    assert pk(holes, 0, FAKE, need) == -1
+    fp = lib.sq_fire_pack_weights
+    fp.argtypes = [ctypes.c_void_p, ctypes.c_void_p, sz, ctypes.c_int, ctypes.c_int]
+    assert fp(NULL, FAKE, 65536, 16, 64) == -1
+    assert fp(FAKE, FAKE, 65535, 16, 64) == -4
+    assert fp(FAKE, FAKE, 65536, 12, 64) == -3
+    assert fp(FAKE, FAKE, 65536, 0, 64) == -2
+    net = lib.sq_squeezenet_forward_packed
+    net.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                    ctypes.c_void_p, sz, ctypes.POINTER(ctypes.c_void_p)]
+    lib.sq_squeezenet_workspace_bytes.restype = sz
+    wsb = lib.sq_squeezenet_workspace_bytes(1)
+    ws = ctypes.c_void_p(0x2000)
+    assert net(FAKE, params, NULL, FAKE, 1, ws, wsb, None) == -1
+    assert net(FAKE, params, ctypes.c_void_p(0x1010), FAKE, 1, ws, wsb, None) == -4
+    assert net(FAKE, params, FAKE, FAKE, 0, ws, wsb, None) == -2
+    assert net(FAKE, params, FAKE, FAKE, 1, ws, wsb - 1, None) == -4
+    ff = lib.sq_fire_forward_packed
+    ff.argtypes = [ctypes.c_void_p] * 9 + [ctypes.c_int] * 7 + [ctypes.c_void_p, sz]
+    mapb = (2 * 16 * 55 * 55 * 4 + 255) // 256 * 256
+    good = [2, 96, 55, 55, 16, 64, 64]
+    assert ff(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, NULL, FAKE, *good, ws, mapb) == -1
+    assert ff(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, *good, ws, mapb - 1) == -4
+    assert ff(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 2, 96, 55, 55, 12, 64, 64, ws, mapb) == -3
+    # reduced precision is a mode of the calling thread: the fp32-only calls refuse it, and say so before anything else
+    assert lib.sq_set_dtype(1) == 0
+    try:
+        assert ff(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, *good, ws, mapb) == -3
+        plain = lib.sq_squeezenet_forward
+        plain.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, sz,
+                          ctypes.POINTER(ctypes.c_void_p)]
+        assert plain(FAKE, params, FAKE, 1, ws, wsb, None) == -3
+        # packed network in reduced precision: the checks of the reduced-precision network apply (batch limit 907)
+        assert net(FAKE, params, FAKE, FAKE, 908, ws, sz(1 << 40), None) == -3
+        assert net(FAKE, params, FAKE, FAKE, 454, ws, 16, None) == -4
+    finally:
+        assert lib.sq_set_dtype(0) == 0
+
+
+def test_two_host_threads_call_entry_points_at_once(lib):
+    """Stream, arithmetic mode and last error belong to the calling thread; size queries and argument checks
+    run concurrently without sharing anything that is written."""
+    import threading
+    sz = ctypes.c_size_t
+    lib.sq_fire_workspace_bytes.restype = sz
+    lib.sq_squeezenet_workspace_bytes.restype = sz
+    fire = lib.sq_fire_forward
+    fire.argtypes = [ctypes.c_void_p] * 8 + [ctypes.c_int] * 7 + [ctypes.c_void_p, sz]
+    need = lib.sq_fire_workspace_bytes(2, 55, 55, 16, 64)
+    errors, barrier = [], threading.Barrier(2)
+
+    def worker(mode):
+        try:
+            barrier.wait()
+            assert lib.sq_set_dtype(mode) == 0
+            assert lib.sq_set_stream(ctypes.c_void_p(0)) == 0
+            for i in range(2000):
+                # the other thread keeps the other mode: this thread's answer never changes
+                rc = fire(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 2, 96, 55, 55, 16, 64, 64, NULL, need)
+                assert rc == (-4 if mode == 0 else -3), (mode, i, rc)
+                assert lib.sq_squeezenet_workspace_bytes(1 + i % 7) > 0
+                assert lib.sq_conv2d_forward(FAKE, FAKE, FAKE, FAKE, 1, 3, 8, 8, 4, 3, 0, 1, 1) == -2
+                assert lib.sq_maxpool(FAKE, FAKE, 1, 1, 2, 8, 3, 2) == -2
+                assert lib.sq_last_hip_error() == 0
+        except Exception as e:       # noqa: BLE001 - reported by the main thread
+            errors.append(e)
+        finally:
+            lib.sq_set_dtype(0)
+
+    threads = [threading.Thread(target=worker, args=(m,)) for m in (0, 1)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors

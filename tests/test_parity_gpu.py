@@ -259,15 +259,15 @@ def test_network_with_pooling_inside_the_squeeze_layers(sq):
     by_policy, taps = sq.sq_squeezenet_forward(x, params, want_taps=True)
     assert torch.equal(by_policy, sq.sq_squeezenet_forward(x, params))   # pooled maps kept or not: same bits
     assert taps["pool1"].shape == (3, 96, 55, 55) and bool((taps["pool4"] >= 0).all())
-    sq.lib.sq_internal_fuse_pools_f32(0)
+    sq.lib.sq_tune_fuse_pools_f32(0)
     try:
         separate = sq.sq_squeezenet_forward(x, params)
         for mask in (1, 2, 4, 7):
-            sq.lib.sq_internal_fuse_pools_f32(mask)
+            sq.lib.sq_tune_fuse_pools_f32(mask)
             fused = sq.sq_squeezenet_forward(x, params)
             assert_close(fused, separate.cpu().numpy(), FP32_TOL, f"mask {mask}")
     finally:
-        sq.lib.sq_internal_fuse_pools_f32(-1)
+        sq.lib.sq_tune_fuse_pools_f32(-1)
     ref = oracle.squeezenet(cfg["x"], cfg["params"])
     assert_close(fused, ref, FP32_TOL, "all pools fused")
 
@@ -322,9 +322,9 @@ def test_fire_with_both_expands_in_one_launch(sq, cin, sq_c, e, h, n):
     args = [dev(a) for a in (x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3)]
     fused_ran = 0
     try:
-        sq.lib.sq_internal_expand_pair(0)          # the other one-launch form would take these layers first
+        sq.lib.sq_tune_expand_pair(0)          # the other one-launch form would take these layers first
         for v in [-3, -2, -1] + list(range(sq.sq_conv_variant_count())):
-            sq.lib.sq_internal_force_expand(v)
+            sq.lib.sq_tune_force_expand(v)
             sq.sq_profile_begin(16)
             got = sq.sq_fire_forward(*args)
             stages = {r["name"].split("|")[0] for r in sq.sq_profile_end()}
@@ -332,8 +332,8 @@ def test_fire_with_both_expands_in_one_launch(sq, cin, sq_c, e, h, n):
             assert v != -3 or "fire/e1+e3" not in stages
             fused_ran += v >= 0 and "fire/e1+e3" in stages
     finally:
-        sq.lib.sq_internal_force_expand(-2)
-        sq.lib.sq_internal_expand_pair(-1)
+        sq.lib.sq_tune_force_expand(-2)
+        sq.lib.sq_tune_expand_pair(-1)
     assert fused_ran >= 3 or sq_c % 4        # several tilings took the fused form (input layers must fill their chunks)
 
 
@@ -355,7 +355,7 @@ def test_fire_expand_pair_is_bit_identical_to_its_two_parts(sq, cin, sq_c, e, h,
     ran = 0
     try:
         for i, e1_name in enumerate(["k1s1_64x128_w2x2_m32_c16_o2", "k1s1_64x256_w1x4_m32_c16_o2"]):
-            sq.lib.sq_internal_expand_pair(1 + i)
+            sq.lib.sq_tune_expand_pair(1 + i)
             sq.sq_profile_begin(16)
             got = sq.sq_fire_forward(*args)
             recs = [r["name"] for r in sq.sq_profile_end()]
@@ -368,12 +368,12 @@ def test_fire_expand_pair_is_bit_identical_to_its_two_parts(sq, cin, sq_c, e, h,
             e1 = sq.sq_conv2d_forward_ex(sq_map, args[3], args[4], 1, 0, True, algo=sq.SQ_ALGO_VARIANT0 + names.index(e1_name))
             assert torch.equal(got[:, :e], e1) and torch.equal(got[:, e:], e3), e1_name
             assert_close(got, oracle.fire(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3), FP32_TOL, e1_name)
-        sq.lib.sq_internal_expand_pair(0)
+        sq.lib.sq_tune_expand_pair(0)
         sq.sq_profile_begin(16)
         assert_close(sq.sq_fire_forward(*args), oracle.fire(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3), FP32_TOL, "pair off")
         assert not any("+k1s1" in r["name"] for r in sq.sq_profile_end())
     finally:
-        sq.lib.sq_internal_expand_pair(-1)
+        sq.lib.sq_tune_expand_pair(-1)
     assert ran == (0 if sq_c % 16 else 2)
 
 

@@ -190,15 +190,15 @@ def test_blocked_fire_matches_oracle(sq, shape):
             return sq.sq_blocked_fire_forward(to_blocked(x).cuda(), Cin, packed[0], dev(bs), packed[1], dev(b_e1), packed[2],
                                               dev(b_e3), Csq, Ce, Ce, workspace=ws)
         try:
-            sq.lib.sq_internal_fire_one_launch(0)          # squeeze into the workspace, then both expands in one launch
+            sq.lib.sq_tune_fire_one_launch(0)          # squeeze into the workspace, then both expands in one launch
             out = run()
             s_gpu = from_blocked(ws.view(torch.bfloat16).view(N, Csq // 8, H, H, 8), Csq)
-            sq.lib.sq_internal_fire_one_launch(1)          # the whole layer in one launch, squeeze map in LDS
+            sq.lib.sq_tune_fire_one_launch(1)          # the whole layer in one launch, squeeze map in LDS
             sq.sq_profile_begin(8)
             out1 = run()
             stages = [r["name"] for r in sq.sq_profile_end()]
         finally:
-            sq.lib.sq_internal_fire_one_launch(-1)
+            sq.lib.sq_tune_fire_one_launch(-1)
         assert len(stages) == 1 and stages[0].startswith("fire|fire1_bf16"), stages
         assert torch.equal(out.view(torch.int16), out1.view(torch.int16)), "one launch and two launches differ"
         got = from_blocked(out, 2 * Ce)
@@ -329,8 +329,9 @@ def test_network_end_to_end_against_the_fp32_oracle_and_fp32_gpu(sq):
     m16, m32 = taps["means"].cpu().numpy().astype(np.float64), taps32["means"].cpu().numpy().astype(np.float64)
     spread = m32.std(axis=1, keepdims=True)
     rel = np.abs(m16 - m32) / spread
-    assert rel.max() < 0.25, rel.max()
-    assert np.sqrt((rel ** 2).mean()) < 0.05
+    # measured: maximum 3-6 % of the spread, rms 0.6 %; the bounds are twice the worst seen
+    assert rel.max() < 0.12, rel.max()
+    assert np.sqrt((rel ** 2).mean()) < 0.02
     ref_p, ref_t = oracle.squeezenet(cfg["x"][:1], cfg["params"], want_taps=True)
     assert_close(taps["means"][:1].cpu().numpy(), ref_t["means"], 5e-2, "class means of image 0 against the oracle")
     # top-1: wherever the fp32 winner leads the runner-up by more than the measured error, both agree
@@ -363,7 +364,7 @@ def test_networks_at_odd_batch_sizes(sq, n):
     _, probs16, taps16 = _network(sq, cfg, x)
     m16, m32 = taps16["means"].cpu().numpy().astype(np.float64), taps32["means"].cpu().numpy().astype(np.float64)
     rel = np.abs(m16 - m32) / m32.std(axis=1, keepdims=True)
-    assert rel.max() < 0.25 and np.sqrt((rel ** 2).mean()) < 0.05, (rel.max(), np.sqrt((rel ** 2).mean()))
+    assert rel.max() < 0.12 and np.sqrt((rel ** 2).mean()) < 0.02, (rel.max(), np.sqrt((rel ** 2).mean()))
     assert abs(float(probs16.sum()) - n) < 1e-3
 
 

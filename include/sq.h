@@ -248,6 +248,29 @@ int sq_fire_forward(const void *in, const void *w_sq, const float *b_sq,
 size_t sq_fire_workspace_bytes(int N, int H, int W, int Csq, int Ce3);
 
 /*
+ * sq_fire_forward for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * operation, same kernels and same results as sq_fire_forward, bit for bit; the squeeze map and
+ * the transformed 3x3 kernels live in an array of SQ_FIRE_STATIC_SCRATCH_BYTES bytes that is
+ * part of the library's device code (each GPU the library runs on holds its own copy until the
+ * process ends).  The call allocates and frees nothing.
+ *   Limit: sq_fire_workspace_bytes(N, H, W, Csq, Ce3) <= SQ_FIRE_STATIC_SCRATCH_BYTES, otherwise
+ *   SQ_ERR_WORKSPACE and nothing is enqueued (fire2 of the network fits up to 172 images, fire9
+ *   up to 751).
+ *   All calls on one GPU share that GPU's array: two such calls in flight at once on one GPU --
+ *   from two streams or two threads -- race.  Calls on one stream are ordered and safe.  Nothing
+ *   in the array needs clearing between calls: every byte a call reads it has written first.
+ *   The first call on a device (or sq_init()) looks the array's device address up once
+ *   (hipGetSymbolAddress); call sq_init() before capturing this entry point in a graph.
+ * Errors: as sq_fire_forward.
+ */
+#define SQ_FIRE_STATIC_SCRATCH_BYTES (32u << 20)
+int sq_fire_forward_static(const void *in, const void *w_sq, const float *b_sq,
+                           const void *w_e1, const float *b_e1, const void *w_e3,
+                           const float *b_e3, float *out, int N, int Cin, int H, int W,
+                           int Csq, int Ce1, int Ce3);
+
+/*
  * The fire layer on kernels re-ordered ahead of time (section "Zero-overhead Vectorization":
  * the paper re-orders the kernels once, offline, into the order its threads read them).
  * Here the re-ordered form of the expand3x3 kernels is their minimal-filtering transform

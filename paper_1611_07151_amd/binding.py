@@ -47,6 +47,7 @@ lib.sq_fire_workspace_bytes.argtypes = [_i] * 5
 lib.sq_squeezenet_forward.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _i, _vp, _sz, ctypes.POINTER(_vp)]
 lib.sq_squeezenet_workspace_bytes.restype = _sz
 lib.sq_squeezenet_workspace_bytes.argtypes = [_i]
+lib.sq_fire_forward_static.argtypes = [_vp] * 8 + [_i] * 7
 lib.sq_fire_packed_bytes.restype = _sz
 lib.sq_fire_packed_bytes.argtypes = [_i, _i]
 lib.sq_fire_pack_weights.argtypes = [_vp, _vp, _sz, _i, _i]
@@ -289,6 +290,26 @@ def sq_fire_forward(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, workspace=None, out=N
                              _dev(b_e3, f32, "b_e3"), _dev(out, f32, "out"), N, Cin, H, W, Csq, Ce1, Ce3,
                              _dev(workspace), workspace.numel() * workspace.element_size())
     _check(rc, "sq_fire_forward")
+    return out
+
+
+SQ_FIRE_STATIC_SCRATCH_BYTES = 32 << 20   # as in include/sq.h
+
+
+def sq_fire_forward_static(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, out):
+    """The fire layer with its scratch inside the library: the caller passes inputs and the output tensor,
+    and nothing is allocated here or in the library."""
+    N, Cin, H, W = x.shape
+    Csq, Ce1, Ce3 = w_sq.shape[0], w_e1.shape[0], w_e3.shape[0]
+    if tuple(w_sq.shape) != (Csq, Cin, 1, 1) or tuple(w_e1.shape) != (Ce1, Csq, 1, 1) \
+            or tuple(w_e3.shape) != (Ce3, Csq, 3, 3) or tuple(out.shape) != (N, Ce1 + Ce3, H, W):
+        raise ValueError("fire kernel or output shapes")
+    f32 = torch.float32
+    _use_current_stream()
+    rc = lib.sq_fire_forward_static(_dev(x, f32, "x"), _dev(w_sq, f32, "w_sq"), _dev(b_sq, f32, "b_sq"),
+                                    _dev(w_e1, f32, "w_e1"), _dev(b_e1, f32, "b_e1"), _dev(w_e3, f32, "w_e3"),
+                                    _dev(b_e3, f32, "b_e3"), _dev(out, f32, "out"), N, Cin, H, W, Csq, Ce1, Ce3)
+    _check(rc, "sq_fire_forward_static")
     return out
 
 

@@ -259,9 +259,14 @@ int sq_set_dtype(int dtype)
     return SQ_OK;
 }
 
+namespace { int static_scratch(void **ptr); }
+
 int sq_init(void)
 {
     (void)num_cus();
+    void *unused = nullptr;
+    const int rs = static_scratch(&unused);
+    if (rs) return rs;
     const bool ok = conv_mfma_register_kernels() & blocked_register_kernels() & fire_bf16_register_kernels();
     if (!ok) {
         const int rc = check_launch();
@@ -455,6 +460,57 @@ int sq_fire_forward(const void *in, const void *w_sq, const float *b_sq, const v
 {
     return fire_checked(in, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, nullptr, out, N, Cin, H, W, Csq, Ce1, Ce3, workspace,
                         workspace_bytes);
+}
+
+// ---- the fire layer for callers that cannot allocate: scratch in a static device array ---------------------
+// Every GPU the library runs on holds its own copy of the array, at its own address, until the process ends.
+// In host code the array's name is only a handle: its device address is asked for once per device (with that
+// device current) and kept; the kernels get that address as an argument, as they get a caller's workspace.
+namespace {
+__device__ __align__(256) unsigned char scratch[SQ_FIRE_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+int static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        const int rc = check_launch();
+        return rc ? rc : SQ_ERR_HIP;
+    }
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+        if (!p) {
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+                const int rc = check_launch();
+                return rc ? rc : SQ_ERR_HIP;
+            }
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *ptr = p;
+    return SQ_OK;
+}
+}  // namespace
+
+int sq_fire_forward_static(const void *in, const void *w_sq, const float *b_sq, const void *w_e1, const float *b_e1,
+                           const void *w_e3, const float *b_e3, float *out, int N, int Cin, int H, int W, int Csq, int Ce1,
+                           int Ce3)
+{
+    if (!in || !w_sq || !w_e1 || !w_e3 || !out) return SQ_ERR_NULL;
+    if (N <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Csq <= 0 || Ce1 <= 0 || Ce3 <= 0) return SQ_ERR_SHAPE;
+    // the sizes are checked in 64 bits before anything else: a layer beyond the array is refused, never truncated
+    const unsigned long long map = ((unsigned long long)N * Csq * H * W * sizeof(float) + 255) / 256 * 256;
+    if (map > SQ_FIRE_STATIC_SCRATCH_BYTES || map + conv_workspace_bytes(Csq, Ce3, 3, 1, 1) > SQ_FIRE_STATIC_SCRATCH_BYTES)
+        return SQ_ERR_WORKSPACE;
+    void *ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc) return rc;
+    return fire_checked(in, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, nullptr, out, N, Cin, H, W, Csq, Ce1, Ce3, ptr,
+                        SQ_FIRE_STATIC_SCRATCH_BYTES);
 }
 
 size_t sq_fire_packed_bytes(int Csq, int Ce3)

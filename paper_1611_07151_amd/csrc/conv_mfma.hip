@@ -36,6 +36,8 @@
 
 namespace sq {
 size_t wino_transformed_bytes(int Cout, int Cin);
+size_t wino_auto_offset(int Cout, int Cin);
+size_t wino_auto_bytes(int Cout, int Cin);
 namespace {
 
 using namespace mfma;
@@ -45,21 +47,25 @@ struct Variant {
     const char *name;
     int KS, S, BM, BN, MT, CC, PE, NBUF, NT;
     bool conv1_type;      // the persistent 7x7/stride-2/three-layer kernel
-    bool wino;            // the minimal-filtering F(2x2, 3x3) kernel (BN = tiles of 2x2 pixels)
+    bool wino;            // a minimal-filtering F(2x2, 3x3) kernel (BN = tiles of 2x2 pixels)
+    bool wino_auto;       // ... the one with autonomous wavefronts (BM x BN per wavefront item)
 };
 
 #define SQ_V(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                               \
     {"k" #KS "s" #S "_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC "_o" #MINW, KS, S, BM, BN, MT, CC, PE, 2, \
-     WM * WN * 64, false, false},
-#define SQ_C(NW) {"k7s2c3_waves" #NW, 7, 2, 96, 32 * NW, 32, 3, 64, 2, 64 * NW, true, false},
-#define SQ_C1(NW) {"k7s2c3_waves" #NW "_m32", 7, 2, 32, 32 * NW, 32, 3, 64, 2, 64 * NW, true, false},
-#define SQ_W(BM, BT, CC) {"k3s1_f2x2_" #BM "x" #BT "_c" #CC, 3, 1, BM, BT, 32, CC, 0, 2, 256, false, true},
+     WM * WN * 64, false, false, false},
+#define SQ_C(NW) {"k7s2c3_waves" #NW, 7, 2, 96, 32 * NW, 32, 3, 64, 2, 64 * NW, true, false, false},
+#define SQ_C1(NW) {"k7s2c3_waves" #NW "_m32", 7, 2, 32, 32 * NW, 32, 3, 64, 2, 64 * NW, true, false, false},
+#define SQ_W(BM, BT, CC) {"k3s1_f2x2_" #BM "x" #BT "_c" #CC, 3, 1, BM, BT, 32, CC, 0, 2, 256, false, true, false},
+#define SQ_WA(BM, BT) {"k3s1_f2x2a_" #BM "x" #BT, 3, 1, BM, BT, 16, 8, 0, 1, kWinoAutoWaves * 64, false, true, true},
+static_assert(kWinoAutoLayers == 32 && kWinoAutoTiles == 16, "the WA() entry of the variant list names these");
 static_assert(kWinoBM == 64 && kWinoBT == 32 && kWinoCC == 8, "the W() entry of the variant list names these");
-const Variant kVariants[] = {SQ_VARIANT_LIST(SQ_V, SQ_V, SQ_C, SQ_W, SQ_C1)};
+const Variant kVariants[] = {SQ_VARIANT_LIST(SQ_V, SQ_V, SQ_C, SQ_W, SQ_C1, SQ_WA)};
 #undef SQ_V
 #undef SQ_C
 #undef SQ_C1
 #undef SQ_W
+#undef SQ_WA
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 struct Plan {
@@ -100,7 +106,7 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
         return false;
     if (v.conv1_type && (a.Cin != 3 || a.Cout > 96 || a.Cout % 8 != 0)) return false;
     if (v.wino && (a.P != 1 || a.Cin % v.CC != 0 || a.Cout % 32 != 0 || !a.ws || ((uintptr_t)a.ws & 15) ||
-                   a.ws_bytes < wino_transformed_bytes(a.Cout, a.Cin)))
+                   a.ws_bytes < conv_workspace_bytes(a.Cin, a.Cout, 3, 1, 1)))
         return false;
 
     pl.blocks_y = 1;
@@ -131,6 +137,14 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
         if (wino_transformed_bytes(a.Cout, a.Cin) >= (size_t)kMaxBufferElems * 4) return false;   // read through a buffer
         k.wu = (const float *)a.ws;
         k.wu_bytes = (uint32_t)wino_transformed_bytes(a.Cout, a.Cin);
+        if (v.wino_auto) {
+            // steps of four input layers; items = layer blocks x tile groups
+            k.nchunks = a.Cin / 4;
+            k.mtiles = a.Cout / kWinoAutoLayers;
+            k.wu = (const float *)((const char *)a.ws + wino_auto_offset(a.Cout, a.Cin));
+            k.wu_bytes = (uint32_t)wino_auto_bytes(a.Cout, a.Cin);
+            if ((long long)k.mtiles * k.ntiles >= (1ll << 30)) return false;
+        }
     } else if (v.KS == 1 && v.S == 1) {
         if (a.P != 0) return false;  // a padded 1x1 is left to the direct kernel
         k.VH = a.Ho; k.LW = a.Wo; k.LWs = a.Wo; k.PRcap = 0;
@@ -169,6 +183,15 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
         blocks = (tiles + NW - 1) / NW;
         if (blocks > num_cus()) blocks = num_cus();
         if (v.BM == 32) pl.blocks_y = (unsigned)k.mtiles;   // one workgroup per block of 32 output layers
+    } else if (v.wino_auto) {
+        blocks = std::min<long long>((long long)k.mtiles * k.ntiles, num_cus());   // persistent: one workgroup per CU
+        if (blocks >= k.mtiles) {
+            k.wa_cnt = (int)(blocks / k.mtiles); k.wa_big = (int)(blocks % k.mtiles);
+            k.wa_q0 = k.ntiles / k.wa_cnt; k.wa_r0 = k.ntiles % k.wa_cnt;
+            k.wa_q1 = k.ntiles / (k.wa_cnt + 1); k.wa_r1 = k.ntiles % (k.wa_cnt + 1);
+            k.dwa0 = make_fastdiv(k.wa_cnt); k.dwa1 = make_fastdiv(k.wa_cnt + 1);
+        }
+        pl.lds_bytes = (size_t)k.nchunks * kWinoAutoStep * sizeof(float) + 64;   // U of one layer block + the item counter
     } else if (v.wino) {
         blocks = std::min<long long>(blocks, 2ll * num_cus());   // persistent: two workgroups per CU
         pl.lds_bytes = (size_t)(2 * 16 * 2 * kWinoBT * 4) * sizeof(float);   // two V images
@@ -260,11 +283,10 @@ int tuned_variant(const ConvArgs &a)
 // padding, times the number of rounds the tiles need on the CUs.  Lower is better.
 double estimate(const Variant &v, const Plan &pl, const ConvArgs &a)
 {
-    (void)a;
     const double tiles = (double)pl.kp.mtiles * pl.kp.ntiles;
     // the minimal-filtering kernel multiplies 16 times per 2x2 pixels and input layer, i.e.
     // 4 per pixel where the direct form needs 9; BN counts tiles of 4 pixels there
-    const double kpad = v.conv1_type ? 148.0 : (double)pl.kp.nchunks * v.CC * (v.wino ? 16 : v.KS * v.KS);
+    const double kpad = v.conv1_type ? 148.0 : v.wino_auto ? a.Cin * 16.0 : (double)pl.kp.nchunks * v.CC * (v.wino ? 16 : v.KS * v.KS);
     const double work_per_tile = (double)v.BM * v.BN * kpad;
     const double occ = v.conv1_type ? 1.0 : ((size_t)2 * pl.lds_bytes <= (size_t)kLdsBytes ? 2.0 : 1.0);
     const double rounds = ceil(tiles / (num_cus() * occ));
@@ -289,7 +311,7 @@ extern "C" long long sq_tune_fastdiv_mismatches(unsigned d, unsigned x_max)
 size_t conv_workspace_bytes(int Cin, int Cout, int K, int S, int P)
 {
     if (K == 3 && S == 1 && P == 1 && Cin % kWinoCC == 0 && Cout % 32 == 0)
-        return align_up(wino_transformed_bytes(Cout, Cin), 256);
+        return wino_auto_offset(Cout, Cin) + align_up(wino_auto_bytes(Cout, Cin), 256);   // both layouts of the transformed kernels
     return 0;
 }
 
@@ -410,23 +432,39 @@ int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1)
     if (!expand_pair_wanted(a3) || a1.dtype != SQ_F32) return SQ_ERR_UNSUPPORTED;
     if (a1.K != 1 || a1.S != 1 || a1.P != 0 || a1.pool_H || a1.in != a3.in || a1.out != a3.out || a1.N != a3.N) return SQ_ERR_UNSUPPORTED;
     Plan p3, p1;
-    const int v3 = wino_choice(a3, p3, true);
-    if (v3 < 0 || kVariants[v3].NT != 256) return SQ_ERR_UNSUPPORTED;
-    // The expand1x1 tiling.  Measured inside the pair on whole passes at batches 32 to 256 (the stand-alone winners
-    // 64x64 and 48x64 lose here, 128x128 too): 64x128 first, 64x256 first from batch 128 on.
-    auto variant_of = [](const PairKernel &pk) {
+    auto variant_named = [](const char *name) {
         for (int i = 0; i < kNumVariants; ++i)
-            if (!strcmp(kVariants[i].name, pk.e1_variant)) return i;
+            if (!strcmp(kVariants[i].name, name)) return i;
         return -1;
     };
-    const int prefer = g_expand_pair > 0 ? g_expand_pair - 1 : (a1.N >= 128 ? 1 : 0);
+    // Which compiled pair.  Pair 2 is the autonomous-wavefront form of the expand3x3 with the expand1x1 inside its
+    // items; pairs 0 and 1 the four-wavefront form with expand1x1 tiles of 64x128 / 64x256 behind it (the stand-alone
+    // winners 64x64 and 48x64 lose there, 128x128 too).  Measured per fire layer inside whole passes at batch 64
+    // (pair 2 against pair 0, us): 16 -> 64 at 55x55 41-46 / 41, 32 -> 128 at 55x55 103 / 112, 32 -> 128 at 27x27
+    // 36.9 / 36.1, 48 -> 192 at 27x27 58 / 60, 64 -> 256 at 27x27 92.2 / 92.5, 64 -> 256 at 13x13 32.5 / 32.4: pair 2
+    // from 48 input layers on and for 32 input layers on the large maps; pair 1 instead of pair 0 from batch 128 on.
+    const bool auto_form = a3.H * a3.W >= 27 * 27 && (a3.Cin >= 48 || (a3.Cin >= 32 && a3.H * a3.W >= 55 * 55));
+    const int prefer = g_expand_pair > 0 ? g_expand_pair - 1 : (auto_form ? 2 : a1.N >= 128 ? 1 : 0);
     if (prefer >= num_expand_pair_kernels) return SQ_ERR_UNSUPPORTED;
-    int pair = -1;
+    int pair = -1, v3 = -1;
     for (int k = 0; k < num_expand_pair_kernels && pair < 0; ++k) {
-        if (g_expand_pair > 0 && k > 0) break;                    // a forced tiling has no substitute
+        if (g_expand_pair > 0 && k > 0) break;                    // a forced pair has no substitute
         const int i = (prefer + k) % num_expand_pair_kernels;     // the preferred one first, then the others
-        const int v = variant_of(expand_pair_kernels[i]);
-        if (v >= 0 && a1.Cin % kVariants[v].CC == 0 && plan(kVariants[v], a1, p1)) pair = i;
+        v3 = variant_named(expand_pair_kernels[i].e3_variant);
+        if (v3 < 0 || !plan(kVariants[v3], a3, p3)) continue;
+        if (!expand_pair_kernels[i].e1_variant) {
+            // the expand1x1 runs inside the items of the autonomous-wavefront expand3x3: same layers, steps in fours
+            if (a1.Cout != a3.Cout || a1.Cin % 16 != 0 || !kVariants[v3].wino_auto) continue;
+            KParams &k = p3.kp;
+            k.w1 = (const float *)a1.w; k.b1 = a1.b; k.Cout1 = a1.Cout; k.coff1 = a1.c_offset;
+            p3.lds_bytes += (size_t)k.nchunks * 128 * sizeof(float);
+            if (p3.lds_bytes > (size_t)kLdsBytes) continue;
+            p1.blocks = 0; p1.blocks_y = 1; p1.lds_bytes = 0; p1.kp = p3.kp;
+            pair = i;
+            continue;
+        }
+        const int v = variant_named(expand_pair_kernels[i].e1_variant);
+        if (v >= 0 && a1.Cin % kVariants[v].CC == 0 && plan(kVariants[v], a1, p1) && kVariants[v].NT == kVariants[v3].NT) pair = i;
     }
     if (pair < 0) return SQ_ERR_UNSUPPORTED;
     const long long blocks = (long long)p3.blocks + p1.blocks;
@@ -442,8 +480,8 @@ int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1)
         if (rc) return rc;
     }
     LaunchScope scope(pk.name, conv_flops(a3) + conv_flops(a1), conv_bytes(a3) + conv_bytes(a1));
-    hipLaunchKernelGGL(pk.fn, dim3((unsigned)blocks), dim3(256), std::max(p3.lds_bytes, p1.lds_bytes), current_stream(), p3.kp,
-                       p1.kp, (int)p3.blocks);
+    hipLaunchKernelGGL(pk.fn, dim3((unsigned)blocks), dim3(kVariants[v3].NT), std::max(p3.lds_bytes, p1.lds_bytes), current_stream(),
+                       p3.kp, p1.kp, (int)p3.blocks);
     return check_launch();
 }
 

@@ -15,7 +15,8 @@ namespace mfma {
      nullptr, nullptr},
 #define SQ_C(NW) {nullptr, nullptr, nullptr, nullptr},
 #define SQ_W(BM, BT, CC) {conv_wino_kernel<uint16_t>, nullptr, nullptr, nullptr},
-const KernelSet conv_mfma_kernels_bf16[] = {SQ_VARIANT_LIST(SQ_V, SQ_E, SQ_C, SQ_W, SQ_C)};
+#define SQ_WA(BM, BT) {conv_wino_auto_kernel<uint16_t>, nullptr, nullptr, nullptr},
+const KernelSet conv_mfma_kernels_bf16[] = {SQ_VARIANT_LIST(SQ_V, SQ_E, SQ_C, SQ_W, SQ_C, SQ_WA)};
 
 }  // namespace mfma
 }  // namespace sq

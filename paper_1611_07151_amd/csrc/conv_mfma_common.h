@@ -84,6 +84,11 @@ struct KParams {
     const float *wu;     // its transformed kernels (written by wino_kernel_transform)
     uint32_t wu_bytes;
     int Win, HWin;       // 1x1 kernels with pooling on the way in: row length and plane size of the map in memory
+    // minimal-filtering kernel with autonomous wavefronts: how its workgroups are shared out over the layer blocks
+    // (the first wa_big blocks have wa_cnt + 1 workgroups, the others wa_cnt), and tile groups per workgroup of a
+    // block with wa_cnt (q0, remainder r0) or wa_cnt + 1 (q1, r1) workgroups
+    int wa_big, wa_cnt, wa_q0, wa_r0, wa_q1, wa_r1;
+    FastDiv dwa0, dwa1;
 };
 
 template <int MT> struct Mfma;
@@ -220,6 +225,7 @@ struct PairKernel {
     const char *e1_variant;   // name of the 1x1 tiling in the variant list
     const char *name;         // name of the pair in profiles
     PairFn fn;
+    const char *e3_variant;   // name of the minimal-filtering tiling it runs
 };
 extern const PairKernel expand_pair_kernels[];
 extern const int num_expand_pair_kernels;
@@ -231,6 +237,13 @@ KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers, bool bf16_inputs, int
 constexpr int kWinoBM = 64, kWinoBT = 32, kWinoCC = 8;
 constexpr int kWinoImage = 16 * 2 * 64 * 4;
 constexpr int kWinoMaxJobs = 8;
+
+// The same form with autonomous wavefronts (conv_wino_auto_kernel.h): output layers and tiles per wavefront
+// item, wavefronts per workgroup, and the floats of the transformed kernels of one layer block and one step of
+// four input layers, in LDS and in memory: [8 position pairs][64 lanes][4] with the 4 = (position parity, row
+// block of 16 layers); lane = k * 16 + layer % 16.
+constexpr int kWinoAutoLayers = 32, kWinoAutoTiles = 16, kWinoAutoWaves = 8;
+constexpr int kWinoAutoStep = 8 * 64 * 4;
 
 constexpr int kConv7TileRows = 2, kConv7TileCols = 16;   // output pixels per wavefront tile
 size_t conv7s2c3_lds_bytes(int NW, int TM);

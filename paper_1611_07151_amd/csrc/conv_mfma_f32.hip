@@ -25,12 +25,15 @@ template <int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE,
      conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false, true>, nullptr},
 #define SQ_C(NW) {nullptr, nullptr, nullptr, nullptr},
 #define SQ_W(BM, BT, CC) {conv_wino_kernel<float>, nullptr, nullptr, nullptr},
-const KernelSet conv_mfma_kernels_f32[] = {SQ_VARIANT_LIST(SQ_V, SQ_E, SQ_C, SQ_W, SQ_C)};
+#define SQ_WA(BM, BT) {conv_wino_auto_kernel<float>, nullptr, nullptr, nullptr},
+const KernelSet conv_mfma_kernels_f32[] = {SQ_VARIANT_LIST(SQ_V, SQ_E, SQ_C, SQ_W, SQ_C, SQ_WA)};
 
 #define SQ_PAIR(BM, BN, WM, WN, MT, CC)                                                                 \
     {"k1s1_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC "_o2",                                      \
-     "k3s1_f2x2_64x32_c8+k1s1_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC, expand_pair_kernel<BM, BN, WM, WN, MT, CC>},
-const PairKernel expand_pair_kernels[] = {SQ_PAIR(64, 128, 2, 2, 32, 16) SQ_PAIR(64, 256, 1, 4, 32, 16)};
+     "k3s1_f2x2_64x32_c8+k1s1_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC, expand_pair_kernel<BM, BN, WM, WN, MT, CC>,         \
+     "k3s1_f2x2_64x32_c8"},
+const PairKernel expand_pair_kernels[] = {SQ_PAIR(64, 128, 2, 2, 32, 16) SQ_PAIR(64, 256, 1, 4, 32, 16)
+                                          {nullptr, "k3s1_f2x2a_32x16+k1a", expand_pair_auto_kernel<float>, "k3s1_f2x2a_32x16"}};
 const int num_expand_pair_kernels = sizeof(expand_pair_kernels) / sizeof(expand_pair_kernels[0]);
 
 }  // namespace mfma

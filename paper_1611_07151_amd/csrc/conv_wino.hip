@@ -9,6 +9,13 @@ size_t wino_transformed_bytes(int Cout, int Cin)
     return mtiles * ((size_t)Cin / mfma::kWinoCC) * mfma::kWinoImage * sizeof(float);
 }
 
+// the second layout (conv_wino_auto_kernel.h) follows the first in the same scratch area
+size_t wino_auto_offset(int Cout, int Cin) { return align_up(wino_transformed_bytes(Cout, Cin), 256); }
+size_t wino_auto_bytes(int Cout, int Cin)
+{
+    return (size_t)((Cout + 31) / 32) * (Cin / 4) * mfma::kWinoAutoStep * sizeof(float);
+}
+
 int conv_prepare_kernels(const KernelPrepJob *jobs, int n, int dtype)
 {
     using namespace mfma;
@@ -19,12 +26,12 @@ int conv_prepare_kernels(const KernelPrepJob *jobs, int n, int dtype)
     wj.first[0] = 0;
     for (int j = 0; j < kWinoMaxJobs; ++j) {
         const KernelPrepJob &job = jobs[j < n ? j : n - 1];
-        wj.w[j] = job.w; wj.u[j] = (float *)job.ws; wj.Cout[j] = job.Cout; wj.Cin[j] = job.Cin;
+        wj.w[j] = job.w; wj.u[j] = (float *)job.ws; wj.u2[j] = (float *)((char *)job.ws + wino_auto_offset(job.Cout, job.Cin)); wj.Cout[j] = job.Cout; wj.Cin[j] = job.Cin;
         if (j < n) {
             const long long padded = (long long)((job.Cout + kWinoBM - 1) / kWinoBM * kWinoBM) * job.Cin;
             if (wj.first[j] + padded >= (1ll << 30)) return SQ_ERR_UNSUPPORTED;
             wj.first[j + 1] = wj.first[j] + (int)padded;
-            bytes += (dtype == SQ_BF16 ? 2.0 : 4.0) * 9.0 * job.Cout * job.Cin + 4.0 * 16.0 * (double)padded;
+            bytes += (dtype == SQ_BF16 ? 2.0 : 4.0) * 9.0 * job.Cout * job.Cin + 4.0 * 16.0 * ((double)padded + (double)job.Cout * job.Cin);
         } else {
             wj.first[j + 1] = wj.first[j];
         }

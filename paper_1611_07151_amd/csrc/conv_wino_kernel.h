@@ -40,6 +40,7 @@
 
 #include "conv_mfma_common.h"
 #include "conv_mfma_kernel.h"
+#include "conv_wino_auto_kernel.h"
 
 namespace sq {
 namespace mfma {
@@ -51,6 +52,7 @@ namespace mfma {
 struct WinoJobs {
     const void *w[kWinoMaxJobs];
     float *u[kWinoMaxJobs];
+    float *u2[kWinoMaxJobs];       // the same values in the order of conv_wino_auto_kernel.h (layers < Cout only)
     int Cout[kWinoMaxJobs], Cin[kWinoMaxJobs];
     int first[kWinoMaxJobs + 1];   // running totals of Cout (rounded up to 64) * Cin
     int n;
@@ -85,13 +87,19 @@ __global__ __launch_bounds__(256) void wino_kernel_transform(const WinoJobs jobs
     const int cl = c % kWinoCC;
     float *dst = jobs.u[j] + ((size_t)(m / kWinoBM) * (Cin / kWinoCC) + c / kWinoCC) * kWinoImage + (cl & 1) * 256 +
                  (m % kWinoBM) * 4 + (cl >> 1);
+    // second layout: [m / 32][c / 4][position / 2][lane = (c % 4) * 16 + m % 16][2 * (position % 2) + (m % 32) / 16]
+    float *dst2 = jobs.u2[j] + ((size_t)(m / 32) * (Cin / 4) + c / 4) * kWinoAutoStep + ((c & 3) * 16 + (m & 15)) * 4 + ((m & 31) >> 4);
+    const bool second = m < Cout;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const float s = tt[r][0] + tt[r][2];
-        dst[(4 * r + 0) * 512] = tt[r][0];
-        dst[(4 * r + 1) * 512] = 0.5f * (s + tt[r][1]);
-        dst[(4 * r + 2) * 512] = 0.5f * (s - tt[r][1]);
-        dst[(4 * r + 3) * 512] = tt[r][2];
+        const float u4[4] = {tt[r][0], 0.5f * (s + tt[r][1]), 0.5f * (s - tt[r][1]), tt[r][2]};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int pos = 4 * r + q;
+            dst[pos * 512] = u4[q];
+            if (second) dst2[(pos >> 1) * 256 + 2 * (pos & 1)] = u4[q];
+        }
     }
 }
 

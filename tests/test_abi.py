@@ -83,9 +83,9 @@ def test_conv_workspace_entry_point_checks_its_scratch(lib):
     sz = ctypes.c_size_t
     lib.sq_conv2d_workspace_bytes.restype = sz
     need = lib.sq_conv2d_workspace_bytes(32, 128, 3, 1, 1)
-    # transformed kernels: 16 values per (layer, input layer), layers rounded up to 64
-    assert need == 16 * 128 * 32 * 4
-    assert lib.sq_conv2d_workspace_bytes(32, 96, 3, 1, 1) == 16 * 128 * 32 * 4
+    # transformed kernels: 16 values per (layer, input layer), in two orders: layers rounded up to 64, and layers as they are
+    assert need == 16 * 128 * 32 * 4 + 16 * 128 * 32 * 4
+    assert lib.sq_conv2d_workspace_bytes(32, 96, 3, 1, 1) == 16 * 128 * 32 * 4 + 16 * 96 * 32 * 4
     assert lib.sq_conv2d_workspace_bytes(32, 128, 3, 2, 1) == 0     # stride 2: no algorithm needs scratch
     assert lib.sq_conv2d_workspace_bytes(32, 128, 1, 1, 0) == 0
     # space-to-depth form of a strided layer: the copy [N][Cin*S*S][Ho+K'-1][Wo+K'-1] and the regrouped kernels, fp32
@@ -293,10 +293,10 @@ def test_dtype_setter_and_packed_entry_points_validate_before_any_gpu_call(lib):
     assert lib.sq_set_dtype(0) == 0 and lib.sq_set_dtype(7) == -3
     # fp32: the sixteen-value transforms of the eight expand3x3 kernel sets (output layers in blocks of 64)
     fires = [(16, 64), (16, 64), (32, 128), (32, 128), (48, 192), (48, 192), (64, 256), (64, 256)]
-    assert lib.sq_packed_weights_bytes(0) == sum(16 * 4 * sq * ((e + 63) // 64 * 64) for sq, e in fires)
+    assert lib.sq_packed_weights_bytes(0) == sum(16 * 4 * sq * ((e + 63) // 64 * 64) + 16 * 4 * sq * e for sq, e in fires)
     assert lib.sq_packed_weights_bytes(1) == lib.sq_squeezenet_bf16_packed_bytes()
     assert lib.sq_packed_weights_bytes(5) == 0
-    assert lib.sq_fire_packed_bytes(16, 64) == 16 * 4 * 16 * 64
+    assert lib.sq_fire_packed_bytes(16, 64) == 2 * 16 * 4 * 16 * 64
     assert lib.sq_fire_packed_bytes(12, 64) == 0 and lib.sq_fire_packed_bytes(16, 0) == 0
     params = (ctypes.c_void_p * 52)(*([0x1000] * 52))
     pk = lib.sq_pack_weights
@@ -310,10 +310,10 @@ def test_dtype_setter_and_packed_entry_points_validate_before_any_gpu_call(lib):
     assert pk(holes, 0, FAKE, need) == -1
     fp = lib.sq_fire_pack_weights
     fp.argtypes = [ctypes.c_void_p, ctypes.c_void_p, sz, ctypes.c_int, ctypes.c_int]
-    assert fp(NULL, FAKE, 65536, 16, 64) == -1
-    assert fp(FAKE, FAKE, 65535, 16, 64) == -4
-    assert fp(FAKE, FAKE, 65536, 12, 64) == -3
-    assert fp(FAKE, FAKE, 65536, 0, 64) == -2
+    assert fp(NULL, FAKE, 131072, 16, 64) == -1
+    assert fp(FAKE, FAKE, 131071, 16, 64) == -4
+    assert fp(FAKE, FAKE, 131072, 12, 64) == -3
+    assert fp(FAKE, FAKE, 131072, 0, 64) == -2
     net = lib.sq_squeezenet_forward_packed
     net.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
                     ctypes.c_void_p, sz, ctypes.POINTER(ctypes.c_void_p)]

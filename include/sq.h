@@ -227,6 +227,28 @@ int sq_avgpool_global(const float *in, float *out, int N, int C, int H, int W);
 int sq_softmax(const float *in, float *out, int N, int C);
 
 /*
+ * The classifier end of the network as one operation (sections "Convolutional Neural Networks"
+ * and "Pooling and Softmax"): 1 x 1 convolution with bias and ReLU, average pooling over the
+ * whole plane, softmax over the layers:
+ *   means[n][m] = mean over h,w of relu(b[m] + sum_c in[n][c][h][w] * w[m][c]),
+ *   probs[n][m] = exp(means[n][m] - max_n) / sum_m exp(means[n][m] - max_n).
+ * The convolution's map [N][Cout][H][W] is not formed in memory where the library has a kernel
+ * for that (the convolution then writes per-image sums of its results, and a second launch
+ * finishes means and softmax); otherwise the three layers run one after the other.  The result
+ * is the same up to rounding.
+ *   in [N][Cin][H][W], w [Cout][Cin], b [Cout] or NULL, all fp32 (device).
+ *   means [N][Cout] or NULL (not wanted); probs [N][Cout].
+ *   workspace: device scratch of at least sq_classifier_workspace_bytes(N, Cin, H, W, Cout)
+ *   bytes, 256-byte aligned; contents on return are unspecified.
+ * Errors: SQ_ERR_NULL, SQ_ERR_SHAPE, SQ_ERR_WORKSPACE, SQ_ERR_UNSUPPORTED (under
+ * sq_set_dtype(SQ_BF16)), SQ_ERR_HIP.
+ */
+size_t sq_classifier_workspace_bytes(int N, int Cin, int H, int W, int Cout);
+int sq_classifier_forward(const float *in, const float *w, const float *b, float *means,
+                          float *probs, int N, int Cin, int H, int W, int Cout,
+                          void *workspace, size_t workspace_bytes);
+
+/*
  * Fire layer (section "Convolutional Neural Networks": one squeeze layer and two
  * expand layers).  s = relu(conv1x1(in; w_sq, b_sq)) with Csq layers;
  * out layers [0, Ce1)        = relu(conv1x1(s; w_e1, b_e1)),

@@ -17,8 +17,15 @@ extern "C" {
  * (bit 0 pool1, bit 1 pool4, bit 2 pool8); -1 = by batch size (default). */
 void sq_tune_fuse_pools_f32(int mask);
 
+/* fp32 network and sq_classifier_forward: the last convolution writes plane sums for the average pooling
+ * instead of its map (1), convolution, pooling and softmax run one after the other (0), or the batch size decides
+ * (-1, default: plane sums from eight images on). */
+void sq_tune_fuse_classifier(int on);
+
 /* fp32 fire layer, both expands in one launch behind the minimal-filtering expand3x3:
- * -1 = from three images on (default), 0 = never, 1 + i = with the i-th compiled expand1x1 tiling. */
+ * -1 = from three images on, in the form measured faster for the layer (default), 0 = never,
+ * 1 + i = in the i-th compiled form (0, 1: four-wavefront expand3x3 with expand1x1 tiles of 64x128 / 64x256 behind it;
+ * 2: autonomous-wavefront expand3x3 with the expand1x1 inside its items). */
 void sq_tune_expand_pair(int v);
 
 /* fp32 fire layer, both expands inside the tiles of one direct 3x3 kernel: -3 = never, -2 = up to

@@ -13,7 +13,7 @@ from .binding import (  # noqa: F401
     sq_conv2d_workspace_bytes, sq_conv2d_strided_workspace_bytes, sq_conv_variant_count,
     sq_conv_variant_name, sq_fire_forward, sq_fire_workspace_bytes, sq_maxpool, sq_maxpool_conv2d_forward, sq_softmax,
     sq_profile_begin, sq_profile_end, sq_squeezenet_forward, sq_init, sq_set_dtype, sq_fire_packed_bytes, sq_fire_pack_weights,
-    sq_fire_forward_packed, sq_fire_forward_static, SQ_FIRE_STATIC_SCRATCH_BYTES, sq_packed_weights_bytes, sq_pack_weights, sq_squeezenet_forward_packed,
+    sq_fire_forward_packed, sq_classifier_forward, sq_fire_forward_static, SQ_FIRE_STATIC_SCRATCH_BYTES, sq_packed_weights_bytes, sq_pack_weights, sq_squeezenet_forward_packed,
     sq_blocked_map_bytes, sq_blocked_pack, sq_blocked_unpack, sq_blocked_kernel_bytes, sq_blocked_pack_kernels,
     sq_blocked_conv2d_forward, sq_blocked_kernel7_bytes, sq_blocked_pack_kernels7, sq_blocked_conv7s2_forward, sq_blocked_fire_forward, sq_blocked_pool_conv2d_forward,
     sq_blocked_maxpool, sq_blocked_avgpool_global, sq_squeezenet_bf16_packed_bytes,

@@ -47,6 +47,9 @@ lib.sq_fire_workspace_bytes.argtypes = [_i] * 5
 lib.sq_squeezenet_forward.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _i, _vp, _sz, ctypes.POINTER(_vp)]
 lib.sq_squeezenet_workspace_bytes.restype = _sz
 lib.sq_squeezenet_workspace_bytes.argtypes = [_i]
+lib.sq_classifier_workspace_bytes.restype = _sz
+lib.sq_classifier_workspace_bytes.argtypes = [_i] * 5
+lib.sq_classifier_forward.argtypes = [_vp] * 5 + [_i] * 5 + [_vp, _sz]
 lib.sq_fire_forward_static.argtypes = [_vp] * 8 + [_i] * 7
 lib.sq_fire_packed_bytes.restype = _sz
 lib.sq_fire_packed_bytes.argtypes = [_i, _i]
@@ -266,6 +269,24 @@ def sq_softmax(x):
     _use_current_stream()
     _check(lib.sq_softmax(_dev(x, torch.float32, "x"), _dev(out), N, C), "sq_softmax")
     return out
+
+
+def sq_classifier_forward(x, w, b=None, want_means=False, workspace=None):
+    """relu(conv1x1) -> global average pooling -> softmax.  x [N][Cin][H][W], w [Cout][Cin][1][1] or [Cout][Cin];
+    returns probs [N][Cout], or (probs, means) with want_means."""
+    N, Cin, H, W = x.shape
+    Cout = w.shape[0]
+    if w.numel() != Cout * Cin:
+        raise ValueError("kernel shape does not match the input")
+    if workspace is None:
+        workspace = torch.empty(max(256, int(lib.sq_classifier_workspace_bytes(N, Cin, H, W, Cout))), device=x.device, dtype=torch.uint8)
+    probs = torch.empty((N, Cout), device=x.device, dtype=torch.float32)
+    means = torch.empty((N, Cout), device=x.device, dtype=torch.float32) if want_means else None
+    _use_current_stream()
+    rc = lib.sq_classifier_forward(_dev(x, torch.float32, "x"), _dev(w, torch.float32, "w"), _dev(b, torch.float32, "b"),
+                                   _dev(means), _dev(probs), N, Cin, H, W, Cout, _dev(workspace), workspace.numel())
+    _check(rc, "sq_classifier_forward")
+    return (probs, means) if want_means else probs
 
 
 def sq_fire_workspace_bytes(N, H, W, Csq, Ce3) -> int:

@@ -13,6 +13,12 @@ namespace {
 thread_local hipStream_t g_stream = nullptr;
 thread_local int g_last_hip = 0;
 thread_local int g_dtype = SQ_F32;
+// Whether a 1x1 convolution that is followed directly by global average pooling writes plane sums instead of its map
+// (1), the layers run one after the other (0), or the batch size decides (-1, default: plane sums from eight images
+// on; measured on whole fp32 passes, the two forms are within 3 us of each other at every batch -- at batch 1 the
+// three short launches are 2.8 us faster, at batch 64 the plane sums 2.6 us -- but from there on the convolution's
+// map, 676 KB per image, is neither written nor read).  Tuning hook (sq_tune_fuse_classifier).
+thread_local int g_fuse_classifier = -1;
 }  // namespace
 
 hipStream_t current_stream() { return g_stream; }
@@ -426,6 +432,55 @@ int sq_softmax(const float *in, float *out, int N, int C)
     return softmax(in, out, N, C);
 }
 
+size_t sq_classifier_workspace_bytes(int N, int Cin, int H, int W, int Cout)
+{
+    if (N <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0) return 0;
+    // room for either form: the plane sums of the fused form, or the map and the means of the three separate layers
+    const ConvArgs a = make_args((const void *)256, (const void *)256, nullptr, (float *)256, N, Cin, H, W, Cout, 1, 1, 0, 1, Cout, 0, SQ_F32);
+    const size_t fused = conv_mfma_avg_bytes(a, -1);
+    const size_t plain = align_up((size_t)N * Cout * H * W * sizeof(float), 256) + align_up((size_t)N * Cout * sizeof(float), 256);
+    return align_up(fused > plain ? fused : plain, 256);
+}
+
+int sq_classifier_forward(const float *in, const float *w, const float *b, float *means, float *probs, int N, int Cin, int H,
+                          int W, int Cout, void *workspace, size_t workspace_bytes)
+{
+    if (!in || !w || !probs) return SQ_ERR_NULL;
+    if (N <= 0 || Cin <= 0 || H <= 0 || W <= 0 || Cout <= 0) return SQ_ERR_SHAPE;
+    if (g_dtype != SQ_F32) return SQ_ERR_UNSUPPORTED;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < sq_classifier_workspace_bytes(N, Cin, H, W, Cout))
+        return SQ_ERR_WORKSPACE;
+    ConvArgs a = make_args(in, w, b, (float *)workspace, N, Cin, H, W, Cout, 1, 1, 0, 1, Cout, 0, SQ_F32);
+    AvgLayout lay;
+    set_stage("classifier/conv");
+    int rc = (g_fuse_classifier < 0 ? N >= 8 : g_fuse_classifier) ? conv_mfma_avg(a, -1, (float *)workspace, workspace_bytes, &lay)
+                                                                   : (int)SQ_ERR_UNSUPPORTED;
+    if (rc == SQ_OK) {
+        set_stage("classifier/avgpool+softmax");
+        rc = avg_softmax((const float *)workspace, lay, means, probs, N, Cout, H * W);
+        if (rc != SQ_ERR_UNSUPPORTED) {
+            set_stage("");
+            return rc;
+        }
+    }
+    if (rc != SQ_ERR_UNSUPPORTED) {
+        set_stage("");
+        return rc;
+    }
+    // the three layers one after the other
+    float *map = (float *)workspace;
+    float *mean_buf = means ? means : (float *)((char *)workspace + align_up((size_t)N * Cout * H * W * sizeof(float), 256));
+    if (!(rc = run_conv(a, SQ_ALGO_AUTO))) {
+        set_stage("classifier/avgpool");
+        if (!(rc = avgpool_global(map, mean_buf, N, Cout, H, W))) {
+            set_stage("classifier/softmax");
+            rc = softmax(mean_buf, probs, N, Cout);
+        }
+    }
+    set_stage("");
+    return rc;
+}
+
 size_t sq_fire_workspace_bytes(int N, int H, int W, int Csq, int Ce3)
 {
     if (N <= 0 || H <= 0 || W <= 0 || Csq <= 0 || Ce3 <= 0) return 0;
@@ -559,6 +614,7 @@ size_t sq_squeezenet_workspace_bytes(int N)
 // workgroups to hide nine loads per element; pool8 from batch 64 on).  A call with taps keeps every pooled
 // map, but runs the squeeze with the tiling the fused form would use, so the results are the same bit for bit.
 // The setter is a tuning hook, not part of the public interface.
+extern "C" void sq_tune_fuse_classifier(int on) { g_fuse_classifier = on < 0 ? -1 : on ? 1 : 0; }
 thread_local int g_fuse_pools_f32 = -1;
 extern "C" void sq_tune_fuse_pools_f32(int mask) { g_fuse_pools_f32 = mask; }
 int fuse_pools_f32_policy(int N) { return 1 | (N >= 4 ? 2 : 0) | (N >= 64 ? 4 : 0); }
@@ -683,17 +739,34 @@ static int squeezenet_f32(const void *in, const void *const *params, const void 
             { float *t = cur; cur = nxt; nxt = t; }
         }
     }
+    // conv10 -> global average pooling -> softmax.  The convolution writes per-image plane sums of its results instead
+    // of the 1000 x 13 x 13 map (which is then never written or read), and one more launch turns them into class means
+    // and probabilities.  A caller who wants to see the map gets it from an extra, plain run of the convolution; means
+    // and probabilities come from the same two launches either way, so taps do not change them.
+    const ConvArgs a10 = make_args(cur, params[50], P(51), nxt, N, 512, H, H, 1000, 1, 1, 0, 1, 1000, 0, SQ_F32);
     set_stage("conv10");
-    rc = run_conv(make_args(cur, params[50], P(51), nxt, N, 512, H, H, 1000, 1, 1, 0, 1, 1000, 0, SQ_F32),
-                  SQ_ALGO_AUTO);
-    if (rc) return rc;
-    if ((rc = copy_tap(taps, 12, nxt, n * 1000 * H * H))) return rc;
-    set_stage("avgpool");
-    if ((rc = avgpool_global(nxt, means, N, 1000, H, H))) return rc;
-    if ((rc = copy_tap(taps, 13, means, n * 1000))) return rc;
-    set_stage("softmax");
-    if ((rc = softmax(means, probs, N, 1000))) return rc;
+    bool have_map = false;
+    if (taps && taps[12]) {
+        if ((rc = run_conv(a10, SQ_ALGO_AUTO))) return rc;
+        if ((rc = copy_tap(taps, 12, nxt, n * 1000 * H * H))) return rc;
+        have_map = true;
+    }
+    AvgLayout lay;
+    rc = (g_fuse_classifier < 0 ? N >= 8 : g_fuse_classifier) ? conv_mfma_avg(a10, -1, bufS, n * kBufS * 4, &lay) : (int)SQ_ERR_UNSUPPORTED;
+    if (rc == SQ_OK) {
+        set_stage("avgpool+softmax");
+        if ((rc = avg_softmax(bufS, lay, means, probs, N, 1000, H * H))) return rc;
+    } else if (rc == SQ_ERR_UNSUPPORTED || rc == SQ_ERR_WORKSPACE) {
+        if (!have_map && (rc = run_conv(a10, SQ_ALGO_AUTO))) return rc;
+        set_stage("avgpool");
+        if ((rc = avgpool_global(nxt, means, N, 1000, H, H))) return rc;
+        set_stage("softmax");
+        if ((rc = softmax(means, probs, N, 1000))) return rc;
+    } else {
+        return rc;
+    }
     set_stage("");
+    if ((rc = copy_tap(taps, 13, means, n * 1000))) return rc;
     return copy_tap(taps, 14, probs, n * 1000);
 }
 

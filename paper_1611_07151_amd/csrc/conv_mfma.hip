@@ -45,7 +45,7 @@ using namespace mfma;
 // ---------------------------------------------------------------------------------------
 struct Variant {
     const char *name;
-    int KS, S, BM, BN, MT, CC, PE, NBUF, NT;
+    int KS, S, BM, BN, MT, CC, PE, NBUF, NT, WN;
     bool conv1_type;      // the persistent 7x7/stride-2/three-layer kernel
     bool wino;            // a minimal-filtering F(2x2, 3x3) kernel (BN = tiles of 2x2 pixels)
     bool wino_auto;       // ... the one with autonomous wavefronts (BM x BN per wavefront item)
@@ -53,11 +53,11 @@ struct Variant {
 
 #define SQ_V(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                               \
     {"k" #KS "s" #S "_" #BM "x" #BN "_w" #WM "x" #WN "_m" #MT "_c" #CC "_o" #MINW, KS, S, BM, BN, MT, CC, PE, 2, \
-     WM * WN * 64, false, false, false},
-#define SQ_C(NW) {"k7s2c3_waves" #NW, 7, 2, 96, 32 * NW, 32, 3, 64, 2, 64 * NW, true, false, false},
-#define SQ_C1(NW) {"k7s2c3_waves" #NW "_m32", 7, 2, 32, 32 * NW, 32, 3, 64, 2, 64 * NW, true, false, false},
-#define SQ_W(BM, BT, CC) {"k3s1_f2x2_" #BM "x" #BT "_c" #CC, 3, 1, BM, BT, 32, CC, 0, 2, 256, false, true, false},
-#define SQ_WA(BM, BT) {"k3s1_f2x2a_" #BM "x" #BT, 3, 1, BM, BT, 16, 8, 0, 1, kWinoAutoWaves * 64, false, true, true},
+     WM * WN * 64, WN, false, false, false},
+#define SQ_C(NW) {"k7s2c3_waves" #NW, 7, 2, 96, 32 * NW, 32, 3, 64, 2, 64 * NW, 1, true, false, false},
+#define SQ_C1(NW) {"k7s2c3_waves" #NW "_m32", 7, 2, 32, 32 * NW, 32, 3, 64, 2, 64 * NW, 1, true, false, false},
+#define SQ_W(BM, BT, CC) {"k3s1_f2x2_" #BM "x" #BT "_c" #CC, 3, 1, BM, BT, 32, CC, 0, 2, 256, 1, false, true, false},
+#define SQ_WA(BM, BT) {"k3s1_f2x2a_" #BM "x" #BT, 3, 1, BM, BT, 16, 8, 0, 1, kWinoAutoWaves * 64, 1, false, true, true},
 static_assert(kWinoAutoLayers == 32 && kWinoAutoTiles == 16, "the WA() entry of the variant list names these");
 static_assert(kWinoBM == 64 && kWinoBT == 32 && kWinoCC == 8, "the W() entry of the variant list names these");
 const Variant kVariants[] = {SQ_VARIANT_LIST(SQ_V, SQ_V, SQ_C, SQ_W, SQ_C1, SQ_WA)};
@@ -354,7 +354,7 @@ bool conv_mfma_register_kernels()
     bool ok = true;
     for (int i = 0; i < kNumVariants; ++i)
         for (const KernelSet *ks : {&conv_mfma_kernels_f32[i], &conv_mfma_kernels_bf16[i]})
-            for (KernelFn fn : {ks->plain, ks->tail, ks->fused_e1, ks->pooled}) ok &= allow_big_lds((const void *)fn);
+            for (KernelFn fn : {ks->plain, ks->tail, ks->fused_e1, ks->pooled, ks->avg}) ok &= allow_big_lds((const void *)fn);
     for (int nw : {4, 8})
         for (int full = 0; full < 2; ++full)
             for (int bf = 0; bf < 2; ++bf)
@@ -482,6 +482,55 @@ int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1)
     LaunchScope scope(pk.name, conv_flops(a3) + conv_flops(a1), conv_bytes(a3) + conv_bytes(a1));
     hipLaunchKernelGGL(pk.fn, dim3((unsigned)blocks), dim3(kVariants[v3].NT), std::max(p3.lds_bytes, p1.lds_bytes), current_stream(),
                        p3.kp, p1.kp, (int)p3.blocks);
+    return check_launch();
+}
+
+// 1x1 convolution (+bias, ReLU) whose result is wanted only as per-image plane sums: the averaging form of the
+// tiling the automatic choice would run (variant < 0) or of tiling `variant`.  sums: the table the kernel writes,
+// [lay->ntiles][lay->WN][lay->slots][Cout] floats.  SQ_ERR_UNSUPPORTED where that tiling has no such form.
+static bool plan_avg(const ConvArgs &a, int variant, Plan &pl, int &vi, AvgLayout &lay)
+{
+    if (a.K != 1 || a.S != 1 || a.P != 0 || a.dtype != SQ_F32 || a.pool_H) return false;
+    if (variant >= 0) {
+        if (variant >= kNumVariants || !plan(kVariants[variant], a, pl)) return false;
+        vi = variant;
+    } else {
+        vi = choose_variant(a, pl);
+    }
+    if (vi < 0) return false;
+    const Variant &v = kVariants[vi];
+    if (!kernel_set(v, a.dtype).avg || a.Cin % v.CC != 0) return false;
+    lay.ntiles = pl.kp.ntiles; lay.WN = v.WN; lay.BN = v.BN;
+    lay.slots = (a.Ho * a.Wo + v.BN - 2) / (a.Ho * a.Wo) + 1;
+    return true;
+}
+
+size_t conv_mfma_avg_bytes(const ConvArgs &a, int variant)
+{
+    Plan pl; int vi; AvgLayout lay;
+    if (!plan_avg(a, variant, pl, vi, lay)) return 0;
+    return (size_t)lay.ntiles * lay.WN * lay.slots * a.Cout * sizeof(float);
+}
+
+int conv_mfma_avg(const ConvArgs &a, int variant, float *sums, size_t sums_bytes, AvgLayout *lay)
+{
+    Plan pl; int vi;
+    if (!plan_avg(a, variant, pl, vi, *lay)) return SQ_ERR_UNSUPPORTED;
+    if (sums_bytes < (size_t)lay->ntiles * lay->WN * lay->slots * a.Cout * sizeof(float)) return SQ_ERR_WORKSPACE;
+    const Variant &v = kVariants[vi];
+    KernelFn fn = kernel_set(v, a.dtype).avg;
+    if (!allow_big_lds((const void *)fn)) {
+        const int rc = check_launch();
+        return rc ? rc : SQ_ERR_HIP;
+    }
+    pl.kp.out = sums;
+    pl.kp.avg_slots = lay->slots;
+    static const struct Names {
+        char name[kNumVariants][64];
+        Names() { for (int i = 0; i < kNumVariants; ++i) snprintf(name[i], sizeof(name[i]), "%s+planesums", kVariants[i].name); }
+    } names;
+    LaunchScope scope(names.name[vi], conv_flops(a), conv_bytes(a) - 4.0 * a.N * a.Cout * a.Ho * a.Wo + 4.0 * lay->ntiles * lay->WN * lay->slots * a.Cout);
+    hipLaunchKernelGGL(fn, dim3(pl.blocks, pl.blocks_y), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
     return check_launch();
 }
 

@@ -87,6 +87,7 @@ struct KParams {
     // minimal-filtering kernel with autonomous wavefronts: how its workgroups are shared out over the layer blocks
     // (the first wa_big blocks have wa_cnt + 1 workgroups, the others wa_cnt), and tile groups per workgroup of a
     // block with wa_cnt (q0, remainder r0) or wa_cnt + 1 (q1, r1) workgroups
+    int avg_slots;       // averaging form of the 1x1 kernels: images a pixel tile can touch
     int wa_big, wa_cnt, wa_q0, wa_r0, wa_q1, wa_r1;
     FastDiv dwa0, dwa1;
 };
@@ -213,9 +214,9 @@ __device__ __forceinline__ void st_f32(float *base, uint32_t byte_off, float v)
 typedef void (*KernelFn)(const KParams);
 
 // Kernels of one tiling: plain, input layers not a multiple of CC, fused 1x1 expand, 1x1 with 3x3 stride-2
-// max pooling on the way in.
+// max pooling on the way in, 1x1 writing per-image plane sums instead of its results.
 struct KernelSet {
-    KernelFn plain, tail, fused_e1, pooled;
+    KernelFn plain, tail, fused_e1, pooled, avg;
 };
 extern const KernelSet conv_mfma_kernels_f32[], conv_mfma_kernels_bf16[];
 // Both expands of a fire layer in one launch (expand_pair_kernel): the compiled expand1x1 tilings, each named

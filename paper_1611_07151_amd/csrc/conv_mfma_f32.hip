@@ -15,17 +15,24 @@ template <int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE,
     else return nullptr;
 }
 
+// The averaging form exists for every 1x1 tiling (input layers a multiple of the chunk).
+template <int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW> constexpr KernelFn avg_kernel()
+{
+    if constexpr (KS == 1 && S == 1) return conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false, false, false, true>;
+    else return nullptr;
+}
+
 #define SQ_V(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                                 \
     {conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false>,                       \
      conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, true>, nullptr,               \
-     pooled_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW>()},
+     pooled_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW>(), avg_kernel<KS, S, BM, BN, WM, WN, MT, CC, PE, MINW>()},
 #define SQ_E(KS, S, BM, BN, WM, WN, MT, CC, PE, MINW)                                                 \
     {conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false>,                       \
      conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, true>,                        \
-     conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false, true>, nullptr},
-#define SQ_C(NW) {nullptr, nullptr, nullptr, nullptr},
-#define SQ_W(BM, BT, CC) {conv_wino_kernel<float>, nullptr, nullptr, nullptr},
-#define SQ_WA(BM, BT) {conv_wino_auto_kernel<float>, nullptr, nullptr, nullptr},
+     conv_mfma_kernel<float, KS, S, BM, BN, WM, WN, MT, CC, PE, MINW, false, true>, nullptr, nullptr},
+#define SQ_C(NW) {nullptr, nullptr, nullptr, nullptr, nullptr},
+#define SQ_W(BM, BT, CC) {conv_wino_kernel<float>, nullptr, nullptr, nullptr, nullptr},
+#define SQ_WA(BM, BT) {conv_wino_auto_kernel<float>, nullptr, nullptr, nullptr, nullptr},
 const KernelSet conv_mfma_kernels_f32[] = {SQ_VARIANT_LIST(SQ_V, SQ_E, SQ_C, SQ_W, SQ_C, SQ_WA)};
 
 #define SQ_PAIR(BM, BN, WM, WN, MT, CC)                                                                 \

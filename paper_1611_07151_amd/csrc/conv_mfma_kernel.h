@@ -51,8 +51,14 @@ namespace mfma {
 // conv_mfma_tile is the work of one workgroup (tile number `block` of the launch), conv_mfma_kernel the
 // kernel that consists of nothing else; the expand pair kernel (conv_wino_kernel.h) runs the same tiles
 // behind its own.
+// AVG (1x1 kernels only): instead of the results themselves the tile writes, per output layer, the sums of its
+// ReLU'd results over the pixels of each image it touches -- the first half of a global average pooling (section
+// "Pooling and Softmax") that follows the convolution directly, so that the convolution's map is never written.
+// p.out is then a table [pixel tile][WN][p.avg_slots][Cout]: slot s of pixel tile pt holds the sum over the pixels of
+// image (first image of the tile) + s among the BN / WN pixels of wavefront column wn; whoever adds the slots of an
+// image up (avg_softmax_kernel) has the plane sums.  Slots without pixels hold zero.
 template <typename TIN, int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, bool TAIL, bool E1 = false,
-          bool POOL = false>
+          bool POOL = false, bool AVG = false>
 __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block)
 {
     using M = Mfma<MT>;
@@ -72,6 +78,7 @@ __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block
     static_assert(!POINTWISE || (NT % BN == 0 && BN % 64 == 0 && (CC * BN) % NT == 0), "pointwise staging split");
     static_assert(!E1 || (KS % 2 == 1 && S == 1 && !TAIL), "fused expand needs a centre tap");
     static_assert(!POOL || (POINTWISE && !TAIL && !E1), "pooling on the way in is for plain 1x1 kernels");
+    static_assert(!AVG || (POINTWISE && !E1 && !POOL), "plane sums are for plain 1x1 kernels");
     constexpr int ESZ = (int)sizeof(TIN);
     constexpr int LD1 = CC + 1;                       // LDS row stride of the 1x1 kernels
     constexpr int W1BUF = E1 ? BM * LD1 : 0;
@@ -379,6 +386,34 @@ __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block
         __syncthreads();
     }
 
+    if constexpr (AVG) {
+        // ---- epilogue of the averaging form: per-image sums over this wavefront's pixels ----
+        const float lowest = p.relu ? 0.f : -__builtin_inff();
+        const int imgA = fdiv(P0, p.dHoWo);
+        int slot_of[TN];
+#pragma unroll
+        for (int y = 0; y < TN; ++y) {
+            const int pp = P0 + wn * (BN / WN) + y * MT + li;
+            slot_of[y] = pp < p.PT ? fdiv(pp, p.dHoWo) - imgA : -1;
+        }
+        float *part = p.out + (size_t)(pt * WN + wn) * p.avg_slots * p.Cout;
+        for (int s = 0; s < p.avg_slots; ++s) {
+#pragma unroll
+            for (int x = 0; x < TM; ++x)
+#pragma unroll
+                for (int r = 0; r < M::NR; ++r) {
+                    float v = 0.f;
+#pragma unroll
+                    for (int y = 0; y < TN; ++y) v += slot_of[y] == s ? fmaxf(acc[x][y][r], lowest) : 0.f;
+#pragma unroll
+                    for (int off = MT / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+                    const int mu = mw + x * MT + M::row_reg(r) + lrow;
+                    if (li == 0 && mu < p.Cout) part[s * p.Cout + mu] = v;
+                }
+        }
+        return;
+    }
+
     // ---- epilogue: ReLU, store into layers [coff, coff+Cout) ------------------------------
     // An accumulator register holds MT consecutive pixels across lanes, so each store
     // instruction writes contiguous runs: uniform layer part in the scalar offset, per-lane
@@ -421,10 +456,10 @@ __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block
 }
 
 template <typename TIN, int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW, bool TAIL, bool E1 = false,
-          bool POOL = false>
+          bool POOL = false, bool AVG = false>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KParams p)
 {
-    conv_mfma_tile<TIN, KS, S, BM, BN, WM, WN, MT, CC, PE, TAIL, E1, POOL>(p, (int)blockIdx.x);
+    conv_mfma_tile<TIN, KS, S, BM, BN, WM, WN, MT, CC, PE, TAIL, E1, POOL, AVG>(p, (int)blockIdx.x);
 }
 
 }  // namespace mfma

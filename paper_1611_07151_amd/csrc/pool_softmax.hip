@@ -165,7 +165,91 @@ __global__ __launch_bounds__(256) void softmax_kernel(const float *__restrict__ 
     for (int c = t; c < C; c += 256) y[c] = expf(x[c] - mx) * inv;
 }
 
+// Second half of "1x1 convolution -> global average pooling -> softmax" (section "Pooling and Softmax") when the
+// convolution has written per-image plane sums per pixel tile (conv_mfma_kernel.h, averaging form): one workgroup per
+// image adds the slots that belong to its image, divides by the plane size, optionally writes the means, and applies
+// the max-shifted softmax.  sums: [pixel tile][WN][slots][C]; pixel tile pt covers pixels [pt * BN, (pt + 1) * BN) of the
+// batch-flattened pixel index n * HW + pixel, and its slot s belongs to image (pt * BN) / HW + s.  C <= 256 * kAvgPer.
+constexpr int kAvgPer = 8, kAvgTerms = 16;
+__global__ __launch_bounds__(256) void avg_softmax_kernel(const float *__restrict__ sums, float *__restrict__ means,
+                                                          float *__restrict__ probs, int C, int HW, int BN, int WN, int slots)
+{
+    __shared__ float red[4];
+    __shared__ float bcast;
+    const int n = blockIdx.x, t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const int t0 = (n * HW) / BN, t1 = (n * HW + HW - 1) / BN;
+    const float inv_hw = 1.f / (float)HW;
+    // The (pixel tile, wavefront column) terms of this image, in the order they are added.  Up to kAvgTerms of them
+    // have their table offsets worked out once (they are the same for every thread) and their loads issued together;
+    // an image spread over more terms takes the plain loop.
+    const int nterms = (t1 - t0 + 1) * WN;
+    uint32_t off[kAvgTerms];
+#pragma unroll
+    for (int k = 0; k < kAvgTerms; ++k) {
+        const int pt = t0 + k / WN, wn = k - (k / WN) * WN;
+        const int slot = n - (pt * BN) / HW;
+        off[k] = k < nterms ? (uint32_t)__builtin_amdgcn_readfirstlane(((pt * WN + wn) * slots + slot) * C) : 0u;
+    }
+    float v[kAvgPer];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < kAvgPer; ++j) {
+        const int c = t + 256 * j;
+        float s = 0.f;
+        if (c < C) {
+            if (nterms <= kAvgTerms) {
+                float term[kAvgTerms];
+#pragma unroll
+                for (int k = 0; k < kAvgTerms; ++k) term[k] = k < nterms ? sums[off[k] + c] : 0.f;
+#pragma unroll
+                for (int k = 0; k < kAvgTerms; ++k) s += term[k];
+            } else {
+                for (int pt = t0; pt <= t1; ++pt) {
+                    const int slot = n - (pt * BN) / HW;
+                    for (int wn = 0; wn < WN; ++wn) s += sums[((size_t)(pt * WN + wn) * slots + slot) * C + c];
+                }
+            }
+            s *= inv_hw;
+            if (means) means[(size_t)n * C + c] = s;
+            mx = fmaxf(mx, s);
+        }
+        v[j] = s;
+    }
+    mx = wave_max(mx);
+    if (lane == 0) red[wv] = mx;
+    __syncthreads();
+    if (t == 0) bcast = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    mx = bcast;
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < kAvgPer; ++j) {
+        v[j] = t + 256 * j < C ? expf(v[j] - mx) : 0.f;
+        s += v[j];
+    }
+    s = wave_sum(s);
+    __syncthreads();
+    if (lane == 0) red[wv] = s;
+    __syncthreads();
+    if (t == 0) bcast = (red[0] + red[1]) + (red[2] + red[3]);
+    __syncthreads();
+    const float inv = 1.f / bcast;
+#pragma unroll
+    for (int j = 0; j < kAvgPer; ++j)
+        if (t + 256 * j < C) probs[(size_t)n * C + t + 256 * j] = v[j] * inv;
+}
+
 }  // namespace
+
+int avg_softmax(const float *sums, const AvgLayout &lay, float *means, float *probs, int N, int C, int HW)
+{
+    if (C > 256 * kAvgPer || (long long)N * HW >= (1ll << 31) || (long long)lay.ntiles * lay.WN * lay.slots * C >= (1ll << 31))
+        return SQ_ERR_UNSUPPORTED;
+    LaunchScope scope("planesums+softmax", 0.0, 4.0 * ((double)lay.ntiles * lay.WN * lay.slots * C + 2.0 * N * C));
+    hipLaunchKernelGGL(avg_softmax_kernel, dim3((unsigned)N), dim3(256), 0, current_stream(), sums, means, probs, C, HW, lay.BN,
+                       lay.WN, lay.slots);
+    return check_launch();
+}
 
 int maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int S)
 {

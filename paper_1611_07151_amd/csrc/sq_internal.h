@@ -69,6 +69,16 @@ int conv_mfma(const ConvArgs &a, int variant);
 // measured choice for a3 is the minimal-filtering kernel and a compiled expand1x1 tiling fits; SQ_ERR_UNSUPPORTED
 // otherwise.
 int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1);
+// 1x1 convolution (+bias, ReLU) followed directly by a global average pooling: the convolution kernel writes per-image
+// plane sums of its results (a table of conv_mfma_avg_bytes() bytes, laid out as AvgLayout says) instead of the results;
+// avg_softmax() adds them up, divides by the plane size and applies softmax.  variant < 0 = the tiling of the
+// automatic choice.  SQ_ERR_UNSUPPORTED / 0 bytes where that tiling has no averaging form.
+struct AvgLayout {
+    int ntiles, WN, slots, BN;
+};
+size_t conv_mfma_avg_bytes(const ConvArgs &a, int variant);
+int conv_mfma_avg(const ConvArgs &a, int variant, float *sums, size_t sums_bytes, AvgLayout *lay);
+int avg_softmax(const float *sums, const AvgLayout &lay, float *means, float *probs, int N, int C, int HW);
 // The tiling conv_mfma(a, -1) runs, or -1.
 int conv_mfma_choice(const ConvArgs &a);
 // Fused expand of a fire layer: the 3x3 convolution a3 and a 1x1 convolution of the same

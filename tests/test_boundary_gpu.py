@@ -205,3 +205,62 @@ def test_two_host_threads_on_two_streams(sq):
     assert not errors, errors
     for i in range(2):
         assert_close(results[i], cases[i][1], FP32_TOL, f"thread {i}")
+
+
+@pytest.mark.parametrize("n,cin,h,w,cout", [(1, 512, 13, 13, 1000), (3, 512, 13, 13, 1000), (64, 512, 13, 13, 1000), (5, 64, 7, 9, 40),
+                                            (2, 32, 20, 20, 24), (130, 16, 3, 3, 8), (2, 48, 1, 1, 10), (7, 16, 13, 13, 2100)])
+def test_classifier_matches_oracle_in_both_forms(sq, n, cin, h, w, cout):
+    """1x1 convolution + ReLU -> global average pooling -> softmax as one call: with the convolution writing plane
+    sums (its map never exists) and as three layers; both against the oracle's three functions."""
+    rng = np.random.default_rng(n * 1000 + cout)
+    x = synth.uniform01(rng, (n, cin, h, w))
+    wt, b = synth.conv_params(rng, cout, cin, 1)
+    m_ref = oracle.avgpool_global(oracle.conv2d(x, wt, b, 1, 0, True))
+    p_ref = oracle.softmax(m_ref)
+    xd, wd, bd = dev(x), dev(wt), dev(b)
+    try:
+        for fused in (1, 0):
+            sq.lib.sq_tune_fuse_classifier(fused)
+            sq.sq_profile_begin(16)
+            probs, means = sq.sq_classifier_forward(xd, wd, bd, want_means=True)
+            names = [r["name"] for r in sq.sq_profile_end()]
+            assert_close(means, m_ref, FP32_TOL, f"means fused={fused}")
+            assert_close(probs, p_ref, FP32_TOL, f"probs fused={fused}")
+            assert np.abs(probs.double().sum(1).cpu().numpy() - 1).max() < 1e-5
+            only = sq.sq_classifier_forward(xd, wd, bd)
+            assert torch.equal(only, probs)
+            if fused and cin % 64 == 0 and cout <= 2048:
+                assert any("+planesums" in k for k in names) and not any("|avgpool" in k for k in names), names
+            if not fused:
+                assert not any("planesums" in k for k in names), names
+        # no bias
+        sq.lib.sq_tune_fuse_classifier(-1)
+        p0 = sq.sq_classifier_forward(xd, wd, None)
+        assert_close(p0, oracle.softmax(oracle.avgpool_global(oracle.conv2d(x, wt, None, 1, 0, True))), FP32_TOL, "no bias")
+    finally:
+        sq.lib.sq_tune_fuse_classifier(-1)
+
+
+def test_network_classifier_fusion_does_not_change_what_taps_show(sq):
+    """The network's last three layers run as convolution-with-plane-sums + one more launch; a call that asks for the
+    stage maps gets conv10's map from an extra plain run, and the same means and probabilities bit for bit."""
+    cfg = synth.config_squeezenet(seed=12, n=9)
+    params = [dev(p) for p in cfg["params"]]
+    x = dev(cfg["x"])
+    sq.sq_profile_begin(64)
+    plain = sq.sq_squeezenet_forward(x, params)
+    names = [r["name"] for r in sq.sq_profile_end()]
+    assert any(k.startswith("conv10|") and k.endswith("+planesums") for k in names), names
+    assert any(k == "avgpool+softmax|planesums+softmax" for k in names) and not any(k.startswith("avgpool|") for k in names), names
+    probs, taps = sq.sq_squeezenet_forward(x, params, want_taps=True)
+    assert torch.equal(plain, probs) and torch.equal(taps["probs"], probs)
+    ref_p, ref_t = oracle.squeezenet(cfg["x"][4:5], cfg["params"], want_taps=True)
+    assert_close(taps["conv10"][4:5], ref_t["conv10"], FP32_TOL, "conv10 map")
+    assert_close(taps["means"][4:5], ref_t["means"], FP32_TOL, "means")
+    assert_close(probs[4:5], ref_p, FP32_TOL, "probs")
+    try:
+        sq.lib.sq_tune_fuse_classifier(0)
+        unfused = sq.sq_squeezenet_forward(x, params)
+    finally:
+        sq.lib.sq_tune_fuse_classifier(-1)
+    assert_close(unfused, probs.cpu().numpy(), 1e-6, "three separate layers")

@@ -514,9 +514,10 @@ def test_benchmark_configuration_runs_the_kernels_it_reports(sq):
     assert sum("/e1+e3|k3s1_f2x2" in n and "+k1" in n for n in names) == 8, names
     assert "kernel transform|f2x2_kernel_transform" in names
     assert not any("direct" in k for k in kernels), kernels
-    # conv1, eight fire layers of two launches (squeeze; both expands), conv10, global average pooling, softmax,
+    # conv1, eight fire layers of two launches (squeeze; both expands), conv10 writing plane sums, average + softmax,
     # kernel transform; the three max-pooling layers run inside the squeeze layers that read them
-    assert len(names) == 21 and not any("maxpool" in k for k in kernels), names
+    assert len(names) == 20 and not any("maxpool" in k for k in kernels), names
+    assert "avgpool+softmax|planesums+softmax" in names and any(n.startswith("conv10|") and n.endswith("+planesums") for n in names)
 
 
 # ----------------------------------------------------------------- workload 5

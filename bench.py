@@ -46,6 +46,18 @@ HBM_PEAK_GBS = 8000.0
 FLOP_PER_IMAGE = 2 * 832_667_936  # 2 x multiply-accumulates of the 26 convolutions
 
 
+def kernel_sources_hash():
+    """SHA-256 over the kernel sources (csrc/*.hip, *.h, *.inc), in name order: identifies what the library was built from."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_1611_07151_amd", "csrc", "*"))):
+        if path.endswith((".hip", ".h", ".inc")):
+            h.update(os.path.basename(path).encode())
+            h.update(open(path, "rb").read())
+    return h.hexdigest()
+
+
 def power_sensor():
     """Path of the GPU's power reading (hwmon, microwatts), or None."""
     import glob
@@ -78,6 +90,82 @@ def sample_power(path, seconds, work, settle=0.0):
     return dict(mean_w=sum(vals) / len(vals), samples=len(vals))
 
 
+def layer_sweep(sq, synth, torch, mode, B, net="squeezenet", only=None):
+    """Times every convolution shape of a network on its own at batch B; mode "f32" / "bf16" (NCHW inputs of that
+    type, fp32 accumulate and output) or "blocked" (the reduced-precision kernels on blocked bfloat16 maps)."""
+    dt_in = torch.bfloat16 if mode == "bf16" else torch.float32
+    esz = 2 if mode == "bf16" else 4
+    out_note = "bfloat16 maps and kernels, fp32 accumulate" if mode == "blocked" else f"{mode} inputs, fp32 accumulate/output"
+    gen = torch.Generator(device="cuda").manual_seed(4)
+    layers, total_flop, total_us, total_bytes = {}, 0.0, 0.0, 0.0
+    net_layers = synth.conv_layers() if net == "squeezenet" else synth.second_network_layers()
+    if only:
+        net_layers = [l for l in net_layers if only in l[0]]
+    for name, cin, cout, k, s_, p_, h in net_layers:
+        ho = (h + 2 * p_ - k) // s_ + 1
+        if mode == "blocked":
+            # the same shape through the reduced-precision kernels: blocked bfloat16 in and out, kernels packed ahead
+            xf = torch.randn((B, cin, h, h), device="cuda", generator=gen)
+            wf = torch.randn((cout, cin, k, k), device="cuda", generator=gen) * (2.0 / (cin * k * k)) ** 0.5
+            b = torch.rand(cout, device="cuda", generator=gen) * 0.2 - 0.1
+            if k == 7:
+                wp = sq.sq_blocked_pack_kernels7(wf)
+                run = lambda: sq.sq_blocked_conv7s2_forward(xf, wp, b, cout, p_, True, out=outm)
+                in_bytes = 4.0 * B * cin * h * h
+            elif sq.lib.sq_blocked_kernel_bytes(cout, cin, k) and cin % 16 == 0 and k in (1, 3, 5) and s_ == 1 and p_ == k // 2:
+                xm = sq.sq_blocked_pack(xf)
+                wp = sq.sq_blocked_pack_kernels(wf)
+                run = lambda: sq.sq_blocked_conv2d_forward(xm, wp, b, cin, cout, k, p_, True, out=outm)
+                in_bytes = 2.0 * B * cin * h * h
+            else:
+                continue                      # a shape the blocked kernels do not cover
+            outm = torch.empty((B, (cout + 7) // 8, ho, ho, 8), device="cuda", dtype=torch.bfloat16)
+            for _ in range(3):
+                run()
+            sq.sq_profile_begin(64)
+            for _ in range(10):
+                run()
+            recs = sq.sq_profile_end()
+            us = sum(r["ms"] for r in recs) / 10 * 1e3
+            flop = 2.0 * B * cout * ho * ho * cin * k * k
+            byts = in_bytes + 2.0 * cout * cin * k * k + 2.0 * B * cout * ho * ho
+            layers[name] = dict(us=round(us, 1), tflops=round(flop / us / 1e6, 1), gbs=round(byts / us / 1e3),
+                                kernel=recs[0]["name"].split("|")[1])
+            total_flop += flop
+            total_us += us
+            total_bytes += byts
+            del xf, wf, outm
+            continue
+        x = torch.randn((B, cin, h, h), device="cuda", generator=gen).to(dt_in)
+        w = (torch.randn((cout, cin, k, k), device="cuda", generator=gen) * (2.0 / (cin * k * k)) ** 0.5).to(dt_in)
+        b = torch.rand(cout, device="cuda", generator=gen) * 0.2 - 0.1
+        out = torch.empty((B, cout, ho, ho), device="cuda")
+        scratch = torch.empty(max(256, sq.sq_conv2d_workspace_bytes(cin, cout, k, s_, p_),
+                                  sq.sq_conv2d_strided_workspace_bytes(B, cin, h, h, cout, k, s_, p_)), device="cuda",
+                              dtype=torch.uint8)
+        for _ in range(3):
+            sq.sq_conv2d_forward_ws(x, w, b, s_, p_, True, out=out, workspace=scratch)
+        sq.sq_profile_begin(64)
+        for _ in range(10):
+            sq.sq_conv2d_forward_ws(x, w, b, s_, p_, True, out=out, workspace=scratch)
+        recs = sq.sq_profile_end()
+        us = sum(r["ms"] for r in recs) / 10 * 1e3   # kernel transform included where one runs
+        flop = 2.0 * B * cout * ho * ho * cin * k * k
+        byts = esz * (B * cin * h * h + cout * cin * k * k) + 4.0 * B * cout * ho * ho
+        layers[name] = dict(us=round(us, 1), tflops=round(flop / us / 1e6, 1), gbs=round(byts / us / 1e3),
+                            kernel=max(recs, key=lambda r: r["ms"])["name"].split("|")[1])
+        total_flop += flop
+        total_us += us
+        total_bytes += byts
+        del x, w, out
+    return {"metric": f"per-layer convolution sweep, batch {B}, {out_note}",
+            "value": round(total_flop / total_us / 1e6, 2), "unit": "TFLOP/s (all layers)",
+            "gbs_all_layers": round(total_bytes / total_us / 1e3),
+            "n_gpus": 1, "dtype": "bf16" if mode == "blocked" else mode, "data": "synthetic",
+            "config": {"workload": f"{len(net_layers)} convolution shapes ({net}) at batch {B}"},
+            "total_us": round(total_us, 1), "layers": layers}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -85,6 +173,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--calibrate-copy", action="store_true")
+    ap.add_argument("--print-kernel-hash", action="store_true", help="print the hash of the kernel sources and exit")
     ap.add_argument("--layer-sweep", choices=["f32", "bf16", "blocked"], default=None,
                     help="instead of the network: time every convolution shape on its own at --batch "
                          "(workload 5 is --layer-sweep bf16 --batch 256) and print one JSON line; "
@@ -97,9 +186,14 @@ def main() -> int:
                     help="length of each power-sampling window (0 = leave the energy measurement out)")
     ap.add_argument("--skip-reduced", action="store_true", help="leave the reduced-precision (bf16) network out")
     ap.add_argument("--skip-batch1", action="store_true", help="leave the batch-1 timing out (for profiler runs)")
+    ap.add_argument("--skip-sweep", action="store_true",
+                    help="leave the per-layer sweep at batch 256 with bfloat16 inputs (workload 5) out")
     ap.add_argument("--cpu-sample", type=int, default=64,
                     help="images of the workload the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
+    if args.print_kernel_hash:
+        print(kernel_sources_hash())
+        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (images are independent, so more GPUs "
               "would each take a slice of the batch with no communication); use --gpus 1",
@@ -136,75 +230,7 @@ def main() -> int:
         idle_w = sample_power(sensor, min(2.0, args.energy_seconds), lambda: time.sleep(0.01))
 
     if args.layer_sweep:
-        dt_in = torch.bfloat16 if args.layer_sweep == "bf16" else torch.float32
-        esz = 2 if args.layer_sweep == "bf16" else 4
-        out_note = "bfloat16 maps and kernels, fp32 accumulate" if args.layer_sweep == "blocked" else \
-            f"{args.layer_sweep} inputs, fp32 accumulate/output"
-        gen = torch.Generator(device="cuda").manual_seed(4)
-        layers, total_flop, total_us = {}, 0.0, 0.0
-        net_layers = synth.conv_layers() if args.net == "squeezenet" else synth.second_network_layers()
-        if args.only:
-            net_layers = [l for l in net_layers if args.only in l[0]]
-        for name, cin, cout, k, s_, p_, h in net_layers:
-            ho = (h + 2 * p_ - k) // s_ + 1
-            if args.layer_sweep == "blocked":
-                # the same shape through the reduced-precision kernels: blocked bfloat16 in and out, kernels packed ahead
-                xf = torch.randn((B, cin, h, h), device="cuda", generator=gen)
-                wf = torch.randn((cout, cin, k, k), device="cuda", generator=gen) * (2.0 / (cin * k * k)) ** 0.5
-                b = torch.rand(cout, device="cuda", generator=gen) * 0.2 - 0.1
-                if k == 7:
-                    wp = sq.sq_blocked_pack_kernels7(wf)
-                    run = lambda: sq.sq_blocked_conv7s2_forward(xf, wp, b, cout, p_, True, out=outm)
-                    in_bytes = 4.0 * B * cin * h * h
-                elif sq.lib.sq_blocked_kernel_bytes(cout, cin, k) and cin % 16 == 0 and k in (1, 3, 5) and s_ == 1 and p_ == k // 2:
-                    xm = sq.sq_blocked_pack(xf)
-                    wp = sq.sq_blocked_pack_kernels(wf)
-                    run = lambda: sq.sq_blocked_conv2d_forward(xm, wp, b, cin, cout, k, p_, True, out=outm)
-                    in_bytes = 2.0 * B * cin * h * h
-                else:
-                    continue                      # a shape the blocked kernels do not cover
-                outm = torch.empty((B, (cout + 7) // 8, ho, ho, 8), device="cuda", dtype=torch.bfloat16)
-                for _ in range(3):
-                    run()
-                sq.sq_profile_begin(64)
-                for _ in range(10):
-                    run()
-                recs = sq.sq_profile_end()
-                us = sum(r["ms"] for r in recs) / 10 * 1e3
-                flop = 2.0 * B * cout * ho * ho * cin * k * k
-                byts = in_bytes + 2.0 * cout * cin * k * k + 2.0 * B * cout * ho * ho
-                layers[name] = dict(us=round(us, 1), tflops=round(flop / us / 1e6, 1), gbs=round(byts / us / 1e3),
-                                    kernel=recs[0]["name"].split("|")[1])
-                total_flop += flop
-                total_us += us
-                del xf, wf, outm
-                continue
-            x = torch.randn((B, cin, h, h), device="cuda", generator=gen).to(dt_in)
-            w = (torch.randn((cout, cin, k, k), device="cuda", generator=gen) * (2.0 / (cin * k * k)) ** 0.5).to(dt_in)
-            b = torch.rand(cout, device="cuda", generator=gen) * 0.2 - 0.1
-            out = torch.empty((B, cout, ho, ho), device="cuda")
-            scratch = torch.empty(max(256, sq.sq_conv2d_workspace_bytes(cin, cout, k, s_, p_),
-                                      sq.sq_conv2d_strided_workspace_bytes(B, cin, h, h, cout, k, s_, p_)), device="cuda",
-                                  dtype=torch.uint8)
-            for _ in range(3):
-                sq.sq_conv2d_forward_ws(x, w, b, s_, p_, True, out=out, workspace=scratch)
-            sq.sq_profile_begin(64)
-            for _ in range(10):
-                sq.sq_conv2d_forward_ws(x, w, b, s_, p_, True, out=out, workspace=scratch)
-            recs = sq.sq_profile_end()
-            us = sum(r["ms"] for r in recs) / 10 * 1e3   # kernel transform included where one runs
-            flop = 2.0 * B * cout * ho * ho * cin * k * k
-            byts = esz * (B * cin * h * h + cout * cin * k * k) + 4.0 * B * cout * ho * ho
-            layers[name] = dict(us=round(us, 1), tflops=round(flop / us / 1e6, 1), gbs=round(byts / us / 1e3),
-                                kernel=max(recs, key=lambda r: r["ms"])["name"].split("|")[1])
-            total_flop += flop
-            total_us += us
-            del x, w, out
-        print(json.dumps({"metric": f"per-layer convolution sweep, batch {B}, {out_note}",
-                          "value": round(total_flop / total_us / 1e6, 2), "unit": "TFLOP/s (all layers)",
-                          "n_gpus": 1, "dtype": "bf16" if args.layer_sweep == "blocked" else args.layer_sweep, "data": "synthetic",
-                          "config": {"workload": f"{len(net_layers)} convolution shapes ({args.net}) at batch {B}"},
-                          "total_us": round(total_us, 1), "layers": layers}))
+        print(json.dumps(layer_sweep(sq, synth, torch, args.layer_sweep, B, args.net, args.only)))
         return 0
 
     def setup(seed, n):
@@ -245,28 +271,59 @@ def main() -> int:
     for r in recs:
         stage, kernel = r["name"].split("|")
         for table, key in ((kernels, kernel), (stages, stage)):
-            e = table.setdefault(key, dict(launches=0, ms=0.0, flops=0.0, bytes=0.0))
-            for f in ("launches", "ms", "flops", "bytes"):
+            e = table.setdefault(key, dict(launches=0, ms=0.0, flops=0.0, bytes=0.0, mfma_flops=0.0))
+            for f in ("launches", "ms", "flops", "bytes", "mfma_flops"):
                 e[f] += r[f]
     dom_name, dom = max(kernels.items(), key=lambda kv: kv[1]["ms"])
     dom_ms = dom["ms"] / dom["launches"]
     achieved = dom["flops"] / dom["launches"] / (dom_ms * 1e-3) / 1e12
-    traffic = None
+    # HBM bytes per launch of the dominant kernel from the rocprofv3 counter runs summarised under profiles/: only
+    # valid for the kernels they were measured on, so the file carries a hash of the kernel sources and a figure
+    # measured on other sources is not reported
+    traffic, traffic_note = None, "profiles/traffic.json has no entry for this kernel"
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(dom_name)
+        tj = json.load(open(tpath))
+        if tj.get("kernel_sources_sha256") != kernel_sources_hash():
+            traffic_note = "profiles/traffic.json was measured on other kernel sources than the ones built here"
+        elif dom_name in tj.get("bytes_per_launch", {}):
+            traffic, traffic_note = tj["bytes_per_launch"][dom_name], "FETCH_SIZE + WRITE_SIZE per launch, scaled by the copy calibration (profiles/hbm_traffic.md)"
+    executed = dom["mfma_flops"] / dom["launches"] / (dom_ms * 1e-3) / 1e12
     roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=FP32_MFMA_PEAK_TFLOPS,
                     unit="TFLOP/s", frac=round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), traffic=traffic,
+                    traffic_note=traffic_note,
+                    executed_tflops=round(executed, 2), executed_frac=round(executed / FP32_MFMA_PEAK_TFLOPS, 4),
+                    note="achieved/frac count the layer definition's 2 x MACs (algorithmic); executed_* count the "
+                         "operations the kernel's MFMA instructions really issue (padding included; the "
+                         "minimal-filtering part forms 16 products where the definition has 36) = matrix-core utilisation",
                     kernel=dom_name, launches_per_step=dom["launches"] / K,
                     avg_launch_us=round(dom_ms * 1e3, 2),
                     flop_per_launch=dom["flops"] / dom["launches"],
+                    mfma_flop_per_launch=dom["mfma_flops"] / dom["launches"],
                     share_of_gpu_time=round(dom["ms"] / sum(k["ms"] for k in kernels.values()), 3))
+    all_mfma = sum(k["mfma_flops"] for k in kernels.values()) / K
+    all_ms = sum(k["ms"] for k in kernels.values()) / K
     layers = {}
     for name, e in stages.items():
         us = e["ms"] / K * 1e3
         layers[name] = dict(us=round(us, 1),
                             tflops=round(e["flops"] / K / us / 1e6, 1) if e["flops"] else None,
+                            executed_tflops=round(e["mfma_flops"] / K / us / 1e6, 1) if e["flops"] else None,
                             gbs=round(e["bytes"] / K / us / 1e3, 0))
+    # One row per module of the network (a fire layer = its squeeze and both expands; the classifier = conv10, average
+    # pooling and softmax): algorithmic TFLOP/s against the fp32 matrix peak and algorithmic GB/s against the HBM peak.
+    modules = {}
+    for name, e in stages.items():
+        mod = name.split("/")[0] if name.startswith("fire") else "classifier" if name in ("conv10", "avgpool", "softmax", "avgpool+softmax") else name
+        m = modules.setdefault(mod, dict(us=0.0, flops=0.0, bytes=0.0))
+        m["us"] += e["ms"] / K * 1e3
+        m["flops"] += e["flops"] / K
+        m["bytes"] += e["bytes"] / K
+    for m in modules.values():
+        tf, gb = m["flops"] / m["us"] / 1e6, m["bytes"] / m["us"] / 1e3
+        m.update(us=round(m["us"], 1), tflops=round(tf, 1), pct_fp32_mfma_peak=round(100 * tf / FP32_MFMA_PEAK_TFLOPS, 1),
+                 gbs=round(gb), pct_hbm_peak=round(100 * gb / HBM_PEAK_GBS, 1))
+        del m["flops"], m["bytes"]
     # Every launch that does convolution work counts; the squeeze layers behind a max pooling do that pooling
     # while they read their input (kernel names "pool3s2+..."), so the pooling time is in this figure too.
     conv_ms = sum(e["ms"] for e in stages.values() if e["flops"]) / K
@@ -276,13 +333,15 @@ def main() -> int:
     plain_tflops = (B * FLOP_PER_IMAGE - sum(r["flops"] for r in pooling) / K) / (plain_ms * 1e-3) / 1e12
 
     # ---------------------------------------------------------------- batch 1
-    k1, dt1, dt1g, graph_ok = 1, float("nan"), float("nan"), None
+    k1, dt1, dt1g, graph_ok, launches1 = 1, float("nan"), float("nan"), None, None
     if not args.skip_batch1:
         cfg1, x1, params1, ws1, probs1 = setup(2, 1)
         for _ in range(20):
             sq.sq_squeezenet_forward_packed(x1, params1[0], params1[1], workspace=ws1, probs=probs1)
         k1 = max(200, K)
         dt1, _ = timed(x1, params1, ws1, probs1, k1, False)
+        _, recs1 = timed(x1, params1, ws1, probs1, 10, True)
+        launches1 = sum(r["launches"] for r in recs1) // 10
         params1, packed1_32 = params1
         # the same batch-1 pass replayed from a HIP graph (the library call allocates nothing and
         # does not synchronise, so the caller can capture it); checked against the eager result
@@ -404,6 +463,31 @@ def main() -> int:
                    sample=f"first {n} images of the batch-{B} workload, one oracle.squeezenet call "
                           f"({cdt:.1f} s)", gflops=round(n * FLOP_PER_IMAGE / cdt / 1e9, 2),
                    max_scaled_error_gpu_vs_oracle=err)
+        # the paper's own baseline is one image on one core ("sequential"): the batch-1 workload on a single thread
+        threads = oracle.num_threads()
+        cfg_one = synth.config_squeezenet(seed=2, n=1)
+        oracle.set_num_threads(1)
+        try:
+            t0 = time.perf_counter()
+            oracle.squeezenet(cfg_one["x"], cfg_one["params"])
+            sdt = time.perf_counter() - t0
+        finally:
+            oracle.set_num_threads(threads)
+        cpu["single_thread"] = dict(seconds_per_image=round(sdt, 3), images_per_s=round(1.0 / sdt, 3), cores=1,
+                                    gflops=round(FLOP_PER_IMAGE / sdt / 1e9, 3),
+                                    sample="the batch-1 workload (seed 2), one image, one thread")
+
+    # ---------------------------------------------------------------- workload 5: per-layer sweep, batch 256, bf16 inputs
+    sweep = None
+    if not args.skip_sweep:
+        del x, ws
+        torch.cuda.empty_cache()
+        sw = layer_sweep(sq, synth, torch, "bf16", 256)
+        sweep = dict(workload="every convolution shape of the network on its own at batch 256, bfloat16 inputs and kernels "
+                              "(NCHW), fp32 accumulate and output, seed 4",
+                     tflops_all_layers=sw["value"], gbs_all_layers=sw["gbs_all_layers"], total_us=sw["total_us"],
+                     pct_hbm_peak=round(100 * sw["gbs_all_layers"] / HBM_PEAK_GBS, 1),
+                     slowest={k: v for k, v in sorted(sw["layers"].items(), key=lambda kv: -kv[1]["us"])[:3]})
 
     out = {
         "metric": "SqueezeNet v1.0 forward images/sec at batch 64 (conv TFLOP/s and % fp32 MFMA peak beside it)",
@@ -421,10 +505,13 @@ def main() -> int:
         "end_to_end_tflops": round(B * FLOP_PER_IMAGE / (ms_per_step * 1e-3) / 1e12, 2),
         "batch1_images_per_sec": None if args.skip_batch1 else round(k1 / dt1, 1),
         "batch1_ms": None if args.skip_batch1 else round(dt1 / k1 * 1e3, 4),
+        "batch1_launches": launches1,
         "batch1_graph_images_per_sec": None if args.skip_batch1 else round(k1 / dt1g, 1),
         "batch1_graph_matches_eager": graph_ok,
         "ms_per_step_with_events": round(dt_events / K * 1e3, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "energy": energy, "reduced_precision": reduced, "layers": layers,
+        "mfma_utilisation_whole_pass": round(all_mfma / (all_ms * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS, 4),
+        "roofline": roofline, "cpu_baseline": cpu, "energy": energy, "reduced_precision": reduced,
+        "layer_sweep_bf16_batch256": sweep, "modules": modules, "layers": layers,
     }
     print(json.dumps(out))
     return 0

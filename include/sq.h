@@ -478,6 +478,12 @@ int sq_profile_end(void);
 int sq_profile_count(void);
 int sq_profile_get(int index, char *name, int name_cap, long long *launches,
                    double *total_ms, double *flops, double *bytes);
+/* For the same entry: the floating-point operations its launches issued on the matrix cores (2 x the
+ * multiply-accumulates of the MFMA instructions executed: padding of tiles, contraction and layers
+ * included; for the minimal-filtering kernels the products they really form, 16 instead of 36 per input
+ * layer and 2 x 2 pixels).  Divided by the time this is matrix-core utilisation, where flops / time is
+ * the algorithmic rate.  0 for kernels without MFMA instructions. */
+int sq_profile_get_mfma_flops(int index, double *mfma_flops);
 
 #ifdef __cplusplus
 }

@@ -84,6 +84,7 @@ lib.sq_squeezenet_bf16_workspace_bytes.argtypes = [_i]
 lib.sq_squeezenet_forward_bf16.argtypes = [_vp, _i, ctypes.POINTER(_vp), _vp, _vp, _i, _vp, _sz, ctypes.POINTER(_vp)]
 
 lib.sq_profile_begin.argtypes = [_i]
+lib.sq_profile_get_mfma_flops.argtypes = [_i, ctypes.POINTER(ctypes.c_double)]
 lib.sq_profile_get.argtypes = [_i, ctypes.c_char_p, _i, ctypes.POINTER(ctypes.c_longlong),
                                ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                ctypes.POINTER(ctypes.c_double)]
@@ -647,7 +648,7 @@ def sq_profile_begin(max_launches: int = 4096) -> None:
 
 
 def sq_profile_end():
-    """Returns a list of dicts: name ("stage|kernel"), launches, ms, flops, bytes."""
+    """Returns a list of dicts: name ("stage|kernel"), launches, ms, flops, bytes, mfma_flops."""
     _check(lib.sq_profile_end(), "sq_profile_end")
     out = []
     for i in range(lib.sq_profile_count()):
@@ -656,6 +657,8 @@ def sq_profile_end():
         fl, by = ctypes.c_double(), ctypes.c_double()
         _check(lib.sq_profile_get(i, name, 128, ctypes.byref(n), ctypes.byref(ms), ctypes.byref(fl),
                                   ctypes.byref(by)), "sq_profile_get")
+        mf = ctypes.c_double()
+        _check(lib.sq_profile_get_mfma_flops(i, ctypes.byref(mf)), "sq_profile_get_mfma_flops")
         out.append(dict(name=name.value.decode(), launches=n.value, ms=ms.value, flops=fl.value,
-                        bytes=by.value))
+                        bytes=by.value, mfma_flops=mf.value))
     return out

@@ -78,12 +78,12 @@ struct ProfRecord {
     hipEvent_t start, stop;
     const char *kernel;
     const char *stage;
-    double flops, bytes;
+    double flops, bytes, mfma_flops;
 };
 struct ProfEntry {
     char name[96];
     long long launches;
-    double ms, flops, bytes;
+    double ms, flops, bytes, mfma_flops;
 };
 thread_local ProfRecord *g_prof = nullptr;
 thread_local int g_prof_cap = 0, g_prof_used = 0;
@@ -94,12 +94,12 @@ thread_local int g_num_entries = 0;
 
 void set_stage(const char *stage) { g_stage = stage ? stage : ""; }
 
-LaunchScope::LaunchScope(const char *kernel, double flops, double bytes) : slot(-1)
+LaunchScope::LaunchScope(const char *kernel, double flops, double bytes, double mfma_flops) : slot(-1)
 {
     if (!g_prof || g_prof_used >= g_prof_cap) return;
     slot = g_prof_used++;
     ProfRecord &r = g_prof[slot];
-    r.kernel = kernel; r.stage = g_stage; r.flops = flops; r.bytes = bytes;
+    r.kernel = kernel; r.stage = g_stage; r.flops = flops; r.bytes = bytes; r.mfma_flops = mfma_flops < 0 ? flops : mfma_flops;
     (void)hipEventRecord(r.start, g_stream);
 }
 
@@ -318,9 +318,10 @@ int sq_profile_end(void)
             if (g_num_entries == 128) continue;
             ++g_num_entries;
             snprintf(g_entries[e].name, sizeof(g_entries[e].name), "%s", name);
-            g_entries[e].launches = 0; g_entries[e].ms = g_entries[e].flops = g_entries[e].bytes = 0;
+            g_entries[e].launches = 0; g_entries[e].ms = g_entries[e].flops = g_entries[e].bytes = g_entries[e].mfma_flops = 0;
         }
         g_entries[e].launches += 1; g_entries[e].ms += ms; g_entries[e].flops += r.flops; g_entries[e].bytes += r.bytes;
+        g_entries[e].mfma_flops += r.mfma_flops;
     }
     for (int i = 0; i < g_prof_cap; ++i) {
         (void)hipEventDestroy(g_prof[i].start);
@@ -344,6 +345,14 @@ int sq_profile_get(int index, char *name, int name_cap, long long *launches, dou
     *total_ms = g_entries[index].ms;
     *flops = g_entries[index].flops;
     *bytes = g_entries[index].bytes;
+    return SQ_OK;
+}
+
+int sq_profile_get_mfma_flops(int index, double *mfma_flops)
+{
+    if (index < 0 || index >= g_num_entries) return SQ_ERR_SHAPE;
+    if (!mfma_flops) return SQ_ERR_NULL;
+    *mfma_flops = g_entries[index].mfma_flops;
     return SQ_OK;
 }
 

@@ -53,7 +53,7 @@ int conv_direct(const ConvArgs &a)
     size_t blocks = (total + 255) / 256;
     if (blocks > (1u << 20)) blocks = 1u << 20;
     dim3 grid((unsigned)blocks), block(256);
-    LaunchScope scope("conv_direct", conv_flops(a), conv_bytes(a));
+    LaunchScope scope("conv_direct", conv_flops(a), conv_bytes(a), 0.0);   // vector-ALU arithmetic, no MFMA
     if (a.dtype == SQ_F32) {
         hipLaunchKernelGGL(conv_direct_kernel<float>, grid, block, 0, current_stream(),
                            (const float *)a.in, (const float *)a.w, a.b, a.out, a.N, a.Cin, a.H,

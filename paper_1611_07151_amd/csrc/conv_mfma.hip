@@ -216,6 +216,21 @@ struct PooledNames {
 };
 const PooledNames kPooledNames;
 
+// Floating-point operations the MFMA instructions of a launch of tiling v execute (all padding included).
+double mfma_flops_of(const Variant &v, const Plan &pl, const ConvArgs &a, bool e1)
+{
+    const KParams &k = pl.kp;
+    if (v.conv1_type) {
+        // tiles of 32 pixels, 74 steps of two k-values, all layer blocks of 32 the workgroups compute
+        const double layer_rows = v.BM == 32 ? 32.0 * k.mtiles : 96.0;
+        return 2.0 * k.ntiles * 32.0 * layer_rows * 148.0;
+    }
+    if (v.wino_auto) return 2.0 * k.mtiles * k.ntiles * (double)kWinoAutoLayers * kWinoAutoTiles * a.Cin * (e1 ? 20.0 : 16.0);
+    if (v.wino) return 2.0 * k.mtiles * k.ntiles * (double)v.BM * v.BN * 16.0 * k.nchunks * v.CC;
+    const double kk = v.KS * v.KS;
+    return 2.0 * k.mtiles * k.ntiles * (double)v.BM * v.BN * k.nchunks * v.CC * (kk + (e1 ? 1.0 : 0.0));
+}
+
 int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullptr)
 {
     const Variant &v = kVariants[vi];
@@ -238,7 +253,7 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
         const int rc = conv_prepare_kernels(&job, 1, a.dtype);
         if (rc) return rc;
     }
-    LaunchScope scope(a.pool_H ? kPooledNames.name[vi] : v.name, flops, bytes);
+    LaunchScope scope(a.pool_H ? kPooledNames.name[vi] : v.name, flops, bytes, mfma_flops_of(v, pl, a, e1 != nullptr));
     hipLaunchKernelGGL(fn, dim3(pl.blocks, pl.blocks_y), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
     return check_launch();
 }
@@ -479,7 +494,9 @@ int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1)
         const int rc = conv_prepare_kernels(&job, 1, a3.dtype);
         if (rc) return rc;
     }
-    LaunchScope scope(pk.name, conv_flops(a3) + conv_flops(a1), conv_bytes(a3) + conv_bytes(a1));
+    const bool folded = !pk.e1_variant;
+    LaunchScope scope(pk.name, conv_flops(a3) + conv_flops(a1), conv_bytes(a3) + conv_bytes(a1),
+                      mfma_flops_of(kVariants[v3], p3, a3, folded) + (folded ? 0.0 : mfma_flops_of(kVariants[variant_named(pk.e1_variant)], p1, a1, false)));
     hipLaunchKernelGGL(pk.fn, dim3((unsigned)blocks), dim3(kVariants[v3].NT), std::max(p3.lds_bytes, p1.lds_bytes), current_stream(),
                        p3.kp, p1.kp, (int)p3.blocks);
     return check_launch();
@@ -529,7 +546,8 @@ int conv_mfma_avg(const ConvArgs &a, int variant, float *sums, size_t sums_bytes
         char name[kNumVariants][64];
         Names() { for (int i = 0; i < kNumVariants; ++i) snprintf(name[i], sizeof(name[i]), "%s+planesums", kVariants[i].name); }
     } names;
-    LaunchScope scope(names.name[vi], conv_flops(a), conv_bytes(a) - 4.0 * a.N * a.Cout * a.Ho * a.Wo + 4.0 * lay->ntiles * lay->WN * lay->slots * a.Cout);
+    LaunchScope scope(names.name[vi], conv_flops(a), conv_bytes(a) - 4.0 * a.N * a.Cout * a.Ho * a.Wo + 4.0 * lay->ntiles * lay->WN * lay->slots * a.Cout,
+                      mfma_flops_of(v, pl, a, false));
     hipLaunchKernelGGL(fn, dim3(pl.blocks, pl.blocks_y), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
     return check_launch();
 }

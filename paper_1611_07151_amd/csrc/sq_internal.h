@@ -137,8 +137,11 @@ int softmax(const float *in, float *out, int N, int C);
 // launch with a pair of HIP events on the library's stream when profiling is on and
 // costs one thread-local load when it is off.  flops and bytes are the algorithmic
 // figures of the launch (2 * MACs; compulsory input + kernel + output bytes).
+// mfma_flops: the floating-point operations the launch issues on the matrix cores (2 x the multiply-accumulates of
+// its MFMA instructions: tile, contraction and layer padding included, and for the minimal-filtering kernels the
+// products they really form); negative = the same as flops, 0 = none (a kernel without MFMA instructions).
 struct LaunchScope {
-    LaunchScope(const char *kernel, double flops, double bytes);
+    LaunchScope(const char *kernel, double flops, double bytes, double mfma_flops = -1.0);
     ~LaunchScope();
     int slot;
 };

@@ -189,7 +189,6 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
             k.wa_cnt = (int)(blocks / k.mtiles); k.wa_big = (int)(blocks % k.mtiles);
             k.wa_q0 = k.ntiles / k.wa_cnt; k.wa_r0 = k.ntiles % k.wa_cnt;
             k.wa_q1 = k.ntiles / (k.wa_cnt + 1); k.wa_r1 = k.ntiles % (k.wa_cnt + 1);
-            k.dwa0 = make_fastdiv(k.wa_cnt); k.dwa1 = make_fastdiv(k.wa_cnt + 1);
         }
         pl.lds_bytes = (size_t)k.nchunks * kWinoAutoStep * sizeof(float) + 64;   // U of one layer block + the item counter
     } else if (v.wino) {

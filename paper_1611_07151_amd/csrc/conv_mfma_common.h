@@ -84,12 +84,11 @@ struct KParams {
     const float *wu;     // its transformed kernels (written by wino_kernel_transform)
     uint32_t wu_bytes;
     int Win, HWin;       // 1x1 kernels with pooling on the way in: row length and plane size of the map in memory
+    int avg_slots;       // averaging form of the 1x1 kernels: images a pixel tile can touch
     // minimal-filtering kernel with autonomous wavefronts: how its workgroups are shared out over the layer blocks
     // (the first wa_big blocks have wa_cnt + 1 workgroups, the others wa_cnt), and tile groups per workgroup of a
     // block with wa_cnt (q0, remainder r0) or wa_cnt + 1 (q1, r1) workgroups
-    int avg_slots;       // averaging form of the 1x1 kernels: images a pixel tile can touch
     int wa_big, wa_cnt, wa_q0, wa_r0, wa_q1, wa_r1;
-    FastDiv dwa0, dwa1;
 };
 
 template <int MT> struct Mfma;

@@ -334,20 +334,24 @@ __device__ __forceinline__ void conv_wino_auto_items(const KParams &p, const int
 // The share of workgroup w of W: items are (layer block, tile group) pairs.  With at least as many workgroups as
 // layer blocks every workgroup stays with one block (its U is staged once): the first p.wa_big blocks have
 // p.wa_cnt + 1 workgroups each, the others p.wa_cnt, and the workgroups of a block split its tile groups evenly
-// (quotients and remainders come from the host).  With fewer workgroups each takes whole blocks w, w + W, ...
+// (quotients and remainders come from the host).  Workgroups are dealt to the eight XCDs in turn, so the k-th
+// workgroup of every block is given a place on the same XCD (rank = position in the order XCD by XCD; block =
+// rank mod blocks): the blocks that read the same stretch of the input then share one L2 instead of fetching it
+// once per XCD.  With fewer workgroups than blocks each takes whole blocks w, w + W, ...
 template <typename TIN, bool E1>
 __device__ __forceinline__ void conv_wino_auto_share(const KParams &p, const int w, const int W)
 {
     const int nb = p.mtiles, G = p.ntiles;
     if (W >= nb) {
-        const int nbig = p.wa_big * (p.wa_cnt + 1);
-        int blk, idx, q, r;
-        if (w < nbig) {
-            blk = fdiv(w, p.dwa1); idx = w - blk * (p.wa_cnt + 1); q = p.wa_q1; r = p.wa_r1;
+        const int rank = (W & 7) == 0 ? (w & 7) * (W >> 3) + (w >> 3) : w;
+        const int even = nb * p.wa_cnt;   // ranks below this go round the blocks; the rest are the big blocks' last
+        int blk, idx;
+        if (rank < even) {
+            idx = fdiv(rank, p.dMtiles); blk = rank - idx * nb;
         } else {
-            const int b2 = fdiv(w - nbig, p.dwa0);
-            blk = p.wa_big + b2; idx = w - nbig - b2 * p.wa_cnt; q = p.wa_q0; r = p.wa_r0;
+            blk = rank - even; idx = p.wa_cnt;
         }
+        const int q = blk < p.wa_big ? p.wa_q1 : p.wa_q0, r = blk < p.wa_big ? p.wa_r1 : p.wa_r0;
         const int lo = idx * q + min(idx, r);
         conv_wino_auto_items<TIN, E1>(p, __builtin_amdgcn_readfirstlane(blk), lo, lo + q + (idx < r ? 1 : 0));
     } else {

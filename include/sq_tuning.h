@@ -14,7 +14,9 @@ extern "C" {
 #endif
 
 /* fp32 network: which 3x3 stride-2 max poolings run inside the squeeze layer that reads them
- * (bit 0 pool1, bit 1 pool4, bit 2 pool8); -1 = by batch size (default). */
+ * (bit 0 pool1, bit 1 pool4, bit 2 pool8), and which are split between the layer before them, which
+ * pools the columns as it writes, and that squeeze layer, which pools the rows as it reads (bits 3, 4, 5;
+ * a split without a kernel for its shape runs like bits 0..2); -1 = by batch size (default). */
 void sq_tune_fuse_pools_f32(int mask);
 
 /* fp32 network and sq_classifier_forward: the last convolution writes plane sums for the average pooling

@@ -169,20 +169,33 @@ ConvArgs make_args(const void *in, const void *w, const float *b, float *out, in
 }
 
 // Unchecked fire layer: squeeze into `sq_map`, then both expands into `out`.  With pool_H != 0 `in` is a
-// map of pool_H x pool_W pixels that the squeeze max-pools (3x3, stride 2) down to H x W while it reads it.
+// map of pool_H x pool_W pixels that the squeeze max-pools (3x3, stride 2) down to H x W while it reads it; with
+// cp_in as well, a column-pooled map of which the squeeze pools the rows.  cp_out: the expands write a column-pooled
+// map for the layer behind a pooling layer; SQ_ERR_UNSUPPORTED before anything is launched where
+// no kernel does that for this shape.
 int fire_impl(const void *in, const void *w_sq, const float *b_sq, const void *w_e1,
               const float *b_e1, const void *w_e3, const float *b_e3, float *out, int N, int Cin,
               int H, int W, int Csq, int Ce1, int Ce3, float *sq_map, void *conv_ws, size_t conv_ws_bytes,
-              bool conv_ws_ready, const char *const *stages, int pool_H = 0, int pool_W = 0, int sq_algo = SQ_ALGO_AUTO)
+              bool conv_ws_ready, const char *const *stages, int pool_H = 0, int pool_W = 0, int sq_algo = SQ_ALGO_AUTO,
+              const ColPool *cp_in = nullptr, const ColPool *cp_out = nullptr)
 {
+    ConvArgs a1 = make_args(sq_map, w_e1, b_e1, out, N, Csq, H, W, Ce1, 1, 1, 0, 1, Ce1 + Ce3, 0, SQ_F32);
+    ConvArgs a3 = make_args(sq_map, w_e3, b_e3, out, N, Csq, H, W, Ce3, 3, 1, 1, 1, Ce1 + Ce3, Ce1, SQ_F32);
+    a3.ws = conv_ws; a3.ws_bytes = conv_ws_bytes; a3.ws_ready = conv_ws_ready;
+    if (cp_out) {
+        a1.cp_out = a3.cp_out = true;
+        a1.cp = a3.cp = *cp_out;
+        if (!conv_expand_pair_supported(a3, a1)) return SQ_ERR_UNSUPPORTED;
+    }
     set_stage(stages[0]);
     ConvArgs asq = make_args(in, w_sq, b_sq, sq_map, N, Cin, H, W, Csq, 1, 1, 0, 1, Csq, 0, SQ_F32);
     asq.pool_H = pool_H; asq.pool_W = pool_W;
+    if (cp_in) {
+        asq.cp_in = true;
+        asq.cp = *cp_in;
+    }
     int rc = run_conv(asq, sq_algo);
     if (rc) return rc;
-    const ConvArgs a1 = make_args(sq_map, w_e1, b_e1, out, N, Csq, H, W, Ce1, 1, 1, 0, 1, Ce1 + Ce3, 0, SQ_F32);
-    ConvArgs a3 = make_args(sq_map, w_e3, b_e3, out, N, Csq, H, W, Ce3, 3, 1, 1, 1, Ce1 + Ce3, Ce1, SQ_F32);
-    a3.ws = conv_ws; a3.ws_bytes = conv_ws_bytes; a3.ws_ready = conv_ws_ready;
     // Both expands in one launch: the expand1x1 tiles behind the persistent workgroups of a minimal-filtering
     // expand3x3 (batches of three images and more), else both in the tiles of one direct 3x3 kernel (small
     // batches, where a fused tiling exists for the shape), else two launches.
@@ -618,15 +631,19 @@ size_t sq_squeezenet_workspace_bytes(int N)
 }
 
 // Which max-pooling layers of the fp32 network run inside the squeeze layer that reads them: bit 0 = pool1,
-// bit 1 = pool4, bit 2 = pool8; -1 = the default policy: what made the whole pass faster when measured at
-// batches 1 to 256 (pool1 everywhere; pool4 from batch 4 on, below that the squeeze of fire5 has too few
-// workgroups to hide nine loads per element; pool8 from batch 64 on).  A call with taps keeps every pooled
-// map, but runs the squeeze with the tiling the fused form would use, so the results are the same bit for bit.
+// bit 1 = pool4, bit 2 = pool8; bits 3..5 = the same three, split between the layer before (columns) and the
+// squeeze (rows); -1 = the default policy: what made the whole pass faster when measured at batches 1 to 256.
+// Inside the squeeze: pool1 everywhere; pool4 from batch 4 on (below that the squeeze of fire5 has too few
+// workgroups to hide nine loads per element); pool8 from batch 64 on.  Split: all three from batch 64 on, where the
+// maps no longer stay in the memory-side cache between two layers and bytes count (whole pass 1010 -> 970 us at
+// batch 64, 1964 -> 1823 at 128, 3853 -> 3675 at 256; at batch 32 and below the split changes nothing or costs
+// 1-2 %: conv1 pays 8 % for the column maxima).  A call with taps keeps every pooled map, but runs the squeeze with
+// the tiling the fused forms would use, so the results are the same bit for bit.
 // The setter is a tuning hook, not part of the public interface.
 extern "C" void sq_tune_fuse_classifier(int on) { g_fuse_classifier = on < 0 ? -1 : on ? 1 : 0; }
 thread_local int g_fuse_pools_f32 = -1;
 extern "C" void sq_tune_fuse_pools_f32(int mask) { g_fuse_pools_f32 = mask; }
-int fuse_pools_f32_policy(int N) { return 1 | (N >= 4 ? 2 : 0) | (N >= 64 ? 4 : 0); }
+int fuse_pools_f32_policy(int N) { return 1 | (N >= 4 ? 2 : 0) | (N >= 64 ? 4 : 0) | (N >= 64 ? 56 : 0); }
 
 namespace {
 size_t packed_f32_bytes()
@@ -687,13 +704,38 @@ static int squeezenet_f32(const void *in, const void *const *params, const void 
         set_stage("kernel transform");
         if ((rc = conv_prepare_kernels(prep, nprep, SQ_F32))) return rc;
     }
+    // Pooling layers (bits 0..2 = pool1, pool4, pool8): `inside` = pooled by the squeeze that reads the map (nine loads
+    // per element of the full map), `split` = columns pooled by the layer before, rows by that squeeze (ColPool: half
+    // the bytes written and read); a split that has no kernel for its shape falls back to `inside`.  A call with
+    // taps keeps every map, but runs the squeezes with the tiling the fused forms would use: same bits either way.
+    const int mask = g_fuse_pools_f32 >= 0 ? g_fuse_pools_f32 : fuse_pools_f32_policy(N);
+    const int pools_in_squeeze = (mask | (mask >> 3)) & 7;
+    const int fuse_pools = taps ? 0 : pools_in_squeeze;
+    const int split_pools = taps ? 0 : (mask >> 3) & 7;
+    ColPool cp_pending;          // geometry of the column-pooled map `cur`, if it is one
+    bool cp_is_pending = false;
+    auto colpool_of = [&](int shift, int slots_row, int rows, int Wo) {
+        ColPool cp;
+        cp.shift = shift; cp.slots_row = slots_row; cp.slots_image = slots_row * rows;
+        cp.row_stride = colpool_row_stride(Wo, shift);
+        return cp;
+    };
     set_stage("conv1");
-    rc = run_conv(make_args(in, params[0], P(1), bufA, N, 3, 224, 224, 96, 7, 2, 2, 1, 96, 0, SQ_F32),
-                      SQ_ALGO_AUTO);
+    ConvArgs a_conv1 = make_args(in, params[0], P(1), bufA, N, 3, 224, 224, 96, 7, 2, 2, 1, 96, 0, SQ_F32);
+    if (split_pools & 1) {
+        // conv1 tiles: 2 rows x 16 columns = 8 pooled columns, 56 x 7 per image
+        ConvArgs c = a_conv1;
+        c.cp_out = true;
+        c.cp = colpool_of(3, 56, 56, 111);
+        if (conv_mfma_choice(c) >= 0) {
+            a_conv1 = c;
+            cp_pending = c.cp;
+            cp_is_pending = true;
+        }
+    }
+    rc = run_conv(a_conv1, SQ_ALGO_AUTO);
     if (rc) return rc;
     if ((rc = copy_tap(taps, 0, bufA, n * 96 * 111 * 111))) return rc;
-    const int pools_in_squeeze = g_fuse_pools_f32 >= 0 ? g_fuse_pools_f32 : fuse_pools_f32_policy(N);
-    const int fuse_pools = taps ? 0 : pools_in_squeeze;
     // tiling of the squeeze behind pool `bit` when the pooled map is kept although the policy would not keep it
     auto squeeze_algo = [&](int bit, int f, int C, int H_in) {
         if (!(pools_in_squeeze & bit) || (fuse_pools & bit)) return (int)SQ_ALGO_AUTO;
@@ -723,9 +765,28 @@ static int squeezenet_f32(const void *in, const void *const *params, const void 
         // input and output in the same buffer as without the fusion (with the roles exchanged instead, conv1
         // and several later layers ran measurably slower at batch 32).
         float *dst = pooled_from ? cur : nxt;
-        rc = fire_impl(cur, params[p], P(p + 1), params[p + 2], P(p + 3), params[p + 4], P(p + 5), dst,
-                       N, C, H, H, fc.sq, fc.e, fc.e, bufS, conv_ws[f], conv_ws_bytes[f], conv_ws_ready[f], kFireStages[f],
-                       pooled_from, pooled_from, sq_algo);
+        const bool pool_behind = f == 2 || f == 6;    // pooling follows fire4 and fire8
+        const int pool_bit = f == 2 ? 2 : 4;
+        const ColPool cp_in = cp_pending;
+        const bool has_cp_in = cp_is_pending;
+        cp_is_pending = false;
+        rc = SQ_ERR_UNSUPPORTED;
+        if (pool_behind && (split_pools & pool_bit)) {
+            // tile groups of the expand pair: 16 tiles of 2 x 2 pixels in a row of (H + 1) / 2, numbered through the batch
+            const int TX = (H + 1) / 2;
+            const ColPool cp_out = colpool_of(4, TX, TX, H);
+            rc = fire_impl(cur, params[p], P(p + 1), params[p + 2], P(p + 3), params[p + 4], P(p + 5), dst,
+                           N, C, H, H, fc.sq, fc.e, fc.e, bufS, conv_ws[f], conv_ws_bytes[f], conv_ws_ready[f], kFireStages[f],
+                           pooled_from, pooled_from, sq_algo, has_cp_in ? &cp_in : nullptr, &cp_out);
+            if (rc == SQ_OK) {
+                cp_pending = cp_out;
+                cp_is_pending = true;
+            }
+        }
+        if (rc == SQ_ERR_UNSUPPORTED)
+            rc = fire_impl(cur, params[p], P(p + 1), params[p + 2], P(p + 3), params[p + 4], P(p + 5), dst,
+                           N, C, H, H, fc.sq, fc.e, fc.e, bufS, conv_ws[f], conv_ws_bytes[f], conv_ws_ready[f], kFireStages[f],
+                           pooled_from, pooled_from, sq_algo, has_cp_in ? &cp_in : nullptr, nullptr);
         sq_algo = SQ_ALGO_AUTO;
         if (rc) return rc;
         p += 6;
@@ -733,9 +794,9 @@ static int squeezenet_f32(const void *in, const void *const *params, const void 
         if ((rc = copy_tap(taps, tap++, dst, n * C * H * H))) return rc;
         if (!pooled_from) { float *t = cur; cur = nxt; nxt = t; }
         pooled_from = 0;
-        if (f == 2 || f == 6) {  // pooling follows fire4 and fire8
-            sq_algo = squeeze_algo(f == 2 ? 2 : 4, f + 1, C, H);
-            if (fuse_pools & (f == 2 ? 2 : 4)) {
+        if (pool_behind) {
+            sq_algo = squeeze_algo(pool_bit, f + 1, C, H);
+            if (fuse_pools & pool_bit) {
                 pooled_from = H;
                 H = (H - 3) / 2 + 1;
                 ++tap;

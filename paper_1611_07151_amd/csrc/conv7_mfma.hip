@@ -25,6 +25,13 @@
 //   * results are kept in a second accumulator set and stored, one store per MFMA step,
 //     during the MFMA loop of the following tile;
 //   * the bias comes out of the contraction and ReLU is the only vector work per result.
+//
+// Column-pooled form (CP; the max pooling behind conv1 split between this kernel and the squeeze layer that
+// follows, see ColPool).  The 16 pixels of a tile row sit in the 16 lanes of a DPP row, so the maximum over columns
+// c, c+1, c+2 is two v_max with a row shift (lanes past the row read zero, which a ReLU'd value never falls below).
+// Even lanes then hold the eight pooled columns of the tile and store them to the column-pooled map (tile cb of a row
+// at positions 9 cb .. 9 cb + 7); the eighth lacks the first column of the next tile, which that tile's lane 0
+// writes, unpooled, into the seam slot between the two (position 9 cb - 1 of its own row).
 #include "conv_mfma_common.h"
 
 namespace sq {
@@ -81,9 +88,10 @@ __host__ __device__ constexpr int step_offset(int s)
 // triples the number of wavefronts and cuts the MFMA chain of a tile to a third -- for small batches,
 // where there are too few tiles to fill the GPU and a pass is bound by the latency of each launch).
 // TIN: float, or uint16_t = bfloat16 input and kernels, widened to fp32 while staged.
-template <typename TIN, int NW, bool FULL, int MINW, int TM>
+template <typename TIN, int NW, bool FULL, int MINW, int TM, bool CP = false>
 __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams p)
 {
+    static_assert(!CP || (FULL && sizeof(TIN) == 4), "the column-pooled form is for fp32 and 96 layers");
     constexpr int kTM = TM, kBM = 32 * TM, kWsFloats = ws_floats(TM);
     const int m0 = (int)blockIdx.y * kBM;          // first output layer of this workgroup
     constexpr int ESZ = (int)sizeof(TIN);
@@ -139,7 +147,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
 
     const int tiles_per_image = p.RG * p.CB;
     const int ntiles = p.N * tiles_per_image;
-    const uint32_t hs1 = (uint32_t)(p.HoWo * 4);
+    const uint32_t hs1 = (uint32_t)((CP ? p.Ho * p.cpRS : p.HoWo) * 4);   // layer stride of the map written
 
     // tile -> image n, first output row oh0, first output column ow0 (all uniform)
     // (readfirstlane tells the compiler these are wavefront-uniform, so all row arithmetic
@@ -192,13 +200,38 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
         int n, oh0, ow0;
         decode(tile, n, oh0, ow0);
         const int oh = oh0 + prow, ow = ow0 + pcol;
+        if constexpr (CP) {
+            // even lanes: pooled column j = ow / 2 of row oh, at position j + j / 8 (a seam slot after every eighth)
+            const int j = ow >> 1;
+            const uint32_t off = (uint32_t)((((n * p.ldc + p.coff + M::row_lane(lane)) * p.Ho + oh) * p.cpRS + j + (j >> 3)) * 4);
+            return (oh < p.Ho && !(pcol & 1) && j < p.cpWp) ? off : kOob;
+        }
         const uint32_t off = (uint32_t)(((n * p.ldc + p.coff + M::row_lane(lane)) * p.HoWo + oh * p.Wo + ow) * 4);
         return (oh < p.Ho && ow < p.Wo) ? off : kOob;
+    };
+    // seam slot of this lane: the one before the tile's first pooled column, written by the lanes of the tile's
+    // first column (the first tile of a row has none)
+    auto seam_offset = [&](int tile) -> uint32_t {
+        int n, oh0, ow0;
+        decode(tile, n, oh0, ow0);
+        const int oh = oh0 + prow, j = ow0 >> 1;
+        const uint32_t off = (uint32_t)((((n * p.ldc + p.coff + M::row_lane(lane)) * p.Ho + oh) * p.cpRS + j + (j >> 3) - 1) * 4);
+        return (pcol == 0 && ow0 > 0 && oh < p.Ho) ? off : kOob;
+    };
+    // one result register of a finished tile: the plain value, or its column maximum plus the seam value
+    auto put = [&](uint32_t off, uint32_t soff, int mu, float val) {
+        if constexpr (CP) {
+            const float u = fmaxf(fmaxf(val, row_shl<1>(val)), row_shl<2>(val));
+            buf_st(rout, off, (uint32_t)mu * hs1, u);
+            buf_st(rout, soff, (uint32_t)mu * hs1, val);
+        } else {
+            buf_st(rout, off, (uint32_t)mu * hs1, val);
+        }
     };
 
     // One tile: 74 MFMA steps into `acc`, with the previous tile's results (`prev`, already
     // ReLU'd) stored one per MFMA step at the walking byte offset prev_off.
-    auto tile_mfma = [&](int buf, Acc (&acc)[kTM], const Acc (&prev)[kTM], uint32_t prev_off) {
+    auto tile_mfma = [&](int buf, Acc (&acc)[kTM], const Acc (&prev)[kTM], uint32_t prev_off, uint32_t prev_soff) {
         const float *xs = Xw + buf * kXbuf;
         auto b_read = [&](int s) -> float {
             if (s == 73) return xs[b4];
@@ -232,7 +265,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
                 // upper), and Cout is a multiple of 8, so the layer test is uniform
                 const int x = s / 16, r = s % 16;
                 const int mu = m0 + x * 32 + M::row_reg(r);
-                if (FULL || mu < p.Cout) buf_st(rout, prev_off, (uint32_t)mu * hs1, prev[x][r]);
+                if (FULL || mu < p.Cout) put(prev_off, prev_soff, mu, prev[x][r]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -270,6 +303,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
 #pragma unroll
         for (int r = 0; r < 16; ++r) accA[x][r] = accB[x][r] = 0.f;
     uint32_t offA = kOob, offB = kOob;   // nothing to store yet
+    uint32_t soffA = kOob, soffB = kOob;
     bool lastA = true;
 
     // two tiles per trip: even tiles use patch buffer 0 and accumulators A, odd ones 1 and B
@@ -278,8 +312,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
             const int next = draw();
             const bool more = next < ntiles;
             if (more) load_patch(next);
-            tile_mfma(0, accA, accB, offB);
+            tile_mfma(0, accA, accB, offB, soffB);
             offA = out_offset(tile);
+            if constexpr (CP) soffA = seam_offset(tile);
             lastA = true;
             if (!more) break;
             store_patch(1);
@@ -289,8 +324,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
             const int next = draw();
             const bool more = next < ntiles;
             if (more) load_patch(next);
-            tile_mfma(1, accB, accA, offA);
+            tile_mfma(1, accB, accA, offA, soffA);
             offB = out_offset(tile);
+            if constexpr (CP) soffB = seam_offset(tile);
             lastA = false;
             if (!more) break;
             store_patch(0);
@@ -303,14 +339,21 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int mu = m0 + x * 32 + M::row_reg(r);
-            if (FULL || mu < p.Cout) buf_st(rout, lastA ? offA : offB, (uint32_t)mu * hs1, lastA ? accA[x][r] : accB[x][r]);
+            if (FULL || mu < p.Cout) put(lastA ? offA : offB, lastA ? soffA : soffB, mu, lastA ? accA[x][r] : accB[x][r]);
         }
 }
 
 }  // namespace
 
-KernelFn conv7s2c3_kernel_for(int NW, bool full, bool bf16, int TM)
+KernelFn conv7s2c3_kernel_for(int NW, bool full, bool bf16, int TM, bool colpool)
 {
+    if (colpool) {
+        if (!full || bf16) return nullptr;
+        if (TM == 1) return NW == 4 ? conv7s2c3_kernel<float, 4, true, 2, 1, true> : nullptr;
+        if (NW == 8) return conv7s2c3_kernel<float, 8, true, 1, 3, true>;
+        if (NW == 4) return conv7s2c3_kernel<float, 4, true, 1, 3, true>;
+        return nullptr;
+    }
     if (TM == 1) {
         if (NW != 4) return nullptr;
         if (bf16) return full ? conv7s2c3_kernel<uint16_t, 4, true, 2, 1> : conv7s2c3_kernel<uint16_t, 4, false, 2, 1>;

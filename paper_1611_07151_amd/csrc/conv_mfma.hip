@@ -92,12 +92,16 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
 {
     const KernelSet &ks = kernel_set(v, a.dtype);
     if (e1 && (!ks.fused_e1 || a.Cin % v.CC != 0)) return false;
-    if (a.pool_H && (!ks.pooled || e1 || a.Cin % v.CC != 0)) return false;
+    if (a.pool_H && (!(a.cp_in ? ks.rowpool : ks.pooled) || e1 || a.Cin % v.CC != 0)) return false;
+    if (a.cp_in && (a.dtype != SQ_F32 || a.W != (a.pool_W - 3) / 2 + 1 || a.cp.row_stride < colpool_row_stride(a.pool_W, a.cp.shift))) return false;
+    // a column-pooled map is written by the conv1-type kernels and by the expand pair of autonomous wavefronts
+    const int Wp = a.cp_out ? (a.Wo - 3) / 2 + 1 : 0;
+    if (a.cp_out && (!(v.conv1_type || v.wino_auto) || a.dtype != SQ_F32 || !a.relu || a.Wo < 3 || a.cp.row_stride < colpool_row_stride(a.Wo, a.cp.shift))) return false;
     if (a.K != v.KS || a.S != v.S) return false;
     if (!v.conv1_type && !ks.plain) return false;
     if (a.W + 2 * a.P < a.K) return false;
-    const long long in_elems = (long long)a.N * a.Cin * (a.pool_H ? (long long)a.pool_H * a.pool_W : (long long)a.H * a.W);
-    const long long out_elems = (long long)a.N * a.out_channels * a.Ho * a.Wo;
+    const long long in_elems = (long long)a.N * a.Cin * (a.cp_in ? (long long)a.pool_H * a.cp.row_stride : a.pool_H ? (long long)a.pool_H * a.pool_W : (long long)a.H * a.W);
+    const long long out_elems = (long long)a.N * a.out_channels * a.Ho * (a.cp_out ? a.cp.row_stride : a.Wo);
     const long long pixels = (long long)a.N * a.Ho * a.Wo;
     // per-lane addresses are 32-bit byte offsets from a uniform base
     const long long w_elems = (long long)a.Cout * a.Cin * a.K * a.K;
@@ -115,7 +119,8 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
     k.N = a.N; k.Cin = a.Cin; k.H = a.H; k.W = a.W; k.Cout = a.Cout; k.P = a.P; k.relu = a.relu;
     k.Ho = a.Ho; k.Wo = a.Wo; k.HoWo = a.Ho * a.Wo; k.HW = a.H * a.W;
     k.ldc = a.out_channels; k.coff = a.c_offset;
-    k.Win = a.pool_W; k.HWin = a.pool_H * a.pool_W;
+    k.Win = a.cp_in ? a.cp.row_stride : a.pool_W; k.HWin = a.pool_H * k.Win;
+    k.cpShift = a.cp.shift; k.cpSlotsRow = a.cp.slots_row; k.cpSlotsImage = a.cp.slots_image; k.cpWp = Wp; k.cpRS = a.cp.row_stride;
     k.PT = (int)pixels;
     k.mtiles = ((e1 && e1->Cout1 > a.Cout ? e1->Cout1 : a.Cout) + v.BM - 1) / v.BM;
     k.w1 = e1 ? (const float *)e1->w1 : nullptr; k.b1 = e1 ? e1->b1 : nullptr;
@@ -179,6 +184,7 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
         k.dRG = make_fastdiv(k.RG); k.dCB = make_fastdiv(k.CB);
         k.dMtiles = make_fastdiv(k.RG * k.CB);
         k.ntiles = (int)tiles;
+        if (a.cp_out && (a.cp.shift != 3 || a.cp.slots_row != 8 * k.CB || a.cp.slots_image != 8 * k.CB * k.RG)) return false;
         pl.lds_bytes = conv7s2c3_lds_bytes(NW, v.BM / 32);
         blocks = (tiles + NW - 1) / NW;
         if (blocks > num_cus()) blocks = num_cus();
@@ -190,6 +196,7 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
             k.wa_q0 = k.ntiles / k.wa_cnt; k.wa_r0 = k.ntiles % k.wa_cnt;
             k.wa_q1 = k.ntiles / (k.wa_cnt + 1); k.wa_r1 = k.ntiles % (k.wa_cnt + 1);
         }
+        if (a.cp_out && (a.cp.shift != 4 || a.cp.slots_row != k.TX || a.cp.slots_image != k.TXY)) return false;
         pl.lds_bytes = (size_t)k.nchunks * kWinoAutoStep * sizeof(float) + 64;   // U of one layer block + the item counter
     } else if (v.wino) {
         blocks = std::min<long long>(blocks, 2ll * num_cus());   // persistent: two workgroups per CU
@@ -206,11 +213,17 @@ bool plan(const Variant &v, const ConvArgs &a, Plan &pl, const FusedE1 *e1 = nul
 
 // a launch that pools on the way in is reported under a name of its own ("pool3s2+<tiling>"); the table is
 // filled during static initialisation, so concurrent launches only read it
+// (likewise "poolrows+<tiling>" for a 1x1 kernel that pools the rows of a column-pooled map, "<tiling>+poolcols" for
+// a kernel that writes such a map)
 struct PooledNames {
-    char name[kNumVariants][64];
+    char name[kNumVariants][64], rows[kNumVariants][64], cols[kNumVariants][64];
     PooledNames()
     {
-        for (int i = 0; i < kNumVariants; ++i) snprintf(name[i], sizeof(name[i]), "pool3s2+%s", kVariants[i].name);
+        for (int i = 0; i < kNumVariants; ++i) {
+            snprintf(name[i], sizeof(name[i]), "pool3s2+%s", kVariants[i].name);
+            snprintf(rows[i], sizeof(rows[i]), "poolrows+%s", kVariants[i].name);
+            snprintf(cols[i], sizeof(cols[i]), "%s+poolcols", kVariants[i].name);
+        }
     }
 };
 const PooledNames kPooledNames;
@@ -235,9 +248,10 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
     const Variant &v = kVariants[vi];
     const KernelSet &ks = kernel_set(v, a.dtype);
     KernelFn fn = e1 ? ks.fused_e1 : ks.plain;
-    if (v.conv1_type) fn = conv7s2c3_kernel_for(v.NT / 64, a.Cout == 96, a.dtype == SQ_BF16, v.BM / 32);
+    if (v.conv1_type) fn = conv7s2c3_kernel_for(v.NT / 64, a.Cout == 96, a.dtype == SQ_BF16, v.BM / 32, a.cp_out);
     if (!v.conv1_type && !v.wino && !e1 && a.Cin % v.CC != 0) fn = ks.tail;
-    if (a.pool_H) fn = ks.pooled;
+    if (a.pool_H) fn = a.cp_in ? ks.rowpool : ks.pooled;
+    if (!fn || (a.cp_out && !v.conv1_type)) return SQ_ERR_UNSUPPORTED;   // (on its own the minimal-filtering kernel writes plain maps)
     if (!allow_big_lds((const void *)fn)) {
         const int rc = check_launch();
         return rc ? rc : SQ_ERR_HIP;
@@ -252,7 +266,8 @@ int launch(int vi, const Plan &pl, const ConvArgs &a, const FusedE1 *e1 = nullpt
         const int rc = conv_prepare_kernels(&job, 1, a.dtype);
         if (rc) return rc;
     }
-    LaunchScope scope(a.pool_H ? kPooledNames.name[vi] : v.name, flops, bytes, mfma_flops_of(v, pl, a, e1 != nullptr));
+    LaunchScope scope(a.cp_in ? kPooledNames.rows[vi] : a.pool_H ? kPooledNames.name[vi] : a.cp_out ? kPooledNames.cols[vi] : v.name, flops, bytes,
+                      mfma_flops_of(v, pl, a, e1 != nullptr));
     hipLaunchKernelGGL(fn, dim3(pl.blocks, pl.blocks_y), dim3(v.NT), pl.lds_bytes, current_stream(), pl.kp);
     return check_launch();
 }
@@ -368,12 +383,17 @@ bool conv_mfma_register_kernels()
     bool ok = true;
     for (int i = 0; i < kNumVariants; ++i)
         for (const KernelSet *ks : {&conv_mfma_kernels_f32[i], &conv_mfma_kernels_bf16[i]})
-            for (KernelFn fn : {ks->plain, ks->tail, ks->fused_e1, ks->pooled, ks->avg}) ok &= allow_big_lds((const void *)fn);
+            for (KernelFn fn : {ks->plain, ks->tail, ks->fused_e1, ks->pooled, ks->avg, ks->rowpool}) ok &= allow_big_lds((const void *)fn);
     for (int nw : {4, 8})
         for (int full = 0; full < 2; ++full)
             for (int bf = 0; bf < 2; ++bf)
                 for (int tm : {1, 3}) ok &= allow_big_lds((const void *)conv7s2c3_kernel_for(nw, full, bf, tm));
-    for (int i = 0; i < num_expand_pair_kernels; ++i) ok &= allow_big_lds((const void *)expand_pair_kernels[i].fn);
+    for (int i = 0; i < num_expand_pair_kernels; ++i) {
+        ok &= allow_big_lds((const void *)expand_pair_kernels[i].fn);
+        ok &= allow_big_lds((const void *)expand_pair_kernels[i].fn_colpool);
+    }
+    for (int nw : {4, 8})
+        for (int tm : {1, 3}) ok &= allow_big_lds((const void *)conv7s2c3_kernel_for(nw, true, false, tm, true));
     return ok;
 }
 
@@ -441,11 +461,12 @@ int conv_mfma_choice(const ConvArgs &a)
     return choose_variant(a, pl);
 }
 
-int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1)
+// Which compiled pair runs (a3, a1), with its launch parameters; < 0 if none does.
+static int plan_expand_pair(const ConvArgs &a3, const ConvArgs &a1, Plan &p3, Plan &p1, int &v3)
 {
-    if (!expand_pair_wanted(a3) || a1.dtype != SQ_F32) return SQ_ERR_UNSUPPORTED;
-    if (a1.K != 1 || a1.S != 1 || a1.P != 0 || a1.pool_H || a1.in != a3.in || a1.out != a3.out || a1.N != a3.N) return SQ_ERR_UNSUPPORTED;
-    Plan p3, p1;
+    if (!expand_pair_wanted(a3) || a1.dtype != SQ_F32) return -1;
+    if (a1.K != 1 || a1.S != 1 || a1.P != 0 || a1.pool_H || a1.in != a3.in || a1.out != a3.out || a1.N != a3.N) return -1;
+    if (a1.cp_out != a3.cp_out || (a3.cp_out && a1.cp.row_stride != a3.cp.row_stride)) return -1;
     auto variant_named = [](const char *name) {
         for (int i = 0; i < kNumVariants; ++i)
             if (!strcmp(kVariants[i].name, name)) return i;
@@ -457,13 +478,15 @@ int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1)
     // (pair 2 against pair 0, us): 16 -> 64 at 55x55 41-46 / 41, 32 -> 128 at 55x55 103 / 112, 32 -> 128 at 27x27
     // 36.9 / 36.1, 48 -> 192 at 27x27 58 / 60, 64 -> 256 at 27x27 92.2 / 92.5, 64 -> 256 at 13x13 32.5 / 32.4: pair 2
     // from 48 input layers on and for 32 input layers on the large maps; pair 1 instead of pair 0 from batch 128 on.
-    const bool auto_form = a3.H * a3.W >= 27 * 27 && (a3.Cin >= 48 || (a3.Cin >= 32 && a3.H * a3.W >= 55 * 55));
+    // Only pair 2 can write a column-pooled map.
+    const bool auto_form = a3.cp_out || (a3.H * a3.W >= 27 * 27 && (a3.Cin >= 48 || (a3.Cin >= 32 && a3.H * a3.W >= 55 * 55)));
     const int prefer = g_expand_pair > 0 ? g_expand_pair - 1 : (auto_form ? 2 : a1.N >= 128 ? 1 : 0);
-    if (prefer >= num_expand_pair_kernels) return SQ_ERR_UNSUPPORTED;
-    int pair = -1, v3 = -1;
+    if (prefer >= num_expand_pair_kernels) return -1;
+    int pair = -1;
     for (int k = 0; k < num_expand_pair_kernels && pair < 0; ++k) {
         if (g_expand_pair > 0 && k > 0) break;                    // a forced pair has no substitute
         const int i = (prefer + k) % num_expand_pair_kernels;     // the preferred one first, then the others
+        if (a3.cp_out && !expand_pair_kernels[i].fn_colpool) continue;
         v3 = variant_named(expand_pair_kernels[i].e3_variant);
         if (v3 < 0 || !plan(kVariants[v3], a3, p3)) continue;
         if (!expand_pair_kernels[i].e1_variant) {
@@ -480,11 +503,29 @@ int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1)
         const int v = variant_named(expand_pair_kernels[i].e1_variant);
         if (v >= 0 && a1.Cin % kVariants[v].CC == 0 && plan(kVariants[v], a1, p1) && kVariants[v].NT == kVariants[v3].NT) pair = i;
     }
+    if (pair < 0) return -1;
+    const long long blocks = (long long)p3.blocks + p1.blocks;
+    if (blocks >= (1ll << 31) || p1.blocks_y != 1) return -1;
+    return pair;
+}
+
+bool conv_expand_pair_supported(const ConvArgs &a3, const ConvArgs &a1)
+{
+    Plan p3, p1;
+    int v3 = -1;
+    return plan_expand_pair(a3, a1, p3, p1, v3) >= 0;
+}
+
+int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1)
+{
+    Plan p3, p1;
+    int v3 = -1;
+    const int pair = plan_expand_pair(a3, a1, p3, p1, v3);
     if (pair < 0) return SQ_ERR_UNSUPPORTED;
     const long long blocks = (long long)p3.blocks + p1.blocks;
-    if (blocks >= (1ll << 31) || p1.blocks_y != 1) return SQ_ERR_UNSUPPORTED;
     const PairKernel &pk = expand_pair_kernels[pair];
-    if (!allow_big_lds((const void *)pk.fn)) {
+    const PairFn fn = a3.cp_out ? pk.fn_colpool : pk.fn;
+    if (!allow_big_lds((const void *)fn)) {
         const int rc = check_launch();
         return rc ? rc : SQ_ERR_HIP;
     }
@@ -494,9 +535,12 @@ int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1)
         if (rc) return rc;
     }
     const bool folded = !pk.e1_variant;
-    LaunchScope scope(pk.name, conv_flops(a3) + conv_flops(a1), conv_bytes(a3) + conv_bytes(a1),
-                      mfma_flops_of(kVariants[v3], p3, a3, folded) + (folded ? 0.0 : mfma_flops_of(kVariants[variant_named(pk.e1_variant)], p1, a1, false)));
-    hipLaunchKernelGGL(pk.fn, dim3((unsigned)blocks), dim3(kVariants[v3].NT), std::max(p3.lds_bytes, p1.lds_bytes), current_stream(),
+    double mf = mfma_flops_of(kVariants[v3], p3, a3, folded);
+    if (!folded)
+        for (int i = 0; i < kNumVariants; ++i)
+            if (!strcmp(kVariants[i].name, pk.e1_variant)) mf += mfma_flops_of(kVariants[i], p1, a1, false);
+    LaunchScope scope(a3.cp_out ? pk.name_colpool : pk.name, conv_flops(a3) + conv_flops(a1), conv_bytes(a3) + conv_bytes(a1), mf);
+    hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3(kVariants[v3].NT), std::max(p3.lds_bytes, p1.lds_bytes), current_stream(),
                        p3.kp, p1.kp, (int)p3.blocks);
     return check_launch();
 }

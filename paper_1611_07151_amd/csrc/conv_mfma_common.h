@@ -85,11 +85,21 @@ struct KParams {
     uint32_t wu_bytes;
     int Win, HWin;       // 1x1 kernels with pooling on the way in: row length and plane size of the map in memory
     int avg_slots;       // averaging form of the 1x1 kernels: images a pixel tile can touch
+    // pooling split between two layers (ColPool): geometry of the column-pooled map.  A 1x1 kernel that pools the rows
+    // on the way in reads such a map; the conv1-type kernel and the autonomous minimal-filtering kernel write one
+    // (p.out, rows of cpRS floats holding cpWp pooled columns and the seam slots; cpWp = 0 = plain map)
+    int cpShift, cpSlotsRow, cpSlotsImage, cpWp, cpRS;
     // minimal-filtering kernel with autonomous wavefronts: how its workgroups are shared out over the layer blocks
     // (the first wa_big blocks have wa_cnt + 1 workgroups, the others wa_cnt), and tile groups per workgroup of a
     // block with wa_cnt (q0, remainder r0) or wa_cnt + 1 (q1, r1) workgroups
     int wa_big, wa_cnt, wa_q0, wa_r0, wa_q1, wa_r1;
 };
+
+// value of lane + n of the same row of 16 lanes (DPP row shift), zero past the row's end
+template <int n> __device__ __forceinline__ float row_shl(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x100 + n, 0xf, 0xf, true));
+}
 
 template <int MT> struct Mfma;
 template <> struct Mfma<32> {
@@ -213,9 +223,10 @@ __device__ __forceinline__ void st_f32(float *base, uint32_t byte_off, float v)
 typedef void (*KernelFn)(const KParams);
 
 // Kernels of one tiling: plain, input layers not a multiple of CC, fused 1x1 expand, 1x1 with 3x3 stride-2
-// max pooling on the way in, 1x1 writing per-image plane sums instead of its results.
+// max pooling on the way in, 1x1 writing per-image plane sums instead of its results, 1x1 pooling the rows of a
+// column-pooled map on the way in.
 struct KernelSet {
-    KernelFn plain, tail, fused_e1, pooled, avg;
+    KernelFn plain, tail, fused_e1, pooled, avg, rowpool;
 };
 extern const KernelSet conv_mfma_kernels_f32[], conv_mfma_kernels_bf16[];
 // Both expands of a fire layer in one launch (expand_pair_kernel): the compiled expand1x1 tilings, each named
@@ -226,11 +237,14 @@ struct PairKernel {
     const char *name;         // name of the pair in profiles
     PairFn fn;
     const char *e3_variant;   // name of the minimal-filtering tiling it runs
+    PairFn fn_colpool;        // the form that writes a column-pooled map and its seam table, or nullptr
+    const char *name_colpool;
 };
 extern const PairKernel expand_pair_kernels[];
 extern const int num_expand_pair_kernels;
 // TM = blocks of 32 output layers per workgroup: 3 (all 96), or 1 with the block chosen by blockIdx.y (NW = 4 only).
-KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers, bool bf16_inputs, int TM);
+// colpool: the form that writes a column-pooled map and its seam table (fp32, 96 layers only), else nullptr.
+KernelFn conv7s2c3_kernel_for(int NW, bool full_96_layers, bool bf16_inputs, int TM, bool colpool = false);
 
 // Minimal-filtering F(2x2, 3x3) kernel: workgroup tile (output layers x tiles of 2x2 pixels),
 // input layers per chunk, and the floats of the kernel image [16 positions][2][64][4] of one chunk.

@@ -47,6 +47,13 @@ namespace mfma {
 // in -- in this network every pooled map is read by exactly one squeeze layer, so it need not
 // exist in memory.  p.H, p.W are the pooled extents, p.Win / p.HWin those of the map in memory; a
 // staged element is the maximum of nine loads (per window row one 8-byte and one 4-byte load).
+// POOL == 2: the layer before has already pooled the columns (column-pooled map, see ColPool): row r of the map
+// in memory holds, for pooled column x, the maximum over columns 2x..2x+2 of that layer's row r -- except in the
+// last pooled column of a column group of the producer (a conv1 tile, a tile group of the minimal-filtering
+// kernel), where the third column belongs to the next group and sits, unpooled, in a seam slot right behind.  This
+// kernel takes the maximum over rows 2y..2y+2 and, at those columns, the seam slots: three 8-byte loads per staged
+// element instead of nine values, and about half the bytes.  The second value of a load is used only at a seam
+// (chosen with a select, so whatever else lies there does no harm).
 //
 // conv_mfma_tile is the work of one workgroup (tile number `block` of the launch), conv_mfma_kernel the
 // kernel that consists of nothing else; the expand pair kernel (conv_wino_kernel.h) runs the same tiles
@@ -58,7 +65,7 @@ namespace mfma {
 // image (first image of the tile) + s among the BN / WN pixels of wavefront column wn; whoever adds the slots of an
 // image up (avg_softmax_kernel) has the plane sums.  Slots without pixels hold zero.
 template <typename TIN, int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, bool TAIL, bool E1 = false,
-          bool POOL = false, bool AVG = false>
+          int POOL = 0, bool AVG = false>
 __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block)
 {
     using M = Mfma<MT>;
@@ -78,6 +85,8 @@ __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block
     static_assert(!POINTWISE || (NT % BN == 0 && BN % 64 == 0 && (CC * BN) % NT == 0), "pointwise staging split");
     static_assert(!E1 || (KS % 2 == 1 && S == 1 && !TAIL), "fused expand needs a centre tap");
     static_assert(!POOL || (POINTWISE && !TAIL && !E1), "pooling on the way in is for plain 1x1 kernels");
+    static_assert(POOL != 2 || sizeof(TIN) == 4, "a column-pooled map is fp32");
+    constexpr int NWIN = POOL == 2 ? 6 : 9;
     static_assert(!AVG || (POINTWISE && !E1 && !POOL), "plane sums are for plain 1x1 kernels");
     constexpr int ESZ = (int)sizeof(TIN);
     constexpr int LD1 = CC + 1;                       // LDS row stride of the 1x1 kernels
@@ -162,11 +171,24 @@ __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block
         }
     }
     uint32_t xsrc[XMAP];
+    uint32_t xsrcB = kOob;   // POOL == 2: the third row
+    bool seamA = false, seamB = false;
     int xdst[XMAP];
     if constexpr (POINTWISE) {
         const int pl = t % BN, pp = P0 + pl;
         const int n = fdiv(pp, p.dHW);
-        if constexpr (POOL) {
+        if constexpr (POOL == 2) {
+            // this pixel's column in rows 2y, 2y+1 (one producer tile row) and 2y+2 (the next one): the position
+            // counts the seam slots before it, which depends on where the row's slots fall in their groups
+            const int pix = pp - n * p.HW, y = fdiv(pix, p.dWo), x = pix - y * p.Wo;
+            const int gm = (1 << p.cpShift) - 1;
+            const int qa = n * p.cpSlotsImage + y * p.cpSlotsRow, qb = qa + p.cpSlotsRow;
+            const int posa = x + ((qa + x) >> p.cpShift) - (qa >> p.cpShift), posb = x + ((qb + x) >> p.cpShift) - (qb >> p.cpShift);
+            xsrc[0] = pp < p.PT ? (uint32_t)((n * p.Cin * p.HWin + 2 * y * p.Win + posa) * ESZ) : kOob;
+            xsrcB = pp < p.PT ? (uint32_t)((n * p.Cin * p.HWin + (2 * y + 2) * p.Win + posb) * ESZ) : kOob;
+            seamA = ((qa + x) & gm) == gm;
+            seamB = ((qb + x) & gm) == gm;
+        } else if constexpr (POOL == 1) {
             // first element of this pixel's window in the map before pooling
             const int pix = pp - n * p.HW, y = fdiv(pix, p.dWo), x = pix - y * p.Wo;
             xsrc[0] = pp < p.PT ? (uint32_t)((n * p.Cin * p.HWin + 2 * y * p.Win + 2 * x) * ESZ) : kOob;
@@ -189,7 +211,7 @@ __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block
     }
     const int cpart = POINTWISE ? __builtin_amdgcn_readfirstlane(t / BN) : 0;
 
-    float wreg[WREG], xreg[XREG], w1reg[W1REG], xwin[POOL ? XREG : 1][9];
+    float wreg[WREG], xreg[XREG], w1reg[W1REG], xwin[POOL ? XREG : 1][NWIN];
 
     // Global loads of one chunk through buffer addressing: the per-lane offsets were fixed
     // above (kOob where the value is padding, which the hardware turns into zero), the chunk
@@ -226,7 +248,21 @@ __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block
 #pragma unroll
             for (int r = 0; r < W1REG; ++r) w1reg[r] = buf_ld_in<TIN>(rw1, w1src[r], (uint32_t)(c0 * ESZ));
         }
-        if constexpr (POOL) {
+        if constexpr (POOL == 2) {
+#pragma unroll
+            for (int r = 0; r < XREG; ++r) {
+                const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane((c0 + cpart + (NT / BN) * r) * p.HWin * ESZ);
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    uint32_t off = i < 2 ? xsrc[0] + (uint32_t)(i * p.Win * ESZ) : xsrcB;
+                    asm volatile("" : "+v"(off));   // the two loads differ by an immediate and merge into one of 8 bytes
+                    xwin[r][2 * i] = buf_ld_in<TIN>(rin, off, so);
+                    xwin[r][2 * i + 1] = buf_ld_in<TIN>(rin, off + (uint32_t)ESZ, so);
+                }
+            }
+            return;
+        }
+        if constexpr (POOL == 1) {
             // the nine values of every window stay in registers until store_chunk takes their maximum, so that
             // the loads are in flight during the MFMAs of the chunk before (an out-of-range pixel reads zeros)
 #pragma unroll
@@ -262,12 +298,19 @@ __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block
             for (int r = 0; r < W1REG; ++r)
                 if (w1dst[r] >= 0) w1s[w1dst[r]] = w1reg[r];
         }
-        if constexpr (POOL) {
+        if constexpr (POOL == 2) {
+#pragma unroll
+            for (int r = 0; r < XREG; ++r) {
+                const float m = fmaxf(fmaxf(xwin[r][0], xwin[r][2]), xwin[r][4]);
+                const float sa = seamA ? fmaxf(xwin[r][1], xwin[r][3]) : 0.f, sb = seamB ? xwin[r][5] : 0.f;
+                xs[(cpart + (NT / BN) * r) * plane + xdst[0]] = fmaxf(m, fmaxf(sa, sb));
+            }
+        } else if constexpr (POOL == 1) {
 #pragma unroll
             for (int r = 0; r < XREG; ++r) {
                 float m = xwin[r][0];
 #pragma unroll
-                for (int e = 1; e < 9; ++e) m = fmaxf(m, xwin[r][e]);
+                for (int e = 1; e < NWIN; ++e) m = fmaxf(m, xwin[r][e]);
                 xs[(cpart + (NT / BN) * r) * plane + xdst[0]] = m;
             }
         } else if constexpr (POINTWISE) {
@@ -456,7 +499,7 @@ __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block
 }
 
 template <typename TIN, int KS, int S, int BM, int BN, int WM, int WN, int MT, int CC, int PE, int MINW, bool TAIL, bool E1 = false,
-          bool POOL = false, bool AVG = false>
+          int POOL = 0, bool AVG = false>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void conv_mfma_kernel(const KParams p)
 {
     conv_mfma_tile<TIN, KS, S, BM, BN, WM, WN, MT, CC, PE, TAIL, E1, POOL, AVG>(p, (int)blockIdx.x);

@@ -43,9 +43,14 @@ namespace mfma {
 // same block of 32 layers, written to layers [p.coff1, p.coff1 + p.Cout1) -- the other expand of a fire layer
 // (section "Convolutional Neural Networks": both expand layers read the squeeze result).  Its B operands are the
 // four centre values of the patch, untransformed; its kernels sit in LDS beside U.
-template <typename TIN, bool E1>
+// CP: the results go out as a column-pooled map (the max pooling behind this layer split between this kernel and the
+// squeeze layer that follows, see ColPool).  The sixteen tiles of an item sit in the sixteen lanes of a DPP row, so
+// pooled column tx = max(both columns of tile tx, first column of tile tx + 1) takes one row shift per pixel row;
+// lane 15 lacks its neighbour, whose item writes that column, unpooled, into the seam slot behind it.
+template <typename TIN, bool E1, bool CP = false>
 __device__ __forceinline__ void conv_wino_auto_items(const KParams &p, const int lbk, const int lo, const int end)
 {
+    static_assert(!CP || sizeof(TIN) == 4, "column-pooled maps come from fp32 layers");
     constexpr uint32_t ESZ = sizeof(TIN);
     using M = Mfma<16>;
     using Acc = M::Acc;
@@ -58,7 +63,7 @@ __device__ __forceinline__ void conv_wino_auto_items(const KParams &p, const int
     const int tj = lane & 15, tk = lane >> 4;
 
     const rsrc_t rout = make_rsrc(p.out, p.out_bytes);
-    const uint32_t hs = (uint32_t)p.HoWo * 4u;
+    const uint32_t hs = (uint32_t)(CP ? p.Ho * p.cpRS : p.HoWo) * 4u;   // layer stride of the map written
     const float lowest = p.relu ? 0.f : -__builtin_inff();
 
     {
@@ -118,6 +123,7 @@ __device__ __forceinline__ void conv_wino_auto_items(const KParams &p, const int
             bool c2ok, c3ok;
             uint32_t o;                 // byte offset of output pixel (2ty, 2tx) in this lane's first layer
             bool ok0, ok1, two;         // rows 2ty, 2ty + 1 exist; column 2tx + 1 exists
+            bool seam;                  // CP: this lane's first column goes into the seam slot before its position
         };
         auto setup = [&](int item, Item &it) {
             const int t0 = item * kWinoAutoTiles;
@@ -136,10 +142,21 @@ __device__ __forceinline__ void conv_wino_auto_items(const KParams &p, const int
             it.c3ok = iw0 + 3 < p.W;
             // output pixels (2ty + pr, 2tx) and (.., 2tx + 1); the lane's first layer goes into the lane offset
             const int oh = 2 * ty, ow = 2 * tx;
-            it.o = (uint32_t)(((n * p.ldc + p.coff + m0 + 4 * tk) * p.HoWo + oh * p.Wo + ow) * 4);
-            it.ok0 = tg < p.T;
-            it.ok1 = tg < p.T && oh + 1 < p.Ho;
-            it.two = ow + 1 < p.Wo;
+            if constexpr (CP) {
+                // pooled column tx of rows 2ty, 2ty + 1 in the column-pooled map: its position counts the group ends
+                // before it in this tile row (tgc is the slot number); the last tile of a row has no pooled column
+                const int pos = tx + (tgc >> 4) - ((tgc - tx) >> 4);
+                it.o = (uint32_t)((((n * p.ldc + p.coff + m0 + 4 * tk) * p.Ho + oh) * p.cpRS + pos) * 4);
+                it.ok0 = tg < p.T && tx < p.cpWp;
+                it.ok1 = it.ok0 && oh + 1 < p.Ho;
+                it.two = oh + 1 < p.Ho;       // (here: the second row exists, for the seam store)
+                it.seam = tj == 0 && tg < p.T && tx > 0;
+            } else {
+                it.o = (uint32_t)(((n * p.ldc + p.coff + m0 + 4 * tk) * p.HoWo + oh * p.Wo + ow) * 4);
+                it.ok0 = tg < p.T;
+                it.ok1 = tg < p.T && oh + 1 < p.Ho;
+                it.two = ow + 1 < p.Wo;
+            }
         };
         // Patch of this lane's (tile, input layer 4 * ks + k).  The step's first input layer goes into the base of
         // the resource (scalar arithmetic): the hardware checks only the lane offset against the size, so a run that
@@ -281,10 +298,25 @@ __device__ __forceinline__ void conv_wino_auto_items(const KParams &p, const int
                 // lane offsets of the two pixel rows: both columns (8-byte store) or, for tiles cut by the right edge
                 // (odd widths), the first column only
                 uint32_t o2[2], o1[2];
-                o2[0] = cur.ok0 && cur.two ? cur.o : kOob;
-                o2[1] = cur.ok1 && cur.two ? cur.o + (uint32_t)(p.Wo * 4) : kOob;
-                o1[0] = cur.ok0 && !cur.two ? cur.o : kOob;
-                o1[1] = cur.ok1 && !cur.two ? cur.o + (uint32_t)(p.Wo * 4) : kOob;
+                o2[0] = !CP && cur.ok0 && cur.two ? cur.o : kOob;
+                o2[1] = !CP && cur.ok1 && cur.two ? cur.o + (uint32_t)(p.Wo * 4) : kOob;
+                o1[0] = cur.ok0 && (CP || !cur.two) ? cur.o : kOob;
+                o1[1] = cur.ok1 && (CP || !cur.two) ? cur.o + (uint32_t)((CP ? p.cpRS : p.Wo) * 4) : kOob;
+                // CP: the two pooled values of this lane's tile column, and lane 0's unpooled first column
+                uint32_t os[2] = {kOob, kOob};
+                if constexpr (CP) {
+                    os[0] = cur.seam ? cur.o - 4u : kOob;
+                    os[1] = cur.seam && cur.two ? cur.o - 4u + (uint32_t)(p.cpRS * 4) : kOob;
+                }
+                auto put_pooled = [&](uint32_t d, int layer, float y00, float y01, float y10, float y11) {
+                    const float h0 = fmaxf(fmaxf(y00, y01), row_shl<1>(y00));
+                    const float h1 = fmaxf(fmaxf(y10, y11), row_shl<1>(y10));
+                    const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(layer) * hs;
+                    buf_st(rout, o1[0] == kOob ? kOob : o1[0] + d, so, h0);
+                    buf_st(rout, o1[1] == kOob ? kOob : o1[1] + d, so, h1);
+                    buf_st(rout, os[0] == kOob ? kOob : os[0] + d, so, y00);
+                    buf_st(rout, os[1] == kOob ? kOob : os[1] + d, so, y10);
+                };
 #pragma unroll
                 for (int lb = 0; lb < 2; ++lb) {
 #pragma unroll
@@ -299,16 +331,20 @@ __device__ __forceinline__ void conv_wino_auto_items(const KParams &p, const int
                         const float y01 = fmaxf(z[0][1] + z[1][1] + z[2][1], lowest);
                         const float y10 = fmaxf(z[1][0] - z[2][0] - z[3][0], lowest);
                         const float y11 = fmaxf(z[1][1] - z[2][1] - z[3][1], lowest);
-                        const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(lb * 16 + r) * hs;
-                        buf_st2(rout, o2[0], so, y00, y01);
-                        buf_st2(rout, o2[1], so, y10, y11);
-                        buf_st(rout, o1[0], so, y00);
-                        buf_st(rout, o1[1], so, y10);
+                        if constexpr (CP) {
+                            put_pooled(0u, lb * 16 + r, y00, y01, y10, y11);
+                        } else {
+                            const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(lb * 16 + r) * hs;
+                            buf_st2(rout, o2[0], so, y00, y01);
+                            buf_st2(rout, o2[1], so, y10, y11);
+                            buf_st(rout, o1[0], so, y00);
+                            buf_st(rout, o1[1], so, y10);
+                        }
                     }
                 }
                 if constexpr (E1) {
                     // ---- the 1x1 part: ReLU and stores, same pixels, layers [coff1 + m0, +32) ----
-                    const uint32_t d1 = (uint32_t)((p.coff1 - p.coff) * p.HoWo * 4);     // modulo 2^32, like the offsets
+                    const uint32_t d1 = (uint32_t)(p.coff1 - p.coff) * hs;               // modulo 2^32, like the offsets
 #pragma unroll
                     for (int lb = 0; lb < 2; ++lb) {
 #pragma unroll
@@ -316,6 +352,10 @@ __device__ __forceinline__ void conv_wino_auto_items(const KParams &p, const int
                             const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(lb * 16 + r) * hs;
                             const float y00 = fmaxf(e[0][lb][r], lowest), y01 = fmaxf(e[1][lb][r], lowest);
                             const float y10 = fmaxf(e[2][lb][r], lowest), y11 = fmaxf(e[3][lb][r], lowest);
+                            if constexpr (CP) {
+                                put_pooled(d1, lb * 16 + r, y00, y01, y10, y11);
+                                continue;
+                            }
                             buf_st2(rout, o2[0] == kOob ? kOob : o2[0] + d1, so, y00, y01);
                             buf_st2(rout, o2[1] == kOob ? kOob : o2[1] + d1, so, y10, y11);
                             buf_st(rout, o1[0] == kOob ? kOob : o1[0] + d1, so, y00);
@@ -338,7 +378,7 @@ __device__ __forceinline__ void conv_wino_auto_items(const KParams &p, const int
 // workgroup of every block is given a place on the same XCD (rank = position in the order XCD by XCD; block =
 // rank mod blocks): the blocks that read the same stretch of the input then share one L2 instead of fetching it
 // once per XCD.  With fewer workgroups than blocks each takes whole blocks w, w + W, ...
-template <typename TIN, bool E1>
+template <typename TIN, bool E1, bool CP = false>
 __device__ __forceinline__ void conv_wino_auto_share(const KParams &p, const int w, const int W)
 {
     const int nb = p.mtiles, G = p.ntiles;
@@ -353,9 +393,9 @@ __device__ __forceinline__ void conv_wino_auto_share(const KParams &p, const int
         }
         const int q = blk < p.wa_big ? p.wa_q1 : p.wa_q0, r = blk < p.wa_big ? p.wa_r1 : p.wa_r0;
         const int lo = idx * q + min(idx, r);
-        conv_wino_auto_items<TIN, E1>(p, __builtin_amdgcn_readfirstlane(blk), lo, lo + q + (idx < r ? 1 : 0));
+        conv_wino_auto_items<TIN, E1, CP>(p, __builtin_amdgcn_readfirstlane(blk), lo, lo + q + (idx < r ? 1 : 0));
     } else {
-        for (int blk = w; blk < nb; blk += W) conv_wino_auto_items<TIN, E1>(p, blk, 0, G);
+        for (int blk = w; blk < nb; blk += W) conv_wino_auto_items<TIN, E1, CP>(p, blk, 0, G);
     }
 }
 
@@ -367,10 +407,11 @@ __global__ __launch_bounds__(kWinoAutoWaves * 64, 1) void conv_wino_auto_kernel(
 
 // Both expands of a fire layer in one launch: every wavefront item is 32 layers x 16 tiles of the expand3x3 followed
 // by the same layers and tiles of the expand1x1 (p.w1, p.b1, p.coff1; the number of layers is the same).
-template <typename TIN>
+// CP: the pair writes a column-pooled map.
+template <typename TIN, bool CP = false>
 __global__ __launch_bounds__(kWinoAutoWaves * 64, 1) void expand_pair_auto_kernel(const KParams p, const KParams, const int)
 {
-    conv_wino_auto_share<TIN, true>(p, (int)blockIdx.x, (int)gridDim.x);
+    conv_wino_auto_share<TIN, true, CP>(p, (int)blockIdx.x, (int)gridDim.x);
 }
 
 }  // namespace mfma

@@ -32,6 +32,24 @@ bool fire_bf16_register_kernels();
 
 // One convolution call after validation.  Ho/Wo are precomputed; the result goes
 // to layers [c_offset, c_offset+Cout) of an [N][out_channels][Ho][Wo] tensor.
+// Max pooling (3x3 window, stride 2, floor mode; section "Pooling and Softmax") split between the layer before it and
+// the 1x1 layer behind it, so that about half of the producer's map goes through memory and the pooled map never
+// exists.  The producer (ReLU on) writes a column-pooled map [N][layers][Ho][row_stride]: for pooled column x
+// (x < Wp = (Wo - 3) / 2 + 1) of its row r the maximum of its columns 2x, 2x+1, 2x+2.  Its work items cover 2 rows x
+// 2^shift pooled columns ("groups"; pooled column x of producer tile row ty of image n is slot q = n * slots_image +
+// ty * slots_row + x, group = q >> shift).  In the last slot of a group the third column lies in the next group:
+// the value there is the maximum of two columns only, and the next group's item writes its first column, unpooled,
+// into a seam slot right behind it.  So column x of tile row ty sits at position x + (number of group ends before
+// it in this row) = x + ((q0 + x) >> shift) - (q0 >> shift), q0 = the row's first slot, and a seam slot follows
+// wherever (q0 + x) % 2^shift is the last of its group.  The consumer takes the maximum over rows 2y..2y+2 and, at
+// those columns, the seam slots (one 8-byte load per row).  Exact: a maximum picks one of the producer's values
+// whatever the order.
+struct ColPool {
+    int shift = 0, slots_row = 0, slots_image = 0;
+    int row_stride = 0;   // floats per row of the map: Wp + (Wp >> shift) + 2 holds every seam slot
+};
+inline int colpool_row_stride(int Wo, int shift) { const int Wp = (Wo - 3) / 2 + 1; return Wp + (Wp >> shift) + 2; }
+
 struct ConvArgs {
     const void *in;
     const void *w;
@@ -46,6 +64,11 @@ struct ConvArgs {
     // 1x1 convolution of a map that is max-pooled (3x3 window, stride 2, no padding) on the way in: extents of
     // the map in memory; H and W are then the pooled extents.  0 = the input is read as it is.
     int pool_H, pool_W;
+    // split pooling: cp_in = `in` is a column-pooled map of pool_H rows (pool_W = the producer's row length before
+    // pooling, W = the number of pooled columns) and this 1x1 layer pools the rows; cp_out = this layer writes such a
+    // map instead of its plain map (conv1-type and expand-pair kernels; Ho, Wo stay the unpooled extents)
+    bool cp_in = false, cp_out = false;
+    ColPool cp;
 };
 
 inline double conv_flops(const ConvArgs &a)
@@ -55,9 +78,9 @@ inline double conv_flops(const ConvArgs &a)
 inline double conv_bytes(const ConvArgs &a)
 {
     const double esz = a.dtype == SQ_BF16 ? 2.0 : 4.0;
-    const double in_plane = a.pool_H ? (double)a.pool_H * a.pool_W : (double)a.H * a.W;
+    const double in_plane = a.cp_in ? (double)a.pool_H * a.cp.row_stride : a.pool_H ? (double)a.pool_H * a.pool_W : (double)a.H * a.W;
     return esz * ((double)a.N * a.Cin * in_plane + (double)a.Cout * a.Cin * a.K * a.K) +
-           4.0 * ((double)a.N * a.Cout * a.Ho * a.Wo + a.Cout);
+           4.0 * ((double)a.N * a.Cout * a.Ho * (a.cp_out ? a.cp.row_stride : a.Wo) + a.Cout);
 }
 
 int conv_direct(const ConvArgs &a);
@@ -69,6 +92,8 @@ int conv_mfma(const ConvArgs &a, int variant);
 // measured choice for a3 is the minimal-filtering kernel and a compiled expand1x1 tiling fits; SQ_ERR_UNSUPPORTED
 // otherwise.
 int conv_expand_pair(const ConvArgs &a3, const ConvArgs &a1);
+// whether conv_expand_pair has a kernel for (a3, a1) -- nothing is launched
+bool conv_expand_pair_supported(const ConvArgs &a3, const ConvArgs &a1);
 // 1x1 convolution (+bias, ReLU) followed directly by a global average pooling: the convolution kernel writes per-image
 // plane sums of its results (a table of conv_mfma_avg_bytes() bytes, laid out as AvgLayout says) instead of the results;
 // avg_softmax() adds them up, divides by the plane size and applies softmax.  variant < 0 = the tiling of the

@@ -272,6 +272,39 @@ def test_network_with_pooling_inside_the_squeeze_layers(sq):
     assert_close(fused, ref, FP32_TOL, "all pools fused")
 
 
+# Pooling split between the layer before (columns, as it writes) and the squeeze behind (rows, as it reads): a maximum
+# picks one of the same values in any order and the squeeze runs the same tiling, so the probabilities are the bits of
+# the form that pools wholly inside the squeeze.  Batches: 3 and 5 (tile groups of the expand pairs run across image
+# borders, 5 x 784 and 5 x 196 tiles are no multiples of 16), 1 (no pair kernel: the split falls back), 64 (the
+# benchmark's launch shapes; the default policy splits there).
+@pytest.mark.parametrize("n", [3, 5, 1, 64])
+def test_network_with_split_pooling(sq, n):
+    cfg = synth.config_squeezenet(seed=6, n=min(n, 4))
+    params = [dev(p) for p in cfg["params"]]
+    x = dev(cfg["x"])
+    if n > 4:
+        x = torch.cat([x.roll(k, 0).roll(3 * k, 3) for k in range((n + 3) // 4)])[:n].contiguous()
+    try:
+        sq.lib.sq_tune_fuse_pools_f32(7)
+        inside = sq.sq_squeezenet_forward(x, params)
+        for mask in (8 | 6, 16 | 5, 32 | 3, 56, 24):
+            sq.lib.sq_tune_fuse_pools_f32(mask)
+            sq.sq_profile_begin(64)
+            split = sq.sq_squeezenet_forward(x, params)
+            names = [r["name"] for r in sq.sq_profile_end()]
+            assert torch.equal(split, inside), f"mask {mask}"
+            if n >= 3:
+                want = ((mask >> 3) & 1) + ((mask >> 4) & 1) + ((mask >> 5) & 1)
+                assert sum("poolrows+" in k for k in names) == want and sum("+poolcols" in k for k in names) == want, names
+        sq.lib.sq_tune_fuse_pools_f32(-1)
+        assert torch.equal(sq.sq_squeezenet_forward(x, params), inside)
+    finally:
+        sq.lib.sq_tune_fuse_pools_f32(-1)
+    if n <= 5:
+        xs = x.cpu().numpy()
+        assert_close(inside, oracle.squeezenet(xs, cfg["params"]), FP32_TOL, "split pooling vs oracle")
+
+
 # planes of up to 256 pixels take the kernel with every load issued up front, one plane per wavefront or, from
 # 16384 planes on, four (16386 planes: the last wavefront has two); larger planes take the loop
 @pytest.mark.parametrize("shape", [(2, 1000, 13, 13), (1, 7, 5, 3), (3, 2, 1, 1), (1, 1, 30, 30), (3, 5462, 13, 13),
@@ -509,13 +542,15 @@ def test_benchmark_configuration_runs_the_kernels_it_reports(sq):
     torch.cuda.synchronize()
     names = [r["name"] for r in sq.sq_profile_end()]
     kernels = {n.split("|")[1] for n in names}
-    assert "conv1|k7s2c3_waves8" in names
+    # conv1 and the expand pairs before a pooling layer pool the columns as they write, the squeezes behind pool the rows
+    assert "conv1|k7s2c3_waves8+poolcols" in names
+    assert sum(n.split("|")[1].startswith("poolrows+") for n in names) == 3 and sum(n.endswith("+poolcols") for n in names) == 3, names
     # both expands of every fire layer in one launch, behind a minimal-filtering expand3x3 in one of its two forms
     assert sum("/e1+e3|k3s1_f2x2" in n and "+k1" in n for n in names) == 8, names
     assert "kernel transform|f2x2_kernel_transform" in names
     assert not any("direct" in k for k in kernels), kernels
     # conv1, eight fire layers of two launches (squeeze; both expands), conv10 writing plane sums, average + softmax,
-    # kernel transform; the three max-pooling layers run inside the squeeze layers that read them
+    # kernel transform; the three max-pooling layers run inside their neighbours
     assert len(names) == 20 and not any("maxpool" in k for k in kernels), names
     assert "avgpool+softmax|planesums+softmax" in names and any(n.startswith("conv10|") and n.endswith("+planesums") for n in names)
 

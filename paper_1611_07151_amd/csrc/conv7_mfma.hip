@@ -28,7 +28,7 @@
 //
 // Column-pooled form (CP; the max pooling behind conv1 split between this kernel and the squeeze layer that
 // follows, see ColPool).  The 16 pixels of a tile row sit in the 16 lanes of a DPP row, so the maximum over columns
-// c, c+1, c+2 is two v_max with a row shift (lanes past the row read zero, which a ReLU'd value never falls below).
+// c, c+1, c+2 is two v_max with a row shift (lanes past the row read zero; the ReLU is left to the reader of the map).
 // Even lanes then hold the eight pooled columns of the tile and store them to the column-pooled map (tile cb of a row
 // at positions 9 cb .. 9 cb + 7); the eighth lacks the first column of the next tile, which that tile's lane 0
 // writes, unpooled, into the seam slot between the two (position 9 cb - 1 of its own row).
@@ -269,7 +269,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (p.relu) {
+        // (CP: no ReLU here -- the layer that reads the column-pooled map ends its maximum with a zero, and
+        // max(relu(a), relu(b)) = relu(max(a, b)); the zeros a row shift brings in past a row's end vanish likewise)
+        if (p.relu && !CP) {
 #pragma unroll
             for (int x = 0; x < kTM; ++x)
 #pragma unroll

@@ -53,7 +53,8 @@ namespace mfma {
 // kernel), where the third column belongs to the next group and sits, unpooled, in a seam slot right behind.  This
 // kernel takes the maximum over rows 2y..2y+2 and, at those columns, the seam slots: three 8-byte loads per staged
 // element instead of nine values, and about half the bytes.  The second value of a load is used only at a seam
-// (chosen with a select, so whatever else lies there does no harm).
+// (chosen with a select, so whatever else lies there does no harm).  The producers leave their ReLU to this kernel:
+// the maximum it takes always contains a zero (the value selected where there is no seam).
 //
 // conv_mfma_tile is the work of one workgroup (tile number `block` of the launch), conv_mfma_kernel the
 // kernel that consists of nothing else; the expand pair kernel (conv_wino_kernel.h) runs the same tiles
@@ -302,6 +303,7 @@ __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block
 #pragma unroll
             for (int r = 0; r < XREG; ++r) {
                 const float m = fmaxf(fmaxf(xwin[r][0], xwin[r][2]), xwin[r][4]);
+                // a missing seam counts as zero, which is also the producer's ReLU
                 const float sa = seamA ? fmaxf(xwin[r][1], xwin[r][3]) : 0.f, sb = seamB ? xwin[r][5] : 0.f;
                 xs[(cpart + (NT / BN) * r) * plane + xdst[0]] = fmaxf(m, fmaxf(sa, sb));
             }

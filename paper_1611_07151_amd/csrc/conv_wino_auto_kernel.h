@@ -64,7 +64,9 @@ __device__ __forceinline__ void conv_wino_auto_items(const KParams &p, const int
 
     const rsrc_t rout = make_rsrc(p.out, p.out_bytes);
     const uint32_t hs = (uint32_t)(CP ? p.Ho * p.cpRS : p.HoWo) * 4u;   // layer stride of the map written
-    const float lowest = p.relu ? 0.f : -__builtin_inff();
+    // CP: no ReLU here -- the layer that reads the column-pooled map ends its maximum with a zero, and
+    // max(relu(a), relu(b)) = relu(max(a, b)); the zeros a row shift brings in at the end of a row vanish the same way
+    const float lowest = p.relu && !CP ? 0.f : -__builtin_inff();
 
     {
         __syncthreads();                                    // everybody has left the previous block
@@ -327,10 +329,10 @@ __device__ __forceinline__ void conv_wino_auto_items(const KParams &p, const int
                             z[i][0] = acc[4 * i][lb][r] + acc[4 * i + 1][lb][r] + acc[4 * i + 2][lb][r];
                             z[i][1] = acc[4 * i + 1][lb][r] - acc[4 * i + 2][lb][r] - acc[4 * i + 3][lb][r];
                         }
-                        const float y00 = fmaxf(z[0][0] + z[1][0] + z[2][0], lowest);
-                        const float y01 = fmaxf(z[0][1] + z[1][1] + z[2][1], lowest);
-                        const float y10 = fmaxf(z[1][0] - z[2][0] - z[3][0], lowest);
-                        const float y11 = fmaxf(z[1][1] - z[2][1] - z[3][1], lowest);
+                        const float y00 = CP ? z[0][0] + z[1][0] + z[2][0] : fmaxf(z[0][0] + z[1][0] + z[2][0], lowest);
+                        const float y01 = CP ? z[0][1] + z[1][1] + z[2][1] : fmaxf(z[0][1] + z[1][1] + z[2][1], lowest);
+                        const float y10 = CP ? z[1][0] - z[2][0] - z[3][0] : fmaxf(z[1][0] - z[2][0] - z[3][0], lowest);
+                        const float y11 = CP ? z[1][1] - z[2][1] - z[3][1] : fmaxf(z[1][1] - z[2][1] - z[3][1], lowest);
                         if constexpr (CP) {
                             put_pooled(0u, lb * 16 + r, y00, y01, y10, y11);
                         } else {
@@ -350,8 +352,8 @@ __device__ __forceinline__ void conv_wino_auto_items(const KParams &p, const int
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
                             const uint32_t so = (uint32_t)__builtin_amdgcn_readfirstlane(lb * 16 + r) * hs;
-                            const float y00 = fmaxf(e[0][lb][r], lowest), y01 = fmaxf(e[1][lb][r], lowest);
-                            const float y10 = fmaxf(e[2][lb][r], lowest), y11 = fmaxf(e[3][lb][r], lowest);
+                            const float y00 = CP ? e[0][lb][r] : fmaxf(e[0][lb][r], lowest), y01 = CP ? e[1][lb][r] : fmaxf(e[1][lb][r], lowest);
+                            const float y10 = CP ? e[2][lb][r] : fmaxf(e[2][lb][r], lowest), y11 = CP ? e[3][lb][r] : fmaxf(e[3][lb][r], lowest);
                             if constexpr (CP) {
                                 put_pooled(d1, lb * 16 + r, y00, y01, y10, y11);
                                 continue;

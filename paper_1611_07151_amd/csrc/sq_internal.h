@@ -34,7 +34,7 @@ bool fire_bf16_register_kernels();
 // to layers [c_offset, c_offset+Cout) of an [N][out_channels][Ho][Wo] tensor.
 // Max pooling (3x3 window, stride 2, floor mode; section "Pooling and Softmax") split between the layer before it and
 // the 1x1 layer behind it, so that about half of the producer's map goes through memory and the pooled map never
-// exists.  The producer (ReLU on) writes a column-pooled map [N][layers][Ho][row_stride]: for pooled column x
+// exists.  The producer (a layer with ReLU) writes a column-pooled map [N][layers][Ho][row_stride]: for pooled column x
 // (x < Wp = (Wo - 3) / 2 + 1) of its row r the maximum of its columns 2x, 2x+1, 2x+2.  Its work items cover 2 rows x
 // 2^shift pooled columns ("groups"; pooled column x of producer tile row ty of image n is slot q = n * slots_image +
 // ty * slots_row + x, group = q >> shift).  In the last slot of a group the third column lies in the next group:
@@ -42,8 +42,9 @@ bool fire_bf16_register_kernels();
 // into a seam slot right behind it.  So column x of tile row ty sits at position x + (number of group ends before
 // it in this row) = x + ((q0 + x) >> shift) - (q0 >> shift), q0 = the row's first slot, and a seam slot follows
 // wherever (q0 + x) % 2^shift is the last of its group.  The consumer takes the maximum over rows 2y..2y+2 and, at
-// those columns, the seam slots (one 8-byte load per row).  Exact: a maximum picks one of the producer's values
-// whatever the order.
+// those columns, the seam slots (one 8-byte load per row), and a zero: the producer's ReLU, which it leaves to the
+// consumer (the map holds values before ReLU; relu(max(a, b)) = max(relu(a), relu(b))).  Exact: a maximum picks one
+// of the producer's values whatever the order.
 struct ColPool {
     int shift = 0, slots_row = 0, slots_image = 0;
     int row_stride = 0;   // floats per row of the map: Wp + (Wp >> shift) + 2 holds every seam slot

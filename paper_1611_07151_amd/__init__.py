@@ -17,4 +17,5 @@ from .binding import (  # noqa: F401
     sq_blocked_map_bytes, sq_blocked_pack, sq_blocked_unpack, sq_blocked_kernel_bytes, sq_blocked_pack_kernels,
     sq_blocked_conv2d_forward, sq_blocked_kernel7_bytes, sq_blocked_pack_kernels7, sq_blocked_conv7s2_forward, sq_blocked_fire_forward, sq_blocked_pool_conv2d_forward,
     sq_blocked_maxpool, sq_blocked_avgpool_global, sq_squeezenet_bf16_packed_bytes,
-    sq_squeezenet_bf16_pack_params, sq_squeezenet_bf16_workspace_bytes, sq_squeezenet_forward_bf16, sq_squeezenet_workspace_bytes, sq_strerror, TAP_NAMES, TAP_SHAPES)
+    sq_squeezenet_bf16_pack_params, sq_squeezenet_bf16_workspace_bytes, sq_squeezenet_forward_bf16, sq_squeezenet_workspace_bytes, sq_strerror, TAP_NAMES, TAP_SHAPES,
+    sq_tune_conv2d_forward_poolcols, sq_tune_fire_forward_poolcols, sq_tune_poolrows_conv2d_forward)

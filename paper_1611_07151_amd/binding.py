@@ -39,6 +39,9 @@ lib.sq_conv2d_strided_workspace_bytes.restype = _sz
 lib.sq_conv2d_strided_workspace_bytes.argtypes = [_i] * 8
 lib.sq_maxpool.argtypes = [_vp, _vp] + [_i] * 6
 lib.sq_maxpool_conv2d_forward.argtypes = [_vp] * 4 + [_i] * 9
+lib.sq_tune_conv2d_forward_poolcols.argtypes = [_vp] * 4 + [_i] * 8 + [ctypes.POINTER(_i)]
+lib.sq_tune_fire_forward_poolcols.argtypes = [_vp] * 8 + [_i] * 7 + [_vp, ctypes.c_size_t, ctypes.POINTER(_i)]
+lib.sq_tune_poolrows_conv2d_forward.argtypes = [_vp] * 4 + [_i] * 9 + [ctypes.POINTER(_i)]
 lib.sq_avgpool_global.argtypes = [_vp, _vp] + [_i] * 4
 lib.sq_softmax.argtypes = [_vp, _vp, _i, _i]
 lib.sq_fire_forward.argtypes = [_vp] * 8 + [_i] * 7 + [_vp, _sz]
@@ -253,6 +256,52 @@ def sq_maxpool_conv2d_forward(x, w, b=None, relu=True, out=None, c_offset=0, alg
                                          _dev(b, torch.float32, "b") if b is not None else None, _dev(out),
                                          N, Cin, H, W, Cout, int(bool(relu)), out.shape[1], int(c_offset), int(algo)),
            "sq_maxpool_conv2d_forward")
+    return out
+
+
+def sq_tune_conv2d_forward_poolcols(x, w, b, pad=2):
+    """conv1-type layer writing the column-pooled map of its result -> (map [N, Cout, Ho, row stride], geometry)."""
+    N, Cin, H, W = x.shape
+    Cout, K, S = w.shape[0], w.shape[2], 2
+    Ho, Wo = (H + 2 * pad - K) // S + 1, (W + 2 * pad - K) // S + 1
+    out = torch.full((N * Cout * Ho * Wo,), float("nan"), device=x.device, dtype=torch.float32)
+    g = (_i * 4)()
+    _use_current_stream()
+    _check(lib.sq_tune_conv2d_forward_poolcols(_dev(x, torch.float32, "x"), _dev(w, torch.float32, "w"), _dev(b, torch.float32, "b"),
+                                               _dev(out), N, Cin, H, W, Cout, K, S, int(pad), g), "sq_tune_conv2d_forward_poolcols")
+    g = list(g)
+    return out[:N * Cout * Ho * g[3]].view(N, Cout, Ho, g[3]), g
+
+
+def sq_tune_fire_forward_poolcols(x, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3):
+    """sq_fire_forward writing the column-pooled map of its result -> (map [N, Ce1 + Ce3, H, row stride], geometry)."""
+    N, Cin, H, W = x.shape
+    Csq, Ce1, Ce3 = w_sq.shape[0], w_e1.shape[0], w_e3.shape[0]
+    ws = torch.empty(max(sq_fire_workspace_bytes(N, H, W, Csq, Ce3), 256), device=x.device, dtype=torch.uint8)
+    out = torch.full((N * (Ce1 + Ce3) * H * W,), float("nan"), device=x.device, dtype=torch.float32)
+    g = (_i * 4)()
+    _use_current_stream()
+    _check(lib.sq_tune_fire_forward_poolcols(_dev(x, torch.float32, "x"), _dev(w_sq, torch.float32, "w_sq"), _dev(b_sq, torch.float32, "b_sq"),
+                                             _dev(w_e1, torch.float32, "w_e1"), _dev(b_e1, torch.float32, "b_e1"),
+                                             _dev(w_e3, torch.float32, "w_e3"), _dev(b_e3, torch.float32, "b_e3"), _dev(out),
+                                             N, Cin, H, W, Csq, Ce1, Ce3, _dev(ws), ws.numel(), g), "sq_tune_fire_forward_poolcols")
+    g = list(g)
+    return out[:N * (Ce1 + Ce3) * H * g[3]].view(N, Ce1 + Ce3, H, g[3]), g
+
+
+def sq_tune_poolrows_conv2d_forward(x, W, w, b, geometry, relu=True, algo=SQ_ALGO_AUTO):
+    """1x1 convolution of a column-pooled map x [N, Cin, H, row stride] of H x W results per layer."""
+    N, Cin, H, rs = x.shape
+    Cout = w.shape[0]
+    if rs != geometry[3]:
+        raise ValueError("row stride of the map and of the geometry differ")
+    out = torch.empty((N, Cout, (H - 3) // 2 + 1, (W - 3) // 2 + 1), device=x.device, dtype=torch.float32)
+    g = (_i * 4)(*[int(v) for v in geometry])
+    _use_current_stream()
+    _check(lib.sq_tune_poolrows_conv2d_forward(_dev(x, torch.float32, "x"), _dev(w, torch.float32, "w"),
+                                               _dev(b, torch.float32, "b") if b is not None else None, _dev(out),
+                                               N, Cin, H, int(W), Cout, int(bool(relu)), Cout, 0, int(algo), g),
+           "sq_tune_poolrows_conv2d_forward")
     return out
 
 

@@ -433,6 +433,62 @@ int sq_maxpool_conv2d_forward(const float *in, const float *w, const float *b, f
     return run_conv(a, algo);
 }
 
+// ---- the kernels of the split pooling one at a time (tests, tuner; declared in sq_tuning.h) -----------------
+int sq_tune_conv2d_forward_poolcols(const float *in, const float *w, const float *b, float *out, int N, int Cin, int H, int W,
+                                    int Cout, int K, int S, int P, int *geometry)
+{
+    if (!in || !w || !out || !geometry) return SQ_ERR_NULL;
+    if (N <= 0 || H <= 0 || W <= 0 || P < 0) return SQ_ERR_SHAPE;
+    if (Cin != 3 || K != 7 || S != 2 || Cout != 96 || g_dtype != SQ_F32) return SQ_ERR_UNSUPPORTED;
+    if (H + 2 * P < K || W + 2 * P < K) return SQ_ERR_SHAPE;
+    ConvArgs a = make_args(in, w, b, out, N, Cin, H, W, Cout, K, S, P, 1, Cout, 0, SQ_F32);
+    if (a.Wo < 3) return SQ_ERR_SHAPE;
+    // tiles of 2 rows x 16 columns = 8 pooled columns
+    const int CB = (a.Wo + 15) / 16, RG = (a.Ho + 1) / 2;
+    a.cp_out = true;
+    a.cp.shift = 3; a.cp.slots_row = 8 * CB; a.cp.slots_image = 8 * CB * RG;
+    a.cp.row_stride = colpool_row_stride(a.Wo, 3);
+    geometry[0] = a.cp.shift; geometry[1] = a.cp.slots_row; geometry[2] = a.cp.slots_image; geometry[3] = a.cp.row_stride;
+    return conv_mfma(a, -1);
+}
+
+int sq_tune_fire_forward_poolcols(const float *in, const float *w_sq, const float *b_sq, const float *w_e1, const float *b_e1,
+                                  const float *w_e3, const float *b_e3, float *out, int N, int Cin, int H, int W, int Csq,
+                                  int Ce1, int Ce3, void *workspace, size_t workspace_bytes, int *geometry)
+{
+    if (!in || !w_sq || !w_e1 || !w_e3 || !out || !geometry) return SQ_ERR_NULL;
+    if (N <= 0 || Cin <= 0 || H <= 0 || W < 3 || Csq <= 0 || Ce1 <= 0 || Ce3 <= 0) return SQ_ERR_SHAPE;
+    if (g_dtype != SQ_F32) return SQ_ERR_UNSUPPORTED;
+    const size_t map_bytes = align_up((size_t)N * Csq * H * W * sizeof(float), 256);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < sq_fire_workspace_bytes(N, H, W, Csq, Ce3)) return SQ_ERR_WORKSPACE;
+    // tile groups of the expand pair: 16 tiles of 2 x 2 pixels, numbered through the batch
+    ColPool cp;
+    cp.shift = 4; cp.slots_row = (W + 1) / 2; cp.slots_image = cp.slots_row * ((H + 1) / 2);
+    cp.row_stride = colpool_row_stride(W, 4);
+    geometry[0] = cp.shift; geometry[1] = cp.slots_row; geometry[2] = cp.slots_image; geometry[3] = cp.row_stride;
+    return fire_impl(in, w_sq, b_sq, w_e1, b_e1, w_e3, b_e3, out, N, Cin, H, W, Csq, Ce1, Ce3, (float *)workspace,
+                     (char *)workspace + map_bytes, workspace_bytes - map_bytes, false, kFireAlone, 0, 0, SQ_ALGO_AUTO, nullptr, &cp);
+}
+
+int sq_tune_poolrows_conv2d_forward(const float *in, const float *w, const float *b, float *out, int N, int Cin, int H, int W,
+                                    int Cout, int relu, int out_channels, int c_offset, int algo, const int *geometry)
+{
+    if (!in || !w || !out || !geometry) return SQ_ERR_NULL;
+    if (N <= 0 || Cin <= 0 || Cout <= 0 || H < 3 || W < 3) return SQ_ERR_SHAPE;
+    if (c_offset < 0 || out_channels <= 0 || (long long)c_offset + Cout > out_channels) return SQ_ERR_SHAPE;
+    if (algo < 0 || algo == SQ_ALGO_DIRECT || g_dtype != SQ_F32) return SQ_ERR_UNSUPPORTED;
+    const int Hp = (H - 3) / 2 + 1, Wp = (W - 3) / 2 + 1;
+    // the geometry must describe rows of (W + 1) / 2 or more slots that hold every seam
+    if (geometry[0] < 1 || geometry[0] > 8 || geometry[1] < Wp || geometry[2] < geometry[1] * ((H + 1) / 2) ||
+        geometry[3] < colpool_row_stride(W, geometry[0]) || (long long)N * geometry[2] >= (1ll << 30))
+        return SQ_ERR_SHAPE;
+    ConvArgs a = make_args(in, w, b, out, N, Cin, Hp, Wp, Cout, 1, 1, 0, relu, out_channels, c_offset, SQ_F32);
+    a.pool_H = H; a.pool_W = W;
+    a.cp_in = true;
+    a.cp.shift = geometry[0]; a.cp.slots_row = geometry[1]; a.cp.slots_image = geometry[2]; a.cp.row_stride = geometry[3];
+    return run_conv(a, algo);
+}
+
 int sq_maxpool(const float *in, float *out, int N, int C, int H, int W, int K, int S)
 {
     if (!in || !out) return SQ_ERR_NULL;

@@ -32,6 +32,8 @@
 // Even lanes then hold the eight pooled columns of the tile and store them to the column-pooled map (tile cb of a row
 // at positions 9 cb .. 9 cb + 7); the eighth lacks the first column of the next tile, which that tile's lane 0
 // writes, unpooled, into the seam slot between the two (position 9 cb - 1 of its own row).
+#include <type_traits>
+
 #include "conv_mfma_common.h"
 
 namespace sq {
@@ -229,19 +231,29 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
         }
     };
 
-    // One tile: 74 MFMA steps into `acc`, with the previous tile's results (`prev`, already
-    // ReLU'd) stored one per MFMA step at the walking byte offset prev_off.
-    auto tile_mfma = [&](int buf, Acc (&acc)[kTM], const Acc (&prev)[kTM], uint32_t prev_off, uint32_t prev_soff) {
+    // What is left to store of a finished tile: lane offsets of its layer blocks (kOob = block not computed, or
+    // nothing to store yet) and of their seam slots (CP).  Where block 0 of the accumulators holds another layer block
+    // than the first, the difference is part of the lane offset, so that the scalar offset of every store stays a
+    // compile-time multiple of the layer stride (computed next to the store it would cost wait states each time).
+    struct Pending {
+        uint32_t off[kTM], soff[kTM];
+    };
+    // One tile: 74 MFMA steps into NB of the accumulators (NB = kTM: all layer blocks, A operands at aoff[];
+    // NB = 1: the one block whose A operands start abase floats behind aoff[0], into acc[0]), with the previous
+    // tile's results (`prev`, already ReLU'd) stored one per MFMA step at the walking byte offsets of `pend`.
+    auto tile_mfma = [&](auto nb_tag, int buf, Acc (&acc)[kTM], int abase, const Acc (&prev)[kTM], const Pending &pend, int pend_mbase) {
+        constexpr int NB = decltype(nb_tag)::value;
         const float *xs = Xw + buf * kXbuf;
+        const float *wsb = Ws + abase;
         auto b_read = [&](int s) -> float {
             if (s == 73) return xs[b4];
             const int base = s < 49 ? b1 : s < 70 ? b2 : b3;
             return xs[base + step_offset(s)];
         };
-        float av[2][kTM], bv[2];
+        float av[2][NB], bv[2];
         auto fetch = [&](int s, float *a, float &b) {
 #pragma unroll
-            for (int x = 0; x < kTM; ++x) a[x] = Ws[aoff[x] + 2 * s];
+            for (int x = 0; x < NB; ++x) a[x] = wsb[aoff[x] + 2 * s];
             b = b_read(s);
         };
         fetch(0, av[0], bv[0]);
@@ -250,7 +262,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
             if (s + 1 < 74) fetch(s + 1, av[(s + 1) & 1], bv[(s + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);  // reads of step s+1 stay ahead of the MFMAs of step s
 #pragma unroll
-            for (int x = 0; x < kTM; ++x) {
+            for (int x = 0; x < NB; ++x) {
                 if (s == 0) {
                     Acc z;
 #pragma unroll
@@ -265,7 +277,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
                 // upper), and Cout is a multiple of 8, so the layer test is uniform
                 const int x = s / 16, r = s % 16;
                 const int mu = m0 + x * 32 + M::row_reg(r);
-                if (FULL || mu < p.Cout) put(prev_off, prev_soff, mu, prev[x][r]);
+                if (FULL || mu + pend_mbase < p.Cout) put(pend.off[x], pend.soff[x], mu, prev[x][r]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -273,7 +285,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
         // max(relu(a), relu(b)) = relu(max(a, b)); the zeros a row shift brings in past a row's end vanish likewise)
         if (p.relu && !CP) {
 #pragma unroll
-            for (int x = 0; x < kTM; ++x)
+            for (int x = 0; x < NB; ++x)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[x][r] = fmaxf(acc[x][r], 0.f);
         }
@@ -284,17 +296,44 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
     // from a counter in LDS, so a wavefront that gets less of the SIMD (the hardware favours the
     // older one of two) simply takes fewer tiles and all finish together.  Every wavefront
     // leaves the loop as soon as its draw is past the last tile.  (Fewer than eight workgroups: plain striding.)
+    //
+    // The last round.  A workgroup's tiles are rarely a multiple of its wavefronts.  With all layer blocks in one
+    // workgroup (kTM = 3) the tiles left over after the last full round are therefore dealt out by layer block, a
+    // third of a tile per draw, where that shortens the round (up to five tiles left for eight wavefronts).  Measured
+    // on the layer alone: 3-11 % faster at batches 2 to 48 (one to nine rounds per wavefront), nothing at batch 64
+    // and above (98 tiles per workgroup = 12 1/4 rounds: there the wavefronts of a CU drift apart by more than a
+    // tile over the launch, and the CUs among themselves, so the last tiles never were a round of their own).
     const bool by_xcd = gridDim.x >= 8;
     const XcdShare share = xcd_share((int)blockIdx.x, (int)gridDim.x, ntiles);
-    auto draw = [&]() -> int {
+    int whole = 1 << 30;   // draws below this are whole tiles
+    int parts = 0;         // draws from `whole` on: one layer block each, this many
+    if (kTM == 3 && by_xcd && share.end > share.first) {
+        const int cnt = (share.end - share.first + share.step - 1) / share.step;
+        const int rem = cnt % NW;
+        if (rem > 0 && (3 * rem + NW - 1) / NW < 3) {
+            whole = cnt - rem;
+            parts = 3 * rem;
+        }
+    }
+    // -> tile (ntiles = none left) and layer block (-1 = all)
+    auto draw = [&](int &part) -> int {
         int k = 0;
         if (lane == 0) k = atomicAdd(next_tile, 1);
         k = __builtin_amdgcn_readfirstlane(k);
+        part = -1;
         if (!by_xcd) return (int)blockIdx.x + k * (int)gridDim.x;
+        if (k >= whole) {
+            const int j = k - whole;
+            if (j >= parts) return ntiles;
+            const int t3 = (j * 11) >> 5;   // j / 3 for j < 32
+            part = j - 3 * t3;
+            k = whole + t3;
+        }
         const long long tl = (long long)share.first + (long long)k * share.step;
         return tl < share.end ? (int)tl : ntiles;
     };
-    int tile = draw();
+    int part = -1;
+    int tile = draw(part);
     if (tile >= ntiles) return;
     load_patch(tile);
     store_patch(0);
@@ -304,44 +343,67 @@ __global__ __launch_bounds__(NW * 64, MINW) void conv7s2c3_kernel(const KParams 
     for (int x = 0; x < kTM; ++x)
 #pragma unroll
         for (int r = 0; r < 16; ++r) accA[x][r] = accB[x][r] = 0.f;
-    uint32_t offA = kOob, offB = kOob;   // nothing to store yet
-    uint32_t soffA = kOob, soffB = kOob;
+    Pending pendA, pendB;   // nothing to store yet
+#pragma unroll
+    for (int x = 0; x < kTM; ++x) pendA.off[x] = pendA.soff[x] = pendB.off[x] = pendB.soff[x] = kOob;
+    int mbaseA = 0, mbaseB = 0;   // first layer of accumulator block 0 (only the partial-layer test needs it)
     bool lastA = true;
+
+    // the tile just computed, as its stores will want it
+    auto pending_of = [&](int tile_, int part_, Pending &pd, int &mbase) {
+        mbase = part_ < 0 ? 0 : part_ * 32;
+        const uint32_t shift = (uint32_t)mbase * hs1;     // kOob + shift stays beyond every range
+        const uint32_t o = out_offset(tile_) + shift;
+        uint32_t so = kOob;
+        if constexpr (CP) so = seam_offset(tile_) + shift;
+#pragma unroll
+        for (int x = 0; x < kTM; ++x) {
+            const bool have = part_ < 0 || x == 0;
+            pd.off[x] = have ? o : kOob;
+            pd.soff[x] = have ? so : kOob;
+        }
+    };
+    auto compute = [&](int buf, int part_, Acc (&acc)[kTM], const Acc (&prev)[kTM], const Pending &pend, int pend_mbase) {
+        if (kTM > 1 && part_ >= 0) tile_mfma(std::integral_constant<int, 1>{}, buf, acc, part_ * 32 * kLDK, prev, pend, pend_mbase);
+        else tile_mfma(std::integral_constant<int, kTM>{}, buf, acc, 0, prev, pend, pend_mbase);
+    };
 
     // two tiles per trip: even tiles use patch buffer 0 and accumulators A, odd ones 1 and B
     while (true) {
         {
-            const int next = draw();
+            int npart;
+            const int next = draw(npart);
             const bool more = next < ntiles;
             if (more) load_patch(next);
-            tile_mfma(0, accA, accB, offB, soffB);
-            offA = out_offset(tile);
-            if constexpr (CP) soffA = seam_offset(tile);
+            compute(0, part, accA, accB, pendB, mbaseB);
+            pending_of(tile, part, pendA, mbaseA);
             lastA = true;
             if (!more) break;
             store_patch(1);
-            tile = next;
+            tile = next; part = npart;
         }
         {
-            const int next = draw();
+            int npart;
+            const int next = draw(npart);
             const bool more = next < ntiles;
             if (more) load_patch(next);
-            tile_mfma(1, accB, accA, offA, soffA);
-            offB = out_offset(tile);
-            if constexpr (CP) soffB = seam_offset(tile);
+            compute(1, part, accB, accA, pendA, mbaseA);
+            pending_of(tile, part, pendB, mbaseB);
             lastA = false;
             if (!more) break;
             store_patch(0);
-            tile = next;
+            tile = next; part = npart;
         }
     }
     // results of the last tile
+    const Pending &pl = lastA ? pendA : pendB;
+    const int mbl = lastA ? mbaseA : mbaseB;
 #pragma unroll
     for (int x = 0; x < kTM; ++x)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int mu = m0 + x * 32 + M::row_reg(r);
-            if (FULL || mu < p.Cout) put(lastA ? offA : offB, lastA ? soffA : soffB, mu, lastA ? accA[x][r] : accB[x][r]);
+            if (FULL || mu + mbl < p.Cout) put(pl.off[x], pl.soff[x], mu, lastA ? accA[x][r] : accB[x][r]);
         }
 }
 

@@ -382,3 +382,61 @@ def test_two_host_threads_call_entry_points_at_once(lib):
     for t in threads:
         t.join()
     assert not errors, errors
+
+
+# ---- split pooling (sq_tuning.h): the map format's own arithmetic, and argument checks without a GPU ----------
+
+def _row_stride(Wo, shift):
+    Wp = (Wo - 3) // 2 + 1
+    return Wp + (Wp >> shift) + 2
+
+
+def test_column_pooled_rows_hold_every_seam_slot():
+    """Position of pooled column x = x + (group ends before it); the reader also loads the slot behind it.  For every
+    width, group size and alignment of a row's first slot both must lie inside the row, positions must not collide, and
+    a seam slot must sit exactly between the last column of a group and the first of the next."""
+    for shift in range(1, 7):
+        gm = (1 << shift) - 1
+        for Wo in list(range(3, 140)) + [223, 224, 511]:
+            Wp = (Wo - 3) // 2 + 1
+            rs = _row_stride(Wo, shift)
+            for q0 in range(0, 3 << shift):
+                pos = [x + ((q0 + x) >> shift) - (q0 >> shift) for x in range(Wp)]
+                assert pos[0] == 0 and pos[-1] + 1 <= rs - 1, (shift, Wo, q0)
+                for x in range(1, Wp):
+                    step = pos[x] - pos[x - 1]
+                    assert step == (2 if ((q0 + x - 1) & gm) == gm else 1), (shift, Wo, q0, x)
+                # the writer of the tile after the row's last pooled column puts its first column one slot before
+                # the position that tile's own pooled column would have: still inside the row
+                after = Wp + ((q0 + Wp) >> shift) - (q0 >> shift)
+                assert after - 1 <= rs - 1
+
+
+def test_split_pooling_hooks_validate_before_any_gpu_call(lib):
+    f = ctypes.c_void_p(256)          # never dereferenced on the host
+    geo = (ctypes.c_int * 4)()
+    conv = lib.sq_tune_conv2d_forward_poolcols
+    conv.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 8 + [ctypes.POINTER(ctypes.c_int)]
+    assert conv(None, f, f, f, 1, 3, 224, 224, 96, 7, 2, 2, geo) == -1
+    assert conv(f, f, f, f, 1, 3, 224, 224, 96, 7, 2, 2, None) == -1
+    assert conv(f, f, f, f, 0, 3, 224, 224, 96, 7, 2, 2, geo) == -2
+    assert conv(f, f, f, f, 1, 3, 224, 224, 64, 7, 2, 2, geo) == -3      # only the conv1-type layer has the form
+    assert conv(f, f, f, f, 1, 3, 224, 224, 96, 3, 1, 1, geo) == -3
+    assert conv(f, f, f, f, 1, 3, 5, 224, 96, 7, 2, 0, geo) == -2        # kernel does not fit
+    assert conv(f, f, f, f, 1, 3, 224, 9, 96, 7, 2, 0, geo) == -2        # fewer than three result columns: nothing to pool
+    fire = lib.sq_tune_fire_forward_poolcols
+    fire.argtypes = [ctypes.c_void_p] * 8 + [ctypes.c_int] * 7 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_int)]
+    assert fire(f, f, f, f, f, f, f, None, 3, 32, 9, 9, 16, 32, 32, f, 1 << 30, geo) == -1
+    assert fire(f, f, f, f, f, f, f, f, 3, 32, 9, 2, 16, 32, 32, f, 1 << 30, geo) == -2
+    assert fire(f, f, f, f, f, f, f, f, 3, 32, 9, 9, 16, 32, 32, None, 0, geo) == -4
+    assert fire(f, f, f, f, f, f, f, f, 3, 32, 9, 9, 16, 32, 32, f, 16, geo) == -4
+    assert fire(f, f, f, f, f, f, f, f, 2, 32, 9, 9, 16, 32, 32, f, 1 << 30, geo) == -3   # no expand pair below three images
+    rows = lib.sq_tune_poolrows_conv2d_forward
+    rows.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 9 + [ctypes.POINTER(ctypes.c_int)]
+    ok = (ctypes.c_int * 4)(4, 6, 30, _row_stride(11, 4))
+    assert rows(None, f, f, f, 1, 16, 9, 11, 16, 1, 16, 0, 0, ok) == -1
+    assert rows(f, f, f, f, 1, 16, 2, 11, 16, 1, 16, 0, 0, ok) == -2
+    assert rows(f, f, f, f, 1, 16, 9, 11, 16, 1, 8, 0, 0, ok) == -2       # layer range outside the output tensor
+    assert rows(f, f, f, f, 1, 16, 9, 11, 16, 1, 16, 0, 1, ok) == -3      # the one-thread-per-output kernel has no such form
+    for bad in ((0, 6, 30, 8), (4, 3, 30, 8), (4, 6, 29, 8), (4, 6, 30, _row_stride(11, 4) - 1)):
+        assert rows(f, f, f, f, 1, 16, 9, 11, 16, 1, 16, 0, 0, (ctypes.c_int * 4)(*bad)) == -2, bad

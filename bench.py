@@ -141,8 +141,9 @@ def layer_sweep(sq, synth, torch, mode, B, net="squeezenet", only=None):
         b = torch.rand(cout, device="cuda", generator=gen) * 0.2 - 0.1
         out = torch.empty((B, cout, ho, ho), device="cuda")
         scratch = torch.empty(max(256, sq.sq_conv2d_workspace_bytes(cin, cout, k, s_, p_),
-                                  sq.sq_conv2d_strided_workspace_bytes(B, cin, h, h, cout, k, s_, p_)), device="cuda",
-                              dtype=torch.uint8)
+                                  sq.sq_conv2d_strided_workspace_bytes(B, cin, h, h, cout, k, s_, p_),
+                                  sq.sq_conv2d_bf16_workspace_bytes(B, cin, h, h, cout, k, s_, p_) if mode == "bf16" else 0),
+                              device="cuda", dtype=torch.uint8)
         for _ in range(3):
             sq.sq_conv2d_forward_ws(x, w, b, s_, p_, True, out=out, workspace=scratch)
         sq.sq_profile_begin(64)

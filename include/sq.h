@@ -171,6 +171,17 @@ int sq_conv2d_forward_ex(const void *in, const void *w, const float *b, float *o
  *     sq_conv2d_strided_workspace_bytes(N, Cin, H, W, Cout, K, S, P) (0 = the
  *     form does not apply) and a matrix-core tiling serves the stride-1 form
  *     (regrouped kernels of 1x1, 3x3 or 5x5: e.g. 11x11 stride 4, 5x5 stride 2).
+ *   With bfloat16 operands (in_dtype = SQ_BF16) and workspace_bytes of at least
+ *     sq_conv2d_bf16_workspace_bytes(N, Cin, H, W, Cout, K, S, P) (0 = the form
+ *     does not apply) SQ_ALGO_AUTO runs the layer on the bfloat16 matrix
+ *     instructions: input and kernels are re-ordered inside the workspace, sums
+ *     are fp32 and the fp32 results are not rounded.  It applies where that is
+ *     faster than widening the operands into the fp32 kernels: 3x3 and 5x5
+ *     layers of stride 1 with pad (K-1)/2, 1x1 layers with at least 128 input
+ *     layers and more output than input layers, the conv1 type (7x7, stride 2, three input layers, at most
+ *     96 output layers); Cin a multiple of 16 (except the conv1 type), Cout a
+ *     multiple of 8.  (Sized for out_channels = Cout; a larger output tensor
+ *     only matters for the 2^31-byte limit.)
  * Everything else as for sq_conv2d_forward_ex; the result is the same up to
  * rounding whichever algorithm runs.
  */
@@ -181,6 +192,7 @@ int sq_conv2d_forward_ws(const void *in, const void *w, const float *b, float *o
 
 size_t sq_conv2d_workspace_bytes(int Cin, int Cout, int K, int S, int P);
 size_t sq_conv2d_strided_workspace_bytes(int N, int Cin, int H, int W, int Cout, int K, int S, int P);
+size_t sq_conv2d_bf16_workspace_bytes(int N, int Cin, int H, int W, int Cout, int K, int S, int P);
 
 /*
  * Max pooling (section "Pooling and Softmax"): out[n][c][oh][ow] = largest of the

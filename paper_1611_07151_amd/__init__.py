@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     SQ_ALGO_AUTO, SQ_ALGO_DIRECT, SQ_ALGO_VARIANT0, SQ_BF16, SQ_F32, SQ_SQUEEZENET_MAX_BATCH, SQ_SQUEEZENET_BF16_MAX_BATCH,
     SqError, lib,
     sq_avgpool_global, sq_conv2d_forward, sq_conv2d_forward_ex, sq_conv2d_forward_ws,
-    sq_conv2d_workspace_bytes, sq_conv2d_strided_workspace_bytes, sq_conv_variant_count,
+    sq_conv2d_workspace_bytes, sq_conv2d_strided_workspace_bytes, sq_conv2d_bf16_workspace_bytes, sq_conv_variant_count,
     sq_conv_variant_name, sq_fire_forward, sq_fire_workspace_bytes, sq_maxpool, sq_maxpool_conv2d_forward, sq_softmax,
     sq_profile_begin, sq_profile_end, sq_squeezenet_forward, sq_init, sq_set_dtype, sq_fire_packed_bytes, sq_fire_pack_weights,
     sq_fire_forward_packed, sq_classifier_forward, sq_fire_forward_static, SQ_FIRE_STATIC_SCRATCH_BYTES, sq_packed_weights_bytes, sq_pack_weights, sq_squeezenet_forward_packed,

@@ -37,6 +37,8 @@ lib.sq_conv2d_workspace_bytes.restype = _sz
 lib.sq_conv2d_workspace_bytes.argtypes = [_i] * 5
 lib.sq_conv2d_strided_workspace_bytes.restype = _sz
 lib.sq_conv2d_strided_workspace_bytes.argtypes = [_i] * 8
+lib.sq_conv2d_bf16_workspace_bytes.restype = _sz
+lib.sq_conv2d_bf16_workspace_bytes.argtypes = [_i] * 8
 lib.sq_maxpool.argtypes = [_vp, _vp] + [_i] * 6
 lib.sq_maxpool_conv2d_forward.argtypes = [_vp] * 4 + [_i] * 9
 lib.sq_tune_conv2d_forward_poolcols.argtypes = [_vp] * 4 + [_i] * 8 + [ctypes.POINTER(_i)]
@@ -190,15 +192,21 @@ def sq_conv2d_strided_workspace_bytes(N, Cin, H, W, Cout, K, stride, pad) -> int
     return int(lib.sq_conv2d_strided_workspace_bytes(N, Cin, H, W, Cout, K, stride, pad))
 
 
+def sq_conv2d_bf16_workspace_bytes(N, Cin, H, W, Cout, K, stride, pad) -> int:
+    return int(lib.sq_conv2d_bf16_workspace_bytes(N, Cin, H, W, Cout, K, stride, pad))
+
+
 def sq_conv2d_forward_ws(x, w, b=None, stride=1, pad=0, relu=False, out=None, c_offset=0,
                          algo=SQ_ALGO_AUTO, workspace=None):
-    """sq_conv2d_forward_ex with device scratch (a uint8 tensor; allocated here at the larger of the sizes
-    sq_conv2d_workspace_bytes and sq_conv2d_strided_workspace_bytes report when None), which makes the
-    kernel-transforming algorithms and the space-to-depth form of strided layers available."""
+    """sq_conv2d_forward_ex with device scratch (a uint8 tensor; allocated here at the largest of the sizes
+    sq_conv2d_workspace_bytes, sq_conv2d_strided_workspace_bytes and, for bfloat16 operands,
+    sq_conv2d_bf16_workspace_bytes report when None), which makes the kernel-transforming algorithms, the
+    space-to-depth form of strided layers and the bf16 matrix instructions available."""
     if workspace is None:
+        shape = (x.shape[0], x.shape[1], x.shape[2], x.shape[3], w.shape[0], w.shape[2], stride, pad)
         need = max(sq_conv2d_workspace_bytes(x.shape[1], w.shape[0], w.shape[2], stride, pad),
-                   sq_conv2d_strided_workspace_bytes(x.shape[0], x.shape[1], x.shape[2], x.shape[3], w.shape[0], w.shape[2],
-                                                     stride, pad))
+                   sq_conv2d_strided_workspace_bytes(*shape),
+                   sq_conv2d_bf16_workspace_bytes(*shape) if x.dtype == torch.bfloat16 else 0)
         workspace = torch.empty(max(need, 256), device=x.device, dtype=torch.uint8)
     return _conv_ex(x, w, b, stride, pad, relu, out, c_offset, algo, workspace, True)
 

@@ -137,6 +137,10 @@ int run_conv(const ConvArgs &a, int algo)
     if (a.pool_H && (algo == SQ_ALGO_DIRECT || a.K != 1 || a.S != 1 || a.P != 0)) return SQ_ERR_UNSUPPORTED;
     if (algo == SQ_ALGO_DIRECT) return conv_direct(a);
     if (algo == SQ_ALGO_AUTO) {
+        if (a.dtype == SQ_BF16 && a.ws) {   // bfloat16 operands and scratch: the bf16 matrix instructions where they pay
+            const int rb = conv_bf16_mfma(a);
+            if (rb != SQ_ERR_UNSUPPORTED && rb != SQ_ERR_WORKSPACE) return rb;
+        }
         if (a.S >= 2 && a.ws) {   // given the scratch for it, a strided layer runs as a stride-1 one where that has a tiling
             const int rs = conv_s2d(a);
             if (rs != SQ_ERR_UNSUPPORTED) return rs;
@@ -403,6 +407,12 @@ int sq_conv2d_forward_ws(const void *in, const void *w, const float *b, float *o
     ConvArgs a = make_args(in, w, b, out, N, Cin, H, W, Cout, K, S, P, relu, out_channels, c_offset, in_dtype);
     a.ws = workspace; a.ws_bytes = workspace ? workspace_bytes : 0;
     return run_conv(a, algo);
+}
+
+size_t sq_conv2d_bf16_workspace_bytes(int N, int Cin, int H, int W, int Cout, int K, int S, int P)
+{
+    if (S < 1) return 0;
+    return conv_bf16_mfma_workspace_bytes(N, Cin, H, W, Cout, K, S, P, Cout);
 }
 
 int sq_conv2d_forward_ex(const void *in, const void *w, const float *b, float *out, int N, int Cin,

@@ -115,12 +115,12 @@ struct ConvParams {
     const void *in;      // blocked [N][Cin/8][H][W][8]
     const void *wp;      // packed kernels
     const float *b;      // [Cout] or nullptr
-    void *out;           // blocked [N][ldcb][H][W][8]
+    void *out;           // blocked [N][ldcb][H][W][8]; F32OUT kernels: fp32 [N][ldcb][H][W]
     uint32_t in_bytes, out_bytes, wp_elems;   // wp_elems: 16-byte elements of wp
     int N, Cin, H, W, HW, Cout, K, P, relu;
     int G;               // Cin / 16
     int steps;           // K*K*G, a multiple of the ring depth
-    int ldcb, coffb;     // layer blocks (of 8) per image in `out`, first block written
+    int ldcb, coffb;     // layer blocks (of 8) per image in `out`, first block written (F32OUT: layers, first layer)
     int PT;              // N*H*W
     int tiles;           // pixel tiles of 32*PB
     int ncblk;           // groups of 32*CB output layers = workgroups that share a pixel range
@@ -131,7 +131,9 @@ struct ConvParams {
 // Two convolutions of the same input and the same CB/PB/D may share a launch (the two expands of
 // a fire layer): workgroups [0, split) run pa, the rest run pb.  A single convolution passes
 // split = gridDim.x.
-template <int CB, int PB, int D>
+// F32OUT: the results leave unrounded, as an fp32 NCHW map (a convolution called on its own with bfloat16 inputs:
+// fp32 accumulate and output); the network's layers write the blocked bfloat16 map the next layer reads.
+template <int CB, int PB, int D, bool F32OUT = false>
 __global__ __launch_bounds__(kThreads, 2) void conv_blocked_kernel(const ConvParams pa, const ConvParams pb, const int split)
 {
     const bool second = (int)blockIdx.x >= split;
@@ -195,7 +197,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv_blocked_kernel(const ConvPar
             const int n = fdiv(gq, p.dHW), pix = gq - n * p.HW;
             const int y = fdiv(pix, p.dW), x = pix - y * p.W;
             ibase[pb] = (uint32_t)((n * (p.Cin >> 3) + h) * p.HW + pix) * 16u;
-            obase[pb] = ok ? (uint32_t)((n * p.ldcb + p.coffb) * p.HW + pix) * 16u + 8u * (uint32_t)h : kOob;
+            obase[pb] = !ok ? kOob
+                        : F32OUT ? (uint32_t)((n * p.ldcb + p.coffb + 4 * h) * p.HW + pix) * 4u
+                                 : (uint32_t)((n * p.ldcb + p.coffb) * p.HW + pix) * 16u + 8u * (uint32_t)h;
             uint32_t m = 0;
             for (int tap = 0; tap < KK; ++tap) {
                 const int ky = fdiv(tap, p.dK), kx = tap - ky * p.K;
@@ -296,7 +300,17 @@ __global__ __launch_bounds__(kThreads, 2) void conv_blocked_kernel(const ConvPar
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int lb = (mb0 + cb) * 4 + q;              // layer block (of 8) inside this convolution
-                if (lb * 8 < p.Cout) {                            // uniform
+                if constexpr (F32OUT) {
+                    // register 4q + i = layer 8 lb + 4h + i: 32 neighbouring pixels per store and half-wavefront
+                    if (lb * 8 < p.Cout) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const uint32_t so = (uint32_t)((lb * 8 + i) * p.HW) * 4u;
+#pragma unroll
+                            for (int pb = 0; pb < PB; ++pb) buf_st(rout, obase[pb], so, fmaxf(acc[cb][pb][4 * q + i], lowest));
+                        }
+                    }
+                } else if (lb * 8 < p.Cout) {                            // uniform
                     const uint32_t so = (uint32_t)lb * hw16;
 #pragma unroll
                     for (int pb = 0; pb < PB; ++pb) {
@@ -559,13 +573,13 @@ int grid_for(long long total, int threads)
 }
 
 typedef void (*BlockedConvFn)(const ConvParams, const ConvParams, int);
-template <int CB, int PB> BlockedConvFn conv_fn(int D)
+template <int CB, int PB, bool F32OUT = false> BlockedConvFn conv_fn(int D)
 {
     switch (D) {
-        case 4: return conv_blocked_kernel<CB, PB, 4>;
-        case 3: return conv_blocked_kernel<CB, PB, 3>;
-        case 2: return conv_blocked_kernel<CB, PB, 2>;
-        default: return conv_blocked_kernel<CB, PB, 1>;
+        case 4: return conv_blocked_kernel<CB, PB, 4, F32OUT>;
+        case 3: return conv_blocked_kernel<CB, PB, 3, F32OUT>;
+        case 2: return conv_blocked_kernel<CB, PB, 2, F32OUT>;
+        default: return conv_blocked_kernel<CB, PB, 1, F32OUT>;
     }
 }
 
@@ -648,11 +662,12 @@ struct ConvPlan {
 
 // Fills the launch parameters of one convolution; CB/PB/D = 0 lets this function choose.
 int plan_conv(ConvPlan &pl, const void *in, const void *wp, const float *b, void *out, int N, int Cin, int H, int W, int Cout,
-              int K, int P, int relu, int ldc_channels, int c_offset, int CB, int PB, int D)
+              int K, int P, int relu, int ldc_channels, int c_offset, int CB, int PB, int D, bool f32_out = false)
 {
-    if (!blocked_conv_supported(Cin, Cout, K, P) || ldc_channels % 8 != 0 || c_offset % 8 != 0) return SQ_ERR_UNSUPPORTED;
+    if (!blocked_conv_supported(Cin, Cout, K, P)) return SQ_ERR_UNSUPPORTED;
+    if (!f32_out && (ldc_channels % 8 != 0 || c_offset % 8 != 0)) return SQ_ERR_UNSUPPORTED;
     const long long in_bytes = (long long)blocked_map_bytes(N, Cin, H, W);
-    const long long out_bytes = (long long)blocked_map_bytes(N, ldc_channels, H, W);
+    const long long out_bytes = f32_out ? (long long)N * ldc_channels * H * W * 4 : (long long)blocked_map_bytes(N, ldc_channels, H, W);
     const long long PT = (long long)N * H * W;
     if (in_bytes >= (1ll << 31) || out_bytes >= (1ll << 31) || PT >= (1ll << 30)) return SQ_ERR_UNSUPPORTED;
 
@@ -664,7 +679,7 @@ int plan_conv(ConvPlan &pl, const void *in, const void *wp, const float *b, void
     p.Hin = H; p.Win = W;
     p.G = Cin / 16;
     p.steps = K * K * p.G;
-    p.ldcb = ldc_channels / 8; p.coffb = c_offset / 8;
+    p.ldcb = f32_out ? ldc_channels : ldc_channels / 8; p.coffb = f32_out ? c_offset : c_offset / 8;
     p.PT = (int)PT;
     p.dHW = make_fastdiv(p.HW); p.dW = make_fastdiv(W); p.dG = make_fastdiv(p.G); p.dK = make_fastdiv(K);
 
@@ -673,8 +688,9 @@ int plan_conv(ConvPlan &pl, const void *in, const void *wp, const float *b, void
     const bool two_fit = 2 * pl.per_mb + 512 <= (size_t)mfma::kLdsBytes / 2;
     if (CB == 0) CB = (Cout > 32 && two_fit) ? 2 : 1;
     if (CB == 2 && !two_fit) return SQ_ERR_UNSUPPORTED;
-    // wavefront tiles of 32 pixels: measured equal to or faster than 64 on every layer of the network
-    if (PB == 0) PB = 1;
+    // wavefront tiles of 32 pixels: measured equal to or faster than 64 on every layer of the network; with fp32 NCHW
+    // results 64 pixels (256-byte runs per layer and store) are 3-20 % faster at batch 256
+    if (PB == 0) PB = f32_out ? 2 : 1;
     if (g_force_cb == 1 || (g_force_cb == 2 && two_fit)) CB = g_force_cb;
     if (g_force_pb == 1 || g_force_pb == 2) PB = g_force_pb;
     if (D == 0) {
@@ -687,12 +703,13 @@ int plan_conv(ConvPlan &pl, const void *in, const void *wp, const float *b, void
     p.ncblk = (Cout + 32 * CB - 1) / (32 * CB);
     p.dNcblk = make_fastdiv(p.ncblk);
     pl.flops = 2.0 * N * Cout * H * W * (double)Cin * K * K;
-    pl.bytes = 2.0 * ((double)N * Cin * H * W + (double)Cout * Cin * K * K + (double)N * Cout * H * W) + 4.0 * Cout;
+    pl.bytes = 2.0 * ((double)N * Cin * H * W + (double)Cout * Cin * K * K) + (f32_out ? 4.0 : 2.0) * N * Cout * H * W + 4.0 * Cout;
     return SQ_OK;
 }
 
-BlockedConvFn kernel_for(int CB, int PB, int D)
+BlockedConvFn kernel_for(int CB, int PB, int D, bool f32_out = false)
 {
+    if (f32_out) return CB == 2 ? (PB == 2 ? conv_fn<2, 2, true>(D) : conv_fn<2, 1, true>(D)) : (PB == 2 ? conv_fn<1, 2, true>(D) : conv_fn<1, 1, true>(D));
     return CB == 2 ? (PB == 2 ? conv_fn<2, 2>(D) : conv_fn<2, 1>(D)) : (PB == 2 ? conv_fn<1, 2>(D) : conv_fn<1, 1>(D));
 }
 
@@ -706,34 +723,36 @@ long long slots_for(const ConvPlan &pl, long long cap)
 }
 
 // the profiler keeps the pointer: one permanent string per shape of launch
-const char *launch_name(int K, int CB, int PB, int D, bool pair)
+const char *launch_name(int K, int CB, int PB, int D, int kind)   // kind: 0 one convolution, 1 expand pair, 2 fp32 NCHW out
 {
     // filled once (function-local statics are initialised under a lock), read-only afterwards
     struct Names {
-        char n[2][6][3][3][5][28];
+        char n[3][6][3][3][5][28];
         Names()
         {
-            for (int pr = 0; pr < 2; ++pr)
+            static const char *const fmt[3] = {"k%db_%dx%d_d%d", "k1b+k%db_%dx%d_d%d", "k%db_%dx%d_d%d_f32out"};
+            for (int pr = 0; pr < 3; ++pr)
                 for (int k = 0; k < 6; ++k)
                     for (int cb = 0; cb < 3; ++cb)
                         for (int pb = 0; pb < 3; ++pb)
                             for (int d = 0; d < 5; ++d)
-                                snprintf(n[pr][k][cb][pb][d], sizeof n[0][0][0][0][0], pr ? "k1b+k%db_%dx%d_d%d" : "k%db_%dx%d_d%d", k, 32 * cb, 32 * pb, d);
+                                snprintf(n[pr][k][cb][pb][d], sizeof n[0][0][0][0][0], fmt[pr], k, 32 * cb, 32 * pb, d);
         }
     };
     static const Names names;
-    return names.n[pair][K][CB][PB][D];
+    return names.n[kind][K][CB][PB][D];
 }
 
 }  // namespace
 
+// f32_out: `out` is an fp32 NCHW map of ldc_channels layers (results unrounded) instead of a blocked bfloat16 one
 int blocked_conv(const void *in, const void *wp, const float *b, void *out, int N, int Cin, int H, int W, int Cout, int K, int P,
-                 int relu, int ldc_channels, int c_offset)
+                 int relu, int ldc_channels, int c_offset, bool f32_out)
 {
     ConvPlan pl;
-    const int rc = plan_conv(pl, in, wp, b, out, N, Cin, H, W, Cout, K, P, relu, ldc_channels, c_offset, 0, 0, 0);
+    const int rc = plan_conv(pl, in, wp, b, out, N, Cin, H, W, Cout, K, P, relu, ldc_channels, c_offset, 0, 0, 0, f32_out);
     if (rc) return rc;
-    BlockedConvFn fn = kernel_for(pl.CB, pl.PB, pl.D);
+    BlockedConvFn fn = kernel_for(pl.CB, pl.PB, pl.D, f32_out);
     if (!allow_lds(fn)) {
         const int e = check_launch();
         return e ? e : SQ_ERR_HIP;
@@ -741,7 +760,7 @@ int blocked_conv(const void *in, const void *wp, const float *b, void *out, int 
     // persistent: at most two workgroups per CU
     const long long wgs = slots_for(pl, 2ll * num_cus()) * pl.p.ncblk;
     const size_t lds = (size_t)pl.CB * pl.per_mb + (size_t)pl.CB * 32 * sizeof(float);
-    LaunchScope scope(launch_name(K, pl.CB, pl.PB, pl.D, false), pl.flops, pl.bytes);
+    LaunchScope scope(launch_name(K, pl.CB, pl.PB, pl.D, f32_out ? 2 : 0), pl.flops, pl.bytes);
     hipLaunchKernelGGL(fn, dim3((unsigned)wgs), dim3(kThreads), lds, current_stream(), pl.p, pl.p, (int)wgs);
     return check_launch();
 }
@@ -777,7 +796,7 @@ int blocked_conv_pair(const void *in, const void *wp1, const float *b1, int Cout
     const long long wgk = slots_for(pk, cap - wg1 > pk.p.ncblk ? cap - wg1 : pk.p.ncblk) * pk.p.ncblk;
     const size_t ldsk = (size_t)pk.CB * pk.per_mb, lds1 = (size_t)p1.CB * p1.per_mb;
     const size_t lds = (ldsk > lds1 ? ldsk : lds1) + (size_t)pk.CB * 32 * sizeof(float);
-    LaunchScope scope(launch_name(K, pk.CB, pk.PB, D, true), p1.flops + pk.flops, p1.bytes + pk.bytes - 2.0 * N * Cin * H * W);
+    LaunchScope scope(launch_name(K, pk.CB, pk.PB, D, 1), p1.flops + pk.flops, p1.bytes + pk.bytes - 2.0 * N * Cin * H * W);
     hipLaunchKernelGGL(fn, dim3((unsigned)(wg1 + wgk)), dim3(kThreads), lds, current_stream(), p1.p, pk.p, (int)wg1);
     return check_launch();
 }
@@ -822,10 +841,49 @@ bool blocked_register_kernels()
     bool ok = true;
     for (int cb = 1; cb <= 2; ++cb)
         for (int pb = 1; pb <= 2; ++pb)
-            for (int d = 1; d <= 4; ++d) ok &= allow_big_lds((const void *)kernel_for(cb, pb, d));
+            for (int d = 1; d <= 4; ++d) ok &= allow_big_lds((const void *)kernel_for(cb, pb, d)) && allow_big_lds((const void *)kernel_for(cb, pb, d, true));
     ok &= allow_big_lds((const void *)pool_conv_blocked_kernel<1, 1>) && allow_big_lds((const void *)pool_conv_blocked_kernel<1, 2>) &&
           allow_big_lds((const void *)pool_conv_blocked_kernel<2, 1>) && allow_big_lds((const void *)pool_conv_blocked_kernel<2, 2>);
     return ok;
+}
+
+// ---- a convolution with bfloat16 NCHW operands on these kernels (see sq_internal.h) ---------------------------
+namespace {
+bool bf16_mfma_conv1_type(int Cin, int Cout, int K, int S) { return Cin == 3 && K == 7 && S == 2 && Cout <= 96 && Cout % 8 == 0; }
+}
+
+size_t conv_bf16_mfma_workspace_bytes(int N, int Cin, int H, int W, int Cout, int K, int S, int P, int out_channels)
+{
+    if (N <= 0 || Cin <= 0 || Cout <= 0 || H <= 0 || W <= 0 || P < 0 || H + 2 * P < K || W + 2 * P < K) return 0;
+    const long long Ho = (H + 2 * P - K) / S + 1, Wo = (W + 2 * P - K) / S + 1;
+    if ((long long)N * out_channels * Ho * Wo * 4 >= (1ll << 31) || (long long)N * Ho * Wo >= (1ll << 30)) return 0;
+    if (bf16_mfma_conv1_type(Cin, Cout, K, S)) {
+        if ((long long)N * 3 * H * W * 2 >= (1ll << 31)) return 0;
+        return align_up(blocked_packed_kernel7_bytes(), 256);
+    }
+    if (S != 1 || !blocked_conv_supported(Cin, Cout, K, P)) return 0;
+    // 1x1 layers: re-ordering the input and writing fp32 costs more than the matrix cores save unless the contraction is
+    // long and the layer widens (measured at batch 256: 512 -> 1000 at 13x13 369 -> 137 us, 64 -> 256 at 27x27 70 -> 77 us)
+    if (K == 1 && (Cout <= Cin || Cin < 128)) return 0;
+    if ((long long)blocked_map_bytes(N, Cin, H, W) >= (1ll << 31)) return 0;
+    return align_up(blocked_map_bytes(N, Cin, H, W), 256) + align_up(blocked_packed_kernel_bytes(Cout, Cin, K), 256);
+}
+
+int conv_bf16_mfma(const ConvArgs &a)
+{
+    if (a.dtype != SQ_BF16 || a.pool_H || a.cp_in || a.cp_out) return SQ_ERR_UNSUPPORTED;
+    const size_t need = conv_bf16_mfma_workspace_bytes(a.N, a.Cin, a.H, a.W, a.Cout, a.K, a.S, a.P, a.out_channels);
+    if (!need) return SQ_ERR_UNSUPPORTED;
+    if (!a.ws || ((uintptr_t)a.ws & 255) || a.ws_bytes < need) return SQ_ERR_WORKSPACE;
+    int rc;
+    if (bf16_mfma_conv1_type(a.Cin, a.Cout, a.K, a.S)) {
+        if ((rc = blocked_pack_kernels7(a.w, SQ_BF16, a.ws, a.Cout))) return rc;
+        return blocked_conv7s2(a.in, SQ_BF16, a.ws, a.b, a.out, a.N, a.H, a.W, a.Cout, a.P, a.relu, a.out_channels, a.c_offset, true);
+    }
+    char *map = (char *)a.ws, *wp = map + align_up(blocked_map_bytes(a.N, a.Cin, a.H, a.W), 256);
+    if ((rc = blocked_pack_map(a.in, SQ_BF16, map, a.N, a.Cin, a.H, a.W))) return rc;
+    if ((rc = blocked_pack_kernels(a.w, SQ_BF16, wp, a.Cout, a.Cin, a.K))) return rc;
+    return blocked_conv(map, wp, a.b, a.out, a.N, a.Cin, a.H, a.W, a.Cout, a.K, a.P, a.relu, a.out_channels, a.c_offset, true);
 }
 
 int blocked_maxpool(const void *in, void *out, int N, int C, int H, int W, int K, int S)

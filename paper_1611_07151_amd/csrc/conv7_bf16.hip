@@ -68,16 +68,18 @@ struct Conv7Params {
     const void *in;     // [N][3][H][W], TIN
     const void *wp;     // packed kernels
     const float *b;     // [Cout] or nullptr
-    void *out;          // blocked [N][ldcb][Ho][Wo][8]
+    void *out;          // blocked [N][ldcb][Ho][Wo][8]; F32OUT: fp32 [N][ldcb][Ho][Wo]
     uint32_t in_bytes, out_bytes;
     int N, H, W, Ho, Wo, HoWo, Cout, P, relu;
-    int ldcb, coffb;
+    int ldcb, coffb;    // layer blocks of 8 per image in `out` and the first one written (F32OUT: layers, first layer)
     int RG, CG;         // tiles per image: row groups, column groups
     int tiles;
     FastDiv dCG, dTilesPerImage;
 };
 
-template <typename TIN>
+// F32OUT: the results leave unrounded, as an fp32 NCHW map (a convolution called on its own with bfloat16 inputs; the
+// network's layers write the blocked bfloat16 map the next layer reads).
+template <typename TIN, bool F32OUT = false>
 __global__ __launch_bounds__(kThreads7, 3) void conv7s2c3_blocked_kernel(const Conv7Params p)
 {
     constexpr uint32_t ESZ = sizeof(TIN);
@@ -180,15 +182,22 @@ __global__ __launch_bounds__(kThreads7, 3) void conv7s2c3_blocked_kernel(const C
             const int n = fdiv(tile, p.dTilesPerImage), rem = tile - n * tiles_per_image;
             const int rg = fdiv(rem, p.dCG), cg = rem - rg * p.CG;
             const int oh = rg * kTR + 2 * wv + pr, ow = cg * kTC + pc;
-            const uint32_t o = oh < p.Ho && ow < p.Wo
-                                   ? (uint32_t)(((n * p.ldcb + p.coffb) * p.HoWo + oh * p.Wo + ow) * 16 + 8 * h)
-                                   : kOob;
+            const uint32_t o = !(oh < p.Ho && ow < p.Wo) ? kOob
+                               : F32OUT ? (uint32_t)(((n * p.ldcb + p.coffb + 4 * h) * p.HoWo + oh * p.Wo + ow) * 4)
+                                        : (uint32_t)(((n * p.ldcb + p.coffb) * p.HoWo + oh * p.Wo + ow) * 16 + 8 * h);
 #pragma unroll
             for (int cb = 0; cb < 3; ++cb)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int lb = cb * 4 + q;
-                    if (lb * 8 < p.Cout) {
+                    if constexpr (F32OUT) {
+                        // register 4q + i = layer 8 lb + 4h + i: 16 neighbouring pixels per store and half-wavefront
+                        if (lb * 8 < p.Cout) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                buf_st(rout, o, (uint32_t)((lb * 8 + i) * p.HoWo) * 4u, fmaxf(acc[cb][4 * q + i], lowest));
+                        }
+                    } else if (lb * 8 < p.Cout) {
                         const float v0 = fmaxf(acc[cb][4 * q + 0], lowest), v1 = fmaxf(acc[cb][4 * q + 1], lowest);
                         const float v2 = fmaxf(acc[cb][4 * q + 2], lowest), v3 = fmaxf(acc[cb][4 * q + 3], lowest);
                         buf_st2(rout, o, (uint32_t)(lb * p.HoWo) * 16u, __builtin_bit_cast(float, pack_bf16x2(v0, v1)),
@@ -224,15 +233,16 @@ int blocked_pack_kernels7(const void *w, int dtype, void *packed, int Cout)
 }
 
 // 7x7, stride 2, pad P, three input layers (NCHW image of type dtype) -> layers [c_offset, +Cout) of a
-// blocked bfloat16 map with ldc_channels layers.
+// blocked bfloat16 map with ldc_channels layers, or (f32_out) of an fp32 NCHW map with ldc_channels layers.
 int blocked_conv7s2(const void *in, int dtype, const void *wp, const float *b, void *out, int N, int H, int W, int Cout, int P,
-                    int relu, int ldc_channels, int c_offset)
+                    int relu, int ldc_channels, int c_offset, bool f32_out)
 {
-    if (Cout > 96 || Cout % 8 != 0 || ldc_channels % 8 != 0 || c_offset % 8 != 0) return SQ_ERR_UNSUPPORTED;
+    if (Cout > 96 || Cout % 8 != 0) return SQ_ERR_UNSUPPORTED;
+    if (!f32_out && (ldc_channels % 8 != 0 || c_offset % 8 != 0)) return SQ_ERR_UNSUPPORTED;
     if (H + 2 * P < 7 || W + 2 * P < 7) return SQ_ERR_SHAPE;
     const int Ho = (H + 2 * P - 7) / 2 + 1, Wo = (W + 2 * P - 7) / 2 + 1;
     const long long in_bytes = (long long)N * 3 * H * W * (dtype == SQ_BF16 ? 2 : 4);
-    const long long out_bytes = (long long)blocked_map_bytes(N, ldc_channels, Ho, Wo);
+    const long long out_bytes = f32_out ? (long long)N * ldc_channels * Ho * Wo * 4 : (long long)blocked_map_bytes(N, ldc_channels, Ho, Wo);
     Conv7Params p;
     p.RG = (Ho + kTR - 1) / kTR;
     p.CG = (Wo + kTC - 1) / kTC;
@@ -241,17 +251,23 @@ int blocked_conv7s2(const void *in, int dtype, const void *wp, const float *b, v
     p.in = in; p.wp = wp; p.b = b; p.out = out;
     p.in_bytes = (uint32_t)in_bytes; p.out_bytes = (uint32_t)out_bytes;
     p.N = N; p.H = H; p.W = W; p.Ho = Ho; p.Wo = Wo; p.HoWo = Ho * Wo; p.Cout = Cout; p.P = P; p.relu = relu;
-    p.ldcb = ldc_channels / 8; p.coffb = c_offset / 8;
+    p.ldcb = f32_out ? ldc_channels : ldc_channels / 8; p.coffb = f32_out ? c_offset : c_offset / 8;
     p.tiles = (int)tiles;
     p.dCG = make_fastdiv(p.CG); p.dTilesPerImage = make_fastdiv(p.RG * p.CG);
     long long blocks = 3ll * num_cus();
     if (blocks > tiles) blocks = tiles;
-    LaunchScope scope("k7s2c3_bf16_8x16", 2.0 * N * Cout * Ho * Wo * 147.0,
-                      (dtype == SQ_BF16 ? 2.0 : 4.0) * N * 3 * H * W + 2.0 * Cout * 147 + 2.0 * N * Cout * Ho * Wo + 4.0 * Cout);
-    if (dtype == SQ_BF16)
+    LaunchScope scope(f32_out ? "k7s2c3_bf16_8x16_f32out" : "k7s2c3_bf16_8x16", 2.0 * N * Cout * Ho * Wo * 147.0,
+                      (dtype == SQ_BF16 ? 2.0 : 4.0) * N * 3 * H * W + 2.0 * Cout * 147 + (f32_out ? 4.0 : 2.0) * N * Cout * Ho * Wo + 4.0 * Cout);
+    if (f32_out) {
+        if (dtype == SQ_BF16)
+            hipLaunchKernelGGL((conv7s2c3_blocked_kernel<uint16_t, true>), dim3((unsigned)blocks), dim3(kThreads7), 0, current_stream(), p);
+        else
+            hipLaunchKernelGGL((conv7s2c3_blocked_kernel<float, true>), dim3((unsigned)blocks), dim3(kThreads7), 0, current_stream(), p);
+    } else if (dtype == SQ_BF16) {
         hipLaunchKernelGGL(conv7s2c3_blocked_kernel<uint16_t>, dim3((unsigned)blocks), dim3(kThreads7), 0, current_stream(), p);
-    else
+    } else {
         hipLaunchKernelGGL(conv7s2c3_blocked_kernel<float>, dim3((unsigned)blocks), dim3(kThreads7), 0, current_stream(), p);
+    }
     return check_launch();
 }
 

@@ -137,12 +137,21 @@ bool blocked_conv_supported(int Cin, int Cout, int K, int P);
 int blocked_pack_map(const void *in, int dtype, void *out, int N, int C, int H, int W);
 int blocked_unpack_map(const void *in, float *out, int N, int C, int H, int W);
 int blocked_pack_kernels(const void *w, int dtype, void *packed, int Cout, int Cin, int K);
+// f32_out: `out` is an fp32 NCHW map of ldc_channels layers and takes the unrounded results
 int blocked_conv(const void *in, const void *wp, const float *b, void *out, int N, int Cin, int H, int W, int Cout, int K, int P,
-                 int relu, int ldc_channels, int c_offset);
+                 int relu, int ldc_channels, int c_offset, bool f32_out = false);
 size_t blocked_packed_kernel7_bytes();
 int blocked_pack_kernels7(const void *w, int dtype, void *packed, int Cout);
 int blocked_conv7s2(const void *in, int dtype, const void *wp, const float *b, void *out, int N, int H, int W, int Cout, int P,
-                    int relu, int ldc_channels, int c_offset);
+                    int relu, int ldc_channels, int c_offset, bool f32_out = false);
+// A convolution with bfloat16 NCHW inputs and kernels on the bf16 matrix instructions: the input is re-ordered into a
+// blocked map and the kernels into operand order in the caller's scratch, and the blocked kernel writes fp32 NCHW
+// results (fp32 accumulate, nothing rounded after the inputs).  For the layers where that beats widening the inputs
+// into the fp32 kernels: 3x3 and 5x5 stride 1, wide 1x1 with more output than input layers, the conv1 type.  Bytes of
+// scratch (0 = the form does not apply to the shape) and the call (SQ_ERR_UNSUPPORTED / SQ_ERR_WORKSPACE: take the
+// other path).
+size_t conv_bf16_mfma_workspace_bytes(int N, int Cin, int H, int W, int Cout, int K, int S, int P, int out_channels);
+int conv_bf16_mfma(const ConvArgs &a);
 int blocked_conv_pair(const void *in, const void *wp1, const float *b1, int Cout1, int c_offset1, const void *wpk,
                       const float *bk, int Coutk, int c_offsetk, int K, void *out, int N, int Cin, int H, int W, int relu,
                       int ldc_channels);

@@ -194,6 +194,38 @@ def test_conv_bf16_inputs(sq, case):
         assert_close(got, ref_q, FP32_TOL, f"bf16 algo {algo} vs rounded-input reference")
 
 
+# With scratch of sq_conv2d_bf16_workspace_bytes a bfloat16 convolution runs on the bf16 matrix instructions where that
+# pays (input and kernels re-ordered in the scratch, fp32 sums, fp32 results unrounded), into its layer range of a
+# larger output tensor; with less scratch, or for the other shapes, on the fp32 kernels with widened operands.
+@pytest.mark.parametrize("case,on_bf16_mfma", [((3, 32, 27, 29, 128, 3, 1, 1), True), ((2, 128, 13, 13, 256, 1, 1, 0), True), ((2, 64, 13, 13, 256, 1, 1, 0), False),
+                                               ((2, 3, 75, 64, 96, 7, 2, 2), True), ((2, 48, 9, 9, 40, 5, 1, 2), True),
+                                               ((2, 96, 27, 27, 16, 1, 1, 0), False), ((2, 24, 9, 9, 32, 3, 1, 1), False),
+                                               ((2, 32, 9, 9, 36, 3, 1, 1), False)], ids=lambda c: str(c))
+def test_conv_bf16_on_the_bf16_matrix_instructions(sq, case, on_bf16_mfma):
+    N, Cin, H, W, Cout, K, S, P = case
+    rng = np.random.default_rng(300 + Cout)
+    x = synth.normal01(rng, (N, Cin, H, W))
+    w, b = synth.conv_params(rng, Cout, Cin, K)
+    xb, wb = dev(x, torch.bfloat16), dev(w, torch.bfloat16)
+    ref_q = oracle.conv2d(xb.float().cpu().numpy(), wb.float().cpu().numpy(), b, S, P, True)
+    need = sq.sq_conv2d_bf16_workspace_bytes(N, Cin, H, W, Cout, K, S, P)
+    assert (need > 0) == on_bf16_mfma
+    Ho, Wo = ref_q.shape[2:]
+    out = torch.full((N, Cout + 11, Ho, Wo), -7.0, device="cuda")
+    sq.sq_profile_begin(16)
+    sq.sq_conv2d_forward_ws(xb, wb, dev(b), S, P, True, out=out, c_offset=5)
+    names = [r["name"] for r in sq.sq_profile_end()]
+    assert any(n.endswith("_f32out") for n in names) == on_bf16_mfma, names
+    assert_close(out[:, 5:5 + Cout], ref_q, FP32_TOL, "fp32 sums of the rounded operands, nothing rounded after")
+    assert (out[:, :5] == -7.0).all() and (out[:, 5 + Cout:] == -7.0).all()
+    if on_bf16_mfma:
+        small = torch.empty(max(need - 256, 256), device="cuda", dtype=torch.uint8)     # too little scratch: the other path
+        sq.sq_profile_begin(16)
+        got = sq.sq_conv2d_forward_ws(xb, wb, dev(b), S, P, True, workspace=small)
+        assert not any(r["name"].endswith("_f32out") for r in sq.sq_profile_end())
+        assert_close(got, ref_q, FP32_TOL, "fp32 kernels on widened operands")
+
+
 @pytest.mark.parametrize("shape,k,s", [((2, 96, 111, 111), 3, 2), ((1, 256, 55, 55), 3, 2),
                                        ((3, 512, 27, 27), 3, 2), ((1, 3, 10, 13), 2, 2),
                                        ((1, 1, 3, 3), 3, 1), ((2, 5, 9, 8), 3, 3)])

@@ -211,10 +211,201 @@ __global__ __launch_bounds__(kThreads7, 3) void conv7s2c3_blocked_kernel(const C
     }
 }
 
+
+// ---- F32OUT for large batches: tiles of 8 output rows x 112 output columns ----------------------------------------
+// An fp32 NCHW map much larger than the memory-side cache is written at a fraction of the memory's rate when its
+// cache lines reach memory in pieces: a 1.2 GB map goes out at 2.0 TB/s in the 64-byte runs of the 8 x 16 tiles
+// above, at 4.4 TB/s when one wavefront writes the pieces of a row one after the other (measured with a store-only
+// kernel).  So here a wavefront owns two whole rows of a tile that spans the image width (up to seven column blocks
+// of 16; wider images take several such tiles per row group), computes them one block of 32 layers at a time
+// (7 accumulators), and stores layer by layer with the column blocks innermost: seven consecutive stores cover
+// the two rows, which lie one behind the other in the plane, of two layers.  The 21 x 230 x 3 patch (29 KB as bfloat16 pairs) has one LDS buffer
+// (wavefront w fetches patch rows w, w + 4, ...: the row is uniform, so its address is scalar arithmetic); with the
+// packed kernels (33 KB) two workgroups fit a CU.
+constexpr int kRBlocks = 7;                          // column blocks of 16 per tile
+constexpr int kRCols = kRBlocks * kTC;               // 112 output columns
+constexpr int kRPairs = kRCols + 3;                  // dwords of a patch row that are read: pairs 0 .. 114
+constexpr int kRRowDw = 116;                         // LDS row stride in dwords
+constexpr int kRRows = 3 * kPR;                      // 63 patch rows (layer, row)
+constexpr int kRPatchDw = kRRows * kRRowDw;
+constexpr int kRPerWave = (kRRows + 3) / 4;          // patch rows a wavefront fetches (16)
+static_assert(kRPairs <= 128 && kRPairs <= kRRowDw, "two column pairs per lane cover a patch row");
+
+__global__ __launch_bounds__(kThreads7, 2) void conv7s2c3_rows_kernel(const Conv7Params p)
+{
+    constexpr uint32_t ESZ = 2;                                          // the image is bfloat16
+    __shared__ __attribute__((aligned(16))) u32x4 wl[kWpElems];          // A operands
+    __shared__ __attribute__((aligned(16))) uint32_t patch[kRPatchDw];   // bfloat16 pairs
+    __shared__ __attribute__((aligned(16))) float bl[96];
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int j = lane & 31, h = lane >> 5;
+    const int pr = j >> 4, pc = j & 15;
+
+    {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(p.wp);
+        for (int e = t; e < kWpElems; e += kThreads7) wl[e] = src[e];
+        if (t < 96) bl[t] = (p.b && t < p.Cout) ? p.b[t] : 0.f;
+    }
+
+    const rsrc_t rin = make_rsrc(p.in, p.in_bytes), rout = make_rsrc(p.out, p.out_bytes);
+    const int tiles_per_image = p.RG * p.CG;
+
+    // tile -> image, first output row, first output column (uniform)
+    auto decode = [&](int tile_, int &n, int &oh0, int &ow0) {
+        const int tile = __builtin_amdgcn_readfirstlane(tile_);
+        n = fdiv(tile, p.dTilesPerImage);
+        const int rem = tile - n * tiles_per_image, rg = fdiv(rem, p.dCG);
+        n = __builtin_amdgcn_readfirstlane(n);
+        oh0 = __builtin_amdgcn_readfirstlane(rg * kTR);
+        ow0 = __builtin_amdgcn_readfirstlane((rem - rg * p.CG) * kRCols);
+    };
+
+    // ---- staging: this wavefront's patch rows R = wv + 4k (layer R / 21, row R % 21), lanes take column pairs
+    // lane and lane + 64.  The two bfloat16 values of a pair are loaded into the halves of one register (the patch
+    // is a plain copy of the image), every load of a tile is issued before the first one is waited for (a row
+    // outside the image gets offsets the range check turns away, not a branch), and the values wait in registers
+    // until the next tile starts.
+    short xr[kRPerWave][2][2];
+    uint32_t xp[kRPerWave][2];
+    auto fetch = [&](int tile) {
+        int n, oh0, ow0;
+        decode(tile, n, oh0, ow0);
+        const int ih0 = oh0 * 2 - p.P, iw0 = ow0 * 2 - p.P;
+        uint32_t loff[2][2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int pj = lane + 64 * q, iw = iw0 + 2 * pj;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) loff[q][e] = (pj < kRPairs && iw + e >= 0 && iw + e < p.W) ? (uint32_t)(iw + e) * ESZ : kOob;
+        }
+#pragma unroll
+        for (int k = 0; k < kRPerWave; ++k) {
+            const int R = wv + 4 * k, c = R / kPR, r = R - c * kPR;      // uniform
+            const int ih = ih0 + r;
+            const bool rok = R < kRRows && ih >= 0 && ih < p.H;
+            const uint32_t row = rok ? (uint32_t)(((n * 3 + c) * p.H + ih) * p.W) * ESZ : 0u;
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+                    xr[k][q][e] = __builtin_amdgcn_raw_buffer_load_b16(rin, (int)(rok ? loff[q][e] : kOob), (int)row, 0);
+        }
+    };
+    // Where this stands in the program is where the loads are waited for (the empty statements keep the compiler
+    // from doing the shifts, and with them the wait, right behind the loads).
+    auto pair_up = [&]() {
+#pragma unroll
+        for (int k = 0; k < kRPerWave; ++k)
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                asm volatile("" : "+v"(xr[k][q][0]), "+v"(xr[k][q][1]));
+                xp[k][q] = (uint32_t)(uint16_t)xr[k][q][0] | ((uint32_t)(uint16_t)xr[k][q][1] << 16);
+            }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int k = 0; k < kRPerWave; ++k) {
+            const int R = wv + 4 * k;
+            if (R < kRRows) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+                    if (lane + 64 * q < kRPairs) patch[R * kRRowDw + lane + 64 * q] = xp[k][q];
+            }
+        }
+    };
+
+    // ---- B operand of column block 0: lane (pixel (pr, pc) of this wavefront's two rows, half h) reads the four
+    // dwords pc .. pc + 3 of patch row  c*21 + 2*(2 wv + pr) + i,  (c, i) = pair 2 s + h; block k lies 16 dwords on
+    const int lane_dw = (2 * (2 * wv + pr)) * kRRowDw + pc;
+    int step_dw[kSteps];
+#pragma unroll
+    for (int s = 0; s < kSteps; ++s) {
+        const int e0 = 2 * s, e1 = 2 * s + 1 < 21 ? 2 * s + 1 : 20;    // the zero pair may read any valid row
+        const int o0 = ((e0 / 7) * kPR + e0 % 7) * kRRowDw, o1 = ((e1 / 7) * kPR + e1 % 7) * kRRowDw;
+        step_dw[s] = lane_dw + (h ? o1 : o0);
+    }
+
+    const mfma::XcdShare share = mfma::xcd_share((int)blockIdx.x, (int)gridDim.x, p.tiles);
+    const float lowest = p.relu ? 0.f : -__builtin_inff();
+    // The next tile's patch is asked for at the start of a tile, behind the stores that fill the memory pipeline a
+    // load takes most of a tile's time to come back.
+    if (share.first < share.end) {
+        fetch(share.first);
+        pair_up();
+    }
+    for (int tile = share.first; tile < share.end; tile += share.step) {
+        const bool more = tile + share.step < share.end;
+        __syncthreads();    // everyone is done with the previous tile's patch
+        stash();
+        __syncthreads();
+        if (more) fetch(tile + share.step);
+
+        // lane byte offsets of this lane's pixel in the seven column blocks (layer 4h of the image's first one)
+        uint32_t o[kRBlocks];
+        {
+            int n, oh0, ow0;
+            decode(tile, n, oh0, ow0);
+            const int oh = oh0 + 2 * wv + pr;
+            const uint32_t base = (uint32_t)(((n * p.ldcb + p.coffb + 4 * h) * p.HoWo + oh * p.Wo + ow0 + pc) * 4);
+#pragma unroll
+            for (int k = 0; k < kRBlocks; ++k) o[k] = (oh < p.Ho && ow0 + 16 * k + pc < p.Wo) ? base + 64u * k : kOob;
+        }
+        // (unrolled: in front of a loop that uses loaded values the compiler waits for every load)
+#pragma unroll
+        for (int cb = 0; cb < 3; ++cb) {
+            if (cb * 32 >= p.Cout) break;
+            f32x16 acc[kRBlocks];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 bv = *reinterpret_cast<const f32x4 *>(bl + cb * 32 + 8 * q + 4 * h);
+#pragma unroll
+                for (int k = 0; k < kRBlocks; ++k) {
+                    acc[k][4 * q + 0] = bv.x; acc[k][4 * q + 1] = bv.y; acc[k][4 * q + 2] = bv.z; acc[k][4 * q + 3] = bv.w;
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < kSteps; ++s) {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, wl[(cb * kSteps + s) * 64 + lane]);
+#pragma unroll
+                for (int k = 0; k < kRBlocks; ++k) {
+                    const uint32_t *pb = patch + step_dw[s] + 16 * k;
+                    u32x4 braw = {pb[0], pb[1], pb[2], pb[3]};
+                    acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, braw), acc[k], 0, 0, 0);
+                }
+            }
+            if (cb == 0 && more) {
+                // Wait for the next tile's patch here, before this block's stores.  Memory operations complete in the
+                // order they were issued, so a wait for loads is also a wait for every older store: here those are
+                // the stores of the tile before, which have had a block's MFMAs to drain; at the start of the next
+                // tile it would be this tile's 336.
+                pair_up();
+            }
+            // register 4q + i = layer 32 cb + 8q + 4h + i; per layer the seven column blocks one after the other
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (cb * 32 + q * 8 < p.Cout) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t layer = (uint32_t)((cb * 32 + q * 8 + i) * p.HoWo) * 4u;
+#pragma unroll
+                        for (int k = 0; k < kRBlocks; ++k) buf_st(rout, o[k], layer, fmaxf(acc[k][4 * q + i], lowest));
+                    }
+                }
+            }
+        }
+    }
+}
+
 }  // namespace
 }  // namespace blocked
 
 using namespace blocked;
+
+// fp32 results through the tiles that span the image width: -1 = by batch size, 0 = never, 1 = always
+thread_local int g_f32out_rows = -1;
+extern "C" void sq_tune_conv7_f32out_rows(int mode) { g_f32out_rows = mode; }
 
 size_t blocked_packed_kernel7_bytes() { return (size_t)kWpElems * 16; }
 
@@ -246,6 +437,11 @@ int blocked_conv7s2(const void *in, int dtype, const void *wp, const float *b, v
     Conv7Params p;
     p.RG = (Ho + kTR - 1) / kTR;
     p.CG = (Wo + kTC - 1) / kTC;
+    // fp32 results of a large batch: tiles that span the image width (see conv7s2c3_rows_kernel), from two of them
+    // per CU on (below that the 8 x 16 tiles fill the GPU better and the map stays in the memory-side cache)
+    const int row_tiles = (Wo + kRCols - 1) / kRCols;
+    const bool rows = f32_out && dtype == SQ_BF16 && (g_f32out_rows < 0 ? (long long)N * p.RG * row_tiles >= 2ll * num_cus() : g_f32out_rows > 0);
+    if (rows) p.CG = row_tiles;
     const long long tiles = (long long)N * p.RG * p.CG;
     if (in_bytes >= (1ll << 31) || out_bytes >= (1ll << 31) || tiles >= (1ll << 30)) return SQ_ERR_UNSUPPORTED;
     p.in = in; p.wp = wp; p.b = b; p.out = out;
@@ -254,11 +450,13 @@ int blocked_conv7s2(const void *in, int dtype, const void *wp, const float *b, v
     p.ldcb = f32_out ? ldc_channels : ldc_channels / 8; p.coffb = f32_out ? c_offset : c_offset / 8;
     p.tiles = (int)tiles;
     p.dCG = make_fastdiv(p.CG); p.dTilesPerImage = make_fastdiv(p.RG * p.CG);
-    long long blocks = 3ll * num_cus();
+    long long blocks = (rows ? 2ll : 3ll) * num_cus();
     if (blocks > tiles) blocks = tiles;
-    LaunchScope scope(f32_out ? "k7s2c3_bf16_8x16_f32out" : "k7s2c3_bf16_8x16", 2.0 * N * Cout * Ho * Wo * 147.0,
+    LaunchScope scope(rows ? "k7s2c3_bf16_8x112_f32out" : f32_out ? "k7s2c3_bf16_8x16_f32out" : "k7s2c3_bf16_8x16", 2.0 * N * Cout * Ho * Wo * 147.0,
                       (dtype == SQ_BF16 ? 2.0 : 4.0) * N * 3 * H * W + 2.0 * Cout * 147 + (f32_out ? 4.0 : 2.0) * N * Cout * Ho * Wo + 4.0 * Cout);
-    if (f32_out) {
+    if (rows) {
+        hipLaunchKernelGGL(conv7s2c3_rows_kernel, dim3((unsigned)blocks), dim3(kThreads7), 0, current_stream(), p);
+    } else if (f32_out) {
         if (dtype == SQ_BF16)
             hipLaunchKernelGGL((conv7s2c3_blocked_kernel<uint16_t, true>), dim3((unsigned)blocks), dim3(kThreads7), 0, current_stream(), p);
         else

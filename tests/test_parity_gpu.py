@@ -226,6 +226,37 @@ def test_conv_bf16_on_the_bf16_matrix_instructions(sq, case, on_bf16_mfma):
         assert_close(got, ref_q, FP32_TOL, "fp32 kernels on widened operands")
 
 
+# The conv1-type bfloat16 convolution with fp32 results has a second kernel for large batches (tiles of 8 output rows
+# spanning up to 112 output columns, so that whole cache lines leave one wavefront); forced here on small shapes: ragged
+# rows and columns, several tiles per row (more than 112 columns), fewer than 96 layers, no padding, no bias, a layer
+# range of a larger tensor.  Both kernels must give the same bits (same operands, same order of the sums).
+@pytest.mark.parametrize("case", [(2, 3, 75, 64, 96, 2, True), (1, 3, 224, 224, 96, 0, True), (3, 3, 21, 470, 40, 3, True),
+                                  (2, 3, 7, 7, 8, 0, False), (1, 3, 36, 250, 96, 2, False)], ids=lambda c: str(c))
+def test_conv1_bf16_row_tiles(sq, case):
+    N, Cin, H, W, Cout, P, relu = case
+    rng = np.random.default_rng(400 + W)
+    x = synth.normal01(rng, (N, Cin, H, W))
+    w, b = synth.conv_params(rng, Cout, Cin, 7)
+    xb, wb = dev(x, torch.bfloat16), dev(w, torch.bfloat16)
+    ref_q = oracle.conv2d(xb.float().cpu().numpy(), wb.float().cpu().numpy(), b, 2, P, relu)
+    Ho, Wo = ref_q.shape[2:]
+    assert sq.sq_conv2d_bf16_workspace_bytes(N, Cin, H, W, Cout, 7, 2, P) > 0
+    outs = []
+    try:
+        for mode, name in ((1, "k7s2c3_bf16_8x112_f32out"), (0, "k7s2c3_bf16_8x16_f32out")):
+            sq.lib.sq_tune_conv7_f32out_rows(mode)
+            out = torch.full((N, Cout + 11, Ho, Wo), -7.0, device="cuda")
+            sq.sq_profile_begin(16)
+            sq.sq_conv2d_forward_ws(xb, wb, dev(b), 2, P, relu, out=out, c_offset=5)
+            assert any(r["name"].endswith(name) for r in sq.sq_profile_end())
+            assert_close(out[:, 5:5 + Cout], ref_q, FP32_TOL, name)
+            assert (out[:, :5] == -7.0).all() and (out[:, 5 + Cout:] == -7.0).all()
+            outs.append(out)
+    finally:
+        sq.lib.sq_tune_conv7_f32out_rows(-1)
+    assert torch.equal(outs[0], outs[1])
+
+
 @pytest.mark.parametrize("shape,k,s", [((2, 96, 111, 111), 3, 2), ((1, 256, 55, 55), 3, 2),
                                        ((3, 512, 27, 27), 3, 2), ((1, 3, 10, 13), 2, 2),
                                        ((1, 1, 3, 3), 3, 1), ((2, 5, 9, 8), 3, 3)])

@@ -468,6 +468,29 @@ __device__ __forceinline__ void conv_mfma_tile(const KParams &p, const int block
     const float lowest = p.relu ? 0.f : -__builtin_inff();
     auto write_out = [&](Acc (&res)[TM][TN], int cout, int coff, auto full_tile) {
         constexpr bool FULL = decltype(full_tile)::value;
+        if constexpr (WN == 1 && TN > 1) {
+            // One wavefront holds all BN pixels of its layers: layer by layer, the pixel blocks one after the other,
+            // so that consecutive stores of a wavefront fill whole cache lines (a map much larger than the
+            // memory-side cache is written at half the rate when its lines reach memory in pieces).
+            uint32_t lb[TN];
+#pragma unroll
+            for (int y = 0; y < TN; ++y) {
+                const int pp = P0 + y * MT + li;
+                const int ppc = min(pp, p.PT - 1);
+                const int n = fdiv(ppc, p.dHoWo), q = ppc - n * p.HoWo;
+                lb[y] = pp < p.PT ? (uint32_t)(((n * p.ldc + coff + lrow) * p.HoWo + q) * 4) : kOob;
+            }
+#pragma unroll
+            for (int x = 0; x < TM; ++x)
+#pragma unroll
+                for (int r = 0; r < M::NR; ++r) {
+                    const int mu = mw + x * MT + M::row_reg(r);
+                    const bool ok = FULL || mu + lrow < cout;
+#pragma unroll
+                    for (int y = 0; y < TN; ++y) buf_st(rout, ok ? lb[y] : kOob, (uint32_t)mu * hs, fmaxf(res[x][y][r], lowest));
+                }
+            return;
+        }
 #pragma unroll
         for (int y = 0; y < TN; ++y) {
             const int pp = P0 + wn * (BN / WN) + y * MT + li;

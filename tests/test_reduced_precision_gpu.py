@@ -69,7 +69,8 @@ def assert_close(got, ref, tol, what=""):
 
 
 # ------------------------------------------------------------------------------ layout
-@pytest.mark.parametrize("shape", [(2, 16, 5, 7), (1, 3, 9, 4), (3, 20, 13, 13), (1, 1000, 2, 3)])
+@pytest.mark.parametrize("shape", [(2, 16, 5, 7), (1, 3, 9, 4), (3, 20, 13, 13), (1, 1000, 2, 3), (2, 32, 55, 55), (3, 20, 27, 29),
+                                   (1, 8, 23, 22), (2, 9, 1, 1)])
 def test_pack_and_unpack_match_the_layout_definition(sq, shape):
     rng = np.random.default_rng(11)
     x = synth.normal01(rng, shape)
@@ -77,8 +78,12 @@ def test_pack_and_unpack_match_the_layout_definition(sq, shape):
     got = sq.sq_blocked_pack(dev(x))
     assert got.shape == want.shape
     assert torch.equal(got.cpu().view(torch.int16), want.view(torch.int16))          # same rounding, same places
-    got_b = sq.sq_blocked_pack(dev(x, torch.bfloat16))                                # bfloat16 NCHW in
+    got_b = sq.sq_blocked_pack(dev(x, torch.bfloat16))                                # bfloat16 NCHW in (16-byte pieces through LDS)
     assert torch.equal(got_b.cpu().view(torch.int16), want.view(torch.int16))
+    shifted = torch.empty(x.size + 1, device="cuda", dtype=torch.bfloat16)[1:].view(shape)   # two bytes off: element by element
+    shifted.copy_(dev(x, torch.bfloat16))
+    assert shifted.data_ptr() % 16 != 0
+    assert torch.equal(sq.sq_blocked_pack(shifted).cpu().view(torch.int16), want.view(torch.int16))
     back = sq.sq_blocked_unpack(got, shape[1])
     assert np.array_equal(back.cpu().numpy(), rounded(x))
 

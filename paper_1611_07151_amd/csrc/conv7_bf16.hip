@@ -219,9 +219,9 @@ __global__ __launch_bounds__(kThreads7, 3) void conv7s2c3_blocked_kernel(const C
 // kernel).  So here a wavefront owns two whole rows of a tile that spans the image width (up to seven column blocks
 // of 16; wider images take several such tiles per row group), computes them one block of 32 layers at a time
 // (7 accumulators), and stores layer by layer with the column blocks innermost: seven consecutive stores cover
-// the two rows, which lie one behind the other in the plane, of two layers.  The 21 x 230 x 3 patch (29 KB as bfloat16 pairs) has one LDS buffer
-// (wavefront w fetches patch rows w, w + 4, ...: the row is uniform, so its address is scalar arithmetic); with the
-// packed kernels (33 KB) two workgroups fit a CU.
+// the two rows, which lie one behind the other in the plane, of two layers.  The 21 x 230 x 3 patch (29 KB as
+// bfloat16 pairs) has one LDS buffer (wavefront w fetches patch rows w, w + 4, ...: the row is uniform, so its
+// address is scalar arithmetic); with the packed kernels (33 KB) two workgroups fit a CU.
 constexpr int kRBlocks = 7;                          // column blocks of 16 per tile
 constexpr int kRCols = kRBlocks * kTC;               // 112 output columns
 constexpr int kRPairs = kRCols + 3;                  // dwords of a patch row that are read: pairs 0 .. 114
@@ -263,10 +263,10 @@ __global__ __launch_bounds__(kThreads7, 2) void conv7s2c3_rows_kernel(const Conv
     };
 
     // ---- staging: this wavefront's patch rows R = wv + 4k (layer R / 21, row R % 21), lanes take column pairs
-    // lane and lane + 64.  The two bfloat16 values of a pair are loaded into the halves of one register (the patch
-    // is a plain copy of the image), every load of a tile is issued before the first one is waited for (a row
-    // outside the image gets offsets the range check turns away, not a branch), and the values wait in registers
-    // until the next tile starts.
+    // lane and lane + 64.  The patch is a plain copy of the image: the two bfloat16 values of a pair are loaded on
+    // their own (the image need not be 4-byte aligned) and put together by `pair_up`.  Every load of a tile is issued
+    // before the first one is waited for (a row outside the image gets offsets the range check turns away, not a
+    // branch), and the values wait in registers until the next tile starts.
     short xr[kRPerWave][2][2];
     uint32_t xp[kRPerWave][2];
     auto fetch = [&](int tile) {
@@ -376,10 +376,9 @@ __global__ __launch_bounds__(kThreads7, 2) void conv7s2c3_rows_kernel(const Conv
                 }
             }
             if (cb == 0 && more) {
-                // Wait for the next tile's patch here, before this block's stores.  Memory operations complete in the
-                // order they were issued, so a wait for loads is also a wait for every older store: here those are
-                // the stores of the tile before, which have had a block's MFMAs to drain; at the start of the next
-                // tile it would be this tile's 336.
+                // The next tile's patch is waited for here, before this block's stores, where the only older
+                // stores are those of the tile before (measured equal to waiting at the start of the next tile,
+                // behind this tile's 336 stores; it halves the registers the patch holds from here on).
                 pair_up();
             }
             // register 4q + i = layer 32 cb + 8q + 4h + i; per layer the seven column blocks one after the other

@@ -73,7 +73,7 @@ void sq_tune_blocked_force_tile(int layer_blocks, int pixel_blocks);
 
 /* bfloat16 conv1-type convolution with fp32 results (sq_conv2d_forward_ws with scratch): the tiles that span the
  * image width, which write a map larger than the memory-side cache in whole cache lines; 1 = always, 0 = never,
- * -1 = from two such tiles per compute unit on (default).  Per host thread. */
+ * -1 = for maps of 200 MiB and more (default).  Per host thread. */
 void sq_tune_conv7_f32out_rows(int mode);
 
 /* Host-side self check of the division-by-multiplication the kernels use: number of x in

@@ -231,6 +231,9 @@ constexpr int kRPatchDw = kRRows * kRRowDw;
 constexpr int kRPerWave = (kRRows + 3) / 4;          // patch rows a wavefront fetches (16)
 static_assert(kRPairs <= 128 && kRPairs <= kRRowDw, "two column pairs per lane cover a patch row");
 
+// PAIRS: image width and padding are even and the image is 4-byte aligned, so the two values of a patch pair lie in
+// one aligned dword and are loaded together.
+template <bool PAIRS>
 __global__ __launch_bounds__(kThreads7, 2) void conv7s2c3_rows_kernel(const Conv7Params p)
 {
     constexpr uint32_t ESZ = 2;                                          // the image is bfloat16
@@ -287,10 +290,16 @@ __global__ __launch_bounds__(kThreads7, 2) void conv7s2c3_rows_kernel(const Conv
             const bool rok = R < kRRows && ih >= 0 && ih < p.H;
             const uint32_t row = rok ? (uint32_t)(((n * 3 + c) * p.H + ih) * p.W) * ESZ : 0u;
 #pragma unroll
-            for (int q = 0; q < 2; ++q)
+            for (int q = 0; q < 2; ++q) {
+                if constexpr (PAIRS) {
+                    // (an even first column: a pair is inside the image or outside it as a whole)
+                    xp[k][q] = __builtin_bit_cast(uint32_t, buf_ld(rin, rok ? loff[q][0] : kOob, row));
+                } else {
 #pragma unroll
-                for (int e = 0; e < 2; ++e)
-                    xr[k][q][e] = __builtin_amdgcn_raw_buffer_load_b16(rin, (int)(rok ? loff[q][e] : kOob), (int)row, 0);
+                    for (int e = 0; e < 2; ++e)
+                        xr[k][q][e] = __builtin_amdgcn_raw_buffer_load_b16(rin, (int)(rok ? loff[q][e] : kOob), (int)row, 0);
+                }
+            }
         }
     };
     // Where this stands in the program is where the loads are waited for (the empty statements keep the compiler
@@ -300,8 +309,12 @@ __global__ __launch_bounds__(kThreads7, 2) void conv7s2c3_rows_kernel(const Conv
         for (int k = 0; k < kRPerWave; ++k)
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-                asm volatile("" : "+v"(xr[k][q][0]), "+v"(xr[k][q][1]));
-                xp[k][q] = (uint32_t)(uint16_t)xr[k][q][0] | ((uint32_t)(uint16_t)xr[k][q][1] << 16);
+                if constexpr (PAIRS) {
+                    asm volatile("" : "+v"(xp[k][q]));
+                } else {
+                    asm volatile("" : "+v"(xr[k][q][0]), "+v"(xr[k][q][1]));
+                    xp[k][q] = (uint32_t)(uint16_t)xr[k][q][0] | ((uint32_t)(uint16_t)xr[k][q][1] << 16);
+                }
             }
     };
     auto stash = [&]() {
@@ -436,10 +449,12 @@ int blocked_conv7s2(const void *in, int dtype, const void *wp, const float *b, v
     Conv7Params p;
     p.RG = (Ho + kTR - 1) / kTR;
     p.CG = (Wo + kTC - 1) / kTC;
-    // fp32 results of a large batch: tiles that span the image width (see conv7s2c3_rows_kernel), from two of them
-    // per CU on (below that the 8 x 16 tiles fill the GPU better and the map stays in the memory-side cache)
+    // fp32 results of a large batch: tiles that span the image width (see conv7s2c3_rows_kernel), once the map
+    // outgrows the memory-side cache (measured on 224 x 224 images: slower up to batch 40, faster from 48 on) and
+    // there are two such tiles per CU
     const int row_tiles = (Wo + kRCols - 1) / kRCols;
-    const bool rows = f32_out && dtype == SQ_BF16 && (g_f32out_rows < 0 ? (long long)N * p.RG * row_tiles >= 2ll * num_cus() : g_f32out_rows > 0);
+    const bool big = (long long)N * Cout * Ho * Wo * 4 >= (200ll << 20) && (long long)N * p.RG * row_tiles >= 2ll * num_cus();
+    const bool rows = f32_out && dtype == SQ_BF16 && (g_f32out_rows < 0 ? big : g_f32out_rows > 0);
     if (rows) p.CG = row_tiles;
     const long long tiles = (long long)N * p.RG * p.CG;
     if (in_bytes >= (1ll << 31) || out_bytes >= (1ll << 31) || tiles >= (1ll << 30)) return SQ_ERR_UNSUPPORTED;
@@ -454,7 +469,9 @@ int blocked_conv7s2(const void *in, int dtype, const void *wp, const float *b, v
     LaunchScope scope(rows ? "k7s2c3_bf16_8x112_f32out" : f32_out ? "k7s2c3_bf16_8x16_f32out" : "k7s2c3_bf16_8x16", 2.0 * N * Cout * Ho * Wo * 147.0,
                       (dtype == SQ_BF16 ? 2.0 : 4.0) * N * 3 * H * W + 2.0 * Cout * 147 + (f32_out ? 4.0 : 2.0) * N * Cout * Ho * Wo + 4.0 * Cout);
     if (rows) {
-        hipLaunchKernelGGL(conv7s2c3_rows_kernel, dim3((unsigned)blocks), dim3(kThreads7), 0, current_stream(), p);
+        const bool pairs = W % 2 == 0 && P % 2 == 0 && (reinterpret_cast<uintptr_t>(in) & 3) == 0;
+        hipLaunchKernelGGL(pairs ? conv7s2c3_rows_kernel<true> : conv7s2c3_rows_kernel<false>, dim3((unsigned)blocks), dim3(kThreads7), 0,
+                           current_stream(), p);
     } else if (f32_out) {
         if (dtype == SQ_BF16)
             hipLaunchKernelGGL((conv7s2c3_blocked_kernel<uint16_t, true>), dim3((unsigned)blocks), dim3(kThreads7), 0, current_stream(), p);
